@@ -1,0 +1,154 @@
+/*
+ * sla.h -- C ABI of the MI355X (gfx950) Sparse-Linear Attention forward library.
+ *
+ * The operation is the attention operator of the paper's inference path
+ * (Section 1.3: SLA computed by a low-bit kernel built on SageAttention;
+ * Section 1.1: SageAttention2++-style 8-bit QK^T / PV plus Sparse-Linear
+ * Attention; Section 2.1: Top-K ratio 0.1 = 90 % block sparsity).  For one
+ * (batch, head) slice with N tokens split into consecutive blocks of block_q
+ * queries / block_k keys (last block possibly short):
+ *
+ *   1. block means of Q and K, score s[i][j] = mean(Q_i).mean(K_j)/sqrt(d);
+ *   2. per query block i: the n_c highest-scoring key blocks are CRITICAL (+1),
+ *      the next n_m MARGINAL (0), the rest NEGLIGIBLE (-1); equal scores rank by
+ *      ascending j;  n_c = min(Tk, max(1, floor(topk_ratio*Tk + 1e-9))),
+ *      n_m = min(Tk - n_c, floor(marginal_ratio*Tk + 1e-9));
+ *   3. sparse branch: softmax attention of the block's queries over the keys of
+ *      its critical blocks, visited in ascending j with a running row maximum;
+ *      K is smoothed (channel mean over all N tokens removed) and quantised to
+ *      INT8 with one scale per key block, Q to INT8 with one scale per query
+ *      block, V to FP8 E4M3 with one scale per channel, the probabilities to
+ *      E4M3 after scaling by 448; both products accumulate exactly (int32) or in
+ *      fp32; the row sum uses the unrounded probabilities;
+ *   4. linear branch: with phi a per-token feature map (softmax over channels by
+ *      default) on the ORIGINAL Q and K, O_l = phi(Q) H_i / (phi(Q).Z_i) where
+ *      H_i = sum of phi(K_j)^T V_j and Z_i = sum of column sums of phi(K_j) over
+ *      the marginal blocks j of i;
+ *   5. out = O_s + O_l W^T (+ b), rounded to bf16 (nearest even); the linear term
+ *      and the bias are absent when n_m == 0.
+ *
+ * General rules for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; `Tq`, `Tk`,
+ *     `n_crit`, `n_marg` out-parameters of sla_block_counts are HOST pointers.
+ *   - Layout: q, k, v, out are [B, H, N, d] contiguous, d fastest, bf16.
+ *   - The library allocates nothing, frees nothing and never synchronises; all
+ *     work is enqueued on `stream`.  Scratch lives in `workspace` (256-byte
+ *     aligned, at least sla_workspace_bytes(...) bytes); its contents are
+ *     undefined before and after a call.  Calls sharing a workspace must be
+ *     stream-ordered.
+ *   - Inputs are never written; outputs must not alias inputs or the workspace.
+ *   - Return value: SLA_OK (0) or a negative sla_status.  Argument errors are
+ *     found on the host before anything is launched (nothing is enqueued then).
+ *     SLA_ERR_HIP reports a failed launch.  Nothing throws or aborts.
+ *   - Supported: d == 128; block_k == 64; block_q in {64, 128}; 1 <= N with
+ *     ceil(N/64) <= 8192; B*H*ceil(N/block_q) < 2^31; phi in sla_phi;
+ *     quant_mode == SLA_QUANT_QK_INT8_PV_FP8.
+ *   - Results are deterministic: no floating-point atomics anywhere.
+ */
+#ifndef SLA_H_
+#define SLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ihipStream_t* sla_stream_t; /* a hipStream_t; NULL = the default stream */
+
+typedef enum {
+  SLA_OK = 0,
+  SLA_ERR_NULL = -1,        /* a required pointer is NULL */
+  SLA_ERR_SHAPE = -2,       /* B, H, N <= 0; d != 128; sizes beyond the stated limits */
+  SLA_ERR_BLOCK = -3,       /* block_q not in {64,128} or block_k != 64 */
+  SLA_ERR_RATIO = -4,       /* topk_ratio not in (0,1], marginal_ratio not in [0,1], or sum > 1 */
+  SLA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or too small */
+  SLA_ERR_UNSUPPORTED = -6, /* phi_kind / quant_mode outside what this build implements */
+  SLA_ERR_HIP = -7          /* a kernel launch reported an error */
+} sla_status;
+
+typedef enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1, SLA_PHI_RELU = 2 } sla_phi;
+
+typedef enum {
+  SLA_QUANT_NONE = 0,            /* reserved: 16-bit products (not built) */
+  SLA_QUANT_QK_INT8 = 1,         /* reserved: INT8 QK^T, 16-bit PV (not built) */
+  SLA_QUANT_QK_INT8_PV_FP8 = 2   /* INT8 QK^T with K-smoothing, FP8 E4M3 PV */
+} sla_quant;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sla_version(void);
+
+/* Static string for a status code (never NULL). */
+const char* sla_status_string(int status);
+
+/* Host-only.  Block grid and per-row counts (step 2 above).  Any out pointer may
+ * be NULL.  Returns SLA_OK, SLA_ERR_SHAPE, SLA_ERR_BLOCK or SLA_ERR_RATIO. */
+int sla_block_counts(int N, int block_q, int block_k, double topk_ratio, double marginal_ratio,
+                     int* Tq, int* Tk, int* n_crit, int* n_marg);
+
+/* Host-only.  Bytes of workspace that any entry point below needs for this
+ * problem (one size serves all of them); 0 if the arguments are invalid. */
+size_t sla_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k,
+                           double topk_ratio, double marginal_ratio, int quant_mode);
+
+/* The whole forward pass, steps 1-5.
+ *   q, k, v   in   bf16 [B,H,N,d]
+ *   out       out  bf16 [B,H,N,d]
+ *   proj_w    in   bf16 [d,d] row-major (out channel, in channel), shared by all
+ *                  heads; NULL = identity
+ *   proj_b    in   bf16 [d]; NULL = none */
+int sla_attention_fwd(const void* q, const void* k, const void* v, void* out,
+                      int B, int H, int N, int d, int block_q, int block_k,
+                      double topk_ratio, double marginal_ratio,
+                      const void* proj_w, const void* proj_b, int phi_kind, int quant_mode,
+                      void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+/* Steps 1-2 alone.
+ *   mask           out  int8  [B,H,Tq,Tk], values +1 / 0 / -1
+ *   crit_idx       out  int32 [B,H,Tq,n_crit], ascending j          (may be NULL)
+ *   marg_idx       out  int32 [B,H,Tq,n_marg], ascending j          (may be NULL)
+ *   pooled_scores  out  fp32  [B,H,Tq,Tk], s[i][j]                  (may be NULL) */
+int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d,
+                        int block_q, int block_k, double topk_ratio, double marginal_ratio,
+                        int8_t* mask, int32_t* crit_idx, int32_t* marg_idx, float* pooled_scores,
+                        void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+/* Step 3 alone, for a caller-supplied critical list.
+ *   crit_idx  in   int32 [B,H,Tq,n_crit]; each row strictly ascending, entries in
+ *                  [0,Tk) (not checked: out-of-range entries are undefined behaviour)
+ *   out_s     out  fp32 [B,H,N,d]   O_s
+ *   lse       out  fp32 [B,H,N]     log-sum-exp of each row's (smoothed, quantised)
+ *                  logits over its critical keys, natural log    (may be NULL) */
+int sla_sparse_attn_fwd(const void* q, const void* k, const void* v,
+                        const int32_t* crit_idx, int n_crit, float* out_s, float* lse,
+                        int B, int H, int N, int d, int block_q, int block_k, int quant_mode,
+                        void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+/* Step 4 and the projection of step 5 alone, for a caller-supplied block mask.
+ *   mask   in   int8 [B,H,Tq,Tk]; blocks with value 0 are the marginal ones
+ *   out_l  out  fp32 [B,H,N,d]   O_l W^T (+ b); zero rows where a query block
+ *               has no marginal block */
+int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_t* mask,
+                        const void* proj_w, const void* proj_b, int phi_kind, float* out_l,
+                        int B, int H, int N, int d, int block_q, int block_k,
+                        void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+/* Format check: converts n fp32 values (device) to FP8 E4M3 codes (device) with
+ * the same instruction sequence the kernels use for P and V (round to nearest
+ * even, saturating at +-448).  For tests of the number format only. */
+int sla_debug_e4m3_encode(const float* in, uint8_t* out, size_t n, sla_stream_t stream);
+
+/* Exposes the quantised operands the sparse branch consumes, in plain layouts,
+ * for tests: K codes int8 [B,H,N,d], their per-block scales fp32 [B,H,Tk], the
+ * channel mean fp32 [B,H,d], V codes (E4M3) uint8 [B,H,N,d] and per-channel scales
+ * fp32 [B,H,d].  Any output may be NULL. */
+int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int d, int block_k,
+                          int8_t* k_codes, float* k_scale, float* k_mean,
+                          uint8_t* v_codes, float* v_scale,
+                          void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLA_H_ */

@@ -1,0 +1,211 @@
+"""ctypes binding of libsla.so: argument marshalling only.
+
+Every function here has the name and the argument order of the C entry point
+it calls (include/sla.h); tensors are PyTorch CUDA tensors used purely as
+device memory, the stream is PyTorch's current stream.  No step of the path
+runs in Python, and there is no fallback: if the library is missing or a call
+returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsla.so")
+
+PHI_SOFTMAX, PHI_ELU1, PHI_RELU = 0, 1, 2
+QUANT_NONE, QUANT_QK_INT8, QUANT_QK_INT8_PV_FP8 = 0, 1, 2
+
+SLA_OK = 0
+ERR_NULL, ERR_SHAPE, ERR_BLOCK, ERR_RATIO, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5, -6, -7
+
+EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
+           "sla_attention_fwd", "sla_classify_blocks", "sla_sparse_attn_fwd",
+           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv")
+
+_lib = None
+
+
+class SLAError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().sla_status_string(status).decode()
+        super().__init__("%s failed: %s (status %d)" % (where, msg, status))
+
+
+def lib():
+    """The loaded C-ABI library (opened on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libsla.so is not built: run `python -m paper_2512_16093_amd.build` "
+                               "(expected at %s)" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        c_int, c_dbl, c_vp, c_sz = ctypes.c_int, ctypes.c_double, ctypes.c_void_p, ctypes.c_size_t
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.sla_version.restype = c_int
+        L.sla_version.argtypes = []
+        L.sla_status_string.restype = ctypes.c_char_p
+        L.sla_status_string.argtypes = [c_int]
+        L.sla_block_counts.restype = c_int
+        L.sla_block_counts.argtypes = [c_int, c_int, c_int, c_dbl, c_dbl, ip, ip, ip, ip]
+        L.sla_workspace_bytes.restype = c_sz
+        L.sla_workspace_bytes.argtypes = [c_int] * 6 + [c_dbl, c_dbl, c_int]
+        L.sla_attention_fwd.restype = c_int
+        L.sla_attention_fwd.argtypes = [c_vp] * 4 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp]
+        L.sla_classify_blocks.restype = c_int
+        L.sla_classify_blocks.argtypes = [c_vp, c_vp] + [c_int] * 6 + [c_dbl, c_dbl] + [c_vp] * 4 + [c_vp, c_sz, c_vp]
+        L.sla_sparse_attn_fwd.restype = c_int
+        L.sla_sparse_attn_fwd.argtypes = [c_vp] * 4 + [c_int, c_vp, c_vp] + [c_int] * 7 + [c_vp, c_sz, c_vp]
+        L.sla_linear_attn_fwd.restype = c_int
+        L.sla_linear_attn_fwd.argtypes = [c_vp] * 6 + [c_int, c_vp] + [c_int] * 6 + [c_vp, c_sz, c_vp]
+        L.sla_debug_e4m3_encode.restype = c_int
+        L.sla_debug_e4m3_encode.argtypes = [c_vp, c_vp, c_sz, c_vp]
+        L.sla_debug_quantize_kv.restype = c_int
+        L.sla_debug_quantize_kv.argtypes = [c_vp, c_vp] + [c_int] * 5 + [c_vp] * 5 + [c_vp, c_sz, c_vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, where):
+    if status != SLA_OK:
+        raise SLAError(status, where)
+
+
+def _bf16_4d(*ts):
+    B, H, N, d = ts[0].shape
+    for t in ts:
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, H, N, d):
+            raise ValueError("expected contiguous CUDA bfloat16 tensors of one shape [B,H,N,d]")
+    return B, H, N, d
+
+
+def sla_version():
+    return lib().sla_version()
+
+
+def sla_status_string(status):
+    return lib().sla_status_string(status).decode()
+
+
+def sla_block_counts(N, block_q, block_k, topk_ratio, marginal_ratio):
+    """(Tq, Tk, n_crit, n_marg); raises SLAError on invalid arguments."""
+    vals = [ctypes.c_int(0) for _ in range(4)]
+    st = lib().sla_block_counts(N, block_q, block_k, topk_ratio, marginal_ratio, *[ctypes.byref(v) for v in vals])
+    _check(st, "sla_block_counts")
+    return tuple(v.value for v in vals)
+
+
+def sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, quant_mode=QUANT_QK_INT8_PV_FP8):
+    return lib().sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, quant_mode)
+
+
+def alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, device="cuda"):
+    """Device scratch of the size the library asks for (torch allocations are 256-byte aligned)."""
+    nbytes = sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio)
+    if nbytes == 0:
+        raise ValueError("invalid problem for sla_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def sla_attention_fwd(q, k, v, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None, proj_b=None,
+                      phi_kind=PHI_SOFTMAX, quant_mode=QUANT_QK_INT8_PV_FP8, workspace=None, out=None):
+    B, H, N, d = _bf16_4d(q, k, v)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    if out is None:
+        out = torch.empty_like(q)
+    st = lib().sla_attention_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, N, d, block_q, block_k,
+                                 topk_ratio, marginal_ratio, _ptr(proj_w), _ptr(proj_b), phi_kind, quant_mode,
+                                 _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_attention_fwd")
+    return out
+
+
+def sla_classify_blocks(q, k, block_q, block_k, topk_ratio, marginal_ratio, want_scores=True, workspace=None):
+    """Returns (mask int8 [B,H,Tq,Tk], crit_idx int32, marg_idx int32, pooled_scores fp32 or None)."""
+    B, H, N, d = _bf16_4d(q, k)
+    Tq, Tk, n_c, n_m = sla_block_counts(N, block_q, block_k, topk_ratio, marginal_ratio)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    dev = q.device
+    mask = torch.empty((B, H, Tq, Tk), dtype=torch.int8, device=dev)
+    crit = torch.empty((B, H, Tq, n_c), dtype=torch.int32, device=dev)
+    marg = torch.empty((B, H, Tq, n_m), dtype=torch.int32, device=dev)
+    scores = torch.empty((B, H, Tq, Tk), dtype=torch.float32, device=dev) if want_scores else None
+    st = lib().sla_classify_blocks(_ptr(q), _ptr(k), B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio,
+                                   _ptr(mask), _ptr(crit), _ptr(marg) if n_m else None, _ptr(scores),
+                                   _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_classify_blocks")
+    return mask, crit, marg, scores
+
+
+def sla_sparse_attn_fwd(q, k, v, crit_idx, block_q, block_k, quant_mode=QUANT_QK_INT8_PV_FP8, want_lse=True,
+                        workspace=None):
+    """Returns (out_s fp32 [B,H,N,d], lse fp32 [B,H,N] or None)."""
+    B, H, N, d = _bf16_4d(q, k, v)
+    if crit_idx.dtype != torch.int32 or not crit_idx.is_contiguous() or crit_idx.dim() != 4:
+        raise ValueError("crit_idx must be a contiguous int32 tensor [B,H,Tq,n_crit]")
+    n_c = crit_idx.shape[-1]
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, 1.0, 0.0, q.device)
+    out = torch.empty((B, H, N, d), dtype=torch.float32, device=q.device)
+    lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device) if want_lse else None
+    st = lib().sla_sparse_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(crit_idx), n_c, _ptr(out), _ptr(lse),
+                                   B, H, N, d, block_q, block_k, quant_mode, _ptr(workspace), workspace.numel(),
+                                   _stream())
+    _check(st, "sla_sparse_attn_fwd")
+    return out, lse
+
+
+def sla_linear_attn_fwd(q, k, v, mask, block_q, block_k, proj_w=None, proj_b=None, phi_kind=PHI_SOFTMAX,
+                        workspace=None):
+    """Returns out_l fp32 [B,H,N,d] = O_l W^T (+ b)."""
+    B, H, N, d = _bf16_4d(q, k, v)
+    if mask.dtype != torch.int8 or not mask.is_contiguous():
+        raise ValueError("mask must be a contiguous int8 tensor [B,H,Tq,Tk]")
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, 1.0, 0.0, q.device)
+    out = torch.empty((B, H, N, d), dtype=torch.float32, device=q.device)
+    st = lib().sla_linear_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(mask), _ptr(proj_w), _ptr(proj_b), phi_kind,
+                                   _ptr(out), B, H, N, d, block_q, block_k, _ptr(workspace), workspace.numel(),
+                                   _stream())
+    _check(st, "sla_linear_attn_fwd")
+    return out
+
+
+def sla_debug_e4m3_encode(x):
+    """uint8 E4M3 codes of a CUDA float32 tensor."""
+    x = x.contiguous()
+    out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _check(lib().sla_debug_e4m3_encode(_ptr(x), _ptr(out), x.numel(), _stream()), "sla_debug_e4m3_encode")
+    return out
+
+
+def sla_debug_quantize_kv(k, v, block_k=64, workspace=None):
+    """Returns (k_codes int8 [B,H,N,d], k_scale [B,H,Tk], k_mean [B,H,d], v_codes uint8, v_scale [B,H,d])."""
+    B, H, N, d = _bf16_4d(k, v)
+    Tk = -(-N // block_k)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, 64, block_k, 1.0, 0.0, k.device)
+    dev = k.device
+    kc = torch.empty((B, H, N, d), dtype=torch.int8, device=dev)
+    ks = torch.empty((B, H, Tk), dtype=torch.float32, device=dev)
+    km = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    vc = torch.empty((B, H, N, d), dtype=torch.uint8, device=dev)
+    vs = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    st = lib().sla_debug_quantize_kv(_ptr(k), _ptr(v), B, H, N, d, block_k, _ptr(kc), _ptr(ks), _ptr(km),
+                                     _ptr(vc), _ptr(vs), _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_debug_quantize_kv")
+    return kc, ks, km, vc, vs

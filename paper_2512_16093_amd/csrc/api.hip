@@ -1,0 +1,232 @@
+// C ABI of the SLA forward library: argument checking, workspace carving and the
+// launch sequence.  See include/sla.h for the contract of every entry point.
+#pragma GCC visibility push(default)
+#include "../../include/sla.h"
+#pragma GCC visibility pop
+
+#include <math.h>
+
+#include "common.h"
+
+using namespace sla;
+
+namespace {
+
+int count_blocks(int N, int block_q, int block_k, double rc, double rm, int* Tq, int* Tk, int* nc,
+                 int* nm) {
+  if (N <= 0) return SLA_ERR_SHAPE;
+  if ((block_q != 64 && block_q != 128) || block_k != BK) return SLA_ERR_BLOCK;
+  if (!(rc > 0.0) || rc > 1.0 || !(rm >= 0.0) || rm > 1.0 || rc + rm > 1.0 + 1e-9) return SLA_ERR_RATIO;
+  const long long tq = ((long long)N + block_q - 1) / block_q, tk = ((long long)N + block_k - 1) / block_k;
+  if (tk > 8192) return SLA_ERR_SHAPE;
+  long long c = (long long)floor(rc * (double)tk + 1e-9);
+  if (c < 1) c = 1;
+  if (c > tk) c = tk;
+  long long m = (long long)floor(rm * (double)tk + 1e-9);
+  if (m > tk - c) m = tk - c;
+  if (Tq) *Tq = (int)tq;
+  if (Tk) *Tk = (int)tk;
+  if (nc) *nc = (int)c;
+  if (nm) *nm = (int)m;
+  return SLA_OK;
+}
+
+// Shape / block / ratio checks shared by every device entry point.
+int make_problem(int B, int H, int N, int d, int block_q, int block_k, double rc, double rm, Problem* p) {
+  if (B <= 0 || H <= 0 || N <= 0 || d != D) return SLA_ERR_SHAPE;
+  int Tq, Tk, nc, nm;
+  const int st = count_blocks(N, block_q, block_k, rc, rm, &Tq, &Tk, &nc, &nm);
+  if (st != SLA_OK) return st;
+  const long long rows = (long long)B * H * Tq;
+  if ((long long)B * H > 65535 || rows >= (1ll << 31) - 8 || (long long)B * H * Tk >= (1ll << 31)) return SLA_ERR_SHAPE;
+  p->B = B; p->H = H; p->N = N; p->block_q = block_q;
+  p->BH = B * H; p->Tq = Tq; p->Tk = Tk; p->n_c = nc; p->n_m = nm;
+  return SLA_OK;
+}
+
+int check_ws(const void* ws, size_t bytes, size_t need) {
+  if (!ws || ((uintptr_t)ws & 255) || bytes < need) return SLA_ERR_WORKSPACE;
+  return SLA_OK;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP; }
+
+template <class T>
+T* at(void* ws, size_t off) { return (T*)((unsigned char*)ws + off); }
+
+void run_stats(const void* q, const void* k, const void* v, const Problem& p, void* ws, const Workspace& W,
+               hipStream_t s) {
+  launch_pool_stats(q, k, v, p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.dq),
+                    at<uint32_t>(ws, W.amax_v), s);
+  launch_finalize_stats(p, at<float>(ws, W.kbar), at<uint32_t>(ws, W.amax_v), at<float>(ws, W.mu_k),
+                        at<float>(ws, W.dv), at<bf16_t>(ws, W.eye), s);
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int sla_version(void) { return 100; }
+
+const char* sla_status_string(int status) {
+  switch (status) {
+    case SLA_OK: return "ok";
+    case SLA_ERR_NULL: return "a required pointer is NULL";
+    case SLA_ERR_SHAPE: return "unsupported shape (need B,H,N > 0, d == 128, sizes within limits)";
+    case SLA_ERR_BLOCK: return "unsupported block size (block_q in {64,128}, block_k == 64)";
+    case SLA_ERR_RATIO: return "ratios out of range (0 < topk <= 1, 0 <= marginal <= 1, sum <= 1)";
+    case SLA_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
+    case SLA_ERR_UNSUPPORTED: return "phi_kind or quant_mode not implemented";
+    case SLA_ERR_HIP: return "a kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int sla_block_counts(int N, int block_q, int block_k, double topk_ratio, double marginal_ratio, int* Tq,
+                     int* Tk, int* n_crit, int* n_marg) {
+  return count_blocks(N, block_q, block_k, topk_ratio, marginal_ratio, Tq, Tk, n_crit, n_marg);
+}
+
+size_t sla_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k, double topk_ratio,
+                           double marginal_ratio, int quant_mode) {
+  Problem p;
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return 0;
+  if (make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p) != SLA_OK) return 0;
+  // the stage entry points take caller-chosen lists (up to every block critical or marginal)
+  return make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m).total;
+}
+
+int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,
+                      int block_q, int block_k, double topk_ratio, double marginal_ratio,
+                      const void* proj_w, const void* proj_b, int phi_kind, int quant_mode, void* workspace,
+                      size_t workspace_bytes, sla_stream_t stream) {
+  if (!q || !k || !v || !out) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  const bool lin = p.n_m > 0;
+
+  run_stats(q, k, v, p, ws, W, s);
+  launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
+  launch_select(p, at<float>(ws, W.scores), at<int8_t>(ws, W.mask), at<int32_t>(ws, W.crit), nullptr, s);
+  const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, true, lin,
+                 at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+  if (lin) {
+    launch_marginal_rows(p, at<int8_t>(ws, W.mask), at<uint8_t>(ws, W.m0), s);
+    launch_lin_accumulate(p, at<uint8_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+  }
+  launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
+                    at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
+                    (const bf16_t*)proj_b, phi_kind, lin, out, false, nullptr, s);
+  return launch_status();
+}
+
+int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d, int block_q, int block_k,
+                        double topk_ratio, double marginal_ratio, int8_t* mask, int32_t* crit_idx,
+                        int32_t* marg_idx, float* pooled_scores, void* workspace, size_t workspace_bytes,
+                        sla_stream_t stream) {
+  if (!q || !k || !mask) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  // V is not an input here: the statistics pass reads K in its place (its V outputs are unused)
+  launch_pool_stats(q, k, k, p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.dq),
+                    at<uint32_t>(ws, W.amax_v), s);
+  float* sc = pooled_scores ? pooled_scores : at<float>(ws, W.scores);
+  launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), sc, s);
+  launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, s);
+  return launch_status();
+}
+
+int sla_sparse_attn_fwd(const void* q, const void* k, const void* v, const int32_t* crit_idx, int n_crit,
+                        float* out_s, float* lse, int B, int H, int N, int d, int block_q, int block_k,
+                        int quant_mode, void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  if (!q || !k || !v || !crit_idx || !out_s) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, 1.0, 0.0, &p);
+  if (st != SLA_OK) return st;
+  if (n_crit < 1 || n_crit > p.Tk) return SLA_ERR_SHAPE;
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
+  // the internal index lists are not used here, so the smallest workspace that
+  // sla_workspace_bytes can return for this shape is enough
+  const Workspace Wmin = make_workspace(p.BH, p.Tq, p.Tk, 1, 0);
+  if ((st = check_ws(workspace, workspace_bytes, Wmin.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  run_stats(q, k, v, p, ws, Wmin, s);
+  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<float>(ws, Wmin.dv), at<bf16_t>(ws, Wmin.eye), 0, true,
+                 false, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8), at<float>(ws, Wmin.dk), nullptr, s);
+  launch_sparse_fwd(q, p, crit_idx, n_crit, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8),
+                    at<float>(ws, Wmin.dq), at<float>(ws, Wmin.dk), at<float>(ws, Wmin.dv), nullptr, nullptr, 0,
+                    false, out_s, true, lse, s);
+  return launch_status();
+}
+
+int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_t* mask, const void* proj_w,
+                        const void* proj_b, int phi_kind, float* out_l, int B, int H, int N, int d,
+                        int block_q, int block_k, void* workspace, size_t workspace_bytes,
+                        sla_stream_t stream) {
+  if (!q || !k || !v || !mask || !out_l) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, 1.0, 0.0, &p);
+  if (st != SLA_OK) return st;
+  if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, 1, 0);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  run_stats(q, k, v, p, ws, W, s);
+  const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, false, true, nullptr,
+                 nullptr, nullptr, at<bf16_t>(ws, W.hz), s);
+  launch_marginal_rows(p, mask, at<uint8_t>(ws, W.m0), s);
+  launch_lin_accumulate(p, at<uint8_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+  // the attention kernel with an empty critical list leaves only the linear term
+  launch_sparse_fwd(q, p, nullptr, 0, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dq),
+                    at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ), (const bf16_t*)proj_b,
+                    phi_kind, true, out_l, true, nullptr, s);
+  return launch_status();
+}
+
+int sla_debug_e4m3_encode(const float* in, uint8_t* out, size_t n, sla_stream_t stream) {
+  if (!in || !out) return SLA_ERR_NULL;
+  launch_e4m3_encode(in, out, n, (hipStream_t)stream);
+  return launch_status();
+}
+
+int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int d, int block_k,
+                          int8_t* k_codes, float* k_scale, float* k_mean, uint8_t* v_codes, float* v_scale,
+                          void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  if (!k || !v) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, 64, block_k, 1.0, 0.0, &p);
+  if (st != SLA_OK) return st;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, 1, 0);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  run_stats(k, k, v, p, ws, W, s);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.eye), 0, true, false,
+                 at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), nullptr, s);
+  launch_unfragment_kv(p, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), k_codes, v_codes, s);
+  const size_t bhd = (size_t)p.BH * D * 4;
+  if (k_scale && hipMemcpyAsync(k_scale, at<float>(ws, W.dk), (size_t)p.BH * p.Tk * 4, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
+  if (k_mean && hipMemcpyAsync(k_mean, at<float>(ws, W.mu_k), bhd, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
+  if (v_scale && hipMemcpyAsync(v_scale, at<float>(ws, W.dv), bhd, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
+  return launch_status();
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

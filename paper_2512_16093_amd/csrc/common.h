@@ -1,0 +1,156 @@
+// Shared device helpers and the workspace map for the SLA forward kernels (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sla {
+
+constexpr int D = 128;          // head dimension (fixed)
+constexpr int BK = 64;          // key block size (fixed)
+constexpr int HZ_ROWS = D + 1;  // per key block: 128 rows of h'^T plus the z row
+constexpr int HZ_ELEMS = HZ_ROWS * D;
+constexpr int KV_FRAG_BYTES = BK * D;  // 8 KiB of INT8 K codes / FP8 V codes per key block
+constexpr float E4M3_MAX = 448.0f;
+constexpr float LOG2_448 = 8.807354922057604f;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// Two fp32 -> two E4M3 codes packed into the low or high half of `old`.  The
+// hardware conversion rounds to nearest even and turns anything above 464 into
+// NaN, so callers keep |x| <= 448 (clamp_e4m3) first.
+__device__ __forceinline__ float clamp_e4m3(float x) { return __builtin_fminf(__builtin_fmaxf(x, -E4M3_MAX), E4M3_MAX); }
+__device__ __forceinline__ int cvt_pk_e4m3(float a, float b, int old, bool hi) {
+  return hi ? __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, true) : __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, false);
+}
+
+// Value held by the partner lane (lane ^ 32) of a 64-wide wavefront.
+__device__ __forceinline__ float partner_f32(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+  // lanes < 32: r[1] is the upper half's value; lanes >= 32: r[0] is the lower half's value
+  return __int_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+__device__ __forceinline__ int partner_i32(int x) {
+  auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  return (threadIdx.x & 32) ? r[0] : r[1];
+}
+
+// ---------------------------------------------------------------------------
+// Fragment order of the quantised K / V tiles (one 8 KiB record per key block).
+//
+// K record: 16-byte chunks indexed [t][s][lane], t = key tile (32 keys), s = step
+// of 32 channels, lane = (key % 32) + 32*hf; the chunk holds channels
+// 32*s + 16*hf + (0..15) of key 32*t + (lane % 32).  A wavefront reading chunk
+// [t][s][its lane] gets the A operand of v_mfma_i32_32x32x32_i8.
+__device__ __forceinline__ int kfrag_offset(int key, int ch) {
+  int t = key >> 5, s = ch >> 5, hf = (ch >> 4) & 1;
+  return (((t * 4 + s) * 64) + (key & 31) + 32 * hf) * 16 + (ch & 15);
+}
+// V record: 16-byte chunks indexed [ct][half][lane], ct = channel tile (32
+// channels), lane = (ch % 32) + 32*hf; byte e of the chunk is key slot
+// u = 16*half + e of that lane, and slot u of lane-half hf is key
+// 32*(u/16) + 8*((u%16)/4) + 4*hf + (u%4) -- the order in which the score
+// accumulators of v_mfma_i32_32x32x32_i8 sit in a lane, so the FP8 P codes can be
+// used as the B operand of v_mfma_f32_32x32x64_f8f6f4 without any shuffle.
+__device__ __forceinline__ int vfrag_offset(int key, int ch) {
+  int t = key >> 5, g = (key >> 3) & 3, hf = (key >> 2) & 1, cc = key & 3;
+  int u = 16 * t + 4 * g + cc;
+  return ((((ch >> 5) * 2 + (u >> 4)) * 64) + (ch & 31) + 32 * hf) * 16 + (u & 15);
+}
+
+// ---------------------------------------------------------------------------
+// Workspace map (all offsets 256-byte aligned).
+struct Workspace {
+  size_t qbar, kbar;        // fp32 [BH,Tq,D], [BH,Tk,D] block means
+  size_t dq;                // fp32 [BH,Tq]  per-query-block INT8 scale
+  size_t mu_k, amax_v, dv;  // fp32 [BH,D]   channel mean of K, max|V| (as uint bits), V scale
+  size_t dk;                // fp32 [BH,Tk]  per-key-block INT8 scale
+  size_t scores;            // fp32 [BH,Tq,Tk]
+  size_t mask;              // int8 [BH,Tq,Tk]
+  size_t m0;                // uint8 [BH,Tq,Tkp] 1 = marginal, rows zero-padded to a multiple of 32
+  size_t crit, marg;        // int32 [BH,Tq,n_c], [BH,Tq,n_m]
+  size_t k8, v8;            // [BH,Tk] records of KV_FRAG_BYTES
+  size_t hz;                // bf16 [BH,Tk,HZ_ROWS,D]
+  size_t HZ;                // bf16 [BH,Tq,HZ_ROWS,D]
+  size_t eye;               // bf16 [D,D] identity (used when no projection is given)
+  size_t total;
+};
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, size_t n_m) {
+  Workspace w;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align256(o + bytes); return r; };
+  w.qbar = take(BH * Tq * D * 4);
+  w.kbar = take(BH * Tk * D * 4);
+  w.dq = take(BH * Tq * 4);
+  w.mu_k = take(BH * D * 4);
+  w.amax_v = take(BH * D * 4);
+  w.dv = take(BH * D * 4);
+  w.dk = take(BH * Tk * 4);
+  w.scores = take(BH * Tq * Tk * 4);
+  w.mask = take(BH * Tq * Tk);
+  w.m0 = take(BH * Tq * ((Tk + 31) / 32 * 32));
+  w.crit = take(BH * Tq * n_c * 4);
+  w.marg = take(BH * Tq * (n_m ? n_m : 1) * 4);
+  w.k8 = take(BH * Tk * KV_FRAG_BYTES);
+  w.v8 = take(BH * Tk * KV_FRAG_BYTES);
+  w.hz = take(BH * Tk * HZ_ELEMS * 2);
+  w.HZ = take(BH * Tq * HZ_ELEMS * 2);
+  w.eye = take(D * D * 2);
+  w.total = o;
+  return w;
+}
+
+// Problem description handed to the launchers.
+struct Problem {
+  int B, H, N, block_q;
+  int BH, Tq, Tk, n_c, n_m;
+};
+
+// Launchers (one per kernel file); every one only enqueues work on `stream`.
+void launch_pool_stats(const void* q, const void* k, const void* v, const Problem& p, float* qbar,
+                       float* kbar, float* dq, uint32_t* amax_v, hipStream_t stream);
+void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,
+                           float* dv, bf16_t* eye, hipStream_t stream);
+void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores, hipStream_t stream);
+void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
+                   hipStream_t stream);
+void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
+                    const bf16_t* proj_w, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
+                    uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream);
+void launch_marginal_rows(const Problem& p, const int8_t* mask, uint8_t* m0, hipStream_t stream);
+void launch_lin_accumulate(const Problem& p, const uint8_t* m0, const bf16_t* hz, bf16_t* HZ,
+                           hipStream_t stream);
+void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
+                       const uint8_t* v8, const float* dq, const float* dk, const float* dv,
+                       const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
+                       void* out, bool out_f32, float* lse, hipStream_t stream);
+void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
+                          uint8_t* v_codes, hipStream_t stream);
+void launch_e4m3_encode(const float* in, uint8_t* out, size_t n, hipStream_t stream);
+
+}  // namespace sla

@@ -1,0 +1,258 @@
+// prep_kv: per key block, the operands of both branches.
+//
+//  * Low-bit sparse branch (Section 1.1 names the scheme; the granularity is this
+//    library's reading, see sla.h): K~ = K - mean_K, INT8 codes with one scale per key
+//    block; V / delta_V[c] as FP8 E4M3 codes.  Both are written in MFMA fragment order
+//    (common.h) so the attention kernel stages them with straight 16-byte copies.
+//  * Linear branch: with phi the per-token feature map on the ORIGINAL K,
+//        hz[o][c] = sum_rows (V W^T)[row][o] * phi(K)[row][c]   (o < 128)
+//        hz[128][c] = sum_rows phi(K)[row][c]
+//    i.e. the block summary h_j with the output projection already folded in
+//    (transposed, c contiguous) and z_j as row 128.  Two bf16 MFMA products with fp32
+//    accumulation; the first product's accumulators are fed to the second as its A
+//    operand directly from registers (the contraction order of the second product is
+//    permuted to match, for both operands).
+//
+// One workgroup (4 wavefronts) per (b,h,j).  HBM-bound: reads 32 KiB, writes 16 KiB of
+// codes and 33 KiB of summaries per block.
+#include "common.h"
+
+namespace sla {
+
+constexpr int STAGE_STRIDE = 2 * D + 16;  // bytes per staged hz row (padded against bank conflicts)
+
+template <int PHI>
+__global__ void __launch_bounds__(256) prep_kv_kernel(
+    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk,
+    const float* __restrict__ mu_k, const float* __restrict__ dv, const bf16_t* __restrict__ W,
+    int want_quant, int want_linear, int8_t* __restrict__ k8, uint8_t* __restrict__ v8,
+    float* __restrict__ dk, bf16_t* __restrict__ hz) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[128 * STAGE_STRIDE + 16 * D * 4];
+  __shared__ float wave_amax[4];
+  unsigned char* kq = smem;                       // [8192]  K codes, fragment order
+  unsigned char* vq = smem + KV_FRAG_BYTES;       // [8192]  V codes, fragment order
+  unsigned char* phit = smem + 2 * KV_FRAG_BYTES; // [16384] phi(K)^T bf16, B-operand order
+  unsigned char* stage = smem;                    // [128][STAGE_STRIDE] aliases the three above
+  float* zred = (float*)(smem + 128 * STAGE_STRIDE);  // [16][128]
+
+  const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk;
+  const int t = threadIdx.x, cg = t & 15, m = t >> 4, lane = t & 63, w = t >> 6;
+  const int valid = min(BK, N - j * BK);
+  const size_t base = ((size_t)bh * N + (size_t)j * BK) * D;
+
+  float kf[4][8], vf[4][8];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = 4 * m + r;
+    uint4 xk = make_uint4(0, 0, 0, 0), xv = make_uint4(0, 0, 0, 0);
+    if (row < valid) {
+      xk = *(const uint4*)(k + base + (size_t)row * D + cg * 8);
+      xv = *(const uint4*)(v + base + (size_t)row * D + cg * 8);
+    }
+    const uint32_t wk[4] = {xk.x, xk.y, xk.z, xk.w}, wv[4] = {xv.x, xv.y, xv.z, xv.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      kf[r][2 * e] = bf16_lo(wk[e]);
+      kf[r][2 * e + 1] = bf16_hi(wk[e]);
+      vf[r][2 * e] = bf16_lo(wv[e]);
+      vf[r][2 * e + 1] = bf16_hi(wv[e]);
+    }
+  }
+
+  if (want_quant) {
+    float mu[8], dvc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      mu[e] = mu_k[(size_t)bh * D + cg * 8 + e];
+      dvc[e] = dv[(size_t)bh * D + cg * 8 + e];
+    }
+    float kt[4][8], amax = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        kt[r][e] = (4 * m + r < valid) ? kf[r][e] - mu[e] : 0.f;
+        amax = fmaxf(amax, fabsf(kt[r][e]));
+      }
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    if (lane == 0) wave_amax[w] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(wave_amax[0], wave_amax[1]), fmaxf(wave_amax[2], wave_amax[3]));
+    const float delta = amax > 0.f ? amax / 127.0f : 1.0f;
+    if (t == 0) dk[(size_t)bh * Tk + j] = delta;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      uint32_t lo = 0, hi = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float c = __builtin_rintf(kt[r][e] / delta);
+        c = fminf(fmaxf(c, -127.f), 127.f);
+        const uint32_t byte = (uint32_t)((int)c) & 0xffu;
+        if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+      }
+      *(uint2*)(kq + kfrag_offset(4 * m + r, cg * 8)) = make_uint2(lo, hi);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float x[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) x[r] = clamp_e4m3(vf[r][e] / dvc[e]);
+      int code = cvt_pk_e4m3(x[0], x[1], 0, false);
+      code = cvt_pk_e4m3(x[2], x[3], code, true);
+      *(int*)(vq + vfrag_offset(4 * m, cg * 8 + e)) = code;
+    }
+    __syncthreads();
+    const size_t rec = ((size_t)bh * Tk + j) * KV_FRAG_BYTES;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int o = (u * 256 + t) * 16;
+      *(uint4*)(k8 + rec + o) = *(const uint4*)(kq + o);
+      *(uint4*)(v8 + rec + o) = *(const uint4*)(vq + o);
+    }
+  }
+  if (!want_linear) return;
+
+  // ---- phi(K): rows live across the 16 lanes that share m
+  float ph[4][8];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const bool ok = 4 * m + r < valid;
+    if (PHI == 0) {
+      float mx = kf[r][0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, kf[r][e]);
+      for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        ph[r][e] = __builtin_amdgcn_exp2f((kf[r][e] - mx) * LOG2E);
+        s += ph[r][e];
+      }
+      for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o);
+      const float inv = ok ? 1.0f / s : 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ph[r][e] *= inv;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = kf[r][e];
+        float y;
+        if (PHI == 1) y = x > 0.f ? x + 1.0f : __builtin_amdgcn_exp2f(x * LOG2E);
+        else y = fmaxf(x, 0.f);
+        ph[r][e] = ok ? y : 0.f;
+      }
+    }
+  }
+  __syncthreads();  // kq / vq reads are done; phit may now be written
+  {
+    const int tt = m >> 3, g = (m & 7) >> 1, hf = m & 1, s2 = tt * 2 + (g >> 1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = cg * 8 + e;
+      const uint2 pk = make_uint2(pack_bf16x2(ph[0][e], ph[1][e]), pack_bf16x2(ph[2][e], ph[3][e]));
+      *(uint2*)(phit + ((s2 * 128 + c) * 2 + hf) * 16 + (g & 1) * 8) = pk;
+      zred[m * D + c] = ph[0][e] + ph[1][e] + ph[2][e] + ph[3][e];
+    }
+  }
+
+  // ---- product 1: VW[row][o] for o in this wavefront's tile of 32 output channels
+  const int hfl = lane >> 5, l32 = lane & 31;
+  v16f d1[2];
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt) {
+    d1[rt] = v16f{};
+    const int row = 32 * rt + l32;
+    const bool ok = row < valid;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      v8bf a = v8bf{};
+      if (ok) a = *(const v8bf*)(v + base + (size_t)row * D + 16 * ks + 8 * hfl);
+      const v8bf b = *(const v8bf*)(W + (size_t)(32 * w + l32) * D + 16 * ks + 8 * hfl);
+      d1[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, d1[rt], 0, 0, 0);
+    }
+  }
+  __syncthreads();  // phit and zred complete
+
+  // ---- product 2: hz[o][c] = sum over rows of VW[row][o] phi[row][c]
+  v16f d2[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) d2[ct] = v16f{};
+#pragma unroll
+  for (int s2 = 0; s2 < 4; ++s2) {
+    v8bf a;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = (__bf16)d1[s2 >> 1][8 * (s2 & 1) + e];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const v8bf b = *(const v8bf*)(phit + ((s2 * 128 + 32 * ct + l32) * 2 + hfl) * 16);
+      d2[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, d2[ct], 0, 0, 0);
+    }
+  }
+  float zsum = 0.f;
+  if (t < D) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) zsum += zred[r * D + t];
+  }
+  __syncthreads();  // every wavefront is done reading phit: the staging area may overwrite it
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int o = 32 * w + 8 * (r >> 2) + 4 * hfl + (r & 3);
+      *(bf16_t*)(stage + o * STAGE_STRIDE + (32 * ct + l32) * 2) = f32_to_bf16(d2[ct][r]);
+    }
+  __syncthreads();
+  bf16_t* dst = hz + ((size_t)bh * Tk + j) * HZ_ELEMS;
+  for (int e = t; e < 128 * 16; e += 256) {
+    const int o = e >> 4, part = e & 15;
+    *(uint4*)(dst + o * D + part * 8) = *(const uint4*)(stage + o * STAGE_STRIDE + part * 16);
+  }
+  if (t < D) dst[D * D + t] = f32_to_bf16(zsum);
+}
+
+// Plain-layout copies of the codes (tests only).
+__global__ void unfragment_kv_kernel(const int8_t* __restrict__ k8, const uint8_t* __restrict__ v8,
+                                     int N, int Tk, int8_t* __restrict__ k_codes,
+                                     uint8_t* __restrict__ v_codes) {
+  const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk;
+  const size_t rec = ((size_t)bh * Tk + j) * KV_FRAG_BYTES;
+  for (int e = threadIdx.x; e < BK * D; e += blockDim.x) {
+    const int key = e / D, ch = e % D;
+    const int row = j * BK + key;
+    if (row >= N) continue;
+    const size_t o = ((size_t)bh * N + row) * D + ch;
+    if (k_codes) k_codes[o] = k8[rec + kfrag_offset(key, ch)];
+    if (v_codes) v_codes[o] = v8[rec + vfrag_offset(key, ch)];
+  }
+}
+
+__global__ void e4m3_encode_kernel(const float* __restrict__ in, uint8_t* __restrict__ out, size_t n) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) out[i] = (uint8_t)(cvt_pk_e4m3(clamp_e4m3(in[i]), 0.f, 0, false) & 0xff);
+}
+
+void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
+                    const bf16_t* proj_w, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
+                    uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream) {
+  const unsigned grid = (unsigned)(p.BH * p.Tk);
+  const bf16_t* kk = (const bf16_t*)k;
+  const bf16_t* vv = (const bf16_t*)v;
+  if (phi_kind == 0)
+    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+  else if (phi_kind == 1)
+    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+  else
+    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+}
+
+void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
+                          uint8_t* v_codes, hipStream_t stream) {
+  unfragment_kv_kernel<<<p.BH * p.Tk, 256, 0, stream>>>(k8, v8, p.N, p.Tk, k_codes, v_codes);
+}
+
+void launch_e4m3_encode(const float* in, uint8_t* out, size_t n, hipStream_t stream) {
+  if (n == 0) return;
+  e4m3_encode_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(in, out, n);
+}
+
+}  // namespace sla

@@ -1,0 +1,345 @@
+// sparse_fwd: the block-sparse low-bit softmax branch with the linear branch fused
+// into its epilogue (Section 1.3: SLA computed by one low-bit attention kernel;
+// Section 1.1: INT8 QK^T / FP8 PV in the SageAttention2++ manner).
+//
+// One workgroup per (b,h,query block); one wavefront per 32 queries.  Everything is
+// computed transposed so that a lane owns ONE query (column) throughout:
+//   S^T[key][query]  = K8 . Q8^T      v_mfma_i32_32x32x32_i8, A = K fragment (LDS), B = Q8 (registers)
+//   P8 = e4m3(448 exp(S - m))         in registers; the running max / sum of a query live
+//                                     in its two lanes (lane, lane^32): one permlane swap per block
+//   O^T[ch][query] += V8^T . P8^T     v_mfma_f32_32x32x64_f8f6f4, A = V fragment (LDS), B = P8 as it
+//                                     sits in the accumulators' order (V was stored in that key order)
+// so the rescale factor, the row sum and the final normalisation are per-lane scalars and P
+// never touches LDS.  K/V fragments of the next critical block are fetched into registers while
+// the current one is consumed, then written to the other LDS buffer (one barrier per block).
+//
+// Epilogue: O_s = acc * delta_V / l;  optional linear term phi(Q) H_i / (phi(Q).Z_i) as bf16 MFMA
+// (H_i already contains the output projection), bias, then a transposing pass through LDS so
+// the global stores are row-contiguous.
+#include "common.h"
+
+namespace sla {
+
+struct SparseArgs {
+  const bf16_t* q;
+  const int32_t* crit;
+  const int8_t* k8;
+  const uint8_t* v8;
+  const float* dq;
+  const float* dk;
+  const float* dv;
+  const bf16_t* HZ;
+  const bf16_t* bias;
+  void* out;
+  float* lse;
+  int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32;
+};
+
+constexpr int STAGE_BYTES = 2 * KV_FRAG_BYTES;  // K + V record of one key block
+constexpr int EPI_STRIDE = 64 * 4 + 16;         // bytes per staged output row (64 fp32 + pad)
+
+__device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
+  uint4 a = make_uint4(0, 0, 0, 0), b = a;
+  if (ok) {
+    a = ((const uint4*)p)[0];
+    b = ((const uint4*)p)[1];
+  }
+  const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    x[2 * e] = bf16_lo(w[e]);
+    x[2 * e + 1] = bf16_hi(w[e]);
+  }
+}
+
+template <int NW>
+__global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(const SparseArgs A) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int NT = NW * 64;
+  constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
+  constexpr int BQ = NW * 32;
+
+  // Consecutive query blocks of a head run on the same XCD (workgroup ids are dealt
+  // round-robin over the 8 XCDs), so neighbours share K/V fragments in that XCD's L2.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rowid = xcd * A.per_xcd + slot;
+  if (rowid >= A.total) return;
+  const int bh = rowid / A.Tq, i = rowid % A.Tq;
+
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int qrow = i * BQ + 32 * w + l32;
+  const bool qok = qrow < A.N;
+  const bf16_t* qptr = A.q + ((size_t)bh * A.N + (qok ? qrow : 0)) * D;
+
+  // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each)
+  const float dqi = A.dq[(size_t)bh * A.Tq + i];
+  v4i q8[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    float x[16];
+    load_q16(qptr + 32 * s + 16 * hf, qok, x);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint32_t wv = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float c = __builtin_rintf(x[4 * g + e] / dqi);
+        c = fminf(fmaxf(c, -127.f), 127.f);
+        wv |= ((uint32_t)((int)c) & 0xffu) << (8 * e);
+      }
+      q8[s][g] = (int)wv;
+    }
+  }
+  const float cq = dqi * (LOG2E / 11.313708498984761f);
+
+  v16f acc[4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
+  float M = -INFINITY, lsum = 0.f;
+
+  const int32_t* crow = A.crit + (size_t)rowid * A.n_c;
+  const size_t rec0 = (size_t)bh * A.Tk * KV_FRAG_BYTES;
+  uint4 pre[CH];
+  auto gload = [&](int j) {
+    const uint4* ks = (const uint4*)(A.k8 + rec0 + (size_t)j * KV_FRAG_BYTES);
+    const uint4* vs = (const uint4*)(A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES);
+#pragma unroll
+    for (int u = 0; u < CH / 2; ++u) {
+      pre[u] = ks[u * NT + t];
+      pre[CH / 2 + u] = vs[u * NT + t];
+    }
+  };
+  auto lstore = [&](int buf) {
+    uint4* kd = (uint4*)(lds + buf * STAGE_BYTES);
+    uint4* vd = kd + KV_FRAG_BYTES / 16;
+#pragma unroll
+    for (int u = 0; u < CH / 2; ++u) {
+      kd[u * NT + t] = pre[u];
+      vd[u * NT + t] = pre[CH / 2 + u];
+    }
+  };
+
+  const int n_c = A.n_c;
+  int j_cur = n_c > 0 ? crow[0] : 0;
+  if (n_c > 0) {
+    gload(j_cur);
+    lstore(0);
+  }
+  __syncthreads();
+  const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
+
+  for (int jj = 0; jj < n_c; ++jj) {
+    const int buf = jj & 1;
+    const int j_next = (jj + 1 < n_c) ? crow[jj + 1] : 0;
+    if (jj + 1 < n_c) gload(j_next);
+    const float c2 = cq * A.dk[(size_t)bh * A.Tk + j_cur];
+
+    const uint4* kl = (const uint4*)(lds + buf * STAGE_BYTES);
+    const uint4* vl = kl + KV_FRAG_BYTES / 16;
+    v16i s0 = v16i{}, s1 = v16i{};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint4 a0 = kl[s * 64 + lane], a1 = kl[(4 + s) * 64 + lane];
+      s0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w}, q8[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w}, q8[s], s1, 0, 0, 0);
+    }
+    if (j_cur == A.Tk - 1 && kvalid_last < BK) {  // keys past the end of the sequence
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (key >= kvalid_last) s0[r] = -(1 << 30);
+        if (32 + key >= kvalid_last) s1[r] = -(1 << 30);
+      }
+    }
+    int imax = s0[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) imax = max(imax, s0[r]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) imax = max(imax, s1[r]);
+    imax = max(imax, partner_i32(imax));
+    const float Mn = fmaxf(M, (float)imax * c2);
+    if (__any(Mn > M)) {
+      const float alpha = __builtin_amdgcn_exp2f(M - Mn);
+      lsum *= alpha;
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ct][r] *= alpha;
+    }
+    M = Mn;
+    const float offs = LOG2_448 - M;
+    v8i pb;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float p[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s0[4 * g + e], c2, offs));
+        lsum += p[e];
+      }
+      pb[g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s1[4 * g + e], c2, offs));
+        lsum += p[e];
+      }
+      pb[4 + g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
+    }
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      const uint4 a0 = vl[(ct * 2) * 64 + lane], a1 = vl[(ct * 2 + 1) * 64 + lane];
+      const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+      acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 0, 0, 0);
+    }
+    if (jj + 1 < n_c) lstore(buf ^ 1);
+    j_cur = j_next;
+    __syncthreads();
+  }
+
+  // ---- normalise: O_s[q][ch] = acc * delta_V[ch] / l
+  const float ltot = lsum + partner_f32(lsum);
+  const float inv_l = ltot > 0.f ? 1.0f / ltot : 0.f;
+  if (A.lse && hf == 0 && qok)
+    A.lse[(size_t)bh * A.N + qrow] = (M + __builtin_amdgcn_logf(ltot) - LOG2_448) * LN2;
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 d4 = *(const float4*)(A.dv + (size_t)bh * D + 32 * ct + 8 * g + 4 * hf);
+      acc[ct][4 * g + 0] *= d4.x * inv_l;
+      acc[ct][4 * g + 1] *= d4.y * inv_l;
+      acc[ct][4 * g + 2] *= d4.z * inv_l;
+      acc[ct][4 * g + 3] *= d4.w * inv_l;
+    }
+
+  // ---- linear branch: O_l^T[o][q] = sum_c H[o][c] phi(Q)[q][c], divided by phi(Q).Z
+  if (A.has_lin) {
+    const bf16_t* Hi = A.HZ + (size_t)rowid * HZ_ELEMS;
+    v8bf bq[8];
+    float den = 0.f;
+    {
+      float x[64];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) load_q16(qptr + 32 * s + 16 * hf, qok, x + 16 * s);
+      if (A.phi == 0) {
+        float mx = x[0];
+#pragma unroll
+        for (int e = 1; e < 64; ++e) mx = fmaxf(mx, x[e]);
+        mx = fmaxf(mx, partner_f32(mx));
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 64; ++e) {
+          x[e] = __builtin_amdgcn_exp2f((x[e] - mx) * LOG2E);
+          sum += x[e];
+        }
+        sum += partner_f32(sum);
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int e = 0; e < 64; ++e) x[e] *= inv;
+      } else if (A.phi == 1) {
+#pragma unroll
+        for (int e = 0; e < 64; ++e) x[e] = x[e] > 0.f ? x[e] + 1.0f : __builtin_amdgcn_exp2f(x[e] * LOG2E);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 64; ++e) x[e] = fmaxf(x[e], 0.f);
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        float z[16];
+        load_q16(Hi + D * D + 32 * s + 16 * hf, true, z);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const __bf16 pb16 = (__bf16)x[16 * s + e];
+          bq[2 * s + (e >> 3)][e & 7] = pb16;
+          den = __builtin_fmaf((float)pb16, z[e], den);
+        }
+      }
+    }
+    den += partner_f32(den);
+    const float inv_den = den != 0.f ? 1.0f / den : 0.f;  // no marginal block: no linear term
+#pragma unroll
+    for (int ot = 0; ot < 4; ++ot) {
+      v16f al = v16f{};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const v8bf a = *(const v8bf*)(Hi + (size_t)(32 * ot + l32) * D + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
+        al = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[ks], al, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ot][r] = __builtin_fmaf(al[r], inv_den, acc[ot][r]);
+    }
+    if (A.bias) {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          acc[ct][r] += bf16_to_f32(A.bias[32 * ct + 8 * (r >> 2) + 4 * hf + (r & 3)]);
+    }
+  }
+
+  // ---- transpose through LDS (per wavefront: 32 rows x 64 channels fp32 at a time) and store
+  unsigned char* my = lds + w * (32 * EPI_STRIDE);
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    __syncthreads();
+#pragma unroll
+    for (int c2t = 0; c2t < 2; ++c2t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const v16f& a = acc[2 * hh + c2t];
+        *(float4*)(my + l32 * EPI_STRIDE + (32 * c2t + 8 * g + 4 * hf) * 4) =
+            make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+      }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 4 + (lane >> 4), c4 = lane & 15;
+      const int grow = i * BQ + 32 * w + r;
+      const float4 val = *(const float4*)(my + r * EPI_STRIDE + c4 * 16);
+      if (grow < A.N) {
+        const size_t o = ((size_t)bh * A.N + grow) * D + 64 * hh + 4 * c4;
+        if (A.out_f32) {
+          *(float4*)((float*)A.out + o) = val;
+        } else {
+          *(uint2*)((bf16_t*)A.out + o) = make_uint2(pack_bf16x2(val.x, val.y), pack_bf16x2(val.z, val.w));
+        }
+      }
+    }
+  }
+}
+
+void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
+                       const uint8_t* v8, const float* dq, const float* dk, const float* dv,
+                       const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
+                       void* out, bool out_f32, float* lse, hipStream_t stream) {
+  SparseArgs a;
+  a.q = (const bf16_t*)q;
+  a.crit = crit;
+  a.k8 = k8;
+  a.v8 = v8;
+  a.dq = dq;
+  a.dk = dk;
+  a.dv = dv;
+  a.HZ = HZ;
+  a.bias = has_linear ? proj_b : nullptr;
+  a.out = out;
+  a.lse = lse;
+  a.N = p.N;
+  a.Tq = p.Tq;
+  a.Tk = p.Tk;
+  a.n_c = n_c;
+  a.total = p.BH * p.Tq;
+  a.per_xcd = (a.total + 7) / 8;
+  a.phi = phi_kind;
+  a.has_lin = has_linear ? 1 : 0;
+  a.out_f32 = out_f32 ? 1 : 0;
+  const unsigned grid = (unsigned)(8 * a.per_xcd);
+  if (p.block_q == 128) {
+    const size_t ldsb = 2 * STAGE_BYTES > 4 * 32 * EPI_STRIDE ? 2 * STAGE_BYTES : 4 * 32 * EPI_STRIDE;
+    sparse_fwd_kernel<4><<<grid, 256, ldsb, stream>>>(a);
+  } else {
+    sparse_fwd_kernel<2><<<grid, 128, 2 * STAGE_BYTES, stream>>>(a);
+  }
+}
+
+}  // namespace sla

@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, on seeded synthetic inputs.  Sizes here finish in seconds on the CPU side and
+still span several tiles plus ragged tails; the full-size sampled checks are in
+test_gpu_fullsize.py."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import formats
+from oracle import sla_oracle as so
+from paper_2512_16093_amd import binding as sla
+from paper_2512_16093_amd import synth
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+RAGGED = [
+    # (H, grid, block_q, rc, rm): N = 1000 (15 full key blocks + 40), 2080+..., etc.
+    (2, (5, 10, 20), 64, 0.2, 0.4),
+    (2, (5, 10, 20), 128, 0.25, 0.5),
+    (1, (3, 27, 27), 128, 0.1, 0.2),      # N = 2187 = 17*128 + 11 = 34*64 + 11
+    (1, (1, 9, 9), 128, 0.5, 0.5),        # N = 81: one ragged query block, two key blocks
+    (1, (1, 5, 5), 64, 1.0, 0.0),         # N = 25: a single short block
+]
+
+
+def _cfg(H, grid, bq, rc, rm, proj=True, cid=100):
+    return synth.custom_config(1, H, grid, block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=proj, cfg_id=cid)
+
+
+def test_fp8_encoding_matches_software_e4m3():
+    rng = np.random.default_rng(0)
+    pos = formats.e4m3_decode(np.arange(0, 0x7F, dtype=np.uint8))
+    mids = (pos[:-1] + pos[1:]) / 2
+    x = np.concatenate([pos, -pos, mids, -mids, np.nextafter(mids.astype(np.float32), 1e9),
+                        np.nextafter(mids.astype(np.float32), -1e9), rng.uniform(-448, 448, 50000),
+                        np.exp2(rng.uniform(-14, 9, 50000)), [448.0, 449.0, 463.9, 464.0, 480.0, 1e6, -1e6, 1e30]]
+                       ).astype(np.float32)
+    got = sla.sla_debug_e4m3_encode(torch.from_numpy(x).cuda()).cpu().numpy()
+    want = formats.e4m3_encode(x.astype(np.float64))
+    # +0 and -0 are distinct codes of the same value: compare decoded values, then codes off zero
+    nz = x != 0
+    assert np.array_equal(got[nz], want[nz])
+    assert np.array_equal(formats.e4m3_decode(got), formats.e4m3_decode(want))
+
+
+@pytest.mark.parametrize("case", [None] + RAGGED[:3])
+def test_quantised_operands_match_oracle(case):
+    cfg = synth.CONFIGS[0] if case is None else _cfg(*case)
+    q, k, v = synth.make_qkv(cfg)
+    kc, ks, km, vc, vs = (t.cpu().numpy() for t in sla.sla_debug_quantize_kv(*pu.to_dev(k, v)))
+    for h in range(cfg.H):
+        K, V = synth.as_f64(k[0, h]), synth.as_f64(v[0, h])
+        K8, dk, mu = so.quantize_k(K, 64)
+        V8, dv = so.quantize_v(V)
+        assert np.abs(km[0, h] - mu).max() < 2e-6
+        assert np.allclose(ks[0, h], dk, rtol=1e-5)
+        assert np.allclose(vs[0, h], dv, rtol=1e-6)
+        # codes are decided in fp32 on the GPU and fp64 here: equal except at rounding ties
+        dkc = kc[0, h].astype(np.float64) - K8
+        assert np.abs(dkc).max() <= 1 and (dkc != 0).mean() < 1e-3
+        Vg = formats.e4m3_decode(vc[0, h])
+        differs = Vg != V8
+        assert differs.mean() < 1e-3
+        assert (np.abs(Vg - V8)[differs] <= 2.0 ** -3 * np.abs(V8)[differs] + 2.0 ** -9).all()
+
+
+@pytest.mark.parametrize("case", [None] + RAGGED)
+def test_block_classification_matches_oracle(case):
+    cfg = synth.CONFIGS[0] if case is None else _cfg(*case)
+    q, k, v = synth.make_qkv(cfg)
+    mask, crit, marg, scores = sla.sla_classify_blocks(*pu.to_dev(q, k), cfg.block_q, cfg.block_k,
+                                                       cfg.topk_ratio, cfg.marginal_ratio)
+    Tq, Tk, n_c, n_m = so.block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+    assert mask.shape == (1, cfg.H, Tq, Tk) and crit.shape[-1] == n_c and marg.shape[-1] == n_m
+    mask, crit, marg, scores = (t.cpu().numpy() for t in (mask, crit, marg, scores))
+    for h in range(cfg.H):
+        s64 = so.pooled_scores(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), cfg.block_q, cfg.block_k)
+        assert np.abs(scores[0, h] - s64).max() < 2e-5
+        pu.check_mask(mask[0, h], s64, n_c, n_m, "head %d" % h)
+        for i in range(Tq):
+            assert np.array_equal(crit[0, h, i], np.flatnonzero(mask[0, h, i] == 1))
+            assert np.array_equal(marg[0, h, i], np.flatnonzero(mask[0, h, i] == 0))
+
+
+@pytest.mark.parametrize("case", [None] + RAGGED)
+def test_sparse_branch_matches_oracle(case):
+    cfg = synth.CONFIGS[0] if case is None else _cfg(*case)
+    q, k, v = synth.make_qkv(cfg)
+    Tq, Tk, n_c, n_m = so.block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+    masks = np.stack([so.classify(so.pooled_scores(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), cfg.block_q, 64),
+                                  n_c, n_m) for h in range(cfg.H)])[None]
+    crit = pu.lists_from_mask(masks)
+    out, lse = sla.sla_sparse_attn_fwd(*pu.to_dev(q, k, v, crit), cfg.block_q, cfg.block_k)
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for h in range(cfg.H):
+        ref, ref_lse = so.sparse_branch_quant(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
+                                              masks[0, h], cfg.block_q, 64, return_lse=True)
+        pu.check_output(out[0, h], ref, "sparse head %d" % h, max_abs=1e-2)
+        assert np.abs(lse[0, h] - ref_lse).max() < 2e-3
+
+
+@pytest.mark.parametrize("case", [None] + RAGGED[:4])
+@pytest.mark.parametrize("phi", ["softmax", "elu1", "relu"])
+def test_linear_branch_matches_oracle(case, phi):
+    cfg = synth.CONFIGS[0] if case is None else _cfg(*case)
+    if phi != "softmax" and case is not None and case is not RAGGED[0]:
+        pytest.skip("alternative feature maps are checked on two shapes")
+    q, k, v = synth.make_qkv(cfg)
+    W = synth.make_proj(cfg)
+    bias = (torch.arange(cfg.d, dtype=torch.float32) / 64 - 1).to(torch.bfloat16)
+    Tq, Tk, n_c, n_m = so.block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+    masks = np.stack([so.classify(so.pooled_scores(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), cfg.block_q, 64),
+                                  n_c, n_m) for h in range(cfg.H)])[None]
+    kind = {"softmax": sla.PHI_SOFTMAX, "elu1": sla.PHI_ELU1, "relu": sla.PHI_RELU}[phi]
+    dq, dk, dv, dm, dW, db = pu.to_dev(q, k, v, torch.from_numpy(masks), W, bias)
+    out = sla.sla_linear_attn_fwd(dq, dk, dv, dm, cfg.block_q, cfg.block_k, proj_w=dW, proj_b=db,
+                                  phi_kind=kind).cpu().numpy()
+    for h in range(cfg.H):
+        ol = so.linear_branch(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]), masks[0, h],
+                              cfg.block_q, 64, phi)
+        ref = ol @ synth.as_f64(W).T + synth.as_f64(bias)[None, :]
+        pu.check_output(out[0, h], ref, "linear %s head %d" % (phi, h), max_abs=6e-3, min_cos=0.9999)
+    # identity projection, no bias
+    out = sla.sla_linear_attn_fwd(dq, dk, dv, dm, cfg.block_q, cfg.block_k, phi_kind=kind).cpu().numpy()
+    ol = so.linear_branch(synth.as_f64(q[0, 0]), synth.as_f64(k[0, 0]), synth.as_f64(v[0, 0]), masks[0, 0],
+                          cfg.block_q, 64, phi)
+    pu.check_output(out[0, 0], ol, "linear identity", max_abs=6e-3, min_cos=0.9999)
+
+
+@pytest.mark.parametrize("case", [None] + RAGGED)
+@pytest.mark.parametrize("seed", [0, 1])
+def test_full_forward_matches_oracle(case, seed):
+    cfg = synth.CONFIGS[0] if case is None else _cfg(*case)
+    if seed and case is not None:
+        pytest.skip("extra seed only on the named tiny config")
+    q, k, v = synth.make_qkv(cfg, seed=seed)
+    W = synth.make_proj(cfg, seed=seed)
+    out = sla.sla_attention_fwd(*pu.to_dev(q, k, v), cfg.block_q, cfg.block_k, cfg.topk_ratio,
+                                cfg.marginal_ratio, proj_w=W.cuda()).float().cpu().numpy()
+    mask = sla.sla_classify_blocks(*pu.to_dev(q, k), cfg.block_q, cfg.block_k, cfg.topk_ratio,
+                                   cfg.marginal_ratio)[0].cpu().numpy()
+    Tq, Tk, n_c, n_m = so.block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+    for h in range(cfg.H):
+        r = pu.oracle_head(cfg, q, k, v, 0, h, W)
+        nbad, _, _ = pu.check_mask(mask[0, h], r["scores"], n_c, n_m, "head %d" % h)
+        if nbad:   # a tie went the other way: compare against the oracle run on the GPU's mask
+            r = pu.oracle_head(cfg, q, k, v, 0, h, W, mask=mask[0, h])
+        pu.check_output(out[0, h], r["out"], "full head %d" % h)
+
+
+def test_full_forward_bias_batch_and_no_marginal():
+    # B = 2, bias, and a second call with no marginal blocks (no linear term, bias dropped)
+    cfg = synth.custom_config(2, 2, (2, 16, 16), block_q=128, topk_ratio=0.25, marginal_ratio=0.25, cfg_id=101)
+    q, k, v = synth.make_qkv(cfg)
+    W = synth.make_proj(cfg)
+    bias = (torch.linspace(-0.5, 0.5, cfg.d)).to(torch.bfloat16)
+    out = sla.sla_attention_fwd(*pu.to_dev(q, k, v), 128, 64, 0.25, 0.25, proj_w=W.cuda(),
+                                proj_b=bias.cuda()).float().cpu().numpy()
+    for b in range(2):
+        for h in range(2):
+            r = pu.oracle_head(cfg, q, k, v, b, h, W, bias)
+            pu.check_output(out[b, h], r["out"], "b%d h%d" % (b, h))
+    out0 = sla.sla_attention_fwd(*pu.to_dev(q, k, v), 128, 64, 0.25, 0.0, proj_w=W.cuda(),
+                                 proj_b=bias.cuda()).float().cpu().numpy()
+    cfg0 = synth.custom_config(2, 2, (2, 16, 16), block_q=128, topk_ratio=0.25, marginal_ratio=0.0, cfg_id=101)
+    r = pu.oracle_head(cfg0, q, k, v, 1, 1, W, bias)
+    assert r["o_linear"] is None
+    pu.check_output(out0[1, 1], r["out"], "no marginal")
+
+
+def test_all_critical_small_is_close_to_dense_attention():
+    # the isolated dense quantised path (every block critical) at a size the CPU does in full
+    cfg = synth.custom_config(1, 2, (4, 16, 32), block_q=128, topk_ratio=1.0, marginal_ratio=0.0,
+                              use_proj=False, cfg_id=2)
+    q, k, v = synth.make_qkv(cfg)
+    out = sla.sla_attention_fwd(*pu.to_dev(q, k, v), 128, 64, 1.0, 0.0).float().cpu().numpy()
+    for h in range(2):
+        Q, K, V = (synth.as_f64(t[0, h]) for t in (q, k, v))
+        ref = pu.oracle_head(cfg, q, k, v, 0, h)["out"]
+        pu.check_output(out[0, h], ref, "dense-quant head %d" % h)
+        S = Q @ K.T / math.sqrt(cfg.d)
+        P = np.exp(S - S.max(1, keepdims=True))
+        dense = (P / P.sum(1, keepdims=True)) @ V
+        assert pu.cosine(out[0, h], dense) > 0.999
+
+
+def test_deterministic_and_inputs_untouched():
+    cfg = synth.CONFIGS[0]
+    q, k, v = pu.to_dev(*synth.make_qkv(cfg))
+    W = synth.make_proj(cfg).cuda()
+    q0, k0, v0 = q.clone(), k.clone(), v.clone()
+    ws = sla.alloc_workspace(1, cfg.H, cfg.N, cfg.d, 64, 64, 0.2, 0.4)
+    a = sla.sla_attention_fwd(q, k, v, 64, 64, 0.2, 0.4, proj_w=W, workspace=ws).clone()
+    ws.fill_(0xFF)       # workspace contents before a call are undefined: poison them
+    b = sla.sla_attention_fwd(q, k, v, 64, 64, 0.2, 0.4, proj_w=W, workspace=ws)
+    assert torch.equal(a, b)
+    assert torch.equal(q, q0) and torch.equal(k, k0) and torch.equal(v, v0)

@@ -1,0 +1,133 @@
+"""Host-side checks of the C-ABI library (no GPU needed): it loads, exports every
+symbol include/sla.h declares, its host-only functions agree with the oracle's
+block bookkeeping, and every argument error is reported before any launch.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import sla_oracle as so
+from paper_2512_16093_amd import binding as sla
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)      # non-NULL, never dereferenced: validation fails first
+WS = ctypes.c_void_p(0x10000)       # 256-byte aligned fake workspace
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sla.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sla_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sla.lib()
+    names = _declared()
+    assert set(names) == set(sla.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+    assert sla.sla_version() >= 100
+
+
+def test_status_strings():
+    seen = set()
+    for st in range(0, -8, -1):
+        s = sla.sla_status_string(st)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8 and sla.sla_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("N,bq,bk,rc,rm", [
+    (1024, 64, 64, 0.2, 0.4), (32760, 128, 64, 0.1, 0.2), (75600, 128, 64, 0.1, 0.2),
+    (32760, 128, 64, 1.0, 0.0), (100, 64, 64, 0.5, 0.5), (65, 128, 64, 0.1, 0.9),
+    (75600, 128, 64, 0.15, 0.85), (4096, 64, 64, 0.3, 0.3), (1, 64, 64, 0.1, 0.0)])
+def test_block_counts_match_oracle(N, bq, bk, rc, rm):
+    assert sla.sla_block_counts(N, bq, bk, rc, rm) == so.block_counts(N, bq, bk, rc, rm)
+
+
+def test_block_count_errors():
+    L = sla.lib()
+    f = L.sla_block_counts
+    assert f(0, 64, 64, 0.1, 0.2, None, None, None, None) == sla.ERR_SHAPE
+    assert f(64 * 8193, 64, 64, 0.1, 0.2, None, None, None, None) == sla.ERR_SHAPE
+    assert f(1024, 32, 64, 0.1, 0.2, None, None, None, None) == sla.ERR_BLOCK
+    assert f(1024, 64, 128, 0.1, 0.2, None, None, None, None) == sla.ERR_BLOCK
+    for rc, rm in ((0.0, 0.1), (-0.1, 0.1), (1.1, 0.0), (0.5, -0.1), (0.5, 1.5), (0.7, 0.4), (float("nan"), 0.1)):
+        assert f(1024, 64, 64, rc, rm, None, None, None, None) == sla.ERR_RATIO
+    assert f(1024, 64, 64, 0.1, 0.2, None, None, None, None) == sla.SLA_OK
+
+
+def test_workspace_bytes():
+    w0 = sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4)
+    assert w0 > 0 and w0 % 256 == 0
+    # grows with the problem; at the headline shape it holds the 8-bit K/V copies and the
+    # summaries, a few GB, far below the 288 GB of the device
+    w4 = sla.sla_workspace_bytes(1, 40, 75600, 128, 128, 64, 0.1, 0.2)
+    assert 2 * 40 * 75600 * 128 < w4 < 8e9
+    assert sla.sla_workspace_bytes(1, 4, 1024, 128, 64, 64, 0.2, 0.4) > w0
+    # the stage entry points accept the smallest workspace of a shape
+    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 1e-6, 0.0) <= w0
+    for bad in ((0, 2, 1024, 128, 64, 64, 0.2, 0.4), (1, 2, 1024, 64, 64, 64, 0.2, 0.4),
+                (1, 2, 1024, 128, 96, 64, 0.2, 0.4), (1, 2, 1024, 128, 64, 64, 0.0, 0.4)):
+        assert sla.sla_workspace_bytes(*bad) == 0
+    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_NONE) == 0
+
+
+def _fwd(q=FAKE, k=FAKE, v=FAKE, out=FAKE, B=1, H=2, N=1024, d=128, bq=64, bk=64, rc=0.2, rm=0.4,
+         phi=0, quant=2, ws=WS, wsb=1 << 40):
+    return sla.lib().sla_attention_fwd(q, k, v, out, B, H, N, d, bq, bk, rc, rm, None, None, phi, quant,
+                                       ws, wsb, None)
+
+
+def test_attention_fwd_argument_errors_are_found_before_any_launch():
+    assert _fwd(q=None) == sla.ERR_NULL and _fwd(out=None) == sla.ERR_NULL
+    assert _fwd(B=0) == sla.ERR_SHAPE and _fwd(d=64) == sla.ERR_SHAPE and _fwd(N=-5) == sla.ERR_SHAPE
+    assert _fwd(H=70000) == sla.ERR_SHAPE
+    assert _fwd(bq=32) == sla.ERR_BLOCK and _fwd(bk=32) == sla.ERR_BLOCK
+    assert _fwd(rc=0.0) == sla.ERR_RATIO and _fwd(rc=0.8, rm=0.4) == sla.ERR_RATIO
+    assert _fwd(phi=7) == sla.ERR_UNSUPPORTED and _fwd(quant=0) == sla.ERR_UNSUPPORTED
+    assert _fwd(quant=1) == sla.ERR_UNSUPPORTED
+    assert _fwd(ws=None) == sla.ERR_WORKSPACE
+    assert _fwd(ws=ctypes.c_void_p(0x10010)) == sla.ERR_WORKSPACE          # misaligned
+    need = sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4)
+    assert _fwd(wsb=need - 1) == sla.ERR_WORKSPACE
+
+
+def test_stage_entry_points_argument_errors():
+    L = sla.lib()
+    big = 1 << 40
+    assert L.sla_classify_blocks(FAKE, FAKE, 1, 2, 1024, 128, 64, 64, 0.2, 0.4, None, None, None, None,
+                                 WS, big, None) == sla.ERR_NULL
+    assert L.sla_classify_blocks(FAKE, FAKE, 1, 2, 1024, 128, 64, 64, 1.2, 0.4, FAKE, None, None, None,
+                                 WS, big, None) == sla.ERR_RATIO
+    assert L.sla_classify_blocks(FAKE, FAKE, 1, 2, 1024, 128, 64, 64, 0.2, 0.4, FAKE, None, None, None,
+                                 WS, 16, None) == sla.ERR_WORKSPACE
+    assert L.sla_sparse_attn_fwd(FAKE, FAKE, FAKE, None, 3, FAKE, None, 1, 2, 1024, 128, 64, 64, 2,
+                                 WS, big, None) == sla.ERR_NULL
+    assert L.sla_sparse_attn_fwd(FAKE, FAKE, FAKE, FAKE, 0, FAKE, None, 1, 2, 1024, 128, 64, 64, 2,
+                                 WS, big, None) == sla.ERR_SHAPE
+    assert L.sla_sparse_attn_fwd(FAKE, FAKE, FAKE, FAKE, 17, FAKE, None, 1, 2, 1024, 128, 64, 64, 2,
+                                 WS, big, None) == sla.ERR_SHAPE
+    assert L.sla_sparse_attn_fwd(FAKE, FAKE, FAKE, FAKE, 3, FAKE, None, 1, 2, 1024, 128, 64, 64, 0,
+                                 WS, big, None) == sla.ERR_UNSUPPORTED
+    assert L.sla_linear_attn_fwd(FAKE, FAKE, FAKE, None, None, None, 0, FAKE, 1, 2, 1024, 128, 64, 64,
+                                 WS, big, None) == sla.ERR_NULL
+    assert L.sla_linear_attn_fwd(FAKE, FAKE, FAKE, FAKE, None, None, 5, FAKE, 1, 2, 1024, 128, 64, 64,
+                                 WS, big, None) == sla.ERR_UNSUPPORTED
+    assert L.sla_linear_attn_fwd(FAKE, FAKE, FAKE, FAKE, None, None, 0, FAKE, 1, 2, 1024, 128, 64, 64,
+                                 None, big, None) == sla.ERR_WORKSPACE
+    assert L.sla_debug_e4m3_encode(None, FAKE, 4, None) == sla.ERR_NULL
+    assert L.sla_debug_quantize_kv(None, FAKE, 1, 2, 1024, 128, 64, None, None, None, None, None,
+                                   WS, big, None) == sla.ERR_NULL
+
+
+def test_binding_rejects_wrong_tensors():
+    import torch
+    x = torch.zeros((1, 2, 64, 128), dtype=torch.bfloat16)      # CPU tensor
+    with pytest.raises(ValueError):
+        sla.sla_attention_fwd(x, x, x, 64, 64, 0.2, 0.4)
+    with pytest.raises(sla.SLAError):
+        sla.sla_block_counts(0, 64, 64, 0.1, 0.2)
