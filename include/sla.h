@@ -134,6 +134,24 @@ int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_
                         int B, int H, int N, int d, int block_q, int block_k,
                         void* workspace, size_t workspace_bytes, sla_stream_t stream);
 
+/* Optional per-stage timing of sla_attention_fwd (for benchmarks; off by default).
+ * The stages are: 0 pooling + statistics, 1 scores + block selection, 2 K/V
+ * quantisation + linear summaries, 3 marginal-summary accumulation, 4 the fused
+ * sparse attention kernel.
+ *   sla_profile_enable(n): creates the HIP events (host objects, no device memory)
+ *     for timing up to n calls; n <= 0 disables timing and destroys them.  While
+ *     enabled, each sla_attention_fwd call records SLA_N_STAGES + 1 events on its
+ *     stream (no synchronisation) until n calls have been recorded.
+ *   sla_profile_reset(): forget the recorded calls (the next call is record 0).
+ *   sla_profile_read(stage_ms, max_calls, n_calls): HOST pointers; waits for the
+ *     recorded calls to finish and writes stage_ms[call][SLA_N_STAGES] in
+ *     milliseconds and the number of calls read.
+ * Not thread-safe: enable / reset / read must not overlap calls of sla_attention_fwd. */
+#define SLA_N_STAGES 5
+int sla_profile_enable(int max_calls);
+int sla_profile_reset(void);
+int sla_profile_read(float* stage_ms, int max_calls, int* n_calls);
+
 /* Format check: converts n fp32 values (device) to FP8 E4M3 codes (device) with
  * the same instruction sequence the kernels use for P and V (round to nearest
  * even, saturating at +-448).  For tests of the number format only. */

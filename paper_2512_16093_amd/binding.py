@@ -24,7 +24,10 @@ ERR_NULL, ERR_SHAPE, ERR_BLOCK, ERR_RATIO, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_H
 
 EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
            "sla_attention_fwd", "sla_classify_blocks", "sla_sparse_attn_fwd",
-           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv")
+           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv",
+           "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
+N_STAGES = 5
+STAGE_NAMES = ("pool_stats", "scores_select", "prep_kv", "lin_accumulate", "sparse_fwd")
 
 _lib = None
 
@@ -66,6 +69,12 @@ def lib():
         L.sla_debug_e4m3_encode.argtypes = [c_vp, c_vp, c_sz, c_vp]
         L.sla_debug_quantize_kv.restype = c_int
         L.sla_debug_quantize_kv.argtypes = [c_vp, c_vp] + [c_int] * 5 + [c_vp] * 5 + [c_vp, c_sz, c_vp]
+        L.sla_profile_enable.restype = c_int
+        L.sla_profile_enable.argtypes = [c_int]
+        L.sla_profile_reset.restype = c_int
+        L.sla_profile_reset.argtypes = []
+        L.sla_profile_read.restype = c_int
+        L.sla_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), c_int, ip]
         _lib = L
     return _lib
 
@@ -209,3 +218,19 @@ def sla_debug_quantize_kv(k, v, block_k=64, workspace=None):
                                      _ptr(vc), _ptr(vs), _ptr(workspace), workspace.numel(), _stream())
     _check(st, "sla_debug_quantize_kv")
     return kc, ks, km, vc, vs
+
+
+def sla_profile_enable(max_calls):
+    _check(lib().sla_profile_enable(max_calls), "sla_profile_enable")
+
+
+def sla_profile_reset():
+    _check(lib().sla_profile_reset(), "sla_profile_reset")
+
+
+def sla_profile_read(max_calls):
+    """Per-call stage times in ms: list of N_STAGES-long lists (waits for the calls to finish)."""
+    buf = (ctypes.c_float * (max_calls * N_STAGES))()
+    n = ctypes.c_int(0)
+    _check(lib().sla_profile_read(buf, max_calls, ctypes.byref(n)), "sla_profile_read")
+    return [[buf[r * N_STAGES + s] for s in range(N_STAGES)] for r in range(n.value)]

@@ -51,6 +51,17 @@ int check_ws(const void* ws, size_t bytes, size_t need) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? SLA_OK : SLA_ERR_HIP; }
 
+// Optional stage timing of sla_attention_fwd: SLA_N_STAGES + 1 events per recorded call,
+// created by sla_profile_enable and recorded on the call's stream between the stages.
+struct Profiler {
+  hipEvent_t* ev = nullptr;
+  int capacity = 0, used = 0;
+} g_prof;
+
+inline void mark(hipStream_t s, int rec, int idx) {
+  if (rec >= 0) (void)hipEventRecord(g_prof.ev[rec * (SLA_N_STAGES + 1) + idx], s);
+}
+
 template <class T>
 T* at(void* ws, size_t off) { return (T*)((unsigned char*)ws + off); }
 
@@ -112,21 +123,63 @@ int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, in
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   const bool lin = p.n_m > 0;
+  const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
 
+  mark(s, rec, 0);
   run_stats(q, k, v, p, ws, W, s);
+  mark(s, rec, 1);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
   launch_select(p, at<float>(ws, W.scores), at<int8_t>(ws, W.mask), at<int32_t>(ws, W.crit), nullptr, s);
+  mark(s, rec, 2);
   const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
   launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, true, lin,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+  mark(s, rec, 3);
   if (lin) {
     launch_marginal_rows(p, at<int8_t>(ws, W.mask), at<uint8_t>(ws, W.m0), s);
     launch_lin_accumulate(p, at<uint8_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   }
+  mark(s, rec, 4);
   launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
                     at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
                     (const bf16_t*)proj_b, phi_kind, lin, out, false, nullptr, s);
+  mark(s, rec, 5);
   return launch_status();
+}
+
+int sla_profile_enable(int max_calls) {
+  if (g_prof.ev) {
+    for (int i = 0; i < g_prof.capacity * (SLA_N_STAGES + 1); ++i) (void)hipEventDestroy(g_prof.ev[i]);
+    delete[] g_prof.ev;
+    g_prof = Profiler();
+  }
+  if (max_calls <= 0) return SLA_OK;
+  const int n = max_calls * (SLA_N_STAGES + 1);
+  g_prof.ev = new hipEvent_t[n];
+  for (int i = 0; i < n; ++i) {
+    if (hipEventCreate(&g_prof.ev[i]) != hipSuccess) return SLA_ERR_HIP;
+  }
+  g_prof.capacity = max_calls;
+  return SLA_OK;
+}
+
+int sla_profile_reset(void) {
+  g_prof.used = 0;
+  return SLA_OK;
+}
+
+int sla_profile_read(float* stage_ms, int max_calls, int* n_calls) {
+  if (!stage_ms || !n_calls) return SLA_ERR_NULL;
+  const int n = g_prof.used < max_calls ? g_prof.used : max_calls;
+  for (int r = 0; r < n; ++r) {
+    hipEvent_t* e = g_prof.ev + r * (SLA_N_STAGES + 1);
+    if (hipEventSynchronize(e[SLA_N_STAGES]) != hipSuccess) return SLA_ERR_HIP;
+    for (int st = 0; st < SLA_N_STAGES; ++st) {
+      if (hipEventElapsedTime(&stage_ms[r * SLA_N_STAGES + st], e[st], e[st + 1]) != hipSuccess) return SLA_ERR_HIP;
+    }
+  }
+  *n_calls = n;
+  return SLA_OK;
 }
 
 int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d, int block_q, int block_k,

@@ -72,3 +72,18 @@ def lists_from_mask(mask_np):
         for h in range(H):
             crit[b, h] = so.mask_lists(mask_np[b, h])[0]
     return torch.from_numpy(crit)
+
+
+def make_qkv_threaded(cfg, seed=0, workers=8):
+    """All heads of a config, generated with a thread pool (numpy releases the GIL in its kernels)."""
+    from concurrent.futures import ThreadPoolExecutor
+    shape = (cfg.B, cfg.H, cfg.N, cfg.d)
+    q, k, v = (torch.empty(shape, dtype=torch.bfloat16) for _ in range(3))
+
+    def one(bh):
+        b, h = divmod(bh, cfg.H)
+        q[b, h], k[b, h], v[b, h] = synth.make_head(cfg, b, h, seed)
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        list(ex.map(one, range(cfg.B * cfg.H)))
+    return q, k, v
