@@ -10,8 +10,9 @@
 //   O^T[ch][query] += V8^T . P8^T     v_mfma_f32_32x32x64_f8f6f4, A = V fragment (LDS), B = P8 as it
 //                                     sits in the accumulators' order (V was stored in that key order)
 // so the rescale factor, the row sum and the final normalisation are per-lane scalars and P
-// never touches LDS.  K/V fragments of the next critical block are fetched into registers while
-// the current one is consumed, then written to the other LDS buffer (one barrier per block).
+// never touches LDS.  K/V fragments of the next critical block are copied global -> LDS
+// asynchronously (no registers) into the other staging buffer while the current one is
+// consumed (one barrier per block).
 //
 // Epilogue: O_s = acc * delta_V / l;  optional linear term phi(Q) H_i / (phi(Q).Z_i) as bf16 MFMA
 // (H_i already contains the output projection), bias, then a transposing pass through LDS so
@@ -20,18 +21,24 @@
 
 namespace sla {
 
+struct SparseDims {
+  int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32;
+};
+// The pointers are separate __restrict__ kernel parameters (not struct members) so the
+// compiler knows the index list and the scales are never written by this kernel and can
+// fetch them through the scalar unit.
 struct SparseArgs {
-  const bf16_t* q;
-  const int32_t* crit;
-  const int8_t* k8;
-  const uint8_t* v8;
-  const float* dq;
-  const float* dk;
-  const float* dv;
-  const bf16_t* HZ;
-  const bf16_t* bias;
-  void* out;
-  float* lse;
+  const bf16_t* __restrict__ q;
+  const int32_t* __restrict__ crit;
+  const int8_t* __restrict__ k8;
+  const uint8_t* __restrict__ v8;
+  const float* __restrict__ dq;
+  const float* __restrict__ dk;
+  const float* __restrict__ dv;
+  const bf16_t* __restrict__ HZ;
+  const bf16_t* __restrict__ bias;
+  void* __restrict__ out;
+  float* __restrict__ lse;
   int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32;
 };
 
@@ -52,12 +59,94 @@ __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
   }
 }
 
+// One critical block: consume the K/V fragments in LDS buffer `kv`, update the running
+// max M, the row-sum partial lsum and the output accumulators.
+__device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int lane, int hf, const v4i (&q8)[4],
+                                             float c2, bool tail, int kvalid, float& M, float& lsum,
+                                             v16f (&acc)[4]) {
+  const uint4* kl = kv;
+  const uint4* vl = kv + KV_FRAG_BYTES / 16;
+  uint4 kf[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) kf[u] = kl[u * 64 + lane];
+  v16i s0 = v16i{}, s1 = v16i{};
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    s0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[s].x, (int)kf[s].y, (int)kf[s].z, (int)kf[s].w}, q8[s], s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[4 + s].x, (int)kf[4 + s].y, (int)kf[4 + s].z, (int)kf[4 + s].w}, q8[s], s1, 0, 0, 0);
+  }
+  // V fragments: issued now so that their LDS latency hides behind the softmax arithmetic
+  uint4 vf[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) vf[u] = vl[u * 64 + lane];
+  if (tail) {  // keys past the end of the sequence (last key block only)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
+      if (key >= kvalid) s0[r] = -(1 << 30);
+      if (32 + key >= kvalid) s1[r] = -(1 << 30);
+    }
+  }
+  int imax = s0[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) imax = max(imax, s0[r]);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) imax = max(imax, s1[r]);
+  imax = max(imax, partner_i32(imax));
+  const float Mn = fmaxf(M, (float)imax * c2);
+  if (__any(Mn > M)) {
+    const float alpha = __builtin_amdgcn_exp2f(M - Mn);
+    lsum *= alpha;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ct][r] *= alpha;
+  }
+  M = Mn;
+  const float offs = LOG2_448 - M;
+  v8i pb;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    float p[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s0[4 * g + e], c2, offs));
+      lsum += p[e];
+    }
+    pb[g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s1[4 * g + e], c2, offs));
+      lsum += p[e];
+    }
+    pb[4 + g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
+  }
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) {
+    const uint4 a0 = vf[2 * ct], a1 = vf[2 * ct + 1];
+    const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 0, 0, 0);
+  }
+}
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
 template <int NW>
-__global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(const SparseArgs A) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+__global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
+    const bf16_t* __restrict__ q_, const int32_t* __restrict__ crit_, const int8_t* __restrict__ k8_,
+    const uint8_t* __restrict__ v8_, const float* __restrict__ dq_, const float* __restrict__ dk_,
+    const float* __restrict__ dv_, const bf16_t* __restrict__ HZ_, const bf16_t* __restrict__ bias_,
+    void* __restrict__ out_, float* __restrict__ lse_, const SparseDims dims) {
+  const SparseArgs A = {q_, crit_, k8_, v8_, dq_, dk_, dv_, HZ_, bias_, out_, lse_, dims.N, dims.Tq, dims.Tk,
+                        dims.n_c, dims.total, dims.per_xcd, dims.phi, dims.has_lin, dims.out_f32};
   constexpr int NT = NW * 64;
   constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
   constexpr int BQ = NW * 32;
+  // two K/V staging buffers as separate objects (so the compiler can tell the asynchronous
+  // fill of one from the reads of the other) and the epilogue's transposition area
+  __shared__ uint4 stage0[STAGE_BYTES / 16];
+  __shared__ uint4 stage1[STAGE_BYTES / 16];
+  __shared__ __attribute__((aligned(16))) unsigned char lds[NW * 32 * EPI_STRIDE];
 
   // Consecutive query blocks of a head run on the same XCD (workgroup ids are dealt
   // round-robin over the 8 XCDs), so neighbours share K/V fragments in that XCD's L2.
@@ -97,103 +186,69 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(const SparseArgs
   for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
   float M = -INFINITY, lsum = 0.f;
 
-  const int32_t* crow = A.crit + (size_t)rowid * A.n_c;
+  const int n_c = A.n_c;
+  const int32_t* crow = A.crit + (size_t)rowid * n_c;
+  const float* dkrow = A.dk + (size_t)bh * A.Tk;
   const size_t rec0 = (size_t)bh * A.Tk * KV_FRAG_BYTES;
-  uint4 pre[CH];
-  auto gload = [&](int j) {
+  // Asynchronous global -> LDS copy of one block's K and V records (no registers in between):
+  // each wavefront fills 1 KiB pieces, lane l supplying bytes [16 l, 16 l + 16) of a piece.
+  auto fetch = [&](int j, uint4* dst) {
     const uint4* ks = (const uint4*)(A.k8 + rec0 + (size_t)j * KV_FRAG_BYTES);
     const uint4* vs = (const uint4*)(A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES);
 #pragma unroll
     for (int u = 0; u < CH / 2; ++u) {
-      pre[u] = ks[u * NT + t];
-      pre[CH / 2 + u] = vs[u * NT + t];
+      __builtin_amdgcn_global_load_lds((const void*)(ks + u * NT + t), (lds_ptr_t)(dst + u * NT + w * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void*)(vs + u * NT + t),
+                                       (lds_ptr_t)(dst + KV_FRAG_BYTES / 16 + u * NT + w * 64), 16, 0, 0);
     }
   };
-  auto lstore = [&](int buf) {
-    uint4* kd = (uint4*)(lds + buf * STAGE_BYTES);
-    uint4* vd = kd + KV_FRAG_BYTES / 16;
-#pragma unroll
-    for (int u = 0; u < CH / 2; ++u) {
-      kd[u * NT + t] = pre[u];
-      vd[u * NT + t] = pre[CH / 2 + u];
-    }
-  };
-
-  const int n_c = A.n_c;
-  int j_cur = n_c > 0 ? crow[0] : 0;
-  if (n_c > 0) {
-    gload(j_cur);
-    lstore(0);
-  }
-  __syncthreads();
   const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
+  const bool ragged = kvalid_last < BK;
 
-  for (int jj = 0; jj < n_c; ++jj) {
-    const int buf = jj & 1;
-    const int j_next = (jj + 1 < n_c) ? crow[jj + 1] : 0;
-    if (jj + 1 < n_c) gload(j_next);
-    const float c2 = cq * A.dk[(size_t)bh * A.Tk + j_cur];
+  // Index pipeline: while block jj is consumed, block jj+1 is being copied into the other
+  // buffer and the index of block jj+2 is being read.
+  int j_cur = 0, j_next = 0;
+  float dk_cur = 0.f;
+  if (n_c > 0) {
+    j_cur = crow[0];
+    j_next = n_c > 1 ? crow[1] : 0;
+    dk_cur = dkrow[j_cur];
+    fetch(j_cur, stage0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's pieces have landed
+  __syncthreads();
 
-    const uint4* kl = (const uint4*)(lds + buf * STAGE_BYTES);
-    const uint4* vl = kl + KV_FRAG_BYTES / 16;
-    v16i s0 = v16i{}, s1 = v16i{};
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const uint4 a0 = kl[s * 64 + lane], a1 = kl[(4 + s) * 64 + lane];
-      s0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w}, q8[s], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w}, q8[s], s1, 0, 0, 0);
+  for (int jj = 0; jj < n_c; jj += 2) {
+    // ---- even step: consume stage0 while stage1 fills.  The index of block jj+2 is read
+    // into a vector register now and only made scalar after the block's arithmetic, so its
+    // memory latency is never waited for.
+    int jv = (jj + 2 < n_c) ? crow[jj + 2] : 0;
+    float dk_next = 0.f;
+    if (jj + 1 < n_c) {
+      dk_next = dkrow[j_next];
+      fetch(j_next, stage1);
     }
-    if (j_cur == A.Tk - 1 && kvalid_last < BK) {  // keys past the end of the sequence
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key >= kvalid_last) s0[r] = -(1 << 30);
-        if (32 + key >= kvalid_last) s1[r] = -(1 << 30);
-      }
-    }
-    int imax = s0[0];
-#pragma unroll
-    for (int r = 1; r < 16; ++r) imax = max(imax, s0[r]);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) imax = max(imax, s1[r]);
-    imax = max(imax, partner_i32(imax));
-    const float Mn = fmaxf(M, (float)imax * c2);
-    if (__any(Mn > M)) {
-      const float alpha = __builtin_amdgcn_exp2f(M - Mn);
-      lsum *= alpha;
-#pragma unroll
-      for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[ct][r] *= alpha;
-    }
-    M = Mn;
-    const float offs = LOG2_448 - M;
-    v8i pb;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      float p[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s0[4 * g + e], c2, offs));
-        lsum += p[e];
-      }
-      pb[g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s1[4 * g + e], c2, offs));
-        lsum += p[e];
-      }
-      pb[4 + g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
-    }
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-      const uint4 a0 = vl[(ct * 2) * 64 + lane], a1 = vl[(ct * 2 + 1) * 64 + lane];
-      const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
-      acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 0, 0, 0);
-    }
-    if (jj + 1 < n_c) lstore(buf ^ 1);
-    j_cur = j_next;
+    attend_block(stage0, lane, hf, q8, cq * dk_cur, ragged && j_cur == A.Tk - 1, kvalid_last, M, lsum, acc);
+    asm volatile("" : "+v"(jv));
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
+    if (jj + 1 >= n_c) break;
+    // ---- odd step: consume stage1 while stage0 fills
+    j_cur = j_next;
+    j_next = __builtin_amdgcn_readfirstlane(jv);
+    dk_cur = dk_next;
+    jv = (jj + 3 < n_c) ? crow[jj + 3] : 0;
+    if (jj + 2 < n_c) {
+      dk_next = dkrow[j_next];
+      fetch(j_next, stage0);
+    }
+    attend_block(stage1, lane, hf, q8, cq * dk_cur, ragged && j_cur == A.Tk - 1, kvalid_last, M, lsum, acc);
+    asm volatile("" : "+v"(jv));
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __syncthreads();
+    j_cur = j_next;
+    j_next = __builtin_amdgcn_readfirstlane(jv);
+    dk_cur = dk_next;
   }
 
   // ---- normalise: O_s[q][ch] = acc * delta_V[ch] / l
@@ -312,33 +367,22 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
                        const uint8_t* v8, const float* dq, const float* dk, const float* dv,
                        const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
                        void* out, bool out_f32, float* lse, hipStream_t stream) {
-  SparseArgs a;
-  a.q = (const bf16_t*)q;
-  a.crit = crit;
-  a.k8 = k8;
-  a.v8 = v8;
-  a.dq = dq;
-  a.dk = dk;
-  a.dv = dv;
-  a.HZ = HZ;
-  a.bias = has_linear ? proj_b : nullptr;
-  a.out = out;
-  a.lse = lse;
-  a.N = p.N;
-  a.Tq = p.Tq;
-  a.Tk = p.Tk;
-  a.n_c = n_c;
-  a.total = p.BH * p.Tq;
-  a.per_xcd = (a.total + 7) / 8;
-  a.phi = phi_kind;
-  a.has_lin = has_linear ? 1 : 0;
-  a.out_f32 = out_f32 ? 1 : 0;
-  const unsigned grid = (unsigned)(8 * a.per_xcd);
+  SparseDims dm;
+  dm.N = p.N;
+  dm.Tq = p.Tq;
+  dm.Tk = p.Tk;
+  dm.n_c = n_c;
+  dm.total = p.BH * p.Tq;
+  dm.per_xcd = (dm.total + 7) / 8;
+  dm.phi = phi_kind;
+  dm.has_lin = has_linear ? 1 : 0;
+  dm.out_f32 = out_f32 ? 1 : 0;
+  const bf16_t* bias = has_linear ? proj_b : nullptr;
+  const unsigned grid = (unsigned)(8 * dm.per_xcd);
   if (p.block_q == 128) {
-    const size_t ldsb = 2 * STAGE_BYTES > 4 * 32 * EPI_STRIDE ? 2 * STAGE_BYTES : 4 * 32 * EPI_STRIDE;
-    sparse_fwd_kernel<4><<<grid, 256, ldsb, stream>>>(a);
+    sparse_fwd_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse, dm);
   } else {
-    sparse_fwd_kernel<2><<<grid, 128, 2 * STAGE_BYTES, stream>>>(a);
+    sparse_fwd_kernel<2><<<grid, 128, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse, dm);
   }
 }
 
