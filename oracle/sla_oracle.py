@@ -153,18 +153,25 @@ def sparse_branch_exact(Q, K, V, mask, block_q, block_k, q_blocks=None):
 
 
 def sparse_branch_quant(Q, K, V, mask, block_q, block_k, mode=QUANT_QK_INT8_PV_FP8,
-                        q_blocks=None, smooth_k=True, rowsum_quantized=False,
-                        return_lse=False):
+                        q_blocks=None, smooth_k=True, rowsum_quantized=True,
+                        reference="ceil_log2", return_lse=False):
     """Low-bit sparse branch: one pass over the critical blocks in ascending
-    block order with a running row maximum.
+    block order with a running reference level per query row.
 
-    Per query block i (scale dq_i) and critical key block j (scale dk_j):
+    Per query block i (scale dq_i) and critical key block j (scale dk_j), with
+    t = log2(e) * S the logits in base-2 units:
       S  = (Q8_i . K8_j^T) dq_i dk_j / sqrt(d)         integer product, exact
-      m' = max(m, rowmax S);  a = exp(m - m')
-      P~ = exp(S - m');  l = a l + rowsum(P~)
-      P8 = e4m3(448 P~)  (mode qk_int8: unrounded);  acc = a acc + P8 . V8_j
+      r' = max(r, ref(rowmax t));  a = 2^(r - r')       running reference
+      P~ = 2^(t - r')  in (0, 1];  P8 = e4m3(448 P~)    (mode qk_int8: unrounded)
+      l  = a l + rowsum(P8)/448;   acc = a acc + P8 . V8_j
     and O^s = acc * dv / (448 l).  The row constant Q.mu removed by K-smoothing
-    cancels in the softmax, so it is never added back."""
+    cancels in the softmax, so it is never added back.
+
+    reference = "ceil_log2": ref(x) = ceil(x), an integer, so every rescale
+    factor a is a power of two and the largest P~ of a row lies in (1/2, 1];
+    reference = "running": ref(x) = x, the plain running maximum (largest P~ = 1).
+    rowsum_quantized = False sums the unrounded P~ instead of P8/448.  Both
+    alternatives give the same result before rounding."""
     if mode == QUANT_NONE:
         raise ValueError("use sparse_branch_exact for mode 'none'")
     N, d = Q.shape
@@ -174,22 +181,25 @@ def sparse_branch_quant(Q, K, V, mask, block_q, block_k, mode=QUANT_QK_INT8_PV_F
     V8, dv = quantize_v(V, fp8=(mode == QUANT_QK_INT8_PV_FP8))
     out = np.full((N, V.shape[1]), np.nan)
     lse = np.full(N, np.nan)
+    log2e = 1.0 / math.log(2.0)
     for i in (range(len(qs)) if q_blocks is None else q_blocks):
         rows = qs[i].stop - qs[i].start
-        m = np.full(rows, -np.inf)
+        r = np.full(rows, -np.inf)
         l = np.zeros(rows)
         acc = np.zeros((rows, V.shape[1]))
         for j in np.flatnonzero(mask[i] == 1):
             S = (Q8[qs[i]] @ K8[ks[j]].T) * (dq[i] * dk[j] / math.sqrt(d))
-            m_new = np.maximum(m, S.max(axis=1))
-            alpha = np.where(np.isneginf(m), 0.0, np.exp(m - m_new))
-            Pt = np.exp(S - m_new[:, None])
+            t = S * log2e
+            tmax = t.max(axis=1)
+            r_new = np.maximum(r, np.ceil(tmax) if reference == "ceil_log2" else tmax)
+            alpha = np.where(np.isneginf(r), 0.0, np.exp2(r - r_new))
+            Pt = np.exp2(t - r_new[:, None])
             P8 = formats.e4m3_round(P_SCALE * Pt) if mode == QUANT_QK_INT8_PV_FP8 else P_SCALE * Pt
             l = alpha * l + (P8.sum(axis=1) / P_SCALE if rowsum_quantized else Pt.sum(axis=1))
             acc = alpha[:, None] * acc + P8 @ V8[ks[j]]
-            m = m_new
+            r = r_new
         out[qs[i]] = acc * dv[None, :] / (P_SCALE * l[:, None])
-        lse[qs[i]] = m + np.log(l)
+        lse[qs[i]] = (r + np.log2(l)) * math.log(2.0)
     return (out, lse) if return_lse else out
 
 

@@ -5,8 +5,8 @@
 // One workgroup per (b,h,query block); one wavefront per 32 queries.  Everything is
 // computed transposed so that a lane owns ONE query (column) throughout:
 //   S^T[key][query]  = K8 . Q8^T      v_mfma_i32_32x32x32_i8, A = K fragment (LDS), B = Q8 (registers)
-//   P8 = e4m3(448 exp(S - m))         in registers; the running max / sum of a query live
-//                                     in its two lanes (lane, lane^32): one permlane swap per block
+//   P8 = e4m3(448 2^(t - r))          in registers; r = integer running reference of the query, shared
+//                                     by its two lanes (lane, lane^32): one permlane swap per block
 //   O^T[ch][query] += V8^T . P8^T     v_mfma_f32_32x32x64_f8f6f4, A = V fragment (LDS), B = P8 as it
 //                                     sits in the accumulators' order (V was stored in that key order)
 // so the rescale factor, the row sum and the final normalisation are per-lane scalars and P
@@ -44,6 +44,8 @@ struct SparseArgs {
 
 constexpr int STAGE_BYTES = 2 * KV_FRAG_BYTES;  // K + V record of one key block
 constexpr int EPI_STRIDE = 64 * 4 + 16;         // bytes per staged output row (64 fp32 + pad)
+constexpr int BIAS_I = 0x4B400000;              // bit pattern of 1.5 * 2^23
+constexpr float BIAS_F = 12582912.0f;           // 1.5 * 2^23
 
 __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
   uint4 a = make_uint4(0, 0, 0, 0), b = a;
@@ -59,17 +61,28 @@ __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
   }
 }
 
-// One critical block: consume the K/V fragments in LDS buffer `kv`, update the running
-// max M, the row-sum partial lsum and the output accumulators.
+// One critical block: consume the K/V fragments in LDS buffer `kv` and update the row state.
+//
+// Row state (per lane = per query): `r` is the running reference level, an INTEGER number of
+// binary orders of magnitude (r = max over blocks of ceil(log2(e) * row max)), so that
+// P = 448 * 2^(t - r) <= 448 fits E4M3; `R` is the level the accumulators are expressed in.
+// Because r - R is an integer, a block's contribution is brought to level R by the E8M0
+// block scale of the FP8 MFMA (2^(r-R) on the P operand): the accumulators are never
+// rescaled on the vector ALU, except for a rare renormalisation when r - R exceeds 64.
+// The row sum of the rounded P comes out of the same MFMA through a tile of ones.
+template <bool tail>
 __device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int lane, int hf, const v4i (&q8)[4],
-                                             float c2, bool tail, int kvalid, float& M, float& lsum,
-                                             v16f (&acc)[4]) {
+                                             const v16i& bias16, const v8i& ones, float c2, int kvalid,
+                                             float& r, float& R, v16f (&acc)[4], v16f& accl) {
   const uint4* kl = kv;
   const uint4* vl = kv + KV_FRAG_BYTES / 16;
   uint4 kf[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) kf[u] = kl[u * 64 + lane];
-  v16i s0 = v16i{}, s1 = v16i{};
+  // The integer accumulators start from BIAS_I = bits of 1.5 * 2^23, so each finished score,
+  // reinterpreted as fp32, IS the float 1.5 * 2^23 + s (exact for |s| < 2^22; here
+  // |s| <= 127 * 127 * 128): no int -> float conversion is needed afterwards.
+  v16i s0 = bias16, s1 = bias16;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     s0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[s].x, (int)kf[s].y, (int)kf[s].z, (int)kf[s].w}, q8[s], s0, 0, 0, 0);
@@ -79,54 +92,67 @@ __device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int l
   uint4 vf[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) vf[u] = vl[u * 64 + lane];
-  if (tail) {  // keys past the end of the sequence (last key block only)
+  if (tail) {  // keys past the end of the sequence (last key block only) never win the max
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int key = 8 * (r >> 2) + 4 * hf + (r & 3);
-      if (key >= kvalid) s0[r] = -(1 << 30);
-      if (32 + key >= kvalid) s1[r] = -(1 << 30);
+    for (int q = 0; q < 16; ++q) {
+      const int key = 8 * (q >> 2) + 4 * hf + (q & 3);
+      if (key >= kvalid) s0[q] = BIAS_I - 4000000;
+      if (32 + key >= kvalid) s1[q] = BIAS_I - 4000000;
     }
   }
-  int imax = s0[0];
+  int imax = s0[0];  // biased scores order like the scores themselves
 #pragma unroll
-  for (int r = 1; r < 16; ++r) imax = max(imax, s0[r]);
+  for (int q = 1; q < 16; ++q) imax = max(imax, s0[q]);
 #pragma unroll
-  for (int r = 0; r < 16; ++r) imax = max(imax, s1[r]);
+  for (int q = 0; q < 16; ++q) imax = max(imax, s1[q]);
   imax = max(imax, partner_i32(imax));
-  const float Mn = fmaxf(M, (float)imax * c2);
-  if (__any(Mn > M)) {
-    const float alpha = __builtin_amdgcn_exp2f(M - Mn);
-    lsum *= alpha;
+  // t = s * c2 = fma(bias + s, c2, -bias * c2); the guard of one score step keeps t - r <= 0
+  // whatever the rounding of the two products
+  const float nbc2 = -BIAS_F * c2;
+  r = fmaxf(r, __builtin_ceilf(__builtin_fmaf(__int_as_float(imax), c2, nbc2) + c2));
+  if (__any(r - R > 64.f)) {  // first block (R = -inf) or a jump of more than 64 binades
+    const float down = (r - R > 64.f) ? __builtin_amdgcn_exp2f(R - r) : 1.0f;
+    if (r - R > 64.f) R = r;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[ct][r] *= alpha;
+      for (int q = 0; q < 16; ++q) acc[ct][q] *= down;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) accl[q] *= down;
   }
-  M = Mn;
-  const float offs = LOG2_448 - M;
+  const int scale_p = 127 + (int)(r - R);  // E8M0 code of 2^(r-R)
+  const float offs = (LOG2_448 - r) + nbc2;
   v8i pb;
+  int code = 0;
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     float p[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s0[4 * g + e], c2, offs));
-      lsum += p[e];
-    }
-    pb[g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
+    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(__int_as_float(s0[4 * g + e]), c2, offs));
+    if (tail) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)s1[4 * g + e], c2, offs));
-      lsum += p[e];
+      for (int e = 0; e < 4; ++e)
+        if (8 * g + 4 * hf + e >= kvalid) p[e] = 0.f;
     }
-    pb[4 + g] = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], 0, false), true);
+    code = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], code, false), true);  // both halves overwritten
+    pb[g] = code;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(__int_as_float(s1[4 * g + e]), c2, offs));
+    if (tail) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (32 + 8 * g + 4 * hf + e >= kvalid) p[e] = 0.f;
+    }
+    code = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], code, false), true);
+    pb[4 + g] = code;
   }
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) {
     const uint4 a0 = vf[2 * ct], a1 = vf[2 * ct + 1];
     const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
-    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 0, 0, 0);
+    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 127, 0, scale_p);
   }
+  accl = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pb, accl, 0, 0, 0, 127, 0, scale_p);
 }
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -181,10 +207,18 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   }
   const float cq = dqi * (LOG2E / 11.313708498984761f);
 
-  v16f acc[4];
+  v16f acc[4], accl = v16f{};
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
-  float M = -INFINITY, lsum = 0.f;
+  float r = -INFINITY, R = -INFINITY;
+  // A operand that sums P over the keys: FP8 1.0 in rows 0 and 4 of a 32-row tile, so the
+  // row sum of a query lands in accumulator register 0 of both of its lanes.
+  const int one4 = (l32 == 0 || l32 == 4) ? 0x38383838 : 0;
+  v8i ones = {one4, one4, one4, one4, one4, one4, one4, one4};
+  v16i bias16;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) bias16[e] = BIAS_I;
+  asm volatile("" : "+v"(bias16));  // keep it in registers: it is the C operand of every first score MFMA
 
   const int n_c = A.n_c;
   const int32_t* crow = A.crit + (size_t)rowid * n_c;
@@ -192,21 +226,27 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const size_t rec0 = (size_t)bh * A.Tk * KV_FRAG_BYTES;
   // Asynchronous global -> LDS copy of one block's K and V records (no registers in between):
   // each wavefront fills 1 KiB pieces, lane l supplying bytes [16 l, 16 l + 16) of a piece.
+  const int w_s = __builtin_amdgcn_readfirstlane(w);  // wavefront index as a scalar
+  const unsigned lane_off = (unsigned)t * 16u;
   auto fetch = [&](int j, uint4* dst) {
-    const uint4* ks = (const uint4*)(A.k8 + rec0 + (size_t)j * KV_FRAG_BYTES);
-    const uint4* vs = (const uint4*)(A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES);
+    // uniform base (scalar registers) + 32-bit per-lane offset: no vector address arithmetic
+    const char* ks = (const char*)A.k8 + rec0 + (size_t)j * KV_FRAG_BYTES;
+    const char* vs = (const char*)A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES;
 #pragma unroll
     for (int u = 0; u < CH / 2; ++u) {
-      __builtin_amdgcn_global_load_lds((const void*)(ks + u * NT + t), (lds_ptr_t)(dst + u * NT + w * 64), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const void*)(vs + u * NT + t),
-                                       (lds_ptr_t)(dst + KV_FRAG_BYTES / 16 + u * NT + w * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void*)(ks + u * NT * 16 + lane_off),
+                                       (lds_ptr_t)(dst + u * NT + w_s * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void*)(vs + u * NT * 16 + lane_off),
+                                       (lds_ptr_t)(dst + KV_FRAG_BYTES / 16 + u * NT + w_s * 64), 16, 0, 0);
     }
   };
   const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
   const bool ragged = kvalid_last < BK;
 
   // Index pipeline: while block jj is consumed, block jj+1 is being copied into the other
-  // buffer and the index of block jj+2 is being read.
+  // buffer and the index of block jj+2 is being read.  A ragged last key block can only be
+  // the last entry of the (ascending) list; it is peeled off the loop so that the masking of
+  // its missing keys costs the other blocks nothing.
   int j_cur = 0, j_next = 0;
   float dk_cur = 0.f;
   if (n_c > 0) {
@@ -215,10 +255,12 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     dk_cur = dkrow[j_cur];
     fetch(j_cur, stage0);
   }
+  const bool has_tail = ragged && n_c > 0 && crow[n_c - 1] == A.Tk - 1;
+  const int n_main = has_tail ? n_c - 1 : n_c;
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's pieces have landed
   __syncthreads();
 
-  for (int jj = 0; jj < n_c; jj += 2) {
+  for (int jj = 0; jj < n_main; jj += 2) {
     // ---- even step: consume stage0 while stage1 fills.  The index of block jj+2 is read
     // into a vector register now and only made scalar after the block's arithmetic, so its
     // memory latency is never waited for.
@@ -228,21 +270,21 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       dk_next = dkrow[j_next];
       fetch(j_next, stage1);
     }
-    attend_block(stage0, lane, hf, q8, cq * dk_cur, ragged && j_cur == A.Tk - 1, kvalid_last, M, lsum, acc);
+    attend_block<false>(stage0, lane, hf, q8, bias16, ones, cq * dk_cur, 0, r, R, acc, accl);
     asm volatile("" : "+v"(jv));
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    if (jj + 1 >= n_c) break;
-    // ---- odd step: consume stage1 while stage0 fills
     j_cur = j_next;
     j_next = __builtin_amdgcn_readfirstlane(jv);
     dk_cur = dk_next;
+    if (jj + 1 >= n_main) break;
+    // ---- odd step: consume stage1 while stage0 fills
     jv = (jj + 3 < n_c) ? crow[jj + 3] : 0;
     if (jj + 2 < n_c) {
       dk_next = dkrow[j_next];
       fetch(j_next, stage0);
     }
-    attend_block(stage1, lane, hf, q8, cq * dk_cur, ragged && j_cur == A.Tk - 1, kvalid_last, M, lsum, acc);
+    attend_block<false>(stage1, lane, hf, q8, bias16, ones, cq * dk_cur, 0, r, R, acc, accl);
     asm volatile("" : "+v"(jv));
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
@@ -250,12 +292,14 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     j_next = __builtin_amdgcn_readfirstlane(jv);
     dk_cur = dk_next;
   }
+  if (has_tail)
+    attend_block<true>((n_main & 1) ? stage1 : stage0, lane, hf, q8, bias16, ones, cq * dk_cur, kvalid_last, r, R, acc, accl);
 
   // ---- normalise: O_s[q][ch] = acc * delta_V[ch] / l
-  const float ltot = lsum + partner_f32(lsum);
+  const float ltot = accl[0];  // sum of the rounded P (scaled by 448), at level R
   const float inv_l = ltot > 0.f ? 1.0f / ltot : 0.f;
   if (A.lse && hf == 0 && qok)
-    A.lse[(size_t)bh * A.N + qrow] = (M + __builtin_amdgcn_logf(ltot) - LOG2_448) * LN2;
+    A.lse[(size_t)bh * A.N + qrow] = (R + __builtin_amdgcn_logf(ltot) - LOG2_448) * LN2;
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll

@@ -172,12 +172,14 @@ def test_softmax_weights_sum_to_one_over_critical_keys():
     assert np.allclose(o[:, 0], 1.0, atol=1e-13)
     rows_without = np.repeat(mask[:, 5] != 1, 64)
     assert (o[rows_without, 1] == 0).all() and (o[~rows_without, 1] > 0).all()
-    oq = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8)
-    assert np.allclose(oq[:, 0], 1.0, atol=1e-12)          # unrounded P: exact normalisation
-    o8 = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8_PV_FP8)
-    assert np.abs(o8[:, 0] - 1.0).max() < 2.0 ** -4          # FP8 P: within one rounding step
-    o8q = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8_PV_FP8, rowsum_quantized=True)
-    assert np.allclose(o8q[:, 0], 1.0, atol=1e-12)
+    for ref in ("ceil_log2", "running"):
+        oq = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8, reference=ref)
+        assert np.allclose(oq[:, 0], 1.0, atol=1e-12)          # unrounded P: exact normalisation
+        o8 = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8_PV_FP8, reference=ref,
+                                    rowsum_quantized=False)
+        assert np.abs(o8[:, 0] - 1.0).max() < 2.0 ** -4          # FP8 P vs unrounded sum: one rounding step
+        o8q = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8_PV_FP8, reference=ref)
+        assert np.allclose(o8q[:, 0], 1.0, atol=1e-12)         # sum of the rounded P: exact again
 
 
 def test_key_block_permutation_invariance_exact():
@@ -217,9 +219,12 @@ def test_online_softmax_equals_two_pass_when_nothing_is_rounded(monkeypatch):
     mask = so.classify(so.pooled_scores(Q, K, 64, 64), 3, 6)
     monkeypatch.setattr(formats, "int8_quantize", lambda x, delta: np.asarray(x) / delta)
     monkeypatch.setattr(formats, "e4m3_round", lambda x: np.asarray(x, dtype=np.float64))
-    oq, lse = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8_PV_FP8, return_lse=True)
     ex = so.sparse_branch_exact(Q, K, V, mask, 64, 64)
-    assert np.abs(oq - ex).max() < 1e-11
+    for ref in ("running", "ceil_log2"):
+        for rq in (False, True):
+            oq, lse = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8_PV_FP8, return_lse=True,
+                                             reference=ref, rowsum_quantized=rq)
+            assert np.abs(oq - ex).max() < 1e-11
     # log-sum-exp of the smoothed logits over the critical keys
     Kt = K - K.mean(0)
     i = 3
@@ -364,3 +369,16 @@ def test_oracle_reproduces_its_stored_tiny_outputs():
         assert hs["mask"] == hl["mask"]
         for key in (so.QUANT_NONE, so.QUANT_QK_INT8, so.QUANT_QK_INT8_PV_FP8, "scores_row0"):
             assert np.allclose(np.array(hs[key]), np.array(hl[key]), rtol=0, atol=1e-12)
+
+
+def test_integer_reference_keeps_every_rescale_a_power_of_two():
+    # With the ceil reference the largest scaled probability of a row is in (1/2, 1]
+    # and the two reference rules agree to within the FP8 rounding they both apply.
+    cfg, Q, K, V = _tiny()
+    mask = so.classify(so.pooled_scores(Q, K, 64, 64), 3, 6)
+    a = so.sparse_branch_quant(Q, K, V, mask, 64, 64, reference="ceil_log2")
+    b = so.sparse_branch_quant(Q, K, V, mask, 64, 64, reference="running")
+    assert np.abs(a - b).max() < 2e-2 and (a * b).sum() / np.linalg.norm(a) / np.linalg.norm(b) > 0.9995
+    ex = so.sparse_branch_exact(Q, K, V, mask, 64, 64)
+    ea, eb = np.abs(a - ex).mean(), np.abs(b - ex).mean()
+    assert ea < 1.5 * eb          # no worse than the plain running maximum, on average
