@@ -10,8 +10,8 @@
 //   O^T[ch][query] += V8^T . P8^T     v_mfma_f32_32x32x64_f8f6f4, A = V fragment (LDS), B = P8 as it
 //                                     sits in the accumulators' order (V was stored in that key order)
 // so the rescale factor, the row sum and the final normalisation are per-lane scalars and P
-// never touches LDS.  K/V fragments of the next critical block are copied global -> LDS
-// asynchronously (no registers) into the other staging buffer while the current one is
+// never touches LDS.  K/V fragments of the next three critical blocks are copied global -> LDS
+// asynchronously (no registers) into the other staging buffers while the current one is
 // consumed (one barrier per block).
 //
 // Epilogue: O_s = acc * delta_V / l;  optional linear term phi(Q) H_i / (phi(Q).Z_i) as bf16 MFMA
@@ -44,6 +44,7 @@ struct SparseArgs {
 
 constexpr int STAGE_BYTES = 2 * KV_FRAG_BYTES;  // K + V record of one key block
 constexpr int EPI_STRIDE = 64 * 4 + 16;         // bytes per staged output row (64 fp32 + pad)
+constexpr int IDX_CAP = 1024;                   // critical-list entries held in LDS at a time
 constexpr int BIAS_I = 0x4B400000;              // bit pattern of 1.5 * 2^23
 constexpr float BIAS_F = 12582912.0f;           // 1.5 * 2^23
 
@@ -157,6 +158,18 @@ __device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int l
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
+// Workgroup barrier for the staging pipeline.  __syncthreads() would also wait for EVERY
+// outstanding memory operation, including the asynchronous copies of the blocks still in
+// flight, which is exactly what the pipeline must not do.  Each wavefront has already waited
+// (s_waitcnt vmcnt) for its own pieces of the block being published and has consumed (through
+// its MFMAs) every LDS read of the stage being retired, so a bare s_barrier is sufficient; the
+// empty asm statements only stop the compiler from moving memory accesses across it.
+__device__ __forceinline__ void stage_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 template <int NW>
 __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     const bf16_t* __restrict__ q_, const int32_t* __restrict__ crit_, const int8_t* __restrict__ k8_,
@@ -168,11 +181,17 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   constexpr int NT = NW * 64;
   constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
   constexpr int BQ = NW * 32;
-  // two K/V staging buffers as separate objects (so the compiler can tell the asynchronous
-  // fill of one from the reads of the other) and the epilogue's transposition area
+  // Four K/V staging buffers, declared as separate objects so the compiler can tell the
+  // asynchronous fill of one from the reads of another; after the main loop wavefront w
+  // reuses buffer w for the output transposition.  sidx / sdk hold the critical list of this
+  // query block and the matching K scales (IDX_CAP entries at a time).
   __shared__ uint4 stage0[STAGE_BYTES / 16];
   __shared__ uint4 stage1[STAGE_BYTES / 16];
-  __shared__ __attribute__((aligned(16))) unsigned char lds[NW * 32 * EPI_STRIDE];
+  __shared__ uint4 stage2[STAGE_BYTES / 16];
+  __shared__ uint4 stage3[STAGE_BYTES / 16];
+  __shared__ int sidx[IDX_CAP];
+  __shared__ float sdk[IDX_CAP];
+  static_assert(32 * EPI_STRIDE <= STAGE_BYTES, "output staging must fit one stage buffer");
 
   // Consecutive query blocks of a head run on the same XCD (workgroup ids are dealt
   // round-robin over the 8 XCDs), so neighbours share K/V fragments in that XCD's L2.
@@ -243,57 +262,63 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
   const bool ragged = kvalid_last < BK;
 
-  // Index pipeline: while block jj is consumed, block jj+1 is being copied into the other
-  // buffer and the index of block jj+2 is being read.  A ragged last key block can only be
-  // the last entry of the (ascending) list; it is peeled off the loop so that the masking of
+  // Software pipeline over the critical list, three blocks deep: while block b is consumed
+  // from stage b%4, blocks b+1..b+3 are in flight or already resident in the other stages, so
+  // the L2 / HBM latency of a block is covered by the arithmetic of the blocks before it.  One
+  // barrier per block: it publishes block b+1 (every wavefront has waited for its own pieces)
+  // and retires stage b%4, which the next step's copy overwrites.  A ragged last key block can
+  // only be the last entry of the (ascending) list; it is peeled off the loop so that masking
   // its missing keys costs the other blocks nothing.
-  int j_cur = 0, j_next = 0;
-  float dk_cur = 0.f;
-  if (n_c > 0) {
-    j_cur = crow[0];
-    j_next = n_c > 1 ? crow[1] : 0;
-    dk_cur = dkrow[j_cur];
-    fetch(j_cur, stage0);
-  }
   const bool has_tail = ragged && n_c > 0 && crow[n_c - 1] == A.Tk - 1;
-  const int n_main = has_tail ? n_c - 1 : n_c;
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's pieces have landed
-  __syncthreads();
+  constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4F70 : (0x0F70 | (2 * CH));  // s_waitcnt vmcnt(2*CH)
 
-  for (int jj = 0; jj < n_main; jj += 2) {
-    // ---- even step: consume stage0 while stage1 fills.  The index of block jj+2 is read
-    // into a vector register now and only made scalar after the block's arithmetic, so its
-    // memory latency is never waited for.
-    int jv = (jj + 2 < n_c) ? crow[jj + 2] : 0;
-    float dk_next = 0.f;
-    if (jj + 1 < n_c) {
-      dk_next = dkrow[j_next];
-      fetch(j_next, stage1);
-    }
-    attend_block<false>(stage0, lane, hf, q8, bias16, ones, cq * dk_cur, 0, r, R, acc, accl);
-    asm volatile("" : "+v"(jv));
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    j_cur = j_next;
-    j_next = __builtin_amdgcn_readfirstlane(jv);
-    dk_cur = dk_next;
-    if (jj + 1 >= n_main) break;
-    // ---- odd step: consume stage1 while stage0 fills
-    jv = (jj + 3 < n_c) ? crow[jj + 3] : 0;
-    if (jj + 2 < n_c) {
-      dk_next = dkrow[j_next];
-      fetch(j_next, stage0);
-    }
-    attend_block<false>(stage1, lane, hf, q8, bias16, ones, cq * dk_cur, 0, r, R, acc, accl);
-    asm volatile("" : "+v"(jv));
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    j_cur = j_next;
-    j_next = __builtin_amdgcn_readfirstlane(jv);
-    dk_cur = dk_next;
+#define SLA_STEP(B, CUR, FILL)                                                                        \
+  {                                                                                                   \
+    const int b_ = (B);                                                                               \
+    if (b_ + 3 < nb) fetch(__builtin_amdgcn_readfirstlane(jv3), FILL);                                \
+    jv3 = sidx[min(b_ + 4, nb - 1)];                                                                  \
+    const float c2_ = cq * dkv;                                                                       \
+    dkv = sdk[min(b_ + 1, nb - 1)];                                                                   \
+    attend_block<false>(CUR, lane, hf, q8, bias16, ones, c2_, 0, r, R, acc, accl);                    \
+    asm volatile("" : "+v"(jv3), "+v"(dkv));                                                          \
+    if (b_ + 3 < nb) __builtin_amdgcn_s_waitcnt(WAIT_KEEP2); else __builtin_amdgcn_s_waitcnt(0x0F70); \
+    stage_barrier();                                                                                  \
   }
-  if (has_tail)
-    attend_block<true>((n_main & 1) ? stage1 : stage0, lane, hf, q8, bias16, ones, cq * dk_cur, kvalid_last, r, R, acc, accl);
+
+  for (int c0 = 0; c0 < n_c; c0 += IDX_CAP) {
+    const int nb = min(IDX_CAP, n_c - c0);
+    __syncthreads();  // the previous chunk's list and stages are no longer in use
+    for (int e = t; e < nb; e += NT) {
+      const int j = crow[c0 + e];
+      sidx[e] = j;
+      sdk[e] = dkrow[j];
+    }
+    __syncthreads();
+    fetch(__builtin_amdgcn_readfirstlane(sidx[0]), stage0);
+    if (nb > 1) fetch(__builtin_amdgcn_readfirstlane(sidx[1]), stage1);
+    if (nb > 2) fetch(__builtin_amdgcn_readfirstlane(sidx[2]), stage2);
+    int jv3 = sidx[min(3, nb - 1)];   // index of block b+3, read one step ahead of its use
+    float dkv = sdk[0];               // K scale of block b, likewise
+    if (nb > 2) __builtin_amdgcn_s_waitcnt(WAIT_KEEP2); else __builtin_amdgcn_s_waitcnt(0x0F70);
+    stage_barrier();
+    const int nb_main = (has_tail && c0 + nb == n_c) ? nb - 1 : nb;
+    int b = 0;
+    for (; b + 4 <= nb_main; b += 4) {
+      SLA_STEP(b, stage0, stage3)
+      SLA_STEP(b + 1, stage1, stage0)
+      SLA_STEP(b + 2, stage2, stage1)
+      SLA_STEP(b + 3, stage3, stage2)
+    }
+    if (b < nb_main) SLA_STEP(b, stage0, stage3)
+    if (b + 1 < nb_main) SLA_STEP(b + 1, stage1, stage0)
+    if (b + 2 < nb_main) SLA_STEP(b + 2, stage2, stage1)
+    if (nb_main < nb) {  // the ragged last key block (everything has landed: no copy is in flight)
+      const int st = nb_main & 3;
+      const uint4* cur = st == 0 ? stage0 : st == 1 ? stage1 : st == 2 ? stage2 : stage3;
+      attend_block<true>(cur, lane, hf, q8, bias16, ones, cq * sdk[nb_main], kvalid_last, r, R, acc, accl);
+    }
+  }
+#undef SLA_STEP
 
   // ---- normalise: O_s[q][ch] = acc * delta_V[ch] / l
   const float ltot = accl[0];  // sum of the rounded P (scaled by 448), at level R
@@ -377,7 +402,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   }
 
   // ---- transpose through LDS (per wavefront: 32 rows x 64 channels fp32 at a time) and store
-  unsigned char* my = lds + w * (32 * EPI_STRIDE);
+  unsigned char* my = (unsigned char*)(w == 0 ? stage0 : w == 1 ? stage1 : w == 2 ? stage2 : stage3);
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     __syncthreads();
