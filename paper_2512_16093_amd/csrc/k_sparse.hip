@@ -43,7 +43,7 @@ struct SparseArgs {
 };
 
 constexpr int STAGE_BYTES = 2 * KV_FRAG_BYTES;  // K + V record of one key block
-constexpr int EPI_STRIDE = 64 * 4 + 16;         // bytes per staged output row (64 fp32 + pad)
+constexpr int EPI_STRIDE = 32 * 4 + 16;         // bytes per staged output row (32 fp32 + pad)
 constexpr int IDX_CAP = 1024;                   // critical-list entries held in LDS at a time
 constexpr int BIAS_I = 0x4B400000;              // bit pattern of 1.5 * 2^23
 constexpr float BIAS_F = 12582912.0f;           // 1.5 * 2^23
@@ -62,8 +62,6 @@ __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
   }
 }
 
-// One critical block: consume the K/V fragments in LDS buffer `kv` and update the row state.
-//
 // Row state (per lane = per query): `r` is the running reference level, an INTEGER number of
 // binary orders of magnitude (r = max over blocks of ceil(log2(e) * row max)), so that
 // P = 448 * 2^(t - r) <= 448 fits E4M3; `R` is the level the accumulators are expressed in.
@@ -71,28 +69,51 @@ __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
 // block scale of the FP8 MFMA (2^(r-R) on the P operand): the accumulators are never
 // rescaled on the vector ALU, except for a rare renormalisation when r - R exceeds 64.
 // The row sum of the rounded P comes out of the same MFMA through a tile of ones.
-template <bool tail>
-__device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int lane, int hf, const v4i (&q8)[4],
-                                             const v16i& bias16, const v8i& ones, float c2, int kvalid,
-                                             float& r, float& R, v16f (&acc)[4], v16f& accl) {
-  const uint4* kl = kv;
-  const uint4* vl = kv + KV_FRAG_BYTES / 16;
+//
+// The three parts of a block are separate so the main loop can run the P.V product one block
+// behind the scores: in step b a wavefront issues the score MFMAs of block b, then the P.V
+// MFMAs of block b-1, then does the softmax arithmetic of block b on the vector ALU while
+// those MFMAs execute.
+
+// S^T = K8 . Q8^T for one key block (64 keys x this wavefront's 32 queries).  The integer
+// accumulators start from BIAS_I = bits of 1.5 * 2^23, so each finished score, reinterpreted
+// as fp32, IS the float 1.5 * 2^23 + s (exact for |s| < 2^22; here |s| <= 127 * 127 * 128):
+// no int -> float conversion is needed afterwards.
+__device__ __forceinline__ void qk_scores(const uint4* __restrict__ kl, int lane, const v4i (&q8)[4],
+                                          const v16i& bias16, v16i& s0, v16i& s1) {
   uint4 kf[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) kf[u] = kl[u * 64 + lane];
-  // The integer accumulators start from BIAS_I = bits of 1.5 * 2^23, so each finished score,
-  // reinterpreted as fp32, IS the float 1.5 * 2^23 + s (exact for |s| < 2^22; here
-  // |s| <= 127 * 127 * 128): no int -> float conversion is needed afterwards.
-  v16i s0 = bias16, s1 = bias16;
+  s0 = bias16;
+  s1 = bias16;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     s0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[s].x, (int)kf[s].y, (int)kf[s].z, (int)kf[s].w}, q8[s], s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[4 + s].x, (int)kf[4 + s].y, (int)kf[4 + s].z, (int)kf[4 + s].w}, q8[s], s1, 0, 0, 0);
   }
-  // V fragments: issued now so that their LDS latency hides behind the softmax arithmetic
+}
+
+// O^T += V8^T . P8^T (and the row sum through the ones tile), P scaled by 2^(scale_p - 127).
+__device__ __forceinline__ void pv_accumulate(const uint4* __restrict__ vl, int lane, const v8i& pb, int scale_p,
+                                              const v8i& ones, v16f (&acc)[4], v16f& accl) {
   uint4 vf[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) vf[u] = vl[u * 64 + lane];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) {
+    const uint4 a0 = vf[2 * ct], a1 = vf[2 * ct + 1];
+    const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 127, 0, scale_p);
+  }
+  accl = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pb, accl, 0, 0, 0, 127, 0, scale_p);
+}
+
+// First half of a block's softmax: row maximum of the biased scores -> reference level r
+// (and the rare renormalisation of the accumulators).  Returns the exponent offset `offs`
+// such that P = 448 * 2^(t - r) = exp2(fma(biased score, c2, offs)).
+template <bool tail>
+__device__ __forceinline__ float softmax_reference(v16i& s0, v16i& s1, int hf, float c2, int kvalid, float& r,
+                                                   float& R, v16f (&acc)[4], v16f& accl) {
   if (tail) {  // keys past the end of the sequence (last key block only) never win the max
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
@@ -121,9 +142,13 @@ __device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int l
 #pragma unroll
     for (int q = 0; q < 16; ++q) accl[q] *= down;
   }
-  const int scale_p = 127 + (int)(r - R);  // E8M0 code of 2^(r-R)
-  const float offs = (LOG2_448 - r) + nbc2;
-  v8i pb;
+  return (LOG2_448 - r) + nbc2;
+}
+
+// Second half: biased scores -> FP8 codes of P.
+template <bool tail>
+__device__ __forceinline__ void softmax_codes(const v16i& s0, const v16i& s1, int hf, float c2, float offs,
+                                              int kvalid, v8i& pb) {
   int code = 0;
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
@@ -147,13 +172,12 @@ __device__ __forceinline__ void attend_block(const uint4* __restrict__ kv, int l
     code = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], code, false), true);
     pb[4 + g] = code;
   }
-#pragma unroll
-  for (int ct = 0; ct < 4; ++ct) {
-    const uint4 a0 = vf[2 * ct], a1 = vf[2 * ct + 1];
-    const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
-    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 127, 0, scale_p);
-  }
-  accl = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pb, accl, 0, 0, 0, 127, 0, scale_p);
+}
+
+// E8M0 code of 2^(r_prev - R): brings the P codes made at level r_prev to the accumulators'
+// level R (which may have moved up since; far below R the contribution vanishes).
+__device__ __forceinline__ int level_scale(float r_prev, float R) {
+  return 127 + (int)fmaxf(r_prev - R, -127.f);
 }
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -181,17 +205,15 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   constexpr int NT = NW * 64;
   constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
   constexpr int BQ = NW * 32;
-  // Four K/V staging buffers, declared as separate objects so the compiler can tell the
-  // asynchronous fill of one from the reads of another; after the main loop wavefront w
-  // reuses buffer w for the output transposition.  sidx / sdk hold the critical list of this
-  // query block and the matching K scales (IDX_CAP entries at a time).
-  __shared__ uint4 stage0[STAGE_BYTES / 16];
-  __shared__ uint4 stage1[STAGE_BYTES / 16];
-  __shared__ uint4 stage2[STAGE_BYTES / 16];
-  __shared__ uint4 stage3[STAGE_BYTES / 16];
+  // Rings of four K and four V staging buffers, declared as separate objects so the compiler
+  // can tell the asynchronous fill of one from the reads of another; after the main loop
+  // wavefront w reuses K buffer w for the output transposition.  sidx / sdk hold the critical
+  // list of this query block and the matching K scales (IDX_CAP entries at a time).
+  __shared__ uint4 kst0[KV_FRAG_BYTES / 16], kst1[KV_FRAG_BYTES / 16], kst2[KV_FRAG_BYTES / 16], kst3[KV_FRAG_BYTES / 16];
+  __shared__ uint4 vst0[KV_FRAG_BYTES / 16], vst1[KV_FRAG_BYTES / 16], vst2[KV_FRAG_BYTES / 16], vst3[KV_FRAG_BYTES / 16];
   __shared__ int sidx[IDX_CAP];
   __shared__ float sdk[IDX_CAP];
-  static_assert(32 * EPI_STRIDE <= STAGE_BYTES, "output staging must fit one stage buffer");
+  static_assert(32 * EPI_STRIDE <= KV_FRAG_BYTES, "output staging must fit one stage buffer");
 
   // Consecutive query blocks of a head run on the same XCD (workgroup ids are dealt
   // round-robin over the 8 XCDs), so neighbours share K/V fragments in that XCD's L2.
@@ -247,40 +269,78 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   // each wavefront fills 1 KiB pieces, lane l supplying bytes [16 l, 16 l + 16) of a piece.
   const int w_s = __builtin_amdgcn_readfirstlane(w);  // wavefront index as a scalar
   const unsigned lane_off = (unsigned)t * 16u;
-  auto fetch = [&](int j, uint4* dst) {
+  auto fetch_k = [&](int j, uint4* dst) {
     // uniform base (scalar registers) + 32-bit per-lane offset: no vector address arithmetic
     const char* ks = (const char*)A.k8 + rec0 + (size_t)j * KV_FRAG_BYTES;
-    const char* vs = (const char*)A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES;
 #pragma unroll
-    for (int u = 0; u < CH / 2; ++u) {
+    for (int u = 0; u < CH / 2; ++u)
       __builtin_amdgcn_global_load_lds((const void*)(ks + u * NT * 16 + lane_off),
                                        (lds_ptr_t)(dst + u * NT + w_s * 64), 16, 0, 0);
+  };
+  auto fetch_v = [&](int j, uint4* dst) {
+    const char* vs = (const char*)A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES;
+#pragma unroll
+    for (int u = 0; u < CH / 2; ++u)
       __builtin_amdgcn_global_load_lds((const void*)(vs + u * NT * 16 + lane_off),
-                                       (lds_ptr_t)(dst + KV_FRAG_BYTES / 16 + u * NT + w_s * 64), 16, 0, 0);
-    }
+                                       (lds_ptr_t)(dst + u * NT + w_s * 64), 16, 0, 0);
   };
   const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
   const bool ragged = kvalid_last < BK;
 
-  // Software pipeline over the critical list, three blocks deep: while block b is consumed
-  // from stage b%4, blocks b+1..b+3 are in flight or already resident in the other stages, so
-  // the L2 / HBM latency of a block is covered by the arithmetic of the blocks before it.  One
-  // barrier per block: it publishes block b+1 (every wavefront has waited for its own pieces)
-  // and retires stage b%4, which the next step's copy overwrites.  A ragged last key block can
-  // only be the last entry of the (ascending) list; it is peeled off the loop so that masking
-  // its missing keys costs the other blocks nothing.
+  // Software pipeline over the critical list.  In step b a wavefront
+  //   - starts the copies of K(b+3) and V(b+2) into the ring slots retired in step b-1,
+  //   - issues the score MFMAs of block b (K ring slot b%4) and reduces them to the new
+  //     reference level r,
+  //   - then, in ONE scheduling region, issues the P.V MFMAs of block b-1 (V ring slot
+  //     (b-1)%4, P codes kept from step b-1) interleaved with the exp / FP8-pack arithmetic
+  //     that turns the scores of block b into P codes: a wavefront that issues MFMAs back to
+  //     back stalls once the matrix pipe's queue is full, so the vector-ALU work has to sit
+  //     between them in program order to run while they execute,
+  //   - waits for its own pieces of K(b+1) / V(b) and meets the other wavefronts at one barrier,
+  //     which publishes those and retires K slot b%4 and V slot (b-1)%4.
+  // The L2 / HBM latency of a block is thus covered by the arithmetic of three steps.  A ragged
+  // last key block can only be the last entry of the (ascending) list; it is peeled off the
+  // loop so that masking its missing keys costs the other blocks nothing.
   const bool has_tail = ragged && n_c > 0 && crow[n_c - 1] == A.Tk - 1;
   constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4F70 : (0x0F70 | (2 * CH));  // s_waitcnt vmcnt(2*CH)
+  v16i s0, s1;
+  v8i pb_prev = {}, pb_new;   // P codes of block b-1 / b; all-zero codes contribute nothing
+  float r_prev = 0.f;
 
-#define SLA_STEP(B, CUR, FILL)                                                                        \
+#define SLA_STEP(B, KCUR, VPREV, KFILL, VFILL)                                                        \
   {                                                                                                   \
     const int b_ = (B);                                                                               \
-    if (b_ + 3 < nb) fetch(__builtin_amdgcn_readfirstlane(jv3), FILL);                                \
-    jv3 = sidx[min(b_ + 4, nb - 1)];                                                                  \
+    if (b_ + 3 < nb) fetch_k(__builtin_amdgcn_readfirstlane(jk3), KFILL);                             \
+    if (b_ + 2 < nb) fetch_v(__builtin_amdgcn_readfirstlane(jv2), VFILL);                             \
+    jv2 = jk3;                                                                                        \
+    jk3 = sidx[min(b_ + 4, nb - 1)];                                                                  \
     const float c2_ = cq * dkv;                                                                       \
     dkv = sdk[min(b_ + 1, nb - 1)];                                                                   \
-    attend_block<false>(CUR, lane, hf, q8, bias16, ones, c2_, 0, r, R, acc, accl);                    \
-    asm volatile("" : "+v"(jv3), "+v"(dkv));                                                          \
+    qk_scores(KCUR, lane, q8, bias16, s0, s1);                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    const float offs_ = softmax_reference<false>(s0, s1, hf, c2_, 0, r, R, acc, accl);                \
+    const int sc_ = level_scale(r_prev, R);                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    pv_accumulate(VPREV, lane, pb_prev, sc_, ones, acc, accl);                                        \
+    softmax_codes<false>(s0, s1, hf, c2_, offs_, 0, pb_new);                                          \
+    /* 8 LDS reads, then 5 x (1 MFMA, 17 vector-ALU instructions) */                                  \
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
+    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
+    /* anchor: P codes and accumulators are final here (keeps both computations inside this step) */  \
+    asm volatile("" : "+v"(jk3), "+v"(jv2), "+v"(dkv), "+v"(pb_new), "+v"(acc[0]), "+v"(acc[1]),      \
+                 "+v"(acc[2]), "+v"(acc[3]), "+v"(accl));                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                                \
+    pb_prev = pb_new;                                                                                 \
+    r_prev = r;                                                                                       \
     if (b_ + 3 < nb) __builtin_amdgcn_s_waitcnt(WAIT_KEEP2); else __builtin_amdgcn_s_waitcnt(0x0F70); \
     stage_barrier();                                                                                  \
   }
@@ -293,29 +353,49 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       sidx[e] = j;
       sdk[e] = dkrow[j];
     }
+    // step 0 has no previous block: it multiplies all-zero P codes with this all-zero V slot
+    for (int e = t; e < KV_FRAG_BYTES / 16; e += NT) vst3[e] = make_uint4(0, 0, 0, 0);
     __syncthreads();
-    fetch(__builtin_amdgcn_readfirstlane(sidx[0]), stage0);
-    if (nb > 1) fetch(__builtin_amdgcn_readfirstlane(sidx[1]), stage1);
-    if (nb > 2) fetch(__builtin_amdgcn_readfirstlane(sidx[2]), stage2);
-    int jv3 = sidx[min(3, nb - 1)];   // index of block b+3, read one step ahead of its use
+    fetch_k(__builtin_amdgcn_readfirstlane(sidx[0]), kst0);
+    fetch_v(__builtin_amdgcn_readfirstlane(sidx[0]), vst0);
+    if (nb > 1) fetch_k(__builtin_amdgcn_readfirstlane(sidx[1]), kst1);
+    if (nb > 1) fetch_v(__builtin_amdgcn_readfirstlane(sidx[1]), vst1);
+    if (nb > 2) fetch_k(__builtin_amdgcn_readfirstlane(sidx[2]), kst2);
+    int jk3 = sidx[min(3, nb - 1)];   // index of block b+3 (for K), read one step ahead of its use
+    int jv2 = sidx[min(2, nb - 1)];   // index of block b+2 (for V)
     float dkv = sdk[0];               // K scale of block b, likewise
     if (nb > 2) __builtin_amdgcn_s_waitcnt(WAIT_KEEP2); else __builtin_amdgcn_s_waitcnt(0x0F70);
     stage_barrier();
     const int nb_main = (has_tail && c0 + nb == n_c) ? nb - 1 : nb;
     int b = 0;
     for (; b + 4 <= nb_main; b += 4) {
-      SLA_STEP(b, stage0, stage3)
-      SLA_STEP(b + 1, stage1, stage0)
-      SLA_STEP(b + 2, stage2, stage1)
-      SLA_STEP(b + 3, stage3, stage2)
+      SLA_STEP(b, kst0, vst3, kst3, vst2)
+      SLA_STEP(b + 1, kst1, vst0, kst0, vst3)
+      SLA_STEP(b + 2, kst2, vst1, kst1, vst0)
+      SLA_STEP(b + 3, kst3, vst2, kst2, vst1)
     }
-    if (b < nb_main) SLA_STEP(b, stage0, stage3)
-    if (b + 1 < nb_main) SLA_STEP(b + 1, stage1, stage0)
-    if (b + 2 < nb_main) SLA_STEP(b + 2, stage2, stage1)
-    if (nb_main < nb) {  // the ragged last key block (everything has landed: no copy is in flight)
-      const int st = nb_main & 3;
-      const uint4* cur = st == 0 ? stage0 : st == 1 ? stage1 : st == 2 ? stage2 : stage3;
-      attend_block<true>(cur, lane, hf, q8, bias16, ones, cq * sdk[nb_main], kvalid_last, r, R, acc, accl);
+    if (b < nb_main) SLA_STEP(b, kst0, vst3, kst3, vst2)
+    if (b + 1 < nb_main) SLA_STEP(b + 1, kst1, vst0, kst0, vst3)
+    if (b + 2 < nb_main) SLA_STEP(b + 2, kst2, vst1, kst1, vst0)
+    // drain: everything of this chunk has landed and been published (the last step waited for
+    // all copies), so plain reads of any slot are safe from here on
+    if (nb_main < nb) {  // the ragged last key block
+      const int st = nb_main & 3, sp = (nb_main + 3) & 3;
+      const uint4* kc = st == 0 ? kst0 : st == 1 ? kst1 : st == 2 ? kst2 : kst3;
+      const uint4* vp = sp == 0 ? vst0 : sp == 1 ? vst1 : sp == 2 ? vst2 : vst3;
+      qk_scores(kc, lane, q8, bias16, s0, s1);
+      const float c2t = cq * sdk[nb_main];
+      const float offs_t = softmax_reference<true>(s0, s1, hf, c2t, kvalid_last, r, R, acc, accl);
+      pv_accumulate(vp, lane, pb_prev, level_scale(r_prev, R), ones, acc, accl);
+      softmax_codes<true>(s0, s1, hf, c2t, offs_t, kvalid_last, pb_new);
+      pb_prev = pb_new;
+      r_prev = r;
+    }
+    {  // P.V of the chunk's last block
+      const int sl = (nb - 1) & 3;
+      const uint4* vc = sl == 0 ? vst0 : sl == 1 ? vst1 : sl == 2 ? vst2 : vst3;
+      pv_accumulate(vc, lane, pb_prev, level_scale(r_prev, R), ones, acc, accl);
+      pb_prev = v8i{};
     }
   }
 #undef SLA_STEP
@@ -401,27 +481,24 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     }
   }
 
-  // ---- transpose through LDS (per wavefront: 32 rows x 64 channels fp32 at a time) and store
-  unsigned char* my = (unsigned char*)(w == 0 ? stage0 : w == 1 ? stage1 : w == 2 ? stage2 : stage3);
+  // ---- transpose through LDS (per wavefront: 32 rows x 32 channels fp32 at a time) and store
+  unsigned char* my = (unsigned char*)(w == 0 ? kst0 : w == 1 ? kst1 : w == 2 ? kst2 : kst3);
 #pragma unroll
-  for (int hh = 0; hh < 2; ++hh) {
+  for (int ct = 0; ct < 4; ++ct) {
     __syncthreads();
 #pragma unroll
-    for (int c2t = 0; c2t < 2; ++c2t)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const v16f& a = acc[2 * hh + c2t];
-        *(float4*)(my + l32 * EPI_STRIDE + (32 * c2t + 8 * g + 4 * hf) * 4) =
-            make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
-      }
+    for (int g = 0; g < 4; ++g) {
+      const v16f& a = acc[ct];
+      *(float4*)(my + l32 * EPI_STRIDE + (8 * g + 4 * hf) * 4) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
+    }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int r = it * 4 + (lane >> 4), c4 = lane & 15;
-      const int grow = i * BQ + 32 * w + r;
-      const float4 val = *(const float4*)(my + r * EPI_STRIDE + c4 * 16);
+    for (int it = 0; it < 4; ++it) {
+      const int rr = it * 8 + (lane >> 3), c4 = lane & 7;
+      const int grow = i * BQ + 32 * w + rr;
+      const float4 val = *(const float4*)(my + rr * EPI_STRIDE + c4 * 16);
       if (grow < A.N) {
-        const size_t o = ((size_t)bh * A.N + grow) * D + 64 * hh + 4 * c4;
+        const size_t o = ((size_t)bh * A.N + grow) * D + 32 * ct + 4 * c4;
         if (A.out_f32) {
           *(float4*)((float*)A.out + o) = val;
         } else {
