@@ -129,16 +129,14 @@ int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, in
   run_stats(q, k, v, p, ws, W, s);
   mark(s, rec, 1);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
-  launch_select(p, at<float>(ws, W.scores), at<int8_t>(ws, W.mask), at<int32_t>(ws, W.crit), nullptr, s);
+  launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
+                lin ? at<bf16_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
   const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
   launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, true, lin,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   mark(s, rec, 3);
-  if (lin) {
-    launch_marginal_frag(p, at<int8_t>(ws, W.mask), at<bf16_t>(ws, W.m0), s);
-    launch_lin_accumulate(p, at<bf16_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
-  }
+  if (lin) launch_lin_accumulate(p, at<bf16_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   mark(s, rec, 4);
   launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
                     at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
@@ -199,7 +197,7 @@ int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d
                     at<uint32_t>(ws, W.amax_v), s);
   float* sc = pooled_scores ? pooled_scores : at<float>(ws, W.scores);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), sc, s);
-  launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, s);
+  launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, nullptr, s);
   return launch_status();
 }
 

@@ -138,7 +138,7 @@ void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* 
                            float* dv, bf16_t* eye, hipStream_t stream);
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores, hipStream_t stream);
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
-                   hipStream_t stream);
+                   bf16_t* mA, hipStream_t stream);
 void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
                     const bf16_t* proj_w, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream);

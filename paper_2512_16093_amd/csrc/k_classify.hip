@@ -185,84 +185,167 @@ __global__ void __launch_bounds__(256) scores_kernel(const float* __restrict__ q
     }
 }
 
-// select: one workgroup per (b,h,i) row.  Keys (order-preserving score bits, ~j) are
-// sorted descending by a bitonic network in LDS, so equal scores rank by ascending j
-// and the result is exact and deterministic.  Then the class of each j is scattered
-// back and the ascending index lists come from a prefix count.
+// select: one WAVEFRONT per (b,h,i) row; the row's scores live in registers (KPL per lane,
+// block j = lane + 64 m in register m) as order-preserving 32-bit keys.  The n_c-th and the
+// (n_c+n_m)-th largest keys are found exactly by a 4-pass, 8-bit-digit radix select with a
+// 256-bin histogram in LDS (one per wavefront); blocks whose key equals a threshold key are
+// ranked by ascending j with ballots, so equal scores rank by ascending block index and the
+// result is exact and deterministic.  Outputs: the int8 mask row, the ascending critical
+// list, and the marginal indicator as bf16 0/1 in the MFMA fragment order the accumulation
+// kernel reads (16-byte chunk per 8 consecutive blocks; see lin_accumulate).
 __device__ __forceinline__ uint32_t order_bits(float f) {
   const uint32_t u = __float_as_uint(f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ scores, int Tk, int P,
+// Histogram search: given the 256 counters of the current digit (lane l reads bins 4l..4l+3),
+// find the bin that holds descending rank `remaining` among the candidates and the number of
+// candidates in higher bins.
+__device__ __forceinline__ void find_bin(const unsigned* hist, int lane, int remaining, int& digit, int& above) {
+  const unsigned c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+  const int own = (int)(c0 + c1 + c2 + c3);
+  int S = own;  // candidates in bins >= 4 lane (suffix sum over lanes)
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int up = __shfl_down(S, o);
+    if (lane + o < 64) S += up;
+  }
+  const int above_lane = S - own;
+  const bool mine = above_lane < remaining && remaining <= S;
+  int d = 0, ab = 0;
+  if (mine) {
+    int a = above_lane;
+    if (remaining <= a + (int)c3) { d = 4 * lane + 3; ab = a; }
+    else { a += c3;
+      if (remaining <= a + (int)c2) { d = 4 * lane + 2; ab = a; }
+      else { a += c2;
+        if (remaining <= a + (int)c1) { d = 4 * lane + 1; ab = a; }
+        else { a += c1; d = 4 * lane; ab = a; } } }
+  }
+  const int src = __ffsll((long long)__ballot(mine)) - 1;
+  digit = __shfl(d, src);
+  above = __shfl(ab, src);
+}
+
+// Key of descending rank `rank` (1-based) and how many of the keys equal to it belong to the
+// top `rank` (>= 1), given the first digit already resolved (prefix = top byte, remaining).
+// hist: 256 counters owned by this wavefront.
+template <int KPL>
+__device__ __forceinline__ void radix_rest(const uint32_t (&key)[KPL], uint32_t prefix, int remaining,
+                                           unsigned* hist, int lane, uint32_t& kth, int& take) {
+#pragma unroll
+  for (int pass = 1; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) hist[4 * lane + c] = 0;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) {
+      const bool cand = (key[m] >> (shift + 8)) == prefix;
+      if (__any(cand)) {  // few keys survive the first digit: skip the LDS atomic when no lane has one
+        if (cand) atomicAdd(&hist[(key[m] >> shift) & 0xffu], 1u);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+    int digit, above;
+    find_bin(hist, lane, remaining, digit, above);
+    prefix = (prefix << 8) | (uint32_t)digit;
+    remaining -= above;
+    __builtin_amdgcn_wave_barrier();
+  }
+  kth = prefix;
+  take = remaining;
+}
+
+template <int KPL>
+__global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ scores, int rows, int Tq, int Tk,
                                                      int n_c, int n_m, int8_t* __restrict__ mask,
-                                                     int32_t* __restrict__ crit,
-                                                     int32_t* __restrict__ marg) {
-  extern __shared__ unsigned long long smem[];
-  unsigned long long* keys = smem;                 // [P]
-  int8_t* cls = (int8_t*)(keys + P);               // [P]
-  __shared__ int wave_c[4], wave_m[4];
-  const size_t row = blockIdx.x;
-  const int t = threadIdx.x;
+                                                     int32_t* __restrict__ crit, int32_t* __restrict__ marg,
+                                                     bf16_t* __restrict__ mA) {
+  __shared__ unsigned hist_all[4][256];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const size_t row = (size_t)blockIdx.x * 4 + w;
+  if (row >= (size_t)rows) return;  // whole wavefront; no workgroup barrier is used below
+  unsigned* hist = hist_all[w];
   const float* srow = scores + row * Tk;
-  for (int j = t; j < P; j += 256) {
-    keys[j] = (j < Tk) ? (((unsigned long long)order_bits(srow[j]) << 32) | (uint32_t)(~(uint32_t)j)) : 0ull;
-    cls[j] = -1;
+  uint32_t key[KPL];
+#pragma unroll
+  for (int m = 0; m < KPL; ++m) {
+    const int j = lane + 64 * m;
+    key[m] = j < Tk ? order_bits(srow[j]) : 0u;
   }
-  __syncthreads();
-  for (int k = 2; k <= P; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int idx = t; idx < (P >> 1); idx += 256) {
-        const int a = 2 * j * (idx / j) + (idx % j), b = a + j;
-        const bool desc = (a & k) == 0;
-        const unsigned long long x = keys[a], y = keys[b];
-        if ((x < y) == desc) {
-          keys[a] = y;
-          keys[b] = x;
-        }
+  // Spread the keys over the whole 32-bit range (subtract the row minimum, shift out the common
+  // leading zeros): order and ties are unchanged, but the first radix digits now separate the
+  // scores instead of all landing in the one histogram bin of their common exponent.
+  {
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m)
+      if (lane + 64 * m < Tk) {
+        kmin = min(kmin, key[m]);
+        kmax = max(kmax, key[m]);
       }
-      __syncthreads();
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+      kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
     }
+    const uint32_t span = kmax - kmin;
+    const int lz = span ? __builtin_clz(span) : 0;
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) key[m] = (lane + 64 * m < Tk) ? ((key[m] - kmin) << lz) : 0u;  // padding ties with the minimum: never above a threshold
   }
-  for (int p = t; p < n_c + n_m; p += 256) {
-    const uint32_t j = ~(uint32_t)(keys[p] & 0xffffffffull);
-    cls[j] = (p < n_c) ? 1 : 0;
+  uint32_t k1, k2 = 0;
+  int t1, t2 = 0;
+  {
+    // first digit: one histogram of all keys serves both thresholds
+#pragma unroll
+    for (int c = 0; c < 4; ++c) hist[4 * lane + c] = 0;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int m = 0; m < KPL; ++m) atomicAdd(&hist[key[m] >> 24], 1u);
+    __builtin_amdgcn_wave_barrier();
+    int d1, a1, d2 = 0, a2 = 0;
+    find_bin(hist, lane, n_c, d1, a1);
+    if (n_m > 0) find_bin(hist, lane, n_c + n_m, d2, a2);
+    __builtin_amdgcn_wave_barrier();
+    radix_rest<KPL>(key, (uint32_t)d1, n_c - a1, hist, lane, k1, t1);
+    if (n_m > 0) radix_rest<KPL>(key, (uint32_t)d2, n_c + n_m - a2, hist, lane, k2, t2);
   }
-  __syncthreads();
-  if (mask) {
-    for (int j = t; j < Tk; j += 256) mask[row * Tk + j] = cls[j];
-  }
-  if (crit || marg) {
-    const int ch = (Tk + 255) / 256, lo = min(Tk, t * ch), hi = min(Tk, lo + ch);
-    int cc = 0, cm = 0;
-    for (int j = lo; j < hi; ++j) {
-      cc += cls[j] == 1;
-      cm += cls[j] == 0;
-    }
-    int ic = cc, im = cm;  // inclusive scans within the wave
-    const int lane = t & 63, w = t >> 6;
-    for (int o = 1; o < 64; o <<= 1) {
-      const int uc = __shfl_up(ic, o), um = __shfl_up(im, o);
-      if (lane >= o) {
-        ic += uc;
-        im += um;
+
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  const int bh = (int)(row / Tq), i = (int)(row % Tq);
+  const int RT = (Tq + 255) / 256, KT = (Tk + 31) / 32;
+  int eq1 = 0, eq2 = 0, nc = 0, nm = 0;  // running counts in ascending-j order
+#pragma unroll
+  for (int m = 0; m < KPL; ++m) {
+    const int j = lane + 64 * m;
+    if (64 * m >= Tk) break;
+    const bool valid = j < Tk;
+    const bool e1 = valid && key[m] == k1, e2 = valid && n_m > 0 && key[m] == k2;
+    const unsigned long long b1 = __ballot(e1), b2 = __ballot(e2);
+    const int r1 = eq1 + __popcll(b1 & lt), r2 = eq2 + __popcll(b2 & lt);
+    eq1 += __popcll(b1);
+    eq2 += __popcll(b2);
+    const bool is_c = valid && (key[m] > k1 || (e1 && r1 < t1));
+    const bool is_m = valid && !is_c && n_m > 0 && (key[m] > k2 || (e2 && r2 < t2));
+    if (mask && valid) mask[row * Tk + j] = is_c ? 1 : (is_m ? 0 : -1);
+    const unsigned long long bc = __ballot(is_c), bm = __ballot(is_m);
+    if (crit && is_c) crit[row * n_c + nc + __popcll(bc & lt)] = j;
+    if (marg && is_m) marg[row * n_m + nm + __popcll(bm & lt)] = j;
+    nc += __popcll(bc);
+    nm += __popcll(bm);
+    if (mA && lane < 8) {  // lane c packs blocks 64m + 8c .. +7 into one 16-byte chunk
+      const int j0 = 64 * m + 8 * lane, kt = j0 >> 5, pch = (j0 >> 3) & 3;
+      if (kt < KT) {
+        const unsigned bits = (unsigned)(bm >> (8 * lane)) & 0xffu;
+        uint32_t wv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          wv[e] = ((bits >> (2 * e)) & 1u ? 0x3f80u : 0u) | ((bits >> (2 * e + 1)) & 1u ? 0x3f800000u : 0u);
+        uint4* dst = (uint4*)(mA + ((size_t)(bh * RT + (i >> 8)) * KT + kt) * 8192) + (pch * 256 + (i & 255));
+        *dst = make_uint4(wv[0], wv[1], wv[2], wv[3]);
       }
-    }
-    if (lane == 63) {
-      wave_c[w] = ic;
-      wave_m[w] = im;
-    }
-    __syncthreads();
-    int oc = ic - cc, om = im - cm;
-    for (int u = 0; u < w; ++u) {
-      oc += wave_c[u];
-      om += wave_m[u];
-    }
-    for (int j = lo; j < hi; ++j) {
-      if (cls[j] == 1 && crit) crit[row * n_c + oc] = j;
-      if (cls[j] == 1) ++oc;
-      if (cls[j] == 0 && marg) marg[row * n_m + om] = j;
-      if (cls[j] == 0) ++om;
     }
   }
 }
@@ -290,11 +373,16 @@ void launch_scores(const Problem& p, const float* qbar, const float* kbar, float
 }
 
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
-                   hipStream_t stream) {
-  int P = 2;
-  while (P < p.Tk) P <<= 1;
-  const size_t lds = (size_t)P * 9;
-  select_kernel<<<p.BH * p.Tq, 256, lds, stream>>>(scores, p.Tk, P, p.n_c, p.n_m, mask, crit, marg);
+                   bf16_t* mA, hipStream_t stream) {
+  const int rows = p.BH * p.Tq;
+  const unsigned grid = (unsigned)((rows + 3) / 4);
+  const int need = (p.Tk + 63) / 64;
+#define SLA_SELECT(K) select_kernel<K><<<grid, 256, 0, stream>>>(scores, rows, p.Tq, p.Tk, p.n_c, p.n_m, mask, crit, marg, mA)
+  if (need <= 2) SLA_SELECT(2);
+  else if (need <= 8) SLA_SELECT(8);
+  else if (need <= 32) SLA_SELECT(32);
+  else SLA_SELECT(128);
+#undef SLA_SELECT
 }
 
 }  // namespace sla
