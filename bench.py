@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="seeded config id (4 = Wan-14B-720P shape, the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget for the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) a few times, so that "
+                         "FETCH_SIZE / WRITE_SIZE counter runs of this command can be scaled by a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -134,6 +137,13 @@ def main():
         sla.sla_attention_fwd(qd, kd, vd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
                               proj_w=Wd, workspace=ws, out=out)
 
+    if args.copy_calibration:
+        a = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -215,12 +215,15 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   __shared__ float sdk[IDX_CAP];
   static_assert(32 * EPI_STRIDE <= KV_FRAG_BYTES, "output staging must fit one stage buffer");
 
-  // Consecutive query blocks of a head run on the same XCD (workgroup ids are dealt
-  // round-robin over the 8 XCDs), so neighbours share K/V fragments in that XCD's L2.
+  // Workgroup ids are dealt round-robin over the 8 XCDs.  All XCDs work on the SAME head at
+  // the same time, each on its own contiguous eighth of that head's query blocks: the set of
+  // K/V records in use chip-wide is then one head's (a few tens of MB, resident in the
+  // Infinity Cache instead of being re-fetched from HBM), and the workgroups that share an
+  // XCD's L2 are neighbouring query blocks, whose critical sets overlap.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int rowid = xcd * A.per_xcd + slot;
-  if (rowid >= A.total) return;
-  const int bh = rowid / A.Tq, i = rowid % A.Tq;
+  const int bh = slot / A.per_xcd, i = xcd * A.per_xcd + slot % A.per_xcd;  // per_xcd = ceil(Tq / 8)
+  if (i >= A.Tq) return;
+  const int rowid = bh * A.Tq + i;
 
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
   const int qrow = i * BQ + 32 * w + l32;
@@ -519,12 +522,12 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
   dm.Tk = p.Tk;
   dm.n_c = n_c;
   dm.total = p.BH * p.Tq;
-  dm.per_xcd = (dm.total + 7) / 8;
+  dm.per_xcd = (p.Tq + 7) / 8;  // query blocks of one head per XCD
   dm.phi = phi_kind;
   dm.has_lin = has_linear ? 1 : 0;
   dm.out_f32 = out_f32 ? 1 : 0;
   const bf16_t* bias = has_linear ? proj_b : nullptr;
-  const unsigned grid = (unsigned)(8 * dm.per_xcd);
+  const unsigned grid = (unsigned)(8 * dm.per_xcd * p.BH);
   if (p.block_q == 128) {
     sparse_fwd_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse, dm);
   } else {
