@@ -27,6 +27,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_8BIT_TOPS = 5000.0   # MI355X dense INT8 (POP/s) and FP8 (PFLOP/s) MFMA peak, both 5.0e15
+# Bytes moved past L2 per launch of the sparse kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
+# from a 1 GiB copy in the same counter runs), by config id; source: profiles/sla_fwd_wan14b-720p.md.
+SPARSE_TRAFFIC_BYTES = {4: 18.35e9}
 
 
 def parse():
@@ -179,7 +182,8 @@ def main():
         "stage_ms": dict(zip(sla.STAGE_NAMES, [round(x, 4) for x in stage_ms])),
         "roofline": {"kernel": "sparse_fwd_kernel", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK_MFMA_8BIT_TOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_8BIT_TOPS,
-                     "traffic": None, "launch_ms": stage_ms[4], "ops_per_launch": ops},
+                     "traffic": SPARSE_TRAFFIC_BYTES.get(cfg.cfg_id), "traffic_unit": "bytes per launch",
+                     "launch_ms": stage_ms[4], "ops_per_launch": ops},
         "context": "paper: 100-200x end-to-end, 184 s -> 1.9 s on one RTX 5090 (whole pipeline; no kernel-level number)",
     }
     if not args.no_cpu_baseline:
