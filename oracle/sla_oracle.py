@@ -154,7 +154,7 @@ def sparse_branch_exact(Q, K, V, mask, block_q, block_k, q_blocks=None):
 
 def sparse_branch_quant(Q, K, V, mask, block_q, block_k, mode=QUANT_QK_INT8_PV_FP8,
                         q_blocks=None, smooth_k=True, rowsum_quantized=True,
-                        reference="ceil_log2", return_lse=False):
+                        reference="ceil_log2", return_lse=False, ref_tile=None):
     """Low-bit sparse branch: one pass over the critical blocks in ascending
     block order with a running reference level per query row.
 
@@ -170,8 +170,11 @@ def sparse_branch_quant(Q, K, V, mask, block_q, block_k, mode=QUANT_QK_INT8_PV_F
     reference = "ceil_log2": ref(x) = ceil(x), an integer, so every rescale
     factor a is a power of two and the largest P~ of a row lies in (1/2, 1];
     reference = "running": ref(x) = x, the plain running maximum (largest P~ = 1).
-    rowsum_quantized = False sums the unrounded P~ instead of P8/448.  Both
-    alternatives give the same result before rounding."""
+    rowsum_quantized = False sums the unrounded P~ instead of P8/448.
+    ref_tile = T (a divisor of block_k) refreshes the running reference after
+    every T keys of a critical block instead of once per block (the default,
+    T = block_k): the pass then treats each run of T keys as a block of its own.
+    All these alternatives give the same result before rounding."""
     if mode == QUANT_NONE:
         raise ValueError("use sparse_branch_exact for mode 'none'")
     N, d = Q.shape
@@ -188,16 +191,20 @@ def sparse_branch_quant(Q, K, V, mask, block_q, block_k, mode=QUANT_QK_INT8_PV_F
         l = np.zeros(rows)
         acc = np.zeros((rows, V.shape[1]))
         for j in np.flatnonzero(mask[i] == 1):
-            S = (Q8[qs[i]] @ K8[ks[j]].T) * (dq[i] * dk[j] / math.sqrt(d))
-            t = S * log2e
-            tmax = t.max(axis=1)
-            r_new = np.maximum(r, np.ceil(tmax) if reference == "ceil_log2" else tmax)
-            alpha = np.where(np.isneginf(r), 0.0, np.exp2(r - r_new))
-            Pt = np.exp2(t - r_new[:, None])
-            P8 = formats.e4m3_round(P_SCALE * Pt) if mode == QUANT_QK_INT8_PV_FP8 else P_SCALE * Pt
-            l = alpha * l + (P8.sum(axis=1) / P_SCALE if rowsum_quantized else Pt.sum(axis=1))
-            acc = alpha[:, None] * acc + P8 @ V8[ks[j]]
-            r = r_new
+            S_blk = (Q8[qs[i]] @ K8[ks[j]].T) * (dq[i] * dk[j] / math.sqrt(d))
+            V_blk = V8[ks[j]]
+            keys = S_blk.shape[1]
+            tile = keys if ref_tile is None else ref_tile
+            for c0 in range(0, keys, tile):
+                t = S_blk[:, c0:c0 + tile] * log2e
+                tmax = t.max(axis=1)
+                r_new = np.maximum(r, np.ceil(tmax) if reference == "ceil_log2" else tmax)
+                alpha = np.where(np.isneginf(r), 0.0, np.exp2(r - r_new))
+                Pt = np.exp2(t - r_new[:, None])
+                P8 = formats.e4m3_round(P_SCALE * Pt) if mode == QUANT_QK_INT8_PV_FP8 else P_SCALE * Pt
+                l = alpha * l + (P8.sum(axis=1) / P_SCALE if rowsum_quantized else Pt.sum(axis=1))
+                acc = alpha[:, None] * acc + P8 @ V_blk[c0:c0 + tile]
+                r = r_new
         out[qs[i]] = acc * dv[None, :] / (P_SCALE * l[:, None])
         lse[qs[i]] = (r + np.log2(l)) * math.log(2.0)
     return (out, lse) if return_lse else out
@@ -254,13 +261,14 @@ def linear_branch(Q, K, V, mask, block_q, block_k, phi="softmax", q_blocks=None)
 # --------------------------------------------------------------------------
 def sla_forward_head(Q, K, V, block_q, block_k, topk_ratio, marginal_ratio,
                      proj_w=None, proj_b=None, phi="softmax", quant=QUANT_QK_INT8_PV_FP8,
-                     linear=True, q_blocks=None, mask=None):
+                     linear=True, q_blocks=None, mask=None, ref_tile=None):
     """SLA forward of one (batch, head) slice.
 
     O = O^s + O^l W^T (+ b); W = identity when proj_w is None; the linear term
     (and the bias) is absent when there is no marginal block (n_m = 0) or
     linear=False.  Returns a dict with out [N, d] (NaN rows for query blocks
-    outside q_blocks), mask, scores, o_sparse, o_linear."""
+    outside q_blocks), mask, scores, o_sparse, o_linear.  ref_tile is handed to
+    sparse_branch_quant (how often the running reference is refreshed)."""
     N, d = Q.shape
     Tq, Tk, n_c, n_m = block_counts(N, block_q, block_k, topk_ratio, marginal_ratio)
     scores = pooled_scores(Q, K, block_q, block_k)
@@ -269,7 +277,7 @@ def sla_forward_head(Q, K, V, block_q, block_k, topk_ratio, marginal_ratio,
     if quant == QUANT_NONE:
         o_s = sparse_branch_exact(Q, K, V, mask, block_q, block_k, q_blocks)
     else:
-        o_s = sparse_branch_quant(Q, K, V, mask, block_q, block_k, quant, q_blocks)
+        o_s = sparse_branch_quant(Q, K, V, mask, block_q, block_k, quant, q_blocks, ref_tile=ref_tile)
     out = o_s.copy()
     o_l = None
     if linear and n_m > 0:

@@ -6,13 +6,20 @@
 // computed transposed so that a lane owns ONE query (column) throughout:
 //   S^T[key][query]  = K8 . Q8^T      v_mfma_i32_32x32x32_i8, A = K fragment (LDS), B = Q8 (registers)
 //   P8 = e4m3(448 2^(t - r))          in registers; r = integer running reference of the query, shared
-//                                     by its two lanes (lane, lane^32): one permlane swap per block
+//                                     by its two lanes (lane, lane^32): one permlane swap per 32 keys
 //   O^T[ch][query] += V8^T . P8^T     v_mfma_f32_32x32x64_f8f6f4, A = V fragment (LDS), B = P8 as it
 //                                     sits in the accumulators' order (V was stored in that key order)
 // so the rescale factor, the row sum and the final normalisation are per-lane scalars and P
-// never touches LDS.  K/V fragments of the next three critical blocks are copied global -> LDS
-// asynchronously (no registers) into the other staging buffers while the current one is
+// never touches LDS.  K/V fragments of the next critical blocks are copied global -> LDS
+// asynchronously (no registers) into a ring of staging buffers while the current ones are
 // consumed (one barrier per block).
+//
+// The kernel is bound by the vector ALU (exp2, FP8 packing, the row maximum), not by the matrix
+// pipe, and a wavefront issues at most one vector instruction every ~5 cycles; so the main loop
+// is arranged for every MFMA to have independent vector work of the same wavefront behind it:
+// the two 32-key halves of a block are pipelined against each other (while the matrix pipe
+// computes the scores of one half, the vector ALU turns the other half's scores into P codes),
+// and the P.V product runs one block behind.
 //
 // Epilogue: O_s = acc * delta_V / l;  optional linear term phi(Q) H_i / (phi(Q).Z_i) as bf16 MFMA
 // (H_i already contains the output projection), bias, then a transposing pass through LDS so
@@ -42,11 +49,15 @@ struct SparseArgs {
   int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32;
 };
 
-constexpr int STAGE_BYTES = 2 * KV_FRAG_BYTES;  // K + V record of one key block
 constexpr int EPI_STRIDE = 32 * 4 + 16;         // bytes per staged output row (32 fp32 + pad)
-constexpr int IDX_CAP = 1024;                   // critical-list entries held in LDS at a time
-constexpr int BIAS_I = 0x4B400000;              // bit pattern of 1.5 * 2^23
-constexpr float BIAS_F = 12582912.0f;           // 1.5 * 2^23
+// Score bias: the integer accumulators of the score MFMAs start from the bit pattern of the
+// float 1/(2 pi), which the instruction takes as an inline constant (no registers).  A finished
+// accumulator, reinterpreted as fp32, is then the float BIAS_F + s * 2^-26 exactly, for every
+// score |s| <= 127 * 127 * 128 < 0x22F983 (the pattern stays inside the binade [1/8, 1/4)):
+// no int -> float conversion is needed, and patterns order like the scores.
+constexpr int BIAS_I = 0x3E22F983;
+constexpr int BIAS_FLOOR = 0x3E000000;          // pattern below every reachable score (masked keys)
+constexpr float SCORE_STEP = 1.0f / 67108864.f;  // 2^-26: what one score unit adds to the float
 
 __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
   uint4 a = make_uint4(0, 0, 0, 0), b = a;
@@ -63,121 +74,105 @@ __device__ __forceinline__ void load_q16(const bf16_t* p, bool ok, float* x) {
 }
 
 // Row state (per lane = per query): `r` is the running reference level, an INTEGER number of
-// binary orders of magnitude (r = max over blocks of ceil(log2(e) * row max)), so that
-// P = 448 * 2^(t - r) <= 448 fits E4M3; `R` is the level the accumulators are expressed in.
-// Because r - R is an integer, a block's contribution is brought to level R by the E8M0
-// block scale of the FP8 MFMA (2^(r-R) on the P operand): the accumulators are never
-// rescaled on the vector ALU, except for a rare renormalisation when r - R exceeds 64.
-// The row sum of the rounded P comes out of the same MFMA through a tile of ones.
-//
-// The three parts of a block are separate so the main loop can run the P.V product one block
-// behind the scores: in step b a wavefront issues the score MFMAs of block b, then the P.V
-// MFMAs of block b-1, then does the softmax arithmetic of block b on the vector ALU while
-// those MFMAs execute.
+// binary orders of magnitude (r = max over the 32-key tiles seen so far of ceil(log2(e) * row
+// max)), so that P = 448 * 2^(t - r) <= 448 fits E4M3; `R` is the level the accumulators are
+// expressed in.  Because r - R is an integer, a tile's contribution is brought to level R by
+// the E8M0 block scale of the FP8 MFMA (2^(r-R) on the P operand): the accumulators are never
+// rescaled on the vector ALU, except for a rare renormalisation when r - R exceeds 64.  The
+// hardware takes the scale of a lane pair's registers 0..3 (keys 0..31 of the block) from the
+// lower lane and that of registers 4..7 (keys 32..63) from the upper lane, so the two halves of
+// a block may sit at different levels.  The row sum of the rounded P comes out of the same
+// MFMA through a tile of ones.
 
-// S^T = K8 . Q8^T for one key block (64 keys x this wavefront's 32 queries).  The integer
-// accumulators start from BIAS_I = bits of 1.5 * 2^23, so each finished score, reinterpreted
-// as fp32, IS the float 1.5 * 2^23 + s (exact for |s| < 2^22; here |s| <= 127 * 127 * 128):
-// no int -> float conversion is needed afterwards.
-__device__ __forceinline__ void qk_scores(const uint4* __restrict__ kl, int lane, const v4i (&q8)[4],
-                                          const v16i& bias16, v16i& s0, v16i& s1) {
-  uint4 kf[8];
-#pragma unroll
-  for (int u = 0; u < 8; ++u) kf[u] = kl[u * 64 + lane];
-  s0 = bias16;
-  s1 = bias16;
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    s0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[s].x, (int)kf[s].y, (int)kf[s].z, (int)kf[s].w}, q8[s], s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(v4i{(int)kf[4 + s].x, (int)kf[4 + s].y, (int)kf[4 + s].z, (int)kf[4 + s].w}, q8[s], s1, 0, 0, 0);
-  }
+__device__ __forceinline__ v4i as_v4i(const uint4& x) { return v4i{(int)x.x, (int)x.y, (int)x.z, (int)x.w}; }
+__device__ __forceinline__ v8i as_v8i(const uint4& a, const uint4& b) {
+  return v8i{(int)a.x, (int)a.y, (int)a.z, (int)a.w, (int)b.x, (int)b.y, (int)b.z, (int)b.w};
 }
 
-// O^T += V8^T . P8^T (and the row sum through the ones tile), P scaled by 2^(scale_p - 127).
-__device__ __forceinline__ void pv_accumulate(const uint4* __restrict__ vl, int lane, const v8i& pb, int scale_p,
-                                              const v8i& ones, v16f (&acc)[4], v16f& accl) {
-  uint4 vf[8];
+// Four consecutive 16-byte chunks (first, first + 1, ...) of a K or V record from LDS.
+__device__ __forceinline__ void read4(const uint4* __restrict__ rec, int lane, int first, uint4 (&f)[4]) {
 #pragma unroll
-  for (int u = 0; u < 8; ++u) vf[u] = vl[u * 64 + lane];
-#pragma unroll
-  for (int ct = 0; ct < 4; ++ct) {
-    const uint4 a0 = vf[2 * ct], a1 = vf[2 * ct + 1];
-    const v8i av = {(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
-    acc[ct] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, pb, acc[ct], 0, 0, 0, 127, 0, scale_p);
-  }
+  for (int u = 0; u < 4; ++u) f[u] = rec[(first + u) * 64 + lane];
+}
+
+// One step (32 channels) of S^T = K8 . Q8^T for one 32-key half.
+__device__ __forceinline__ v16i qk_step(const uint4& kf, const v4i& q8, const v16i& c) {
+  return __builtin_amdgcn_mfma_i32_32x32x32_i8(as_v4i(kf), q8, c, 0, 0, 0);
+}
+
+// One 32-channel tile of O^T += V8^T . P8^T, P scaled by 2^(scale_p - 127).
+__device__ __forceinline__ void pv_tile(const uint4& v0, const uint4& v1, const v8i& pb, int scale_p, v16f& acc) {
+  acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(as_v8i(v0, v1), pb, acc, 0, 0, 0, 127, 0, scale_p);
+}
+// The row sum of P through the ones tile, same scale.
+__device__ __forceinline__ void pv_rowsum(const v8i& ones, const v8i& pb, int scale_p, v16f& accl) {
   accl = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(ones, pb, accl, 0, 0, 0, 127, 0, scale_p);
 }
 
-// First half of a block's softmax: row maximum of the biased scores -> reference level r
-// (and the rare renormalisation of the accumulators).  Returns the exponent offset `offs`
-// such that P = 448 * 2^(t - r) = exp2(fma(biased score, c2, offs)).
+// Maximum of this lane's 16 biased scores of one half (keys key0 .. key0 + 31), as a pattern.
 template <bool tail>
-__device__ __forceinline__ float softmax_reference(v16i& s0, v16i& s1, int hf, float c2, int kvalid, float& r,
-                                                   float& R, v16f (&acc)[4], v16f& accl) {
+__device__ __forceinline__ int half_max(v16i& s, int key0, int hf, int kvalid) {
   if (tail) {  // keys past the end of the sequence (last key block only) never win the max
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int key = 8 * (q >> 2) + 4 * hf + (q & 3);
-      if (key >= kvalid) s0[q] = BIAS_I - 4000000;
-      if (32 + key >= kvalid) s1[q] = BIAS_I - 4000000;
-    }
+    for (int q = 0; q < 16; ++q)
+      if (key0 + 8 * (q >> 2) + 4 * hf + (q & 3) >= kvalid) s[q] = BIAS_FLOOR;
   }
-  int imax = s0[0];  // biased scores order like the scores themselves
+  int m0 = max(s[0], s[1]), m1 = max(s[2], s[3]);
 #pragma unroll
-  for (int q = 1; q < 16; ++q) imax = max(imax, s0[q]);
-#pragma unroll
-  for (int q = 0; q < 16; ++q) imax = max(imax, s1[q]);
-  imax = max(imax, partner_i32(imax));
-  // t = s * c2 = fma(bias + s, c2, -bias * c2); the guard of one score step keeps t - r <= 0
-  // whatever the rounding of the two products
-  const float nbc2 = -BIAS_F * c2;
-  r = fmaxf(r, __builtin_ceilf(__builtin_fmaf(__int_as_float(imax), c2, nbc2) + c2));
-  if (__any(r - R > 64.f)) {  // first block (R = -inf) or a jump of more than 64 binades
-    const float down = (r - R > 64.f) ? __builtin_amdgcn_exp2f(R - r) : 1.0f;
-    if (r - R > 64.f) R = r;
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[ct][q] *= down;
-#pragma unroll
-    for (int q = 0; q < 16; ++q) accl[q] *= down;
+  for (int q = 4; q < 16; q += 4) {
+    m0 = max(max(m0, s[q]), s[q + 1]);
+    m1 = max(max(m1, s[q + 2]), s[q + 3]);
   }
-  return (LOG2_448 - r) + nbc2;
+  return max(m0, m1);
 }
 
-// Second half: biased scores -> FP8 codes of P.
+// Row maximum over both lanes of the query -> new reference level r.  Returns the exponent
+// offset `offs` such that P = 448 * 2^(t - r) = exp2(fma(biased score as float, c2s, offs)),
+// where c2s = c2 * 2^26 and t = c2 * s.
+__device__ __forceinline__ float new_reference(int imax, float c2s, float& r) {
+  // after the swap one register holds the lower lane's value and the other the upper lane's, in both lanes
+  const auto sw = __builtin_amdgcn_permlane32_swap(imax, imax, false, false);
+  imax = max((int)sw[0], (int)sw[1]);
+  const float nb = -__int_as_float(BIAS_I) * c2s;
+  // the guard of one score step keeps t - r <= 0 whatever the rounding of the two products
+  r = fmaxf(r, __builtin_ceilf(__builtin_fmaf(__int_as_float(imax), c2s, nb) + c2s * SCORE_STEP));
+  return (LOG2_448 - r) + nb;
+}
+
+// Four biased scores (accumulator registers 4g .. 4g+3 of one half) -> four FP8 codes of P in
+// the returned word; `dst` supplies the register to overwrite half by half.
 template <bool tail>
-__device__ __forceinline__ void softmax_codes(const v16i& s0, const v16i& s1, int hf, float c2, float offs,
-                                              int kvalid, v8i& pb) {
-  int code = 0;
+__device__ __forceinline__ int codes_quad(const v16i& s, int g, int key0, int hf, float c2s, float offs, int kvalid,
+                                          int dst) {
+  float p[4];
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    float p[4];
+  for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(__int_as_float(s[4 * g + e]), c2s, offs));
+  if (tail) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(__int_as_float(s0[4 * g + e]), c2, offs));
-    if (tail) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (8 * g + 4 * hf + e >= kvalid) p[e] = 0.f;
-    }
-    code = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], code, false), true);  // both halves overwritten
-    pb[g] = code;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(__int_as_float(s1[4 * g + e]), c2, offs));
-    if (tail) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (32 + 8 * g + 4 * hf + e >= kvalid) p[e] = 0.f;
-    }
-    code = cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], code, false), true);
-    pb[4 + g] = code;
+    for (int e = 0; e < 4; ++e)
+      if (key0 + 8 * g + 4 * hf + e >= kvalid) p[e] = 0.f;
   }
+  return cvt_pk_e4m3(p[2], p[3], cvt_pk_e4m3(p[0], p[1], dst, false), true);
 }
 
 // E8M0 code of 2^(r_prev - R): brings the P codes made at level r_prev to the accumulators'
-// level R (which may have moved up since; far below R the contribution vanishes).
+// level R (r_prev - R <= 64 by the renormalisation rule; far below R the contribution vanishes).
 __device__ __forceinline__ int level_scale(float r_prev, float R) {
-  return 127 + (int)fmaxf(r_prev - R, -127.f);
+  return 127 + (int)__builtin_amdgcn_fmed3f(r_prev - R, -127.f, 127.f);
+}
+
+// Rare: the reference level has run more than 64 binades ahead of the accumulators' level
+// (always so after the first block, whose R starts at "minus infinity"): bring them to level r.
+__device__ __forceinline__ void renormalise(float r, float& R, v16f (&acc)[4], v16f& accl) {
+  const bool up = r - R > 64.f;
+  const float down = up ? __builtin_amdgcn_exp2f(R - r) : 1.0f;
+  if (up) R = r;
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[ct][q] *= down;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) accl[q] *= down;
 }
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -207,12 +202,9 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   constexpr int BQ = NW * 32;
   // Rings of four K and four V staging buffers, declared as separate objects so the compiler
   // can tell the asynchronous fill of one from the reads of another; after the main loop
-  // wavefront w reuses K buffer w for the output transposition.  sidx / sdk hold the critical
-  // list of this query block and the matching K scales (IDX_CAP entries at a time).
+  // wavefront w reuses K buffer w for the output transposition.
   __shared__ uint4 kst0[KV_FRAG_BYTES / 16], kst1[KV_FRAG_BYTES / 16], kst2[KV_FRAG_BYTES / 16], kst3[KV_FRAG_BYTES / 16];
   __shared__ uint4 vst0[KV_FRAG_BYTES / 16], vst1[KV_FRAG_BYTES / 16], vst2[KV_FRAG_BYTES / 16], vst3[KV_FRAG_BYTES / 16];
-  __shared__ int sidx[IDX_CAP];
-  __shared__ float sdk[IDX_CAP];
   static_assert(32 * EPI_STRIDE <= KV_FRAG_BYTES, "output staging must fit one stage buffer");
 
   // Workgroup ids are dealt round-robin over the 8 XCDs.  All XCDs work on the SAME head at
@@ -221,7 +213,9 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   // Infinity Cache instead of being re-fetched from HBM), and the workgroups that share an
   // XCD's L2 are neighbouring query blocks, whose critical sets overlap.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int bh = slot / A.per_xcd, i = xcd * A.per_xcd + slot % A.per_xcd;  // per_xcd = ceil(Tq / 8)
+  // (the division runs on the vector ALU; its uniform result goes back to scalar registers)
+  const int bh = __builtin_amdgcn_readfirstlane(slot / A.per_xcd);  // per_xcd = ceil(Tq / 8)
+  const int i = xcd * A.per_xcd + (slot - bh * A.per_xcd);
   if (i >= A.Tq) return;
   const int rowid = bh * A.Tq + i;
 
@@ -249,12 +243,13 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       q8[s][g] = (int)wv;
     }
   }
-  const float cq = dqi * (LOG2E / 11.313708498984761f);
+  const float cq = dqi * (LOG2E / 11.313708498984761f) * 67108864.f;  // log2(e) / sqrt(d) * delta_Q * 2^26 (see BIAS_I)
 
   v16f acc[4], accl = v16f{};
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
-  float r = -INFINITY, R = -INFINITY;
+  // R starts far below any reachable level, so the first block renormalises (0 * 0) and sets R
+  float r = -1e30f, R = -1e30f;
   // A operand that sums P over the keys: FP8 1.0 in rows 0 and 4 of a 32-row tile, so the
   // row sum of a query lands in accumulator register 0 of both of its lanes.
   const int one4 = (l32 == 0 || l32 == 4) ? 0x38383838 : 0;
@@ -262,146 +257,209 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   v16i bias16;
 #pragma unroll
   for (int e = 0; e < 16; ++e) bias16[e] = BIAS_I;
-  asm volatile("" : "+v"(bias16));  // keep it in registers: it is the C operand of every first score MFMA
+  asm volatile("" : "+v"(bias16));  // kept in registers: the C operand of the first score MFMA of every half
 
   const int n_c = A.n_c;
-  const int32_t* crow = A.crit + (size_t)rowid * n_c;
-  const float* dkrow = A.dk + (size_t)bh * A.Tk;
+  // the critical list and the K scales are read through the scalar unit (uniform addresses)
+  const int32_t* __restrict__ crow = A.crit + (size_t)rowid * n_c;
+  const float* __restrict__ dkrow = A.dk + (size_t)bh * A.Tk;
   const size_t rec0 = (size_t)bh * A.Tk * KV_FRAG_BYTES;
-  // Asynchronous global -> LDS copy of one block's K and V records (no registers in between):
-  // each wavefront fills 1 KiB pieces, lane l supplying bytes [16 l, 16 l + 16) of a piece.
+  // Asynchronous global -> LDS copy of one block's K or V record (no registers in between).
+  // Wavefront w copies the PW adjacent 1 KiB pieces [PW w, PW w + PW) of the record, lane l
+  // supplying bytes [16 l, 16 l + 16) of a piece; the address is a uniform base (scalar
+  // registers) + one 32-bit per-lane offset + the instruction's immediate, which the hardware
+  // adds to the LDS address as well.
+  constexpr int PW = CH / 2;
+  static_assert(PW == 2 || PW == 4, "pieces per wavefront per record");
   const int w_s = __builtin_amdgcn_readfirstlane(w);  // wavefront index as a scalar
-  const unsigned lane_off = (unsigned)t * 16u;
-  auto fetch_k = [&](int j, uint4* dst) {
-    // uniform base (scalar registers) + 32-bit per-lane offset: no vector address arithmetic
-    const char* ks = (const char*)A.k8 + rec0 + (size_t)j * KV_FRAG_BYTES;
-#pragma unroll
-    for (int u = 0; u < CH / 2; ++u)
-      __builtin_amdgcn_global_load_lds((const void*)(ks + u * NT * 16 + lane_off),
-                                       (lds_ptr_t)(dst + u * NT + w_s * 64), 16, 0, 0);
+  unsigned lane_off = (unsigned)(w * PW * 1024 + lane * 16);
+  const char* const k8_bh = (const char*)A.k8 + rec0;  // this (b,h)'s records: uniform, loop invariant
+  const char* const v8_bh = (const char*)A.v8 + rec0;
+  auto fetch_rec = [&](const char* base_bh, int j, uint4* dst) {
+    // the empty asm keeps the (32-bit) offset arithmetic next to its use, so the scalar-base
+    // addressing form is selected: base_bh in scalar registers + one vector offset
+    asm volatile("" : "+v"(lane_off));
+    const char* g = base_bh + (((unsigned)j << 13) + lane_off);
+    static_assert(KV_FRAG_BYTES == 1 << 13, "record size");
+    lds_ptr_t l = (lds_ptr_t)(dst + w_s * PW * 64);
+    __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 1024, 0);
+    if constexpr (PW == 4) {
+      __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 2048, 0);
+      __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 3072, 0);
+    }
   };
-  auto fetch_v = [&](int j, uint4* dst) {
-    const char* vs = (const char*)A.v8 + rec0 + (size_t)j * KV_FRAG_BYTES;
-#pragma unroll
-    for (int u = 0; u < CH / 2; ++u)
-      __builtin_amdgcn_global_load_lds((const void*)(vs + u * NT * 16 + lane_off),
-                                       (lds_ptr_t)(dst + u * NT + w_s * 64), 16, 0, 0);
-  };
+  auto dk_of = [&](int j) { return *(const float*)((const char*)dkrow + ((unsigned)j << 2)); };
   const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
   const bool ragged = kvalid_last < BK;
 
-  // Software pipeline over the critical list.  In step b a wavefront
-  //   - starts the copies of K(b+3) and V(b+2) into the ring slots retired in step b-1,
-  //   - issues the score MFMAs of block b (K ring slot b%4) and reduces them to the new
-  //     reference level r,
-  //   - then, in ONE scheduling region, issues the P.V MFMAs of block b-1 (V ring slot
-  //     (b-1)%4, P codes kept from step b-1) interleaved with the exp / FP8-pack arithmetic
-  //     that turns the scores of block b into P codes: a wavefront that issues MFMAs back to
-  //     back stalls once the matrix pipe's queue is full, so the vector-ALU work has to sit
-  //     between them in program order to run while they execute,
-  //   - waits for its own pieces of K(b+1) / V(b) and meets the other wavefronts at one barrier,
-  //     which publishes those and retires K slot b%4 and V slot (b-1)%4.
-  // The L2 / HBM latency of a block is thus covered by the arithmetic of three steps.  A ragged
-  // last key block can only be the last entry of the (ascending) list; it is peeled off the
-  // loop so that masking its missing keys costs the other blocks nothing.
-  const bool has_tail = ragged && n_c > 0 && crow[n_c - 1] == A.Tk - 1;
-  constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4F70 : (0x0F70 | (2 * CH));  // s_waitcnt vmcnt(2*CH)
+  // Software pipeline over the critical list.  Entering step b, the scores of keys 0..31 of
+  // block b (s0) are finished and the K fragments of its keys 32..63 (kfB) are in registers.
+  // Step b has two phases of the same shape, each a chain of MFMAs with one piece of vector-ALU
+  // work behind every MFMA (scheduling barriers pin the pieces there: a wavefront issues in
+  // order, and the pieces execute while the MFMA in front of them runs):
+  //   phase 1  MFMAs: scores of keys 32..63 of block b (s1), P.V tiles 0, 1 of block b-1
+  //            vector: s0 -> maximum -> reference level -> FP8 codes of keys 0..31 of block b
+  //   phase 2  MFMAs: scores of keys 0..31 of block b+1 (new s0), P.V tiles 2, 3 and the row sum
+  //            of block b-1;  vector: s1 -> ... -> codes of keys 32..63 of block b
+  // Each phase starts by reading from LDS the fragments the NEXT phase's MFMAs need (V of block
+  // b-1, K of block b+1) and by starting the copy of K(b+4) resp. V(b+2) into the ring slot
+  // retired in step b-1 (past the end of the list the last block is copied again, into slots
+  // nothing reads any more: the step stays free of branches).  At its end the wavefront waits
+  // for its own pieces of K(b+2) / V(b) and meets the others at one barrier, which publishes
+  // those and retires K slot (b+1)%4 and V slot (b-1)%4.  The L2 / HBM latency of a block is thus
+  // covered by the arithmetic of two to three steps.  A ragged last key block can only be the
+  // last entry of the (ascending) list; it is peeled off the loop so that masking its missing
+  // keys costs the other blocks nothing.
+  const int last = n_c - 1;
+  const bool has_tail = ragged && n_c > 0 && crow[last] == A.Tk - 1;
+  constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4070 : (0x0070 | (2 * CH));  // s_waitcnt vmcnt(2*CH) lgkmcnt(0)
+  constexpr int WAIT_ALL = 0x0070;                                            // s_waitcnt vmcnt(0) lgkmcnt(0)
   v16i s0, s1;
-  v8i pb_prev = {}, pb_new;   // P codes of block b-1 / b; all-zero codes contribute nothing
-  float r_prev = 0.f;
+  v8i pb_a = {}, pb_b = {};   // P codes of blocks b-1 / b (alternating); all-zero codes contribute nothing
+  uint4 kfA[4], kfB[4], vfa[4], vfb[4];
+  int sc_prev = 127;          // E8M0 scale of the P codes of block b-1 (this lane's half of it)
 
-#define SLA_STEP(B, KCUR, VPREV, KFILL, VFILL)                                                        \
+#define SB __builtin_amdgcn_sched_barrier(0);
+#define SLA_STEP(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)                                             \
   {                                                                                                   \
     const int b_ = (B);                                                                               \
-    if (b_ + 3 < nb) fetch_k(__builtin_amdgcn_readfirstlane(jk3), KFILL);                             \
-    if (b_ + 2 < nb) fetch_v(__builtin_amdgcn_readfirstlane(jv2), VFILL);                             \
-    jv2 = jk3;                                                                                        \
-    jk3 = sidx[min(b_ + 4, nb - 1)];                                                                  \
-    const float c2_ = cq * dkv;                                                                       \
-    dkv = sdk[min(b_ + 1, nb - 1)];                                                                   \
-    qk_scores(KCUR, lane, q8, bias16, s0, s1);                                                        \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-    const float offs_ = softmax_reference<false>(s0, s1, hf, c2_, 0, r, R, acc, accl);                \
-    const int sc_ = level_scale(r_prev, R);                                                           \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-    pv_accumulate(VPREV, lane, pb_prev, sc_, ones, acc, accl);                                        \
-    softmax_codes<false>(s0, s1, hf, c2_, offs_, 0, pb_new);                                          \
-    /* 8 LDS reads, then 5 x (1 MFMA, 17 vector-ALU instructions) */                                  \
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                                                \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-    __builtin_amdgcn_sched_group_barrier(0x002, 17, 0);                                               \
-    /* anchor: P codes and accumulators are final here (keeps both computations inside this step) */  \
-    asm volatile("" : "+v"(jk3), "+v"(jv2), "+v"(dkv), "+v"(pb_new), "+v"(acc[0]), "+v"(acc[1]),      \
-                 "+v"(acc[2]), "+v"(acc[3]), "+v"(accl));                                             \
-    __builtin_amdgcn_sched_barrier(0);                                                                \
-    pb_prev = pb_new;                                                                                 \
-    r_prev = r;                                                                                       \
-    if (b_ + 3 < nb) __builtin_amdgcn_s_waitcnt(WAIT_KEEP2); else __builtin_amdgcn_s_waitcnt(0x0F70); \
+    /* ---- phase 1 */                                                                                \
+    read4(VPREV, lane, 0, vfa);                                                                       \
+    read4(KNEXT, lane, 0, kfA);                                                                       \
+    fetch_rec(k8_bh, j4, KFILL);                                                                       \
+    const int jn_ = crow[min(b_ + 5, last)];                                                          \
+    const float dn_ = dk_of(j4);                                                                      \
+    const float c2s_ = cq * d0;                                                                       \
+    SB s1 = qk_step(kfB[0], q8[0], bias16);                                                           \
+    SB const int mA_ = half_max<false>(s0, 0, hf, 0);                                                 \
+    SB s1 = qk_step(kfB[1], q8[1], s1);                                                               \
+    SB const float offsA_ = new_reference(mA_, c2s_, r);                                              \
+    const float rA_ = r;                                                                              \
+    SB s1 = qk_step(kfB[2], q8[2], s1);                                                               \
+    SB PBN[0] = codes_quad<false>(s0, 0, 0, hf, c2s_, offsA_, 0, PBN[0]);                                      \
+    SB s1 = qk_step(kfB[3], q8[3], s1);                                                               \
+    SB PBN[1] = codes_quad<false>(s0, 1, 0, hf, c2s_, offsA_, 0, PBN[1]);                                      \
+    SB pv_tile(vfa[0], vfa[1], PBP, sc_prev, acc[0]);                                                 \
+    SB PBN[2] = codes_quad<false>(s0, 2, 0, hf, c2s_, offsA_, 0, PBN[2]);                                      \
+    SB pv_tile(vfa[2], vfa[3], PBP, sc_prev, acc[1]);                                                 \
+    SB PBN[3] = codes_quad<false>(s0, 3, 0, hf, c2s_, offsA_, 0, PBN[3]);                                      \
+    /* ---- phase 2 */                                                                                \
+    read4(VPREV, lane, 4, vfb);                                                                       \
+    read4(KNEXT, lane, 4, kfB);                                                                       \
+    fetch_rec(v8_bh, j2, VFILL);                                                                       \
+    SB s0 = qk_step(kfA[0], q8[0], bias16);                                                           \
+    SB const int mB_ = half_max<false>(s1, 32, hf, 0);                                                \
+    SB s0 = qk_step(kfA[1], q8[1], s0);                                                               \
+    SB const float offsB_ = new_reference(mB_, c2s_, r);                                              \
+    SB s0 = qk_step(kfA[2], q8[2], s0);                                                               \
+    SB PBN[4] = codes_quad<false>(s1, 0, 32, hf, c2s_, offsB_, 0, PBN[4]);                                     \
+    SB s0 = qk_step(kfA[3], q8[3], s0);                                                               \
+    SB PBN[5] = codes_quad<false>(s1, 1, 32, hf, c2s_, offsB_, 0, PBN[5]);                                     \
+    SB pv_tile(vfb[0], vfb[1], PBP, sc_prev, acc[2]);                                                 \
+    SB PBN[6] = codes_quad<false>(s1, 2, 32, hf, c2s_, offsB_, 0, PBN[6]);                                     \
+    SB pv_tile(vfb[2], vfb[3], PBP, sc_prev, acc[3]);                                                 \
+    SB PBN[7] = codes_quad<false>(s1, 3, 32, hf, c2s_, offsB_, 0, PBN[7]);                                     \
+    SB pv_rowsum(ones, PBP, sc_prev, accl);                                                           \
+    SB const float rsel_ = hf ? r : rA_;   /* level of this lane's half of the new codes */           \
+    j2 = j3; j3 = j4; j4 = jn_;                                                                       \
+    d0 = d1; d1 = d2; d2 = d3; d3 = dn_;                                                              \
+    /* anchor: keeps every piece inside this step */                                                  \
+    asm volatile("" : "+v"(PBN), "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(accl),  \
+                 "+v"(s0), "+s"(j4), "+s"(d3));                                                       \
+    SB if (__any(r - R > 64.f)) renormalise(r, R, acc, accl);                                         \
+    sc_prev = level_scale(rsel_, R);                                                                  \
+    __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);                                                           \
     stage_barrier();                                                                                  \
   }
 
-  for (int c0 = 0; c0 < n_c; c0 += IDX_CAP) {
-    const int nb = min(IDX_CAP, n_c - c0);
-    __syncthreads();  // the previous chunk's list and stages are no longer in use
-    for (int e = t; e < nb; e += NT) {
-      const int j = crow[c0 + e];
-      sidx[e] = j;
-      sdk[e] = dkrow[j];
-    }
+  if (n_c > 0) {  // (an empty list leaves only the linear term of the epilogue)
     // step 0 has no previous block: it multiplies all-zero P codes with this all-zero V slot
     for (int e = t; e < KV_FRAG_BYTES / 16; e += NT) vst3[e] = make_uint4(0, 0, 0, 0);
-    __syncthreads();
-    fetch_k(__builtin_amdgcn_readfirstlane(sidx[0]), kst0);
-    fetch_v(__builtin_amdgcn_readfirstlane(sidx[0]), vst0);
-    if (nb > 1) fetch_k(__builtin_amdgcn_readfirstlane(sidx[1]), kst1);
-    if (nb > 1) fetch_v(__builtin_amdgcn_readfirstlane(sidx[1]), vst1);
-    if (nb > 2) fetch_k(__builtin_amdgcn_readfirstlane(sidx[2]), kst2);
-    int jk3 = sidx[min(3, nb - 1)];   // index of block b+3 (for K), read one step ahead of its use
-    int jv2 = sidx[min(2, nb - 1)];   // index of block b+2 (for V)
-    float dkv = sdk[0];               // K scale of block b, likewise
-    if (nb > 2) __builtin_amdgcn_s_waitcnt(WAIT_KEEP2); else __builtin_amdgcn_s_waitcnt(0x0F70);
+    // indices of blocks 0..4 and K scales of blocks 0..3 (clamped to the list)
+    const int j0 = crow[0], j1 = crow[min(1, last)];
+    int j2 = crow[min(2, last)], j3 = crow[min(3, last)], j4 = crow[min(4, last)];
+    float d0 = dk_of(j0), d1 = dk_of(j1), d2 = dk_of(j2), d3 = dk_of(j3);
+    // three groups of copies, in the order the steps will wait for them
+    fetch_rec(k8_bh, j0, kst0);
+    fetch_rec(k8_bh, j1, kst1);
+    fetch_rec(k8_bh, j2, kst2);
+    fetch_rec(v8_bh, j0, vst0);
+    fetch_rec(k8_bh, j3, kst3);
+    fetch_rec(v8_bh, j1, vst1);
+    __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);  // K(0), K(1) have landed
     stage_barrier();
-    const int nb_main = (has_tail && c0 + nb == n_c) ? nb - 1 : nb;
+    read4(kst0, lane, 0, kfA);
+    read4(kst0, lane, 4, kfB);
+    s0 = qk_step(kfA[0], q8[0], bias16);
+#pragma unroll
+    for (int u = 1; u < 4; ++u) s0 = qk_step(kfA[u], q8[u], s0);
+    const int nb_main = has_tail ? n_c - 1 : n_c;
     int b = 0;
     for (; b + 4 <= nb_main; b += 4) {
-      SLA_STEP(b, kst0, vst3, kst3, vst2)
-      SLA_STEP(b + 1, kst1, vst0, kst0, vst3)
-      SLA_STEP(b + 2, kst2, vst1, kst1, vst0)
-      SLA_STEP(b + 3, kst3, vst2, kst2, vst1)
+      SLA_STEP(b, kst1, vst3, kst0, vst2, pb_b, pb_a)
+      SLA_STEP(b + 1, kst2, vst0, kst1, vst3, pb_a, pb_b)
+      SLA_STEP(b + 2, kst3, vst1, kst2, vst0, pb_b, pb_a)
+      SLA_STEP(b + 3, kst0, vst2, kst3, vst1, pb_a, pb_b)
     }
-    if (b < nb_main) SLA_STEP(b, kst0, vst3, kst3, vst2)
-    if (b + 1 < nb_main) SLA_STEP(b + 1, kst1, vst0, kst0, vst3)
-    if (b + 2 < nb_main) SLA_STEP(b + 2, kst2, vst1, kst1, vst0)
-    // drain: everything of this chunk has landed and been published (the last step waited for
-    // all copies), so plain reads of any slot are safe from here on
-    if (nb_main < nb) {  // the ragged last key block
-      const int st = nb_main & 3, sp = (nb_main + 3) & 3;
-      const uint4* kc = st == 0 ? kst0 : st == 1 ? kst1 : st == 2 ? kst2 : kst3;
+    // the (up to three) remaining steps keep the a/b alternation by copying the codes back
+    if (b < nb_main) {
+      SLA_STEP(b, kst1, vst3, kst0, vst2, pb_b, pb_a)
+      pb_b = pb_a;
+    }
+    if (b + 1 < nb_main) {
+      SLA_STEP(b + 1, kst2, vst0, kst1, vst3, pb_b, pb_a)
+      pb_b = pb_a;
+    }
+    if (b + 2 < nb_main) {
+      SLA_STEP(b + 2, kst3, vst1, kst2, vst0, pb_b, pb_a)
+      pb_b = pb_a;
+    }
+    // drain: wait for every copy (the repeated ones too) and publish; from here on plain reads
+    __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    stage_barrier();
+    if (has_tail) {  // the ragged last key block: s0 and kfB are ready, P.V of the block before it is due
+      const int sp = (nb_main + 3) & 3;
       const uint4* vp = sp == 0 ? vst0 : sp == 1 ? vst1 : sp == 2 ? vst2 : vst3;
-      qk_scores(kc, lane, q8, bias16, s0, s1);
-      const float c2t = cq * sdk[nb_main];
-      const float offs_t = softmax_reference<true>(s0, s1, hf, c2t, kvalid_last, r, R, acc, accl);
-      pv_accumulate(vp, lane, pb_prev, level_scale(r_prev, R), ones, acc, accl);
-      softmax_codes<true>(s0, s1, hf, c2t, offs_t, kvalid_last, pb_new);
-      pb_prev = pb_new;
-      r_prev = r;
+      read4(vp, lane, 0, vfa);
+      read4(vp, lane, 4, vfb);
+      const float c2t = cq * d0;
+      s1 = qk_step(kfB[0], q8[0], bias16);
+#pragma unroll
+      for (int u = 1; u < 4; ++u) s1 = qk_step(kfB[u], q8[u], s1);
+      pv_tile(vfa[0], vfa[1], pb_b, sc_prev, acc[0]);
+      pv_tile(vfa[2], vfa[3], pb_b, sc_prev, acc[1]);
+      pv_tile(vfb[0], vfb[1], pb_b, sc_prev, acc[2]);
+      pv_tile(vfb[2], vfb[3], pb_b, sc_prev, acc[3]);
+      pv_rowsum(ones, pb_b, sc_prev, accl);
+      const int mAt = half_max<true>(s0, 0, hf, kvalid_last);
+      const float offsAt = new_reference(mAt, c2t, r);
+      const float rAt = r;
+      v8i pb_t = {};
+#pragma unroll
+      for (int g = 0; g < 4; ++g) pb_t[g] = codes_quad<true>(s0, g, 0, hf, c2t, offsAt, kvalid_last, pb_t[g]);
+      const int mBt = half_max<true>(s1, 32, hf, kvalid_last);
+      const float offsBt = new_reference(mBt, c2t, r);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) pb_t[4 + g] = codes_quad<true>(s1, g, 32, hf, c2t, offsBt, kvalid_last, pb_t[4 + g]);
+      pb_b = pb_t;
+      if (__any(r - R > 64.f)) renormalise(r, R, acc, accl);
+      sc_prev = level_scale(hf ? r : rAt, R);
     }
-    {  // P.V of the chunk's last block
-      const int sl = (nb - 1) & 3;
+    {  // P.V of the last block
+      const int sl = last & 3;
       const uint4* vc = sl == 0 ? vst0 : sl == 1 ? vst1 : sl == 2 ? vst2 : vst3;
-      pv_accumulate(vc, lane, pb_prev, level_scale(r_prev, R), ones, acc, accl);
-      pb_prev = v8i{};
+      read4(vc, lane, 0, vfa);
+      read4(vc, lane, 4, vfb);
+      pv_tile(vfa[0], vfa[1], pb_b, sc_prev, acc[0]);
+      pv_tile(vfa[2], vfa[3], pb_b, sc_prev, acc[1]);
+      pv_tile(vfb[0], vfb[1], pb_b, sc_prev, acc[2]);
+      pv_tile(vfb[2], vfb[3], pb_b, sc_prev, acc[3]);
+      pv_rowsum(ones, pb_b, sc_prev, accl);
     }
   }
 #undef SLA_STEP
+#undef SB
 
   // ---- normalise: O_s[q][ch] = acc * delta_V[ch] / l
   const float ltot = accl[0];  // sum of the rounded P (scaled by 448), at level R

@@ -50,13 +50,19 @@ def check_mask(gpu_mask, scores64, n_c, n_m, what):
     return len(bad), excused, ref
 
 
+# The kernel refreshes the running reference of the softmax after every 32 keys (one MFMA key
+# tile) instead of once per 64-key block; the oracle is run the same way (its ref_tile switch),
+# since both sides must round P to FP8 at the same level.
+REF_TILE = 32
+
+
 def oracle_head(cfg, q, k, v, b, h, W=None, bias=None, q_blocks=None, mask=None, phi="softmax"):
     """Oracle forward of one (b,h) slice of CPU bf16 tensors."""
     Q, K, V = (synth.as_f64(t[b, h]) for t in (q, k, v))
     return so.sla_forward_head(Q, K, V, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
                                proj_w=None if W is None else synth.as_f64(W),
                                proj_b=None if bias is None else synth.as_f64(bias),
-                               phi=phi, q_blocks=q_blocks, mask=mask)
+                               phi=phi, q_blocks=q_blocks, mask=mask, ref_tile=REF_TILE)
 
 
 def to_dev(*ts):

@@ -382,3 +382,24 @@ def test_integer_reference_keeps_every_rescale_a_power_of_two():
     ex = so.sparse_branch_exact(Q, K, V, mask, 64, 64)
     ea, eb = np.abs(a - ex).mean(), np.abs(b - ex).mean()
     assert ea < 1.5 * eb          # no worse than the plain running maximum, on average
+
+
+def test_reference_refresh_tile_changes_only_the_rounding():
+    # Refreshing the running reference every 32 keys instead of once per 64-key block is the
+    # same computation before rounding (online softmax is exact for any blocking) ...
+    cfg, Q, K, V = _tiny()
+    mask = so.classify(so.pooled_scores(Q, K, 64, 64), 3, 6)
+    a = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8)
+    b = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8, ref_tile=32)
+    assert np.abs(a - b).max() < 1e-12
+    c = so.sparse_branch_quant(Q, K, V, mask, 64, 64, so.QUANT_QK_INT8, ref_tile=16, reference="running")
+    assert np.abs(a - c).max() < 1e-12
+    # ... and with FP8 P only moves where the codes round: both stay equally close to the exact branch
+    a8, la = so.sparse_branch_quant(Q, K, V, mask, 64, 64, return_lse=True)
+    b8, lb = so.sparse_branch_quant(Q, K, V, mask, 64, 64, return_lse=True, ref_tile=32)
+    assert np.abs(a8 - b8).max() < 2e-2 and np.abs(la - lb).max() < 2e-2
+    ex = so.sparse_branch_exact(Q, K, V, mask, 64, 64)
+    ea, eb = np.abs(a8 - ex).mean(), np.abs(b8 - ex).mean()
+    assert eb < 1.25 * ea and ea < 1.25 * eb
+    # a tile equal to the block is the default
+    assert np.array_equal(a8, so.sparse_branch_quant(Q, K, V, mask, 64, 64, ref_tile=64))
