@@ -130,13 +130,13 @@ int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, in
   mark(s, rec, 1);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
   launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
-                lin ? at<bf16_t>(ws, W.m0) : nullptr, s);
+                lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
   const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
   launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, true, lin,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   mark(s, rec, 3);
-  if (lin) launch_lin_accumulate(p, at<bf16_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+  if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   mark(s, rec, 4);
   launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
                     at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
@@ -242,8 +242,8 @@ int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_
   const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
   launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, false, true, nullptr,
                  nullptr, nullptr, at<bf16_t>(ws, W.hz), s);
-  launch_marginal_frag(p, mask, at<bf16_t>(ws, W.m0), s);
-  launch_lin_accumulate(p, at<bf16_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+  launch_marginal_bits(p, mask, at<uint32_t>(ws, W.m0), s);
+  launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   // the attention kernel with an empty critical list leaves only the linear term
   launch_sparse_fwd(q, p, nullptr, 0, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dq),
                     at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ), (const bf16_t*)proj_b,

@@ -89,7 +89,7 @@ struct Workspace {
   size_t dk;                // fp32 [BH,Tk]  per-key-block INT8 scale
   size_t scores;            // fp32 [BH,Tq,Tk]
   size_t mask;              // int8 [BH,Tq,Tk]
-  size_t m0;                // bf16 marginal indicator in MFMA fragment order: [BH, ceil(Tq/256), ceil(Tk/32)] tiles of 16 KiB
+  size_t m0;                // uint32 marginal bit matrix [BH, ceil(Tk/32), Tq rounded up to 768]: bit e of word (kt, i) = block 32 kt + e marginal for query block i
   size_t crit, marg;        // int32 [BH,Tq,n_c], [BH,Tq,n_m]
   size_t k8, v8;            // [BH,Tk] records of KV_FRAG_BYTES
   size_t hz;                // bf16 [BH,Tk,HZ_ROWS,D]
@@ -113,7 +113,7 @@ inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, siz
   w.dk = take(BH * Tk * 4);
   w.scores = take(BH * Tq * Tk * 4);
   w.mask = take(BH * Tq * Tk);
-  w.m0 = take(BH * ((Tq + 255) / 256) * ((Tk + 31) / 32) * 16384);
+  w.m0 = take(BH * ((Tk + 31) / 32) * ((Tq + 767) / 768 * 768) * 4);
   w.crit = take(BH * Tq * n_c * 4);
   w.marg = take(BH * Tq * (n_m ? n_m : 1) * 4);
   w.k8 = take(BH * Tk * KV_FRAG_BYTES);
@@ -138,12 +138,12 @@ void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* 
                            float* dv, bf16_t* eye, hipStream_t stream);
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores, hipStream_t stream);
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
-                   bf16_t* mA, hipStream_t stream);
+                   uint32_t* mbits, hipStream_t stream);
 void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
                     const bf16_t* proj_w, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream);
-void launch_marginal_frag(const Problem& p, const int8_t* mask, bf16_t* mA, hipStream_t stream);
-void launch_lin_accumulate(const Problem& p, const bf16_t* mA, const bf16_t* hz, bf16_t* HZ,
+void launch_marginal_bits(const Problem& p, const int8_t* mask, uint32_t* mbits, hipStream_t stream);
+void launch_lin_accumulate(const Problem& p, const uint32_t* mbits, const bf16_t* hz, bf16_t* HZ,
                            hipStream_t stream);
 void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
                        const uint8_t* v8, const float* dq, const float* dk, const float* dv,

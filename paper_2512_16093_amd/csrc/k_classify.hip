@@ -261,7 +261,7 @@ template <int KPL>
 __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ scores, int rows, int Tq, int Tk,
                                                      int n_c, int n_m, int8_t* __restrict__ mask,
                                                      int32_t* __restrict__ crit, int32_t* __restrict__ marg,
-                                                     bf16_t* __restrict__ mA) {
+                                                     uint32_t* __restrict__ mbits) {
   __shared__ unsigned hist_all[4][256];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const size_t row = (size_t)blockIdx.x * 4 + w;
@@ -315,7 +315,7 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
 
   const unsigned long long lt = (1ull << lane) - 1ull;
   const int bh = (int)(row / Tq), i = (int)(row % Tq);
-  const int RT = (Tq + 255) / 256, KT = (Tk + 31) / 32;
+  const int KT = (Tk + 31) / 32, TqP = (Tq + 767) / 768 * 768;  // layout of the marginal bit matrix (see lin_accumulate)
   int eq1 = 0, eq2 = 0, nc = 0, nm = 0;  // running counts in ascending-j order
 #pragma unroll
   for (int m = 0; m < KPL; ++m) {
@@ -335,17 +335,9 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
     if (marg && is_m) marg[row * n_m + nm + __popcll(bm & lt)] = j;
     nc += __popcll(bc);
     nm += __popcll(bm);
-    if (mA && lane < 8) {  // lane c packs blocks 64m + 8c .. +7 into one 16-byte chunk
-      const int j0 = 64 * m + 8 * lane, kt = j0 >> 5, pch = (j0 >> 3) & 3;
-      if (kt < KT) {
-        const unsigned bits = (unsigned)(bm >> (8 * lane)) & 0xffu;
-        uint32_t wv[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          wv[e] = ((bits >> (2 * e)) & 1u ? 0x3f80u : 0u) | ((bits >> (2 * e + 1)) & 1u ? 0x3f800000u : 0u);
-        uint4* dst = (uint4*)(mA + ((size_t)(bh * RT + (i >> 8)) * KT + kt) * 8192) + (pch * 256 + (i & 255));
-        *dst = make_uint4(wv[0], wv[1], wv[2], wv[3]);
-      }
+    if (mbits && lane < 2) {  // the marginal ballot of these 64 key blocks = two words of the bit matrix
+      const int kt = 2 * m + lane;
+      if (kt < KT) mbits[((size_t)bh * KT + kt) * TqP + i] = (uint32_t)(bm >> (32 * lane));
     }
   }
 }
@@ -373,11 +365,11 @@ void launch_scores(const Problem& p, const float* qbar, const float* kbar, float
 }
 
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
-                   bf16_t* mA, hipStream_t stream) {
+                   uint32_t* mbits, hipStream_t stream) {
   const int rows = p.BH * p.Tq;
   const unsigned grid = (unsigned)((rows + 3) / 4);
   const int need = (p.Tk + 63) / 64;
-#define SLA_SELECT(K) select_kernel<K><<<grid, 256, 0, stream>>>(scores, rows, p.Tq, p.Tk, p.n_c, p.n_m, mask, crit, marg, mA)
+#define SLA_SELECT(K) select_kernel<K><<<grid, 256, 0, stream>>>(scores, rows, p.Tq, p.Tk, p.n_c, p.n_m, mask, crit, marg, mbits)
   if (need <= 2) SLA_SELECT(2);
   else if (need <= 8) SLA_SELECT(8);
   else if (need <= 32) SLA_SELECT(32);

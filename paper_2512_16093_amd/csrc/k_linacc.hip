@@ -6,48 +6,56 @@
 // runs on bf16 MFMA with fp32 accumulation; gathering n_m summaries per query block
 // instead would move ~50x more bytes.
 //
-// Workgroup = 4 wavefronts (2 x 2), tile 256 query blocks x 256 columns (128 x 128 per
-// wavefront, 256 accumulator registers), looping over the row tiles of its column stripe so
-// the stripe of hz comes from HBM once and is re-read from L2.  Operand tiles for 32 key
-// blocks at a time are copied global -> LDS asynchronously, three stages deep:
-//   A (mask as bf16 0/1) is pre-arranged in global memory in MFMA fragment order by
-//     marginal_frag_kernel, so its copy is linear and its LDS reads are 16-byte, conflict free;
-//   B (hz rows, n contiguous) is copied as is and read back transposed with 2-byte LDS reads
-//     (the contraction index j is the slow index of hz; there is no way around one transposition).
+// The two operands could not be more different: hz is the big one (tens of MB per head) and
+// M0 is a bit matrix.  So a workgroup owns a 128-column stripe of hz for up to 768 query
+// blocks at once -- for the shapes of interest ALL query blocks of the head, so that hz is
+// read from HBM exactly once -- and M0 travels as bits: one 32-bit word per (query block,
+// tile of 32 key blocks), 3 KiB per staged tile against 8 KiB of hz.  The bf16 A operand of a
+// wavefront is made from its mask byte through a 256-entry table in LDS (entry b = the eight
+// bf16 values 0.0 / 1.0 of the bits of b), one 16-byte LDS read per fragment.
+//
+// Workgroup = 8 wavefronts; wavefront w owns query blocks [96 w, 96 w + 96) x 128 columns
+// (3 x 4 MFMA tiles of 32 x 32, 192 accumulator registers).  Operand tiles for 32 key blocks
+// at a time are copied global -> LDS asynchronously, three stages deep.  hz rows are copied
+// as they are (n contiguous) and read back transposed with 2-byte LDS reads: the contraction
+// index j is the slow index of hz, so one transposition is unavoidable, and this is the
+// cheapest place for it (32 narrow LDS reads per 12 MFMAs).
 #include "common.h"
 
 namespace sla {
 
-constexpr int LA_KT = 32;                      // key blocks per staged tile
-constexpr int LA_TM = 256, LA_TN = 256;        // workgroup tile
-constexpr int LA_A_BYTES = LA_TM * LA_KT * 2;  // 16 KiB
-constexpr int LA_B_ROW = LA_TN * 2;            // 512 bytes per staged hz row
-constexpr int LA_B_BYTES = LA_KT * LA_B_ROW + 3 * 64;  // each group of 8 rows starts 64 bytes after the previous
-                                                     // one ends, so the two lane halves hit different banks
-constexpr int LA_STAGE = LA_A_BYTES + LA_B_BYTES + 832;  // keep stages 1 KiB aligned
-static_assert(LA_STAGE % 1024 == 0, "stage alignment");
+constexpr int LA_KT = 32;                        // key blocks per staged tile
+constexpr int LA_ROWS = 768, LA_COLS = 128;      // workgroup tile
+constexpr int LA_WAVES = 8;
+constexpr int LA_B_ROW = LA_COLS * 2;            // 256 bytes per staged hz row
+// each group of 8 staged rows starts 64 bytes after the previous one ends, so the two lane
+// halves (which read rows 8 apart) hit different banks
+constexpr int LA_B_BYTES = LA_KT * LA_B_ROW + 3 * 64;
+constexpr int LA_B_STAGE = 8448;                 // LA_B_BYTES rounded up to a multiple of 256
+constexpr int LA_M_BYTES = LA_ROWS * 4;          // one mask word per query block
+constexpr int LA_STAGE = LA_B_STAGE + LA_M_BYTES;
+static_assert(LA_B_STAGE >= LA_B_BYTES && LA_STAGE % 256 == 0, "stage layout");
+static_assert(HZ_ELEMS % LA_COLS == 0, "the stripes tile a summary exactly");
 
-__host__ __device__ inline int la_row_tiles(int Tq) { return (Tq + LA_TM - 1) / LA_TM; }
 __host__ __device__ inline int la_k_tiles(int Tk) { return (Tk + LA_KT - 1) / LA_KT; }
+__host__ __device__ inline int la_rows_padded(int Tq) { return (Tq + LA_ROWS - 1) / LA_ROWS * LA_ROWS; }
 
-// mA[bh][rt][kt][p][row][e] (bf16): 1.0 where block kt*32 + p*8 + e is marginal for query
-// block rt*256 + row, else 0 (also outside the mask).  One 16-byte chunk per (p, row).
-__global__ void marginal_frag_kernel(const int8_t* __restrict__ mask, int Tq, int Tk, bf16_t* __restrict__ mA) {
-  const int RT = la_row_tiles(Tq), KT = la_k_tiles(Tk);
-  const int kt = blockIdx.x % KT, rt = (blockIdx.x / KT) % RT, bh = blockIdx.x / (KT * RT);
-  uint4* dst = (uint4*)(mA + ((size_t)(bh * RT + rt) * KT + kt) * (LA_A_BYTES / 2));
-  for (int c = threadIdx.x; c < 4 * LA_TM; c += blockDim.x) {
-    const int p = c / LA_TM, row = c % LA_TM, i = rt * LA_TM + row;
-    uint32_t w[4] = {0, 0, 0, 0};
-    if (i < Tq) {
-      const int8_t* src = mask + ((size_t)bh * Tq + i) * Tk;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int j = kt * LA_KT + p * 8 + e;
-        if (j < Tk && src[j] == 0) w[e >> 1] |= (e & 1) ? 0x3f800000u : 0x3f80u;
-      }
+// mbits[bh][kt][i] (i < la_rows_padded(Tq)): bit e = 1 where key block 32 kt + e is marginal
+// for query block i.  Words of rows >= Tq are never written and never matter (their results
+// are not stored); bits of key blocks >= Tk are 0.
+__global__ void marginal_bits_kernel(const int8_t* __restrict__ mask, int Tq, int Tk, int BH,
+                                     uint32_t* __restrict__ mbits) {
+  const int KT = la_k_tiles(Tk), TqP = la_rows_padded(Tq);
+  const size_t total = (size_t)BH * KT * Tq;
+  for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
+    const int i = (int)(x % Tq), kt = (int)((x / Tq) % KT), bh = (int)(x / ((size_t)Tq * KT));
+    const int8_t* src = mask + ((size_t)bh * Tq + i) * Tk;
+    uint32_t w = 0;
+    for (int e = 0; e < 32; ++e) {
+      const int j = kt * LA_KT + e;
+      if (j < Tk && src[j] == 0) w |= 1u << e;
     }
-    dst[c] = make_uint4(w[0], w[1], w[2], w[3]);
+    mbits[((size_t)bh * KT + kt) * TqP + i] = w;
   }
 }
 
@@ -59,117 +67,132 @@ __device__ __forceinline__ void la_barrier() {
   asm volatile("" ::: "memory");
 }
 
-__global__ void __launch_bounds__(256, 1) lin_accumulate_kernel(const bf16_t* __restrict__ mA,
-                                                                const bf16_t* __restrict__ hz, int Tq, int Tk,
-                                                                bf16_t* __restrict__ HZ) {
+__global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const uint32_t* __restrict__ mbits,
+                                                                          const bf16_t* __restrict__ hz, int Tq, int Tk,
+                                                                          bf16_t* __restrict__ HZ) {
   __shared__ __attribute__((aligned(1024))) unsigned char st0[LA_STAGE];
   __shared__ __attribute__((aligned(1024))) unsigned char st1[LA_STAGE];
   __shared__ __attribute__((aligned(1024))) unsigned char st2[LA_STAGE];
-  const int bh = blockIdx.y;
-  const int n0 = min((int)blockIdx.x * LA_TN, HZ_ELEMS - LA_TN);  // the last stripe overlaps its neighbour
+  __shared__ uint4 lut[256];
+  const int n0 = blockIdx.x * LA_COLS, row0 = blockIdx.y * LA_ROWS, bh = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, l32 = lane & 31, hf = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 1, wn = w & 1;
-  const int RT = la_row_tiles(Tq), KT = la_k_tiles(Tk);
-  const char* hz_bh = (const char*)(hz + (size_t)bh * Tk * HZ_ELEMS + n0);
-  const unsigned lane16 = (unsigned)lane * 16u;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int KT = la_k_tiles(Tk), TqP = la_rows_padded(Tq);
 
-  for (int rt = 0; rt < RT; ++rt) {
-    const char* a_rt = (const char*)(mA + ((size_t)(bh * RT + rt) * KT) * (LA_A_BYTES / 2));
-    // asynchronous copy of k-tile kt into a stage: 4 + 4 one-KiB pieces per wavefront
-    auto fetch = [&](int kt, unsigned char* st) {
-      const char* a = a_rt + (size_t)kt * LA_A_BYTES;
+  if (t < 256) {  // table: mask byte -> eight bf16 0.0 / 1.0
+    uint32_t x[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int piece = u * 4 + w;  // 16 pieces of 1 KiB
-        __builtin_amdgcn_global_load_lds((const void*)(a + piece * 1024 + lane16),
-                                         (la_lds_ptr_t)(st + piece * 1024), 16, 0, 0);
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int pr = u * 4 + w;  // pair of hz rows 2*pr, 2*pr+1; lanes 0..31 -> first row
-        const int j = min(kt * LA_KT + 2 * pr + hf, Tk - 1);  // rows past Tk repeat the last one (their mask is 0)
-        __builtin_amdgcn_global_load_lds((const void*)(hz_bh + (size_t)j * (HZ_ELEMS * 2) + (unsigned)l32 * 16u),
-                                         (la_lds_ptr_t)(st + LA_A_BYTES + pr * 1024 + (pr >> 2) * 64), 16, 0, 0);
-      }
-    };
-    v16f acc[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
-
-    auto compute = [&](const unsigned char* st) {
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        v8bf aop[4], bop[4];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-          aop[mt] = *(const v8bf*)(st + (((2 * ks + hf) * LA_TM) + 128 * wm + 32 * mt + l32) * 16);
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-          union { bf16_t h[8]; v8bf v; } u;
-          const int r0 = 16 * ks + 8 * hf;  // 8 consecutive staged rows, all in one shifted/unshifted group
-          const unsigned char* col = st + LA_A_BYTES + r0 * LA_B_ROW + (r0 >> 3) * 64 + (128 * wn + 32 * nt + l32) * 2;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) u.h[e] = *(const bf16_t*)(col + e * LA_B_ROW);
-          bop[nt] = u.v;
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-          for (int nt = 0; nt < 4; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[mt], bop[nt], acc[mt][nt], 0, 0, 0);
-      }
-    };
-
-#define LA_STEP(KTI, CUR, FILL)                                                            \
-  {                                                                                        \
-    const int kt_ = (KTI);                                                                 \
-    if (kt_ + 2 < KT) fetch(kt_ + 2, FILL);                                                \
-    compute(CUR);                                                                          \
-    if (kt_ + 2 < KT) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x0F70); \
-    la_barrier();                                                                          \
+    for (int e = 0; e < 4; ++e)
+      x[e] = ((t >> (2 * e)) & 1 ? 0x3f80u : 0u) | ((t >> (2 * e + 1)) & 1 ? 0x3f800000u : 0u);
+    lut[t] = make_uint4(x[0], x[1], x[2], x[3]);
   }
-    __syncthreads();  // the previous row tile no longer reads any stage
-    fetch(0, st0);
-    if (KT > 1) fetch(1, st1);
-    if (KT > 1) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x0F70);
-    la_barrier();
-    int kt = 0;
-    for (; kt + 3 <= KT; kt += 3) {
-      LA_STEP(kt, st0, st2)
-      LA_STEP(kt + 1, st1, st0)
-      LA_STEP(kt + 2, st2, st1)
+
+  // asynchronous copy of k-tile kt into a stage: wavefront w brings 4 hz rows (1 KiB), the
+  // first three wavefronts also 256 mask words each
+  const char* hz_bh = (const char*)(hz + (size_t)bh * Tk * HZ_ELEMS + n0);  // uniform
+  const char* mb_bh = (const char*)(mbits + (size_t)bh * KT * TqP + row0 + 256 * w);
+  unsigned lane16 = (unsigned)lane * 16u;
+  auto fetch = [&](int kt, unsigned char* st) {
+    const int j = min(kt * LA_KT + 4 * w + (lane >> 4), Tk - 1);  // rows past Tk repeat the last one (their mask bits are 0)
+    unsigned off = (unsigned)j * (unsigned)(HZ_ELEMS * 2) + (unsigned)(lane & 15) * 16u;
+    asm volatile("" : "+v"(off));  // 32-bit offset arithmetic stays next to its use: scalar base + vector offset form
+    __builtin_amdgcn_global_load_lds((const void*)(hz_bh + off), (la_lds_ptr_t)(st + w * 1024 + (w >> 1) * 64), 16, 0, 0);
+    if (w < 3) {
+      asm volatile("" : "+v"(lane16));
+      __builtin_amdgcn_global_load_lds((const void*)(mb_bh + (size_t)kt * TqP * 4 + lane16),
+                                       (la_lds_ptr_t)(st + LA_B_STAGE + w * 1024), 16, 0, 0);
     }
-    if (kt < KT) LA_STEP(kt, st0, st2)
-    if (kt + 1 < KT) LA_STEP(kt + 1, st1, st0)
+  };
+  auto wait_keep = [&](bool keep_one) {  // wait until at most one tile's copies of this wavefront are in flight
+    if (!keep_one) __builtin_amdgcn_s_waitcnt(0x0F70);
+    else if (w < 3) __builtin_amdgcn_s_waitcnt(0x0F72);
+    else __builtin_amdgcn_s_waitcnt(0x0F71);
+  };
+
+  v16f acc[3][4];
+#pragma unroll
+  for (int a = 0; a < 3; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
+
+  auto compute = [&](const unsigned char* st) {
+    uint32_t mw[3];
+#pragma unroll
+    for (int mt = 0; mt < 3; ++mt) mw[mt] = *(const uint32_t*)(st + LA_B_STAGE + (96 * w + 32 * mt + l32) * 4);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      v8bf aop[3], bop[4];
+#pragma unroll
+      for (int mt = 0; mt < 3; ++mt) {
+        const uint4 e = lut[(mw[mt] >> (16 * ks + 8 * hf)) & 0xffu];
+        union { uint4 u; v8bf v; } c;
+        c.u = e;
+        aop[mt] = c.v;
+      }
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        union { bf16_t h[8]; v8bf v; } u;
+        const int r0 = 16 * ks + 8 * hf;  // 8 consecutive staged rows, all in one shifted group
+        const unsigned char* col = st + r0 * LA_B_ROW + (r0 >> 3) * 64 + (32 * nt + l32) * 2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) u.h[e] = *(const bf16_t*)(col + e * LA_B_ROW);
+        bop[nt] = u.v;
+      }
+#pragma unroll
+      for (int mt = 0; mt < 3; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[mt], bop[nt], acc[mt][nt], 0, 0, 0);
+    }
+  };
+
+#define LA_STEP(KTI, CUR, FILL)              \
+  {                                          \
+    const int kt_ = (KTI);                   \
+    if (kt_ + 2 < KT) fetch(kt_ + 2, FILL);  \
+    compute(CUR);                            \
+    wait_keep(kt_ + 2 < KT);                 \
+    la_barrier();                            \
+  }
+  fetch(0, st0);
+  if (KT > 1) fetch(1, st1);
+  wait_keep(KT > 1);
+  __syncthreads();  // also publishes the table
+  int kt = 0;
+  for (; kt + 3 <= KT; kt += 3) {
+    LA_STEP(kt, st0, st2)
+    LA_STEP(kt + 1, st1, st0)
+    LA_STEP(kt + 2, st2, st1)
+  }
+  if (kt < KT) LA_STEP(kt, st0, st2)
+  if (kt + 1 < KT) LA_STEP(kt + 1, st1, st0)
 #undef LA_STEP
 
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+  for (int mt = 0; mt < 3; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
+    for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int i = rt * LA_TM + 128 * wm + 32 * mt + 8 * (r >> 2) + 4 * hf + (r & 3);
-          if (i < Tq)
-            HZ[((size_t)bh * Tq + i) * HZ_ELEMS + n0 + 128 * wn + 32 * nt + l32] = f32_to_bf16(acc[mt][nt][r]);
-        }
-  }
+      for (int r = 0; r < 16; ++r) {
+        const int i = row0 + 96 * w + 32 * mt + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (i < Tq) HZ[((size_t)bh * Tq + i) * HZ_ELEMS + n0 + 32 * nt + l32] = f32_to_bf16(acc[mt][nt][r]);
+      }
 }
 
-size_t marginal_frag_bytes(const Problem& p) {
-  return (size_t)p.BH * la_row_tiles(p.Tq) * la_k_tiles(p.Tk) * LA_A_BYTES;
+size_t marginal_bits_bytes(const Problem& p) {
+  return (size_t)p.BH * la_k_tiles(p.Tk) * la_rows_padded(p.Tq) * 4;
 }
 
-void launch_marginal_frag(const Problem& p, const int8_t* mask, bf16_t* mA, hipStream_t stream) {
-  const unsigned grid = (unsigned)(p.BH * la_row_tiles(p.Tq) * la_k_tiles(p.Tk));
-  marginal_frag_kernel<<<grid, 256, 0, stream>>>(mask, p.Tq, p.Tk, mA);
+void launch_marginal_bits(const Problem& p, const int8_t* mask, uint32_t* mbits, hipStream_t stream) {
+  const size_t total = (size_t)p.BH * la_k_tiles(p.Tk) * p.Tq;
+  const size_t want = (total + 255) / 256;
+  const unsigned grid = (unsigned)(want < 1048560 ? want : 1048560);
+  marginal_bits_kernel<<<grid, 256, 0, stream>>>(mask, p.Tq, p.Tk, p.BH, mbits);
 }
 
-void launch_lin_accumulate(const Problem& p, const bf16_t* mA, const bf16_t* hz, bf16_t* HZ, hipStream_t stream) {
-  dim3 grid((HZ_ELEMS + LA_TN - 1) / LA_TN, p.BH);
-  lin_accumulate_kernel<<<grid, 256, 0, stream>>>(mA, hz, p.Tq, p.Tk, HZ);
+void launch_lin_accumulate(const Problem& p, const uint32_t* mbits, const bf16_t* hz, bf16_t* HZ, hipStream_t stream) {
+  dim3 grid(HZ_ELEMS / LA_COLS, la_rows_padded(p.Tq) / LA_ROWS, p.BH);
+  lin_accumulate_kernel<<<grid, LA_WAVES * 64, 0, stream>>>(mbits, hz, p.Tq, p.Tk, HZ);
 }
 
 }  // namespace sla
