@@ -15,11 +15,13 @@
 // bf16 values 0.0 / 1.0 of the bits of b), one 16-byte LDS read per fragment.
 //
 // Workgroup = 8 wavefronts; wavefront w owns query blocks [96 w, 96 w + 96) x 128 columns
-// (3 x 4 MFMA tiles of 32 x 32, 192 accumulator registers).  Operand tiles for 32 key blocks
+// (3 x 4 MFMA tiles of 32 x 32, 192 accumulator registers), accumulated transposed (the hz
+// fragment is the MFMA's A operand) so that a lane ends up with runs of consecutive entries
+// of one query block's summary and can store 8 bytes at a time.  Operand tiles for 32 key blocks
 // at a time are copied global -> LDS asynchronously, three stages deep.  hz rows are copied
-// as they are (n contiguous) and read back transposed with 2-byte LDS reads: the contraction
-// index j is the slow index of hz, so one transposition is unavoidable, and this is the
-// cheapest place for it (32 narrow LDS reads per 12 MFMAs).
+// as they are (n contiguous) and read back with the LDS transposing read of gfx950
+// (ds_read_b64_tr_b16): the contraction index j is the slow index of hz, so one transposition
+// is unavoidable, and this one costs 8 LDS reads per 12 MFMAs and no vector-ALU work.
 #include "common.h"
 
 namespace sla {
@@ -32,9 +34,7 @@ constexpr int LA_B_ROW = LA_COLS * 2;            // 256 bytes per staged hz row
 // halves (which read rows 8 apart) hit different banks
 constexpr int LA_B_BYTES = LA_KT * LA_B_ROW + 3 * 64;
 constexpr int LA_B_STAGE = 8448;                 // LA_B_BYTES rounded up to a multiple of 256
-constexpr int LA_M_BYTES = LA_ROWS * 4;          // one mask word per query block
-constexpr int LA_STAGE = LA_B_STAGE + LA_M_BYTES;
-static_assert(LA_B_STAGE >= LA_B_BYTES && LA_STAGE % 256 == 0, "stage layout");
+static_assert(LA_B_STAGE >= LA_B_BYTES, "stage layout");
 static_assert(HZ_ELEMS % LA_COLS == 0, "the stripes tile a summary exactly");
 
 __host__ __device__ inline int la_k_tiles(int Tk) { return (Tk + LA_KT - 1) / LA_KT; }
@@ -61,6 +61,28 @@ __global__ void marginal_bits_kernel(const int8_t* __restrict__ mask, int Tq, in
 
 typedef __attribute__((address_space(3))) void* la_lds_ptr_t;
 
+// Asynchronous 16-bytes-per-lane copy global -> LDS: lane l reads base + voff and the data lands
+// at LDS address lds + 16 l.  Written as inline assembly on purpose: the compiler then neither
+// knows nor cares that copies are in flight (it would otherwise make every LDS read it cannot
+// prove disjoint wait for ALL of them); the pipeline below waits for them by explicit counts.
+// Loads the compiler does not know about only make its own waits more conservative.
+__device__ __forceinline__ void la_copy16(const void* base, unsigned voff, const void* lds) {
+  const unsigned lds_addr = (unsigned)(uintptr_t)(la_lds_ptr_t)lds;
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+               :
+               : "s"(base), "v"(voff), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+// LDS read with transposition (16-bit elements): in every group of 16 lanes, lane i receives, for
+// e = 0..3, element i % 4 of the 8 bytes addressed by lane 4 e + i / 4 of the group.  With lane
+// s of a group addressing row s / 4, columns 4 (s % 4) .. +3 of a 4-row x 16-column patch, lane
+// i ends up with the four rows of column i: a k-contiguous MFMA operand out of a row-major tile.
+typedef short v4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4s la_read_tr(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p);
+}
+
 __device__ __forceinline__ void la_barrier() {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
@@ -70,9 +92,10 @@ __device__ __forceinline__ void la_barrier() {
 __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const uint32_t* __restrict__ mbits,
                                                                           const bf16_t* __restrict__ hz, int Tq, int Tk,
                                                                           bf16_t* __restrict__ HZ) {
-  __shared__ __attribute__((aligned(1024))) unsigned char st0[LA_STAGE];
-  __shared__ __attribute__((aligned(1024))) unsigned char st1[LA_STAGE];
-  __shared__ __attribute__((aligned(1024))) unsigned char st2[LA_STAGE];
+  // three stages, each a tile of hz rows and the mask words that go with it; separate objects,
+  // so the compiler can tell the asynchronous fill of one stage from the reads of another
+  __shared__ __attribute__((aligned(1024))) unsigned char hz0[LA_B_STAGE], hz1[LA_B_STAGE], hz2[LA_B_STAGE];
+  __shared__ __attribute__((aligned(1024))) uint32_t mw0[LA_ROWS], mw1[LA_ROWS], mw2[LA_ROWS];
   __shared__ uint4 lut[256];
   const int n0 = blockIdx.x * LA_COLS, row0 = blockIdx.y * LA_ROWS, bh = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, l32 = lane & 31, hf = lane >> 5;
@@ -91,17 +114,12 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const 
   // first three wavefronts also 256 mask words each
   const char* hz_bh = (const char*)(hz + (size_t)bh * Tk * HZ_ELEMS + n0);  // uniform
   const char* mb_bh = (const char*)(mbits + (size_t)bh * KT * TqP + row0 + 256 * w);
-  unsigned lane16 = (unsigned)lane * 16u;
-  auto fetch = [&](int kt, unsigned char* st) {
+  const unsigned lane16 = (unsigned)lane * 16u;
+  auto fetch = [&](int kt, unsigned char* hzs, uint32_t* mws) {
     const int j = min(kt * LA_KT + 4 * w + (lane >> 4), Tk - 1);  // rows past Tk repeat the last one (their mask bits are 0)
-    unsigned off = (unsigned)j * (unsigned)(HZ_ELEMS * 2) + (unsigned)(lane & 15) * 16u;
-    asm volatile("" : "+v"(off));  // 32-bit offset arithmetic stays next to its use: scalar base + vector offset form
-    __builtin_amdgcn_global_load_lds((const void*)(hz_bh + off), (la_lds_ptr_t)(st + w * 1024 + (w >> 1) * 64), 16, 0, 0);
-    if (w < 3) {
-      asm volatile("" : "+v"(lane16));
-      __builtin_amdgcn_global_load_lds((const void*)(mb_bh + (size_t)kt * TqP * 4 + lane16),
-                                       (la_lds_ptr_t)(st + LA_B_STAGE + w * 1024), 16, 0, 0);
-    }
+    const unsigned off = (unsigned)j * (unsigned)(HZ_ELEMS * 2) + (unsigned)(lane & 15) * 16u;
+    la_copy16(hz_bh, off, hzs + w * 1024 + (w >> 1) * 64);
+    if (w < 3) la_copy16(mb_bh + (size_t)kt * TqP * 4, lane16, mws + w * 256);
   };
   auto wait_keep = [&](bool keep_one) {  // wait until at most one tile's copies of this wavefront are in flight
     if (!keep_one) __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -109,74 +127,81 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const 
     else __builtin_amdgcn_s_waitcnt(0x0F71);
   };
 
+  // this lane's address inside a B patch for the transposing reads: lane group g = lane / 16
+  // serves columns 16 (g % 2) .. +15 and staged rows 8 (g / 2) + (0..3) [+ 4 for the second read]
+  const int tr_off = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LA_B_ROW + (lane >> 5) * 64 +
+                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
   v16f acc[3][4];
 #pragma unroll
   for (int a = 0; a < 3; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
 
-  auto compute = [&](const unsigned char* st) {
-    uint32_t mw[3];
-#pragma unroll
-    for (int mt = 0; mt < 3; ++mt) mw[mt] = *(const uint32_t*)(st + LA_B_STAGE + (96 * w + 32 * mt + l32) * 4);
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      v8bf aop[3], bop[4];
-#pragma unroll
-      for (int mt = 0; mt < 3; ++mt) {
-        const uint4 e = lut[(mw[mt] >> (16 * ks + 8 * hf)) & 0xffu];
-        union { uint4 u; v8bf v; } c;
-        c.u = e;
-        aop[mt] = c.v;
-      }
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt) {
-        union { bf16_t h[8]; v8bf v; } u;
-        const int r0 = 16 * ks + 8 * hf;  // 8 consecutive staged rows, all in one shifted group
-        const unsigned char* col = st + r0 * LA_B_ROW + (r0 >> 3) * 64 + (32 * nt + l32) * 2;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) u.h[e] = *(const bf16_t*)(col + e * LA_B_ROW);
-        bop[nt] = u.v;
-      }
-#pragma unroll
-      for (int mt = 0; mt < 3; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aop[mt], bop[nt], acc[mt][nt], 0, 0, 0);
-    }
-  };
-
-#define LA_STEP(KTI, CUR, FILL)              \
-  {                                          \
-    const int kt_ = (KTI);                   \
-    if (kt_ + 2 < KT) fetch(kt_ + 2, FILL);  \
-    compute(CUR);                            \
-    wait_keep(kt_ + 2 < KT);                 \
-    la_barrier();                            \
+#define LA_COMPUTE(HZS, MWS)                                                                              \
+  {                                                                                                       \
+    uint32_t mw[3];                                                                                       \
+    _Pragma("unroll") for (int mt = 0; mt < 3; ++mt) mw[mt] = MWS[96 * w + 32 * mt + l32];                \
+    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                    \
+      v8bf aop[3], bop[4];                                                                                \
+      _Pragma("unroll") for (int mt = 0; mt < 3; ++mt) {                                                  \
+        union { uint4 u; v8bf v; } c;                                                                     \
+        c.u = lut[(mw[mt] >> (16 * ks + 8 * hf)) & 0xffu];                                                \
+        aop[mt] = c.v;                                                                                    \
+      }                                                                                                   \
+      _Pragma("unroll") for (int nt = 0; nt < 4; ++nt) {                                                  \
+        /* staged rows 16 ks + 8 hf + (0..7) of column 32 nt + l32, by two transposing reads */           \
+        union { v4s h[2]; v8bf v; } u;                                                                    \
+        const int r0 = 16 * ks, c0 = 64 * nt;                                                             \
+        u.h[0] = la_read_tr(&HZS[tr_off + r0 * LA_B_ROW + (r0 >> 3) * 64 + c0]);                          \
+        u.h[1] = la_read_tr(&HZS[tr_off + (r0 + 4) * LA_B_ROW + (r0 >> 3) * 64 + c0]);                    \
+        bop[nt] = u.v;                                                                                    \
+      }                                                                                                   \
+      _Pragma("unroll") for (int mt = 0; mt < 3; ++mt)                                                    \
+        _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                                  \
+          acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[nt], aop[mt], acc[mt][nt], 0, 0, 0);  \
+    }                                                                                                     \
   }
-  fetch(0, st0);
-  if (KT > 1) fetch(1, st1);
+
+#define LA_STEP(KTI, HC, MC, HF, MF)           \
+  {                                            \
+    const int kt_ = (KTI);                     \
+    if (kt_ + 2 < KT) fetch(kt_ + 2, HF, MF);  \
+    LA_COMPUTE(HC, MC)                         \
+    wait_keep(kt_ + 2 < KT);                   \
+    la_barrier();                              \
+  }
+  fetch(0, hz0, mw0);
+  if (KT > 1) fetch(1, hz1, mw1);
   wait_keep(KT > 1);
   __syncthreads();  // also publishes the table
   int kt = 0;
   for (; kt + 3 <= KT; kt += 3) {
-    LA_STEP(kt, st0, st2)
-    LA_STEP(kt + 1, st1, st0)
-    LA_STEP(kt + 2, st2, st1)
+    LA_STEP(kt, hz0, mw0, hz2, mw2)
+    LA_STEP(kt + 1, hz1, mw1, hz0, mw0)
+    LA_STEP(kt + 2, hz2, mw2, hz1, mw1)
   }
-  if (kt < KT) LA_STEP(kt, st0, st2)
-  if (kt + 1 < KT) LA_STEP(kt + 1, st1, st0)
+  if (kt < KT) LA_STEP(kt, hz0, mw0, hz2, mw2)
+  if (kt + 1 < KT) LA_STEP(kt + 1, hz1, mw1, hz0, mw0)
 #undef LA_STEP
+#undef LA_COMPUTE
 
+  // The tiles were accumulated transposed (summary entries along the MFMA rows, query blocks
+  // along its columns), so a lane owns ONE query block and runs of 4 consecutive entries of
+  // its summary: 8-byte stores, the two lane halves completing 16 contiguous bytes.
 #pragma unroll
-  for (int mt = 0; mt < 3; ++mt)
+  for (int mt = 0; mt < 3; ++mt) {
+    const int i = row0 + 96 * w + 32 * mt + l32;
+    if (i < Tq) {
+      bf16_t* dst = HZ + ((size_t)bh * Tq + i) * HZ_ELEMS + n0 + 4 * hf;
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int i = row0 + 96 * w + 32 * mt + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (i < Tq) HZ[((size_t)bh * Tq + i) * HZ_ELEMS + n0 + 32 * nt + l32] = f32_to_bf16(acc[mt][nt][r]);
-      }
+        for (int g = 0; g < 4; ++g) {
+          const v16f& a = acc[mt][nt];
+          *(uint2*)(dst + 32 * nt + 8 * g) = make_uint2(pack_bf16x2(a[4 * g], a[4 * g + 1]), pack_bf16x2(a[4 * g + 2], a[4 * g + 3]));
+        }
+    }
+  }
 }
 
 size_t marginal_bits_bytes(const Problem& p) {
