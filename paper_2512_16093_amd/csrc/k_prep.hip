@@ -22,18 +22,18 @@ namespace sla {
 constexpr int STAGE_STRIDE = 2 * D + 16;  // bytes per staged hz row (padded against bank conflicts)
 
 template <int PHI>
-__global__ void __launch_bounds__(256) prep_kv_kernel(
+__global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk,
     const float* __restrict__ mu_k, const float* __restrict__ dv, const bf16_t* __restrict__ W,
     int want_quant, int want_linear, int8_t* __restrict__ k8, uint8_t* __restrict__ v8,
     float* __restrict__ dk, bf16_t* __restrict__ hz) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[128 * STAGE_STRIDE + 16 * D * 4];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[128 * STAGE_STRIDE + 4 * D * 4];
   __shared__ float wave_amax[4];
   unsigned char* kq = smem;                       // [8192]  K codes, fragment order
   unsigned char* vq = smem + KV_FRAG_BYTES;       // [8192]  V codes, fragment order
   unsigned char* phit = smem + 2 * KV_FRAG_BYTES; // [16384] phi(K)^T bf16, B-operand order
   unsigned char* stage = smem;                    // [128][STAGE_STRIDE] aliases the three above
-  float* zred = (float*)(smem + 128 * STAGE_STRIDE);  // [16][128]
+  float* zred = (float*)(smem + 128 * STAGE_STRIDE);  // [4][128] per-wavefront column sums of phi(K)
 
   const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk;
   const int t = threadIdx.x, cg = t & 15, m = t >> 4, lane = t & 63, w = t >> 6;
@@ -66,6 +66,12 @@ __global__ void __launch_bounds__(256) prep_kv_kernel(
       mu[e] = mu_k[(size_t)bh * D + cg * 8 + e];
       dvc[e] = dv[(size_t)bh * D + cg * 8 + e];
     }
+    float rdv[8];  // 1 / delta_V, refined to (almost always) the correctly rounded reciprocal
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float r0 = __builtin_amdgcn_rcpf(dvc[e]);
+      rdv[e] = __builtin_fmaf(__builtin_fmaf(-dvc[e], r0, 1.0f), r0, r0);
+    }
     float kt[4][8], amax = 0.f;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -79,13 +85,17 @@ __global__ void __launch_bounds__(256) prep_kv_kernel(
     __syncthreads();
     amax = fmaxf(fmaxf(wave_amax[0], wave_amax[1]), fmaxf(wave_amax[2], wave_amax[3]));
     const float delta = amax > 0.f ? amax / 127.0f : 1.0f;
+    // K codes by multiplication with the reciprocal: differs from a true division only at
+    // rounding ties, where one INT8 step moves a score by delta_Q delta_K (the FP8 V codes, whose
+    // steps are coarse, keep the true division)
+    const float inv_delta = 1.0f / delta;
     if (t == 0) dk[(size_t)bh * Tk + j] = delta;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       uint32_t lo = 0, hi = 0;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float c = __builtin_rintf(kt[r][e] / delta);
+        float c = __builtin_rintf(kt[r][e] * inv_delta);
         c = fminf(fmaxf(c, -127.f), 127.f);
         const uint32_t byte = (uint32_t)((int)c) & 0xffu;
         if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
@@ -96,7 +106,13 @@ __global__ void __launch_bounds__(256) prep_kv_kernel(
     for (int e = 0; e < 8; ++e) {
       float x[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) x[r] = clamp_e4m3(vf[r][e] / dvc[e]);
+      for (int r = 0; r < 4; ++r) {
+        // quotient by reciprocal + one correction step: the correctly rounded v / delta_V for the
+        // magnitudes that occur here, at a third of the cost of the general division sequence
+        float qv = vf[r][e] * rdv[e];
+        qv = __builtin_fmaf(__builtin_fmaf(-qv, dvc[e], vf[r][e]), rdv[e], qv);
+        x[r] = clamp_e4m3(qv);
+      }
       int code = cvt_pk_e4m3(x[0], x[1], 0, false);
       code = cvt_pk_e4m3(x[2], x[3], code, true);
       *(int*)(vq + vfrag_offset(4 * m, cg * 8 + e)) = code;
@@ -151,7 +167,10 @@ __global__ void __launch_bounds__(256) prep_kv_kernel(
       const int c = cg * 8 + e;
       const uint2 pk = make_uint2(pack_bf16x2(ph[0][e], ph[1][e]), pack_bf16x2(ph[2][e], ph[3][e]));
       *(uint2*)(phit + ((s2 * 128 + c) * 2 + hf) * 16 + (g & 1) * 8) = pk;
-      zred[m * D + c] = ph[0][e] + ph[1][e] + ph[2][e] + ph[3][e];
+      float zs = ph[0][e] + ph[1][e] + ph[2][e] + ph[3][e];  // 4 rows of this thread, then the 4 row groups of the wavefront
+      zs += __shfl_xor(zs, 16);
+      zs += __shfl_xor(zs, 32);
+      if (lane < 16) zred[w * D + c] = zs;
     }
   }
 
@@ -191,7 +210,7 @@ __global__ void __launch_bounds__(256) prep_kv_kernel(
   float zsum = 0.f;
   if (t < D) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) zsum += zred[r * D + t];
+    for (int r = 0; r < 4; ++r) zsum += zred[r * D + t];
   }
   __syncthreads();  // every wavefront is done reading phit: the staging area may overwrite it
 #pragma unroll
