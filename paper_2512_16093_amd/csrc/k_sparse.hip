@@ -126,17 +126,27 @@ __device__ __forceinline__ int half_max(v16i& s, int key0, int hf, int kvalid) {
   return max(m0, m1);
 }
 
-// Row maximum over both lanes of the query -> new reference level r.  Returns the exponent
-// offset `offs` such that P = 448 * 2^(t - r) = exp2(fma(biased score as float, c2s, offs)),
-// where c2s = c2 * 2^26 and t = c2 * s.
-__device__ __forceinline__ float new_reference(int imax, float c2s, float& r) {
+// Per key block: the constants that turn a biased score pattern into exponents.  With
+// c2s = c2 * 2^26 (c2 = log2(e) / sqrt(d) * delta_Q * delta_K) and x the pattern as a float,
+//   t = c2 * s = fma(x, c2s, nb),   nb = -BIAS * c2s.
+struct BlockConsts {
+  float c2s;   // slope
+  float nbg;   // nb + one score step: the guard keeps t - r <= 0 whatever the rounding of the products
+  float lnb;   // log2(448) + nb: offs = lnb - r makes exp2(fma(x, c2s, offs)) = 448 * 2^(t - r)
+};
+__device__ __forceinline__ BlockConsts block_consts(float c2s) {
+  const float nb = -__int_as_float(BIAS_I) * c2s;
+  return BlockConsts{c2s, __builtin_fmaf(c2s, SCORE_STEP, nb), LOG2_448 + nb};
+}
+
+// Row maximum over both lanes of the query -> new reference level r; returns offs (see above).
+__device__ __forceinline__ float new_reference(int imax, const BlockConsts& bc, float pos_inf, float& r) {
   // after the swap one register holds the lower lane's value and the other the upper lane's, in both lanes
   const auto sw = __builtin_amdgcn_permlane32_swap(imax, imax, false, false);
   imax = max((int)sw[0], (int)sw[1]);
-  const float nb = -__int_as_float(BIAS_I) * c2s;
-  // the guard of one score step keeps t - r <= 0 whatever the rounding of the two products
-  r = fmaxf(r, __builtin_ceilf(__builtin_fmaf(__int_as_float(imax), c2s, nb) + c2s * SCORE_STEP));
-  return (LOG2_448 - r) + nb;
+  const float cand = __builtin_ceilf(__builtin_fmaf(__int_as_float(imax), bc.c2s, bc.nbg));
+  r = __builtin_amdgcn_fmed3f(r, cand, pos_inf);  // max(r, cand) in one instruction (both are finite)
+  return bc.lnb - r;
 }
 
 // Four biased scores (accumulator registers 4g .. 4g+3 of one half) -> four FP8 codes of P in
@@ -157,16 +167,20 @@ __device__ __forceinline__ int codes_quad(const v16i& s, int g, int key0, int hf
 
 // E8M0 code of 2^(r_prev - R): brings the P codes made at level r_prev to the accumulators'
 // level R (r_prev - R <= 64 by the renormalisation rule; far below R the contribution vanishes).
-__device__ __forceinline__ int level_scale(float r_prev, float R) {
-  return 127 + (int)__builtin_amdgcn_fmed3f(r_prev - R, -127.f, 127.f);
+// Rm127 = R - 127 is kept alongside R.
+__device__ __forceinline__ int level_scale(float r_prev, float Rm127) {
+  return (int)__builtin_amdgcn_fmed3f(r_prev - Rm127, 0.f, 254.f);
 }
 
 // Rare: the reference level has run more than 64 binades ahead of the accumulators' level
 // (always so after the first block, whose R starts at "minus infinity"): bring them to level r.
-__device__ __forceinline__ void renormalise(float r, float& R, v16f (&acc)[4], v16f& accl) {
+__device__ __forceinline__ void renormalise(float r, float& R, float& Rm127, v16f (&acc)[4], v16f& accl) {
   const bool up = r - R > 64.f;
   const float down = up ? __builtin_amdgcn_exp2f(R - r) : 1.0f;
-  if (up) R = r;
+  if (up) {
+    R = r;
+    Rm127 = r - 127.f;
+  }
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -249,7 +263,9 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
   // R starts far below any reachable level, so the first block renormalises (0 * 0) and sets R
-  float r = -1e30f, R = -1e30f;
+  float r = -1e30f, R = -1e30f, Rm127 = -1e30f;
+  float pos_inf = INFINITY;
+  asm volatile("" : "+s"(pos_inf));  // in a scalar register: the third operand of the med3 that serves as max
   // A operand that sums P over the keys: FP8 1.0 in rows 0 and 4 of a 32-row tile, so the
   // row sum of a query lands in accumulator register 0 of both of its lanes.
   const int one4 = (l32 == 0 || l32 == 4) ? 0x38383838 : 0;
@@ -266,30 +282,42 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const size_t rec0 = (size_t)bh * A.Tk * KV_FRAG_BYTES;
   // Asynchronous global -> LDS copy of one block's K or V record (no registers in between).
   // Wavefront w copies the PW adjacent 1 KiB pieces [PW w, PW w + PW) of the record, lane l
-  // supplying bytes [16 l, 16 l + 16) of a piece; the address is a uniform base (scalar
-  // registers) + one 32-bit per-lane offset + the instruction's immediate, which the hardware
-  // adds to the LDS address as well.
+  // supplying bytes [16 l, 16 l + 16) of a piece; the instruction's immediate offset is added
+  // to the global and to the LDS address alike.
   constexpr int PW = CH / 2;
   static_assert(PW == 2 || PW == 4, "pieces per wavefront per record");
   const int w_s = __builtin_amdgcn_readfirstlane(w);  // wavefront index as a scalar
-  unsigned lane_off = (unsigned)(w * PW * 1024 + lane * 16);
+  const unsigned lane_off = (unsigned)(w * PW * 1024 + lane * 16);
   const char* const k8_bh = (const char*)A.k8 + rec0;  // this (b,h)'s records: uniform, loop invariant
   const char* const v8_bh = (const char*)A.v8 + rec0;
+  // Written as inline assembly so that (a) the record's address stays in scalar registers (base +
+  // j * 8 KiB by scalar arithmetic, one loop-invariant vector offset per lane) and (b) the compiler
+  // does not know copies are in flight: it would otherwise make every LDS read it cannot prove
+  // disjoint wait for ALL of them.  The pipeline waits for them by explicit counts (loads the
+  // compiler does not know about only make its own waits more conservative).
   auto fetch_rec = [&](const char* base_bh, int j, uint4* dst) {
-    // the empty asm keeps the (32-bit) offset arithmetic next to its use, so the scalar-base
-    // addressing form is selected: base_bh in scalar registers + one vector offset
-    asm volatile("" : "+v"(lane_off));
-    const char* g = base_bh + (((unsigned)j << 13) + lane_off);
     static_assert(KV_FRAG_BYTES == 1 << 13, "record size");
-    lds_ptr_t l = (lds_ptr_t)(dst + w_s * PW * 64);
-    __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 1024, 0);
-    if constexpr (PW == 4) {
-      __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 2048, 0);
-      __builtin_amdgcn_global_load_lds((const void*)g, l, 16, 3072, 0);
+    const char* rec = base_bh + (unsigned)__builtin_amdgcn_readfirstlane(j << 13);
+    const unsigned lds_addr = (unsigned)(uintptr_t)(lds_ptr_t)(dst + w_s * PW * 64);
+    if constexpr (PW == 2) {
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                   "global_load_lds_dwordx4 %1, %0\n\t"
+                   "global_load_lds_dwordx4 %1, %0 offset:1024"
+                   :
+                   : "s"(rec), "v"(lane_off), "s"(lds_addr)
+                   : "memory", "m0");
+    } else {
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t"
+                   "global_load_lds_dwordx4 %1, %0\n\t"
+                   "global_load_lds_dwordx4 %1, %0 offset:1024\n\t"
+                   "global_load_lds_dwordx4 %1, %0 offset:2048\n\t"
+                   "global_load_lds_dwordx4 %1, %0 offset:3072"
+                   :
+                   : "s"(rec), "v"(lane_off), "s"(lds_addr)
+                   : "memory", "m0");
     }
   };
-  auto dk_of = [&](int j) { return *(const float*)((const char*)dkrow + ((unsigned)j << 2)); };
+  auto dk_of = [&](int j) { return *(const float*)((const char*)dkrow + (unsigned)__builtin_amdgcn_readfirstlane(j << 2)); };
   const int kvalid_last = A.N - (A.Tk - 1) * BK;  // valid keys of the last key block
   const bool ragged = kvalid_last < BK;
 
@@ -330,20 +358,20 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     fetch_rec(k8_bh, j4, KFILL);                                                                       \
     const int jn_ = crow[min(b_ + 5, last)];                                                          \
     const float dn_ = dk_of(j4);                                                                      \
-    const float c2s_ = cq * d0;                                                                       \
+    const BlockConsts bc_ = block_consts(cq * d0);                                                    \
     SB s1 = qk_step(kfB[0], q8[0], bias16);                                                           \
     SB const int mA_ = half_max<false>(s0, 0, hf, 0);                                                 \
     SB s1 = qk_step(kfB[1], q8[1], s1);                                                               \
-    SB const float offsA_ = new_reference(mA_, c2s_, r);                                              \
+    SB const float offsA_ = new_reference(mA_, bc_, pos_inf, r);                                      \
     const float rA_ = r;                                                                              \
     SB s1 = qk_step(kfB[2], q8[2], s1);                                                               \
-    SB PBN[0] = codes_quad<false>(s0, 0, 0, hf, c2s_, offsA_, 0, PBN[0]);                                      \
+    SB PBN[0] = codes_quad<false>(s0, 0, 0, hf, bc_.c2s, offsA_, 0, PBN[0]);                                      \
     SB s1 = qk_step(kfB[3], q8[3], s1);                                                               \
-    SB PBN[1] = codes_quad<false>(s0, 1, 0, hf, c2s_, offsA_, 0, PBN[1]);                                      \
+    SB PBN[1] = codes_quad<false>(s0, 1, 0, hf, bc_.c2s, offsA_, 0, PBN[1]);                                      \
     SB pv_tile(vfa[0], vfa[1], PBP, sc_prev, acc[0]);                                                 \
-    SB PBN[2] = codes_quad<false>(s0, 2, 0, hf, c2s_, offsA_, 0, PBN[2]);                                      \
+    SB PBN[2] = codes_quad<false>(s0, 2, 0, hf, bc_.c2s, offsA_, 0, PBN[2]);                                      \
     SB pv_tile(vfa[2], vfa[3], PBP, sc_prev, acc[1]);                                                 \
-    SB PBN[3] = codes_quad<false>(s0, 3, 0, hf, c2s_, offsA_, 0, PBN[3]);                                      \
+    SB PBN[3] = codes_quad<false>(s0, 3, 0, hf, bc_.c2s, offsA_, 0, PBN[3]);                                      \
     /* ---- phase 2 */                                                                                \
     read4(VPREV, lane, 4, vfb);                                                                       \
     read4(KNEXT, lane, 4, kfB);                                                                       \
@@ -351,15 +379,15 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     SB s0 = qk_step(kfA[0], q8[0], bias16);                                                           \
     SB const int mB_ = half_max<false>(s1, 32, hf, 0);                                                \
     SB s0 = qk_step(kfA[1], q8[1], s0);                                                               \
-    SB const float offsB_ = new_reference(mB_, c2s_, r);                                              \
+    SB const float offsB_ = new_reference(mB_, bc_, pos_inf, r);                                      \
     SB s0 = qk_step(kfA[2], q8[2], s0);                                                               \
-    SB PBN[4] = codes_quad<false>(s1, 0, 32, hf, c2s_, offsB_, 0, PBN[4]);                                     \
+    SB PBN[4] = codes_quad<false>(s1, 0, 32, hf, bc_.c2s, offsB_, 0, PBN[4]);                                     \
     SB s0 = qk_step(kfA[3], q8[3], s0);                                                               \
-    SB PBN[5] = codes_quad<false>(s1, 1, 32, hf, c2s_, offsB_, 0, PBN[5]);                                     \
+    SB PBN[5] = codes_quad<false>(s1, 1, 32, hf, bc_.c2s, offsB_, 0, PBN[5]);                                     \
     SB pv_tile(vfb[0], vfb[1], PBP, sc_prev, acc[2]);                                                 \
-    SB PBN[6] = codes_quad<false>(s1, 2, 32, hf, c2s_, offsB_, 0, PBN[6]);                                     \
+    SB PBN[6] = codes_quad<false>(s1, 2, 32, hf, bc_.c2s, offsB_, 0, PBN[6]);                                     \
     SB pv_tile(vfb[2], vfb[3], PBP, sc_prev, acc[3]);                                                 \
-    SB PBN[7] = codes_quad<false>(s1, 3, 32, hf, c2s_, offsB_, 0, PBN[7]);                                     \
+    SB PBN[7] = codes_quad<false>(s1, 3, 32, hf, bc_.c2s, offsB_, 0, PBN[7]);                                     \
     SB pv_rowsum(ones, PBP, sc_prev, accl);                                                           \
     SB const float rsel_ = hf ? r : rA_;   /* level of this lane's half of the new codes */           \
     j2 = j3; j3 = j4; j4 = jn_;                                                                       \
@@ -367,8 +395,8 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     /* anchor: keeps every piece inside this step */                                                  \
     asm volatile("" : "+v"(PBN), "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(accl),  \
                  "+v"(s0), "+s"(j4), "+s"(d3));                                                       \
-    SB if (__any(r - R > 64.f)) renormalise(r, R, acc, accl);                                         \
-    sc_prev = level_scale(rsel_, R);                                                                  \
+    SB if (__any(r - R > 64.f)) renormalise(r, R, Rm127, acc, accl);                                  \
+    sc_prev = level_scale(rsel_, Rm127);                                                                  \
     __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);                                                           \
     stage_barrier();                                                                                  \
   }
@@ -423,7 +451,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       const uint4* vp = sp == 0 ? vst0 : sp == 1 ? vst1 : sp == 2 ? vst2 : vst3;
       read4(vp, lane, 0, vfa);
       read4(vp, lane, 4, vfb);
-      const float c2t = cq * d0;
+      const BlockConsts bct = block_consts(cq * d0);
       s1 = qk_step(kfB[0], q8[0], bias16);
 #pragma unroll
       for (int u = 1; u < 4; ++u) s1 = qk_step(kfB[u], q8[u], s1);
@@ -433,18 +461,18 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       pv_tile(vfb[2], vfb[3], pb_b, sc_prev, acc[3]);
       pv_rowsum(ones, pb_b, sc_prev, accl);
       const int mAt = half_max<true>(s0, 0, hf, kvalid_last);
-      const float offsAt = new_reference(mAt, c2t, r);
+      const float offsAt = new_reference(mAt, bct, pos_inf, r);
       const float rAt = r;
       v8i pb_t = {};
 #pragma unroll
-      for (int g = 0; g < 4; ++g) pb_t[g] = codes_quad<true>(s0, g, 0, hf, c2t, offsAt, kvalid_last, pb_t[g]);
+      for (int g = 0; g < 4; ++g) pb_t[g] = codes_quad<true>(s0, g, 0, hf, bct.c2s, offsAt, kvalid_last, pb_t[g]);
       const int mBt = half_max<true>(s1, 32, hf, kvalid_last);
-      const float offsBt = new_reference(mBt, c2t, r);
+      const float offsBt = new_reference(mBt, bct, pos_inf, r);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) pb_t[4 + g] = codes_quad<true>(s1, g, 32, hf, c2t, offsBt, kvalid_last, pb_t[4 + g]);
+      for (int g = 0; g < 4; ++g) pb_t[4 + g] = codes_quad<true>(s1, g, 32, hf, bct.c2s, offsBt, kvalid_last, pb_t[4 + g]);
       pb_b = pb_t;
-      if (__any(r - R > 64.f)) renormalise(r, R, acc, accl);
-      sc_prev = level_scale(hf ? r : rAt, R);
+      if (__any(r - R > 64.f)) renormalise(r, R, Rm127, acc, accl);
+      sc_prev = level_scale(hf ? r : rAt, Rm127);
     }
     {  // P.V of the last block
       const int sl = last & 3;
