@@ -187,74 +187,17 @@ __global__ void __launch_bounds__(256) scores_kernel(const float* __restrict__ q
 
 // select: one WAVEFRONT per (b,h,i) row; the row's scores live in registers (KPL per lane,
 // block j = lane + 64 m in register m) as order-preserving 32-bit keys.  The n_c-th and the
-// (n_c+n_m)-th largest keys are found exactly by a 4-pass, 8-bit-digit radix select with a
-// 256-bin histogram in LDS (one per wavefront); blocks whose key equals a threshold key are
-// ranked by ascending j with ballots, so equal scores rank by ascending block index and the
-// result is exact and deterministic.  Outputs: the int8 mask row, the ascending critical
-// list, and the marginal indicator as bf16 0/1 in the MFMA fragment order the accumulation
-// kernel reads (16-byte chunk per 8 consecutive blocks; see lin_accumulate).
+// (n_c+n_m)-th largest keys are found exactly, bit by bit from the top: a bit of the threshold
+// is set when at least `rank` keys are >= the candidate with that bit set.  The counts come
+// from wave-wide compares (one vector compare per register, the population count and the sum
+// on the scalar unit), so there is no shared-memory traffic and no atomic.  Blocks whose key
+// equals a threshold key are ranked by ascending j with ballots, so equal scores rank by
+// ascending block index and the result is exact and deterministic.  Outputs: the int8 mask
+// row, the ascending critical list, and the marginal ballots as words of the bit matrix the
+// accumulation kernel reads (see lin_accumulate).
 __device__ __forceinline__ uint32_t order_bits(float f) {
   const uint32_t u = __float_as_uint(f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Histogram search: given the 256 counters of the current digit (lane l reads bins 4l..4l+3),
-// find the bin that holds descending rank `remaining` among the candidates and the number of
-// candidates in higher bins.
-__device__ __forceinline__ void find_bin(const unsigned* hist, int lane, int remaining, int& digit, int& above) {
-  const unsigned c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
-  const int own = (int)(c0 + c1 + c2 + c3);
-  int S = own;  // candidates in bins >= 4 lane (suffix sum over lanes)
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int up = __shfl_down(S, o);
-    if (lane + o < 64) S += up;
-  }
-  const int above_lane = S - own;
-  const bool mine = above_lane < remaining && remaining <= S;
-  int d = 0, ab = 0;
-  if (mine) {
-    int a = above_lane;
-    if (remaining <= a + (int)c3) { d = 4 * lane + 3; ab = a; }
-    else { a += c3;
-      if (remaining <= a + (int)c2) { d = 4 * lane + 2; ab = a; }
-      else { a += c2;
-        if (remaining <= a + (int)c1) { d = 4 * lane + 1; ab = a; }
-        else { a += c1; d = 4 * lane; ab = a; } } }
-  }
-  const int src = __ffsll((long long)__ballot(mine)) - 1;
-  digit = __shfl(d, src);
-  above = __shfl(ab, src);
-}
-
-// Key of descending rank `rank` (1-based) and how many of the keys equal to it belong to the
-// top `rank` (>= 1), given the first digit already resolved (prefix = top byte, remaining).
-// hist: 256 counters owned by this wavefront.
-template <int KPL>
-__device__ __forceinline__ void radix_rest(const uint32_t (&key)[KPL], uint32_t prefix, int remaining,
-                                           unsigned* hist, int lane, uint32_t& kth, int& take) {
-#pragma unroll
-  for (int pass = 1; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) hist[4 * lane + c] = 0;
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int m = 0; m < KPL; ++m) {
-      const bool cand = (key[m] >> (shift + 8)) == prefix;
-      if (__any(cand)) {  // few keys survive the first digit: skip the LDS atomic when no lane has one
-        if (cand) atomicAdd(&hist[(key[m] >> shift) & 0xffu], 1u);
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-    int digit, above;
-    find_bin(hist, lane, remaining, digit, above);
-    prefix = (prefix << 8) | (uint32_t)digit;
-    remaining -= above;
-    __builtin_amdgcn_wave_barrier();
-  }
-  kth = prefix;
-  take = remaining;
 }
 
 template <int KPL>
@@ -262,11 +205,9 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
                                                      int n_c, int n_m, int8_t* __restrict__ mask,
                                                      int32_t* __restrict__ crit, int32_t* __restrict__ marg,
                                                      uint32_t* __restrict__ mbits) {
-  __shared__ unsigned hist_all[4][256];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const size_t row = (size_t)blockIdx.x * 4 + w;
   if (row >= (size_t)rows) return;  // whole wavefront; no workgroup barrier is used below
-  unsigned* hist = hist_all[w];
   const float* srow = scores + row * Tk;
   uint32_t key[KPL];
 #pragma unroll
@@ -274,9 +215,10 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
     const int j = lane + 64 * m;
     key[m] = j < Tk ? order_bits(srow[j]) : 0u;
   }
-  // Spread the keys over the whole 32-bit range (subtract the row minimum, shift out the common
-  // leading zeros): order and ties are unchanged, but the first radix digits now separate the
-  // scores instead of all landing in the one histogram bin of their common exponent.
+  // Subtract the row minimum and shift out the common leading zeros: order and ties are
+  // unchanged, padding (key 0) ties with the minimum, and the search below only has to visit
+  // the bits in which the keys can differ.
+  int low;
   {
     uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
@@ -292,25 +234,30 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
     }
     const uint32_t span = kmax - kmin;
     const int lz = span ? __builtin_clz(span) : 0;
+    low = span ? lz : 32;  // all keys equal: nothing to search
 #pragma unroll
     for (int m = 0; m < KPL; ++m) key[m] = (lane + 64 * m < Tk) ? ((key[m] - kmin) << lz) : 0u;  // padding ties with the minimum: never above a threshold
   }
-  uint32_t k1, k2 = 0;
-  int t1, t2 = 0;
-  {
-    // first digit: one histogram of all keys serves both thresholds
+  // k1 / k2: the n_c-th / (n_c+n_m)-th largest key; t1 / t2: how many of the keys equal to
+  // it belong to the top n_c / n_c+n_m (>= 1).  Bits below `low` are zero in every key.
+  uint32_t k1 = 0, k2 = 0;
+  const int rank2 = n_c + n_m;
+  for (int bit = 31; bit >= low; --bit) {
+    const uint32_t c1 = k1 | (1u << bit), c2 = k2 | (1u << bit);
+    int n1 = 0, n2 = 0;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) hist[4 * lane + c] = 0;
-    __builtin_amdgcn_wave_barrier();
+    for (int m = 0; m < KPL; ++m) {  // (padding keys are 0 and never reach a candidate)
+      n1 += __popcll(__ballot(key[m] >= c1));
+      if (n_m > 0) n2 += __popcll(__ballot(key[m] >= c2));
+    }
+    if (n1 >= n_c) k1 = c1;
+    if (n2 >= rank2) k2 = c2;
+  }
+  int t1 = n_c, t2 = rank2;
 #pragma unroll
-    for (int m = 0; m < KPL; ++m) atomicAdd(&hist[key[m] >> 24], 1u);
-    __builtin_amdgcn_wave_barrier();
-    int d1, a1, d2 = 0, a2 = 0;
-    find_bin(hist, lane, n_c, d1, a1);
-    if (n_m > 0) find_bin(hist, lane, n_c + n_m, d2, a2);
-    __builtin_amdgcn_wave_barrier();
-    radix_rest<KPL>(key, (uint32_t)d1, n_c - a1, hist, lane, k1, t1);
-    if (n_m > 0) radix_rest<KPL>(key, (uint32_t)d2, n_c + n_m - a2, hist, lane, k2, t2);
+  for (int m = 0; m < KPL; ++m) {
+    t1 -= __popcll(__ballot(key[m] > k1));
+    if (n_m > 0) t2 -= __popcll(__ballot(key[m] > k2));
   }
 
   const unsigned long long lt = (1ull << lane) - 1ull;
@@ -370,9 +317,18 @@ void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t*
   const unsigned grid = (unsigned)((rows + 3) / 4);
   const int need = (p.Tk + 63) / 64;
 #define SLA_SELECT(K) select_kernel<K><<<grid, 256, 0, stream>>>(scores, rows, p.Tq, p.Tk, p.n_c, p.n_m, mask, crit, marg, mbits)
+  // registers per lane: the smallest instantiation that holds the row
   if (need <= 2) SLA_SELECT(2);
+  else if (need <= 4) SLA_SELECT(4);
   else if (need <= 8) SLA_SELECT(8);
+  else if (need <= 12) SLA_SELECT(12);
+  else if (need <= 16) SLA_SELECT(16);
+  else if (need <= 20) SLA_SELECT(20);
+  else if (need <= 24) SLA_SELECT(24);
   else if (need <= 32) SLA_SELECT(32);
+  else if (need <= 48) SLA_SELECT(48);
+  else if (need <= 64) SLA_SELECT(64);
+  else if (need <= 96) SLA_SELECT(96);
   else SLA_SELECT(128);
 #undef SLA_SELECT
 }
