@@ -27,16 +27,14 @@ __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN): the hardware conversion
+// v_cvt_pk_bf16_f32, two values per instruction.
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v2f{lo, hi}, v2bf));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 // Two fp32 -> two E4M3 codes packed into the low or high half of `old`.  The
 // hardware conversion rounds to nearest even and turns anything above 464 into
@@ -89,7 +87,7 @@ struct Workspace {
   size_t dk;                // fp32 [BH,Tk]  per-key-block INT8 scale
   size_t scores;            // fp32 [BH,Tq,Tk]
   size_t mask;              // int8 [BH,Tq,Tk]
-  size_t m0;                // uint32 marginal bit matrix [BH, ceil(Tk/32), Tq rounded up to 768]: bit e of word (kt, i) = block 32 kt + e marginal for query block i
+  size_t m0;                // uint32 marginal bit matrix [BH, ceil(Tk/32), Tq rounded up to 384, + 128]: bit e of word (kt, i) = block 32 kt + e marginal for query block i
   size_t crit, marg;        // int32 [BH,Tq,n_c], [BH,Tq,n_m]
   size_t k8, v8;            // [BH,Tk] records of KV_FRAG_BYTES
   size_t hz;                // bf16 [BH,Tk,HZ_ROWS,D]
@@ -113,7 +111,7 @@ inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, siz
   w.dk = take(BH * Tk * 4);
   w.scores = take(BH * Tq * Tk * 4);
   w.mask = take(BH * Tq * Tk);
-  w.m0 = take(BH * ((Tk + 31) / 32) * ((Tq + 767) / 768 * 768) * 4);
+  w.m0 = take(BH * ((Tk + 31) / 32) * ((Tq + 383) / 384 * 384 + 128) * 4);
   w.crit = take(BH * Tq * n_c * 4);
   w.marg = take(BH * Tq * (n_m ? n_m : 1) * 4);
   w.k8 = take(BH * Tk * KV_FRAG_BYTES);

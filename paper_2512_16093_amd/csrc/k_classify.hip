@@ -262,7 +262,7 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
 
   const unsigned long long lt = (1ull << lane) - 1ull;
   const int bh = (int)(row / Tq), i = (int)(row % Tq);
-  const int KT = (Tk + 31) / 32, TqP = (Tq + 767) / 768 * 768;  // layout of the marginal bit matrix (see lin_accumulate)
+  const int KT = (Tk + 31) / 32, TqP = (Tq + 383) / 384 * 384 + 128;  // layout of the marginal bit matrix (see lin_accumulate)
   int eq1 = 0, eq2 = 0, nc = 0, nm = 0;  // running counts in ascending-j order
 #pragma unroll
   for (int m = 0; m < KPL; ++m) {

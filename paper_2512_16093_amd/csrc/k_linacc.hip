@@ -7,18 +7,19 @@
 // instead would move ~50x more bytes.
 //
 // The two operands could not be more different: hz is the big one (tens of MB per head) and
-// M0 is a bit matrix.  So a workgroup owns a 128-column stripe of hz for up to 768 query
-// blocks at once -- for the shapes of interest ALL query blocks of the head, so that hz is
-// read from HBM exactly once -- and M0 travels as bits: one 32-bit word per (query block,
+// M0 is a bit matrix.  So a workgroup owns a 128-column stripe of hz for 384 query blocks at
+// once, the (few) row chunks of a stripe run at the same time on one XCD so that hz comes
+// from HBM once, and M0 travels as bits: one 32-bit word per (query block,
 // tile of 32 key blocks), 3 KiB per staged tile against 8 KiB of hz.  The bf16 A operand of a
 // wavefront is made from its mask byte through a 256-entry table in LDS (entry b = the eight
 // bf16 values 0.0 / 1.0 of the bits of b), one 16-byte LDS read per fragment.
 //
-// Workgroup = 8 wavefronts; wavefront w owns query blocks [96 w, 96 w + 96) x 128 columns
+// Workgroup = 4 wavefronts, two workgroups per CU (independent, so the two wavefronts of a
+// SIMD are not in step); wavefront w owns query blocks [96 w, 96 w + 96) x 128 columns
 // (3 x 4 MFMA tiles of 32 x 32, 192 accumulator registers), accumulated transposed (the hz
 // fragment is the MFMA's A operand) so that a lane ends up with runs of consecutive entries
-// of one query block's summary and can store 8 bytes at a time.  Operand tiles for 32 key blocks
-// at a time are copied global -> LDS asynchronously, three stages deep.  hz rows are copied
+// of one query block's summary and can store 8 bytes at a time.  Operand tiles for 64 key blocks
+// at a time are copied global -> LDS asynchronously, three stages deep (one barrier per tile).  hz rows are copied
 // as they are (n contiguous) and read back with the LDS transposing read of gfx950
 // (ds_read_b64_tr_b16): the contraction index j is the slow index of hz, so one transposition
 // is unavoidable, and this one costs 8 LDS reads per 12 MFMAs and no vector-ALU work.
@@ -26,21 +27,26 @@
 
 namespace sla {
 
-constexpr int LA_KT = 32;                        // key blocks per staged tile
-constexpr int LA_ROWS = 768, LA_COLS = 128;      // workgroup tile
-constexpr int LA_WAVES = 8;
+constexpr int LA_KSUB = 2;                       // 32-block groups per staged tile
+constexpr int LA_KT = 32 * LA_KSUB;              // key blocks per staged tile (one barrier per tile)
+constexpr int LA_ROWS = 384, LA_COLS = 128;      // workgroup tile
+constexpr int LA_WAVES = 4;
+constexpr int LA_M_ROWS = 512;                   // mask words staged per 32-block group (two 1 KiB pieces; 384 used)
 constexpr int LA_B_ROW = LA_COLS * 2;            // 256 bytes per staged hz row
 // each group of 8 staged rows starts 64 bytes after the previous one ends, so the two lane
 // halves (which read rows 8 apart) hit different banks
-constexpr int LA_B_BYTES = LA_KT * LA_B_ROW + 3 * 64;
-constexpr int LA_B_STAGE = 8448;                 // LA_B_BYTES rounded up to a multiple of 256
-static_assert(LA_B_STAGE >= LA_B_BYTES, "stage layout");
+constexpr int LA_B_BYTES = LA_KT * LA_B_ROW + (LA_KT / 8 - 1) * 64;
+constexpr int LA_B_STAGE = (LA_B_BYTES + 255) / 256 * 256;
+constexpr int LA_M_PIECES = 2 * LA_KSUB;         // 1 KiB pieces of mask words per tile
 static_assert(HZ_ELEMS % LA_COLS == 0, "the stripes tile a summary exactly");
+static_assert(LA_M_PIECES == LA_WAVES && 8 * LA_KSUB % LA_WAVES == 0, "every wavefront copies the same number of pieces");
 
-__host__ __device__ inline int la_k_tiles(int Tk) { return (Tk + LA_KT - 1) / LA_KT; }
-__host__ __device__ inline int la_rows_padded(int Tq) { return (Tq + LA_ROWS - 1) / LA_ROWS * LA_ROWS; }
+__host__ __device__ inline int la_k_tiles(int Tk) { return (Tk + 31) / 32; }  // word columns of the bit matrix
+__host__ __device__ inline int la_row_chunks(int Tq) { return (Tq + LA_ROWS - 1) / LA_ROWS; }
+// row stride of the bit matrix: the chunks, plus the slack the last chunk's 512-word copies run into
+__host__ __device__ inline int la_rows_padded(int Tq) { return la_row_chunks(Tq) * LA_ROWS + (LA_M_ROWS - LA_ROWS); }
 
-// mbits[bh][kt][i] (i < la_rows_padded(Tq)): bit e = 1 where key block 32 kt + e is marginal
+// mbits[bh][kt][i] (kt < ceil(Tk/32), i < la_rows_padded(Tq)): bit e = 1 where key block 32 kt + e is marginal
 // for query block i.  Words of rows >= Tq are never written and never matter (their results
 // are not stored); bits of key blocks >= Tk are 0.
 __global__ void marginal_bits_kernel(const int8_t* __restrict__ mask, int Tq, int Tk, int BH,
@@ -52,7 +58,7 @@ __global__ void marginal_bits_kernel(const int8_t* __restrict__ mask, int Tq, in
     const int8_t* src = mask + ((size_t)bh * Tq + i) * Tk;
     uint32_t w = 0;
     for (int e = 0; e < 32; ++e) {
-      const int j = kt * LA_KT + e;
+      const int j = kt * 32 + e;
       if (j < Tk && src[j] == 0) w |= 1u << e;
     }
     mbits[((size_t)bh * KT + kt) * TqP + i] = w;
@@ -89,20 +95,21 @@ __device__ __forceinline__ void la_barrier() {
   asm volatile("" ::: "memory");
 }
 
-__global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const uint32_t* __restrict__ mbits,
+__global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const uint32_t* __restrict__ mbits,
                                                                           const bf16_t* __restrict__ hz, int Tq, int Tk,
-                                                                          bf16_t* __restrict__ HZ) {
+                                                                          int n_items, bf16_t* __restrict__ HZ) {
   // three stages, each a tile of hz rows and the mask words that go with it; separate objects,
   // so the compiler can tell the asynchronous fill of one stage from the reads of another
   __shared__ __attribute__((aligned(1024))) unsigned char hz0[LA_B_STAGE], hz1[LA_B_STAGE], hz2[LA_B_STAGE];
-  __shared__ __attribute__((aligned(1024))) uint32_t mw0[LA_ROWS], mw1[LA_ROWS], mw2[LA_ROWS];
+  __shared__ __attribute__((aligned(1024))) uint32_t mw0[LA_KSUB * LA_M_ROWS], mw1[LA_KSUB * LA_M_ROWS], mw2[LA_KSUB * LA_M_ROWS];
   __shared__ uint4 lut[256];
-  const int n0 = blockIdx.x * LA_COLS, row0 = blockIdx.y * LA_ROWS, bh = blockIdx.z;
   const int t = threadIdx.x, lane = t & 63, l32 = lane & 31, hf = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int KT = la_k_tiles(Tk), TqP = la_rows_padded(Tq);
+  const int KT32 = la_k_tiles(Tk), KT = (KT32 + LA_KSUB - 1) / LA_KSUB, TqP = la_rows_padded(Tq);
+  constexpr int STRIPES = HZ_ELEMS / LA_COLS;
+  const int chunks = la_row_chunks(Tq);
 
-  if (t < 256) {  // table: mask byte -> eight bf16 0.0 / 1.0
+  {  // table: mask byte -> eight bf16 0.0 / 1.0 (256 threads = 256 entries)
     uint32_t x[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
@@ -110,37 +117,66 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const 
     lut[t] = make_uint4(x[0], x[1], x[2], x[3]);
   }
 
-  // asynchronous copy of k-tile kt into a stage: wavefront w brings 4 hz rows (1 KiB), the
-  // first three wavefronts also 256 mask words each
-  const char* hz_bh = (const char*)(hz + (size_t)bh * Tk * HZ_ELEMS + n0);  // uniform
-  const char* mb_bh = (const char*)(mbits + (size_t)bh * KT * TqP + row0 + 256 * w);
   const unsigned lane16 = (unsigned)lane * 16u;
-  auto fetch = [&](int kt, unsigned char* hzs, uint32_t* mws) {
-    const int j = min(kt * LA_KT + 4 * w + (lane >> 4), Tk - 1);  // rows past Tk repeat the last one (their mask bits are 0)
-    const unsigned off = (unsigned)j * (unsigned)(HZ_ELEMS * 2) + (unsigned)(lane & 15) * 16u;
-    la_copy16(hz_bh, off, hzs + w * 1024 + (w >> 1) * 64);
-    if (w < 3) la_copy16(mb_bh + (size_t)kt * TqP * 4, lane16, mws + w * 256);
-  };
-  auto wait_keep = [&](bool keep_one) {  // wait until at most one tile's copies of this wavefront are in flight
-    if (!keep_one) __builtin_amdgcn_s_waitcnt(0x0F70);
-    else if (w < 3) __builtin_amdgcn_s_waitcnt(0x0F72);
-    else __builtin_amdgcn_s_waitcnt(0x0F71);
-  };
-
   // this lane's address inside a B patch for the transposing reads: lane group g = lane / 16
   // serves columns 16 (g % 2) .. +15 and staged rows 8 (g / 2) + (0..3) [+ 4 for the second read]
   const int tr_off = (8 * (lane >> 5) + ((lane & 15) >> 2)) * LA_B_ROW + (lane >> 5) * 64 +
                      (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+  __syncthreads();  // publishes the table
+
+  // Persistent workgroups, two per compute unit: each takes work items (b,h, stripe, row chunk)
+  // in turn.  The row chunks of one stripe are consecutive items, and consecutive items go to
+  // workgroups of the same XCD (workgroup ids are dealt round-robin over the 8 XCDs), so the
+  // chunks of a stripe run at the same time on one L2 and the stripe comes from HBM once.  The
+  // stripes of one head run next to each other in time (they share the head's mask words).
+  // The stores of a finished item drain while the next item's copies and MFMAs already run.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;  // gridDim.x is a multiple of 8
+  const int groups = n_items / chunks;  // (b,h, stripe) pairs; group g runs on XCD g % 8
+  for (int it = slot; it < (groups + 7) / 8 * chunks; it += slots) {
+  // item = 8 * (it / chunks) ... : groups of `chunks` consecutive items stay on one XCD
+  const int grp = it / chunks, item = (grp * 8 + xcd) * chunks + it % chunks;
+  if (item >= n_items) continue;  // (uniform)
+  const int chunk = item % chunks, stripe = (item / chunks) % STRIPES, bh = item / (chunks * STRIPES);
+  const int n0 = stripe * LA_COLS, row0 = chunk * LA_ROWS;
+
+  // asynchronous copy of tile kt into a stage, in 1 KiB pieces (4 hz rows, or 256 mask words)
+  // dealt round-robin to the wavefronts
+  const char* hz_bh = (const char*)(hz + (size_t)bh * Tk * HZ_ELEMS + n0);  // uniform
+  const char* mb_bh = (const char*)(mbits + (size_t)bh * KT32 * TqP + row0);
+  auto fetch = [&](int kt, unsigned char* hzs, uint32_t* mws) {
+#pragma unroll
+    for (int u = 0; u < 8 * LA_KSUB / LA_WAVES; ++u) {
+      const int p = w + LA_WAVES * u;
+      const int j = min(kt * LA_KT + 4 * p + (lane >> 4), Tk - 1);  // rows past Tk repeat the last one (their mask bits are 0)
+      const unsigned off = (unsigned)j * (unsigned)(HZ_ELEMS * 2) + (unsigned)(lane & 15) * 16u;
+      la_copy16(hz_bh, off, hzs + p * 1024 + (p >> 1) * 64);
+    }
+    {
+      const int sub = w >> 1, part = w & 1;  // one mask piece per wavefront
+      const int kt32 = min(kt * LA_KSUB + sub, KT32 - 1);  // (a word column past the end is ignored by the consumer)
+      la_copy16(mb_bh + ((size_t)kt32 * TqP + 256 * part) * 4, lane16, mws + sub * LA_M_ROWS + part * 256);
+    }
+  };
+  // copies of a wavefront per tile, and the wait that leaves at most one tile's worth in flight
+  constexpr int PER_TILE = 8 * LA_KSUB / LA_WAVES + 1;
+  static_assert(PER_TILE <= 15, "wait count immediate");
+  auto wait_keep = [&](bool keep_one) {
+    if (keep_one) __builtin_amdgcn_s_waitcnt(0x0F70 | PER_TILE);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+  };
+
   v16f acc[3][4];
 #pragma unroll
   for (int a = 0; a < 3; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
 
-#define LA_COMPUTE(HZS, MWS)                                                                              \
-  {                                                                                                       \
+#define LA_COMPUTE(KTI, HZS, MWS)                                                                         \
+  _Pragma("unroll") for (int sub = 0; sub < LA_KSUB; ++sub) {                                             \
     uint32_t mw[3];                                                                                       \
-    _Pragma("unroll") for (int mt = 0; mt < 3; ++mt) mw[mt] = MWS[96 * w + 32 * mt + l32];                \
+    const bool live = (KTI) * LA_KSUB + sub < KT32; /* uniform: the last tile may be partly past the end */ \
+    _Pragma("unroll") for (int mt = 0; mt < 3; ++mt)                                                      \
+      mw[mt] = live ? MWS[sub * LA_M_ROWS + 96 * w + 32 * mt + l32] : 0u;                                 \
     _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                    \
       v8bf aop[3], bop[4];                                                                                \
       _Pragma("unroll") for (int mt = 0; mt < 3; ++mt) {                                                  \
@@ -149,9 +185,9 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const 
         aop[mt] = c.v;                                                                                    \
       }                                                                                                   \
       _Pragma("unroll") for (int nt = 0; nt < 4; ++nt) {                                                  \
-        /* staged rows 16 ks + 8 hf + (0..7) of column 32 nt + l32, by two transposing reads */           \
+        /* staged rows r0 + 8 hf + (0..7) of column 32 nt + l32, by two transposing reads */              \
         union { v4s h[2]; v8bf v; } u;                                                                    \
-        const int r0 = 16 * ks, c0 = 64 * nt;                                                             \
+        const int r0 = 32 * sub + 16 * ks, c0 = 64 * nt;                                                  \
         u.h[0] = la_read_tr(&HZS[tr_off + r0 * LA_B_ROW + (r0 >> 3) * 64 + c0]);                          \
         u.h[1] = la_read_tr(&HZS[tr_off + (r0 + 4) * LA_B_ROW + (r0 >> 3) * 64 + c0]);                    \
         bop[nt] = u.v;                                                                                    \
@@ -166,14 +202,14 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const 
   {                                            \
     const int kt_ = (KTI);                     \
     if (kt_ + 2 < KT) fetch(kt_ + 2, HF, MF);  \
-    LA_COMPUTE(HC, MC)                         \
+    LA_COMPUTE(kt_, HC, MC)                    \
     wait_keep(kt_ + 2 < KT);                   \
     la_barrier();                              \
   }
   fetch(0, hz0, mw0);
   if (KT > 1) fetch(1, hz1, mw1);
   wait_keep(KT > 1);
-  __syncthreads();  // also publishes the table
+  la_barrier();
   int kt = 0;
   for (; kt + 3 <= KT; kt += 3) {
     LA_STEP(kt, hz0, mw0, hz2, mw2)
@@ -202,6 +238,7 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 1) lin_accumulate_kernel(const 
         }
     }
   }
+  }  // work items
 }
 
 size_t marginal_bits_bytes(const Problem& p) {
@@ -216,8 +253,16 @@ void launch_marginal_bits(const Problem& p, const int8_t* mask, uint32_t* mbits,
 }
 
 void launch_lin_accumulate(const Problem& p, const uint32_t* mbits, const bf16_t* hz, bf16_t* HZ, hipStream_t stream) {
-  dim3 grid(HZ_ELEMS / LA_COLS, la_rows_padded(p.Tq) / LA_ROWS, p.BH);
-  lin_accumulate_kernel<<<grid, LA_WAVES * 64, 0, stream>>>(mbits, hz, p.Tq, p.Tk, HZ);
+  const int n_items = (HZ_ELEMS / LA_COLS) * la_row_chunks(p.Tq) * p.BH;
+  static int n_cu = 0;  // two workgroups per compute unit (192 accumulator registers per lane)
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    n_cu = v;
+  }
+  int grid = 2 * n_cu / 8 * 8;  // a multiple of 8 (see the item order in the kernel)
+  if (grid < 8) grid = 8;
+  lin_accumulate_kernel<<<grid, LA_WAVES * 64, 0, stream>>>(mbits, hz, p.Tq, p.Tk, n_items, HZ);
 }
 
 }  // namespace sla
