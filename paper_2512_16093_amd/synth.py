@@ -60,12 +60,17 @@ CONFIGS = {
     2: SLAConfig(2, "dense-quant", 1, 12, (21, 30, 52), 128, 128, 64, 1.0, 0.0, False),
     3: SLAConfig(3, "wan14b-480p", 1, 40, (21, 30, 52), 128, 128, 64, 0.1, 0.2, True),
     4: SLAConfig(4, "wan14b-720p", 1, 40, (21, 45, 80), 128, 128, 64, 0.1, 0.2, True),
+    # The evaluation setup (Section 3.1) recommends Top-K ratios up to 0.15: that value, with the
+    # other 85 % of the blocks marginal (nothing skipped but the one block per row that flooring both
+    # counts leaves over), at both query block sizes
+    5: SLAConfig(5, "wan14b-720p-top15-noskip", 1, 40, (21, 45, 80), 128, 128, 64, 0.15, 0.85, True),
+    6: SLAConfig(6, "wan14b-720p-top15-noskip-bq64", 1, 40, (21, 45, 80), 128, 64, 64, 0.15, 0.85, True),
 }
 
 
 def custom_config(B, H, grid, d=128, block_q=64, block_k=64, topk_ratio=0.2,
                   marginal_ratio=0.4, use_proj=True, cfg_id=100, name="custom"):
-    """A config outside the five named ones (ragged tails, odd ratios ...)."""
+    """A config outside the named ones (ragged tails, odd ratios ...)."""
     return SLAConfig(cfg_id, name, B, H, tuple(grid), d, block_q, block_k,
                      topk_ratio, marginal_ratio, use_proj)
 

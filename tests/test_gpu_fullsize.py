@@ -16,7 +16,7 @@ import parity_util as pu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg_id,heads", [(1, (0, 11)), (2, (5,)), (4, (0, 17, 39))])
+@pytest.mark.parametrize("cfg_id,heads", [(1, (0, 11)), (2, (5,)), (4, (0, 17, 39)), (5, (3,)), (6, (21,))])
 def test_named_config_sampled_parity(cfg_id, heads):
     cfg = synth.CONFIGS[cfg_id]
     print("config", cfg.name, "generating inputs", flush=True)
