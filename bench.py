@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="seeded config id (4 = Wan-14B-720P shape, the headline)")
+    ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
+                    help="memory order of q, k, v and out: head-major [B,H,N,d] (default) or token-major "
+                         "[B,N,H,d] through the strided entry point")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget for the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -132,13 +135,22 @@ def main():
     print("[bench] inputs for %s generated in %.1f s" % (cfg.name, time.perf_counter() - t0), file=sys.stderr, flush=True)
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
     Wd = None if W is None else W.to(dev)
-    out = torch.empty_like(qd)
+    if args.layout == "bnhd":
+        # token-major memory, indexed [B,H,N,d] through permuted views (no copy at call time)
+        qd, kd, vd = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (qd, kd, vd))
+        out = torch.empty((cfg.B, cfg.N, cfg.H, cfg.d), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
+    else:
+        out = torch.empty_like(qd)
     ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, dev)
     Tq, Tk, n_c, n_m = sla.sla_block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
 
     def step():
-        sla.sla_attention_fwd(qd, kd, vd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
-                              proj_w=Wd, workspace=ws, out=out)
+        if args.layout == "bnhd":
+            sla.sla_attention_fwd_strided(qd, kd, vd, out, cfg.block_q, cfg.block_k, cfg.topk_ratio,
+                                          cfg.marginal_ratio, proj_w=Wd, workspace=ws)
+        else:
+            sla.sla_attention_fwd(qd, kd, vd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                                  proj_w=Wd, workspace=ws, out=out)
 
     if args.copy_calibration:
         a = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
@@ -175,9 +187,9 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8/fp8-e4m3 (fp32 accumulate; bf16 linear branch)",
         "data": "synthetic",
-        "config": {"workload": "%s: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0"
+        "config": {"workload": "%s: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0 layout=%s"
                                % (cfg.name, cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio,
-                                  cfg.marginal_ratio),
+                                  cfg.marginal_ratio, "[B,H,N,d]" if args.layout == "bhnd" else "[B,N,H,d]"),
                    "n_crit": n_c, "n_marg": n_m, "Tq": Tq, "Tk": Tk},
         "stage_ms": dict(zip(sla.STAGE_NAMES, [round(x, 4) for x in stage_ms])),
         "roofline": {"kernel": "sparse_fwd_kernel", "bound": "mfma", "achieved": achieved,

@@ -65,7 +65,9 @@ typedef enum {
   SLA_ERR_RATIO = -4,       /* topk_ratio not in (0,1], marginal_ratio not in [0,1], or sum > 1 */
   SLA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or too small */
   SLA_ERR_UNSUPPORTED = -6, /* phi_kind / quant_mode outside what this build implements */
-  SLA_ERR_HIP = -7          /* a kernel launch reported an error */
+  SLA_ERR_HIP = -7,         /* a kernel launch reported an error */
+  SLA_ERR_LAYOUT = -8       /* strides negative, not multiples of 8 elements, token stride < d, or a
+                               base pointer not 16-byte aligned */
 } sla_status;
 
 typedef enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1, SLA_PHI_RELU = 2 } sla_phi;
@@ -103,6 +105,32 @@ int sla_attention_fwd(const void* q, const void* k, const void* v, void* out,
                       double topk_ratio, double marginal_ratio,
                       const void* proj_w, const void* proj_b, int phi_kind, int quant_mode,
                       void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+/* Where the tokens of a tensor indexed [b][h][n][channel] lie: element (b,h,n,c) is at
+ * base + b*batch + h*head + n*token + c, in ELEMENTS; the d channels of a token are always
+ * contiguous.  [B,H,N,d] is {H*N*d, N*d, d}; the layout a fused QKV projection leaves,
+ * [B,N,H,d], is {N*H*d, d, H*d}; q of a packed [B,N,3,H,d] is {N*3*H*d, d, 3*H*d}. */
+typedef struct {
+  int64_t batch, head, token;
+} sla_strides;
+
+/* sla_attention_fwd for inputs and an output that are not [B,H,N,d]-contiguous (Section 1.3:
+ * the kernel replaces the attention of a DiT block, which sits between a QKV projection and
+ * an output projection that produce and consume token-major tensors; reading and writing
+ * them in place saves three transposes in and one out).  Every argument is as in sla_attention_fwd; in addition
+ *   q_strides, k_strides, v_strides, out_strides   in  HOST pointers, read during the call;
+ *                  NULL = [B,H,N,d] contiguous.
+ * Each stride must be a non-negative multiple of 8 elements with token >= d, and each base
+ * pointer 16-byte aligned, else SLA_ERR_LAYOUT.  Rows of `out` must not overlap each other
+ * or any input (not checked).  Results are bit-identical to the contiguous call on the
+ * same values. */
+int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void* out,
+                              const sla_strides* q_strides, const sla_strides* k_strides,
+                              const sla_strides* v_strides, const sla_strides* out_strides,
+                              int B, int H, int N, int d, int block_q, int block_k,
+                              double topk_ratio, double marginal_ratio,
+                              const void* proj_w, const void* proj_b, int phi_kind, int quant_mode,
+                              void* workspace, size_t workspace_bytes, sla_stream_t stream);
 
 /* Steps 1-2 alone.
  *   mask           out  int8  [B,H,Tq,Tk], values +1 / 0 / -1

@@ -21,15 +21,21 @@ QUANT_NONE, QUANT_QK_INT8, QUANT_QK_INT8_PV_FP8 = 0, 1, 2
 
 SLA_OK = 0
 ERR_NULL, ERR_SHAPE, ERR_BLOCK, ERR_RATIO, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5, -6, -7
+ERR_LAYOUT = -8
 
 EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
-           "sla_attention_fwd", "sla_classify_blocks", "sla_sparse_attn_fwd",
+           "sla_attention_fwd", "sla_attention_fwd_strided", "sla_classify_blocks", "sla_sparse_attn_fwd",
            "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv",
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
 N_STAGES = 5
 STAGE_NAMES = ("pool_stats", "scores_select", "prep_kv", "lin_accumulate", "sparse_fwd")
 
 _lib = None
+
+
+class Strides(ctypes.Structure):
+    """sla_strides of include/sla.h: element strides of the batch, head and token indices."""
+    _fields_ = [("batch", ctypes.c_int64), ("head", ctypes.c_int64), ("token", ctypes.c_int64)]
 
 
 class SLAError(RuntimeError):
@@ -59,6 +65,9 @@ def lib():
         L.sla_workspace_bytes.argtypes = [c_int] * 6 + [c_dbl, c_dbl, c_int]
         L.sla_attention_fwd.restype = c_int
         L.sla_attention_fwd.argtypes = [c_vp] * 4 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp]
+        L.sla_attention_fwd_strided.restype = c_int
+        L.sla_attention_fwd_strided.argtypes = ([c_vp] * 4 + [ctypes.POINTER(Strides)] * 4 + [c_int] * 6 +
+                                                [c_dbl, c_dbl, c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp])
         L.sla_classify_blocks.restype = c_int
         L.sla_classify_blocks.argtypes = [c_vp, c_vp] + [c_int] * 6 + [c_dbl, c_dbl] + [c_vp] * 4 + [c_vp, c_sz, c_vp]
         L.sla_sparse_attn_fwd.restype = c_int
@@ -139,6 +148,32 @@ def sla_attention_fwd(q, k, v, block_q, block_k, topk_ratio, marginal_ratio, pro
                                  topk_ratio, marginal_ratio, _ptr(proj_w), _ptr(proj_b), phi_kind, quant_mode,
                                  _ptr(workspace), workspace.numel(), _stream())
     _check(st, "sla_attention_fwd")
+    return out
+
+
+def _strides_of(t, what):
+    """sla_strides of a [B,H,N,d]-indexed view (any memory order with contiguous channels)."""
+    if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != 4 or t.stride(3) != 1:
+        raise ValueError("%s: expected a CUDA bfloat16 tensor indexed [B,H,N,d] with contiguous channels" % what)
+    return Strides(t.stride(0), t.stride(1), t.stride(2))
+
+
+def sla_attention_fwd_strided(q, k, v, out, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None, proj_b=None,
+                              phi_kind=PHI_SOFTMAX, quant_mode=QUANT_QK_INT8_PV_FP8, workspace=None):
+    """q, k, v, out: tensors indexed [B,H,N,d] in any memory order with contiguous channels
+    (e.g. `x.view(B, N, H, d).permute(0, 2, 1, 3)`); their strides are passed on as they are."""
+    B, H, N, d = q.shape
+    for t in (k, v, out):
+        if tuple(t.shape) != (B, H, N, d):
+            raise ValueError("q, k, v and out must have one shape [B,H,N,d]")
+    sq, sk, sv, so_ = (_strides_of(t, n) for t, n in ((q, "q"), (k, "k"), (v, "v"), (out, "out")))
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    st = lib().sla_attention_fwd_strided(_ptr(q), _ptr(k), _ptr(v), _ptr(out), ctypes.byref(sq), ctypes.byref(sk),
+                                         ctypes.byref(sv), ctypes.byref(so_), B, H, N, d, block_q, block_k,
+                                         topk_ratio, marginal_ratio, _ptr(proj_w), _ptr(proj_b), phi_kind,
+                                         quant_mode, _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_attention_fwd_strided")
     return out
 
 

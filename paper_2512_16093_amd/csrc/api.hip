@@ -41,6 +41,20 @@ int make_problem(int B, int H, int N, int d, int block_q, int block_k, double rc
   if ((long long)B * H > 65535 || rows >= (1ll << 31) - 8 || (long long)B * H * Tk >= (1ll << 31)) return SLA_ERR_SHAPE;
   p->B = B; p->H = H; p->N = N; p->block_q = block_q;
   p->BH = B * H; p->Tq = Tq; p->Tk = Tk; p->n_c = nc; p->n_m = nm;
+  p->lq = p->lk = p->lv = p->lo = contiguous_layout(H, N);
+  return SLA_OK;
+}
+
+// A caller-given layout: rows of d contiguous channels, 16-byte aligned, at non-negative strides.
+int make_layout(const void* base, const sla_strides* st, int H, int N, Layout* L) {
+  if (!st) {
+    *L = contiguous_layout(H, N);
+    return SLA_OK;
+  }
+  if (st->batch < 0 || st->head < 0 || st->token < D) return SLA_ERR_LAYOUT;
+  if ((st->batch | st->head | st->token) & 7) return SLA_ERR_LAYOUT;
+  if ((uintptr_t)base & 15) return SLA_ERR_LAYOUT;
+  L->sb = st->batch; L->sh = st->head; L->sn = st->token;
   return SLA_OK;
 }
 
@@ -90,6 +104,7 @@ const char* sla_status_string(int status) {
     case SLA_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SLA_ERR_UNSUPPORTED: return "phi_kind or quant_mode not implemented";
     case SLA_ERR_HIP: return "a kernel launch failed";
+    case SLA_ERR_LAYOUT: return "unsupported strides (non-negative multiples of 8 elements, token stride >= d, 16-byte aligned base)";
     default: return "unknown status";
   }
 }
@@ -112,10 +127,25 @@ int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, in
                       int block_q, int block_k, double topk_ratio, double marginal_ratio,
                       const void* proj_w, const void* proj_b, int phi_kind, int quant_mode, void* workspace,
                       size_t workspace_bytes, sla_stream_t stream) {
+  return sla_attention_fwd_strided(q, k, v, out, nullptr, nullptr, nullptr, nullptr, B, H, N, d, block_q, block_k,
+                                   topk_ratio, marginal_ratio, proj_w, proj_b, phi_kind, quant_mode, workspace,
+                                   workspace_bytes, stream);
+}
+
+int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void* out,
+                              const sla_strides* q_strides, const sla_strides* k_strides,
+                              const sla_strides* v_strides, const sla_strides* out_strides, int B, int H, int N,
+                              int d, int block_q, int block_k, double topk_ratio, double marginal_ratio,
+                              const void* proj_w, const void* proj_b, int phi_kind, int quant_mode,
+                              void* workspace, size_t workspace_bytes, sla_stream_t stream) {
   if (!q || !k || !v || !out) return SLA_ERR_NULL;
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
+  if ((st = make_layout(q, q_strides, H, N, &p.lq)) != SLA_OK) return st;
+  if ((st = make_layout(k, k_strides, H, N, &p.lk)) != SLA_OK) return st;
+  if ((st = make_layout(v, v_strides, H, N, &p.lv)) != SLA_OK) return st;
+  if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
   if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);

@@ -124,9 +124,20 @@ inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, siz
 }
 
 // Problem description handed to the launchers.
+// Where the d contiguous channels of token n of slice (b,h) of a [B,H,N,d]-indexed bf16 tensor
+// start, in elements: b * sb + h * sh + n * sn.  Any layout with contiguous channels fits
+// ([B,H,N,d]: sn = d; [B,N,H,d]: sh = d, sn = H d; a packed [B,N,3,H,d]: sn = 3 H d).
+struct Layout {
+  long long sb, sh, sn;
+};
+inline Layout contiguous_layout(int H, int N) {
+  return {(long long)H * N * D, (long long)N * D, (long long)D};
+}
+
 struct Problem {
   int B, H, N, block_q;
   int BH, Tq, Tk, n_c, n_m;
+  Layout lq, lk, lv, lo;  // of q, k, v and out
 };
 
 // Launchers (one per kernel file); every one only enqueues work on `stream`.

@@ -18,15 +18,19 @@ namespace sla {
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) pool_stats_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-    int N, int block_q, int Tq, int Tk, int groups, float* __restrict__ qbar,
-    float* __restrict__ kbar, float* __restrict__ dq, uint32_t* __restrict__ amax_v) {
+    int N, int block_q, int Tq, int Tk, int groups, int H, Layout lq, Layout lk, Layout lv,
+    float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ dq,
+    uint32_t* __restrict__ amax_v) {
   __shared__ float sQ[16][2][D];
   __shared__ float sK[16][2][D];
   __shared__ float sV[16][D];
   __shared__ float sQa[2][256];
   const int bh = blockIdx.x / groups, g = blockIdx.x % groups;
   const int t = threadIdx.x, cg = t & 15, rg = t >> 4;
-  const size_t base = ((size_t)bh * N) * D;
+  const int b_ = bh / H, h_ = bh - b_ * H;
+  const bf16_t* qs_ = q + b_ * lq.sb + h_ * lq.sh;
+  const bf16_t* ks_ = k + b_ * lk.sb + h_ * lk.sh;
+  const bf16_t* vs_ = v + b_ * lv.sb + h_ * lv.sh;
   const int row0 = g * 128;
 
   float qs[2][8] = {}, ks[2][8] = {}, va[8] = {}, qa[2] = {0.f, 0.f};
@@ -34,10 +38,9 @@ __global__ void __launch_bounds__(256) pool_stats_kernel(
   for (int r = 0; r < 8; ++r) {
     const int row = row0 + rg + 16 * r, half = r >> 2;
     if (row < N) {
-      const size_t off = base + (size_t)row * D + cg * 8;
-      const uint4 xq = *(const uint4*)(q + off);
-      const uint4 xk = *(const uint4*)(k + off);
-      const uint4 xv = *(const uint4*)(v + off);
+      const uint4 xq = *(const uint4*)(qs_ + row * lq.sn + cg * 8);
+      const uint4 xk = *(const uint4*)(ks_ + row * lk.sn + cg * 8);
+      const uint4 xv = *(const uint4*)(vs_ + row * lv.sn + cg * 8);
       const uint32_t wq[4] = {xq.x, xq.y, xq.z, xq.w}, wk[4] = {xk.x, xk.y, xk.z, xk.w},
                      wv[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
@@ -297,7 +300,8 @@ void launch_pool_stats(const void* q, const void* k, const void* v, const Proble
   const int groups = (p.N + 127) / 128;
   pool_stats_kernel<<<p.BH * groups, 256, 0, stream>>>((const bf16_t*)q, (const bf16_t*)k,
                                                         (const bf16_t*)v, p.N, p.block_q, p.Tq, p.Tk,
-                                                        groups, qbar, kbar, dq, amax_v);
+                                                        groups, p.H, p.lq, p.lk, p.lv, qbar, kbar, dq,
+                                                        amax_v);
 }
 
 void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,

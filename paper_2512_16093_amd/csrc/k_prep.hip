@@ -23,7 +23,7 @@ constexpr int STAGE_STRIDE = 2 * D + 16;  // bytes per staged hz row (padded aga
 
 template <int PHI>
 __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
-    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk,
+    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk, int H, Layout lk, Layout lv,
     const float* __restrict__ mu_k, const float* __restrict__ dv, const bf16_t* __restrict__ W,
     int want_quant, int want_linear, int8_t* __restrict__ k8, uint8_t* __restrict__ v8,
     float* __restrict__ dk, bf16_t* __restrict__ hz) {
@@ -38,7 +38,9 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
   const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk;
   const int t = threadIdx.x, cg = t & 15, m = t >> 4, lane = t & 63, w = t >> 6;
   const int valid = min(BK, N - j * BK);
-  const size_t base = ((size_t)bh * N + (size_t)j * BK) * D;
+  const int b_ = bh / H, h_ = bh - b_ * H;
+  const bf16_t* kblk = k + b_ * lk.sb + h_ * lk.sh + (long long)j * BK * lk.sn;
+  const bf16_t* vblk = v + b_ * lv.sb + h_ * lv.sh + (long long)j * BK * lv.sn;
 
   float kf[4][8], vf[4][8];
 #pragma unroll
@@ -46,8 +48,8 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     const int row = 4 * m + r;
     uint4 xk = make_uint4(0, 0, 0, 0), xv = make_uint4(0, 0, 0, 0);
     if (row < valid) {
-      xk = *(const uint4*)(k + base + (size_t)row * D + cg * 8);
-      xv = *(const uint4*)(v + base + (size_t)row * D + cg * 8);
+      xk = *(const uint4*)(kblk + row * lk.sn + cg * 8);
+      xv = *(const uint4*)(vblk + row * lv.sn + cg * 8);
     }
     const uint32_t wk[4] = {xk.x, xk.y, xk.z, xk.w}, wv[4] = {xv.x, xv.y, xv.z, xv.w};
 #pragma unroll
@@ -185,7 +187,7 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       v8bf a = v8bf{};
-      if (ok) a = *(const v8bf*)(v + base + (size_t)row * D + 16 * ks + 8 * hfl);
+      if (ok) a = *(const v8bf*)(vblk + row * lv.sn + 16 * ks + 8 * hfl);
       const v8bf b = *(const v8bf*)(W + (size_t)(32 * w + l32) * D + 16 * ks + 8 * hfl);
       d1[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, d1[rt], 0, 0, 0);
     }
@@ -257,11 +259,11 @@ void launch_prep_kv(const void* k, const void* v, const Problem& p, const float*
   const bf16_t* kk = (const bf16_t*)k;
   const bf16_t* vv = (const bf16_t*)v;
   if (phi_kind == 0)
-    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
   else if (phi_kind == 1)
-    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
   else
-    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
 }
 
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,

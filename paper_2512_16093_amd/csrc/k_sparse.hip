@@ -29,7 +29,8 @@
 namespace sla {
 
 struct SparseDims {
-  int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32;
+  int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32, H;
+  Layout lq, lo;  // of q and out
 };
 // The pointers are separate __restrict__ kernel parameters (not struct members) so the
 // compiler knows the index list and the scales are never written by this kernel and can
@@ -46,7 +47,8 @@ struct SparseArgs {
   const bf16_t* __restrict__ bias;
   void* __restrict__ out;
   float* __restrict__ lse;
-  int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32;
+  int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32, H;
+  Layout lq, lo;
 };
 
 constexpr int EPI_STRIDE = 32 * 4 + 16;         // bytes per staged output row (32 fp32 + pad)
@@ -210,7 +212,8 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     const float* __restrict__ dv_, const bf16_t* __restrict__ HZ_, const bf16_t* __restrict__ bias_,
     void* __restrict__ out_, float* __restrict__ lse_, const SparseDims dims) {
   const SparseArgs A = {q_, crit_, k8_, v8_, dq_, dk_, dv_, HZ_, bias_, out_, lse_, dims.N, dims.Tq, dims.Tk,
-                        dims.n_c, dims.total, dims.per_xcd, dims.phi, dims.has_lin, dims.out_f32};
+                        dims.n_c, dims.total, dims.per_xcd, dims.phi, dims.has_lin, dims.out_f32, dims.H,
+                        dims.lq, dims.lo};
   constexpr int NT = NW * 64;
   constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
   constexpr int BQ = NW * 32;
@@ -236,7 +239,8 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
   const int qrow = i * BQ + 32 * w + l32;
   const bool qok = qrow < A.N;
-  const bf16_t* qptr = A.q + ((size_t)bh * A.N + (qok ? qrow : 0)) * D;
+  const int b_ = __builtin_amdgcn_readfirstlane(bh / A.H), h_ = bh - b_ * A.H;
+  const bf16_t* qptr = A.q + b_ * A.lq.sb + h_ * A.lq.sh + (qok ? qrow : 0) * A.lq.sn;
 
   // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each)
   const float dqi = A.dq[(size_t)bh * A.Tq + i];
@@ -587,7 +591,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       const int grow = i * BQ + 32 * w + rr;
       const float4 val = *(const float4*)(my + rr * EPI_STRIDE + c4 * 16);
       if (grow < A.N) {
-        const size_t o = ((size_t)bh * A.N + grow) * D + 32 * ct + 4 * c4;
+        const size_t o = (size_t)(b_ * A.lo.sb + h_ * A.lo.sh + grow * A.lo.sn) + 32 * ct + 4 * c4;
         if (A.out_f32) {
           *(float4*)((float*)A.out + o) = val;
         } else {
@@ -612,6 +616,9 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
   dm.phi = phi_kind;
   dm.has_lin = has_linear ? 1 : 0;
   dm.out_f32 = out_f32 ? 1 : 0;
+  dm.H = p.H;
+  dm.lq = p.lq;
+  dm.lo = p.lo;
   const bf16_t* bias = has_linear ? proj_b : nullptr;
   const unsigned grid = (unsigned)(8 * dm.per_xcd * p.BH);
   if (p.block_q == 128) {

@@ -60,7 +60,7 @@ CONFIGS = {
     2: SLAConfig(2, "dense-quant", 1, 12, (21, 30, 52), 128, 128, 64, 1.0, 0.0, False),
     3: SLAConfig(3, "wan14b-480p", 1, 40, (21, 30, 52), 128, 128, 64, 0.1, 0.2, True),
     4: SLAConfig(4, "wan14b-720p", 1, 40, (21, 45, 80), 128, 128, 64, 0.1, 0.2, True),
-    # The evaluation setup (Section 3.1) recommends Top-K ratios up to 0.15: that value, with the
+    # The evaluation setup (Section 2.1) recommends Top-K ratios up to 0.15: that value, with the
     # other 85 % of the blocks marginal (nothing skipped but the one block per row that flooring both
     # counts leaves over), at both query block sizes
     5: SLAConfig(5, "wan14b-720p-top15-noskip", 1, 40, (21, 45, 80), 128, 128, 64, 0.15, 0.85, True),

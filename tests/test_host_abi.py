@@ -33,11 +33,11 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     seen = set()
-    for st in range(0, -8, -1):
+    for st in range(0, -9, -1):
         s = sla.sla_status_string(st)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 8 and sla.sla_status_string(-99) == "unknown status"
+    assert len(seen) == 9 and sla.sla_status_string(-99) == "unknown status"
 
 
 @pytest.mark.parametrize("N,bq,bk,rc,rm", [
@@ -94,6 +94,27 @@ def test_attention_fwd_argument_errors_are_found_before_any_launch():
     assert _fwd(ws=ctypes.c_void_p(0x10010)) == sla.ERR_WORKSPACE          # misaligned
     need = sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4)
     assert _fwd(wsb=need - 1) == sla.ERR_WORKSPACE
+
+
+def test_strided_entry_point_rejects_bad_layouts_before_any_launch():
+    L = sla.lib()
+
+    def call(qs=None, os_=None, q=FAKE, wsb=16):
+        # the workspace is too small on purpose: a layout that passes must reach that check, not a launch
+        ref = lambda s: None if s is None else ctypes.byref(sla.Strides(*s))
+        return L.sla_attention_fwd_strided(q, FAKE, FAKE, FAKE, ref(qs), None, None, ref(os_), 1, 2, 1024, 128,
+                                           64, 64, 0.2, 0.4, None, None, 0, 2, WS, wsb, None)
+
+    ok = (2 * 1024 * 128, 128, 2 * 128)                                     # [B,N,H,d]
+    assert call(qs=ok, os_=ok) == sla.ERR_WORKSPACE
+    assert call(qs=(3 * 2 * 1024 * 128, 128, 3 * 2 * 128)) == sla.ERR_WORKSPACE   # q of a packed [B,N,3,H,d]
+    assert call(qs=(0, 0, 128)) == sla.ERR_WORKSPACE                        # broadcast over batch and head
+    assert call(qs=(2 * 1024 * 128, 128, 64)) == sla.ERR_LAYOUT             # token rows would overlap
+    assert call(qs=(2 * 1024 * 128, 132, 256)) == sla.ERR_LAYOUT            # not a multiple of 8 elements
+    assert call(qs=(-8, 128, 256)) == sla.ERR_LAYOUT
+    assert call(os_=(2 * 1024 * 128, 128, 100)) == sla.ERR_LAYOUT
+    assert call(qs=ok, q=ctypes.c_void_p(0x10008)) == sla.ERR_LAYOUT        # rows not 16-byte aligned
+    assert call(q=None, qs=ok) == sla.ERR_NULL
 
 
 def test_stage_entry_points_argument_errors():
