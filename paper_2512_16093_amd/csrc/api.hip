@@ -79,12 +79,12 @@ inline void mark(hipStream_t s, int rec, int idx) {
 template <class T>
 T* at(void* ws, size_t off) { return (T*)((unsigned char*)ws + off); }
 
-void run_stats(const void* q, const void* k, const void* v, const Problem& p, void* ws, const Workspace& W,
-               hipStream_t s) {
+void run_stats(const void* q, const void* k, const void* v, const void* proj_w, const Problem& p, void* ws,
+               const Workspace& W, hipStream_t s) {
   launch_pool_stats(q, k, v, p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.dq),
                     at<uint32_t>(ws, W.amax_v), s);
   launch_finalize_stats(p, at<float>(ws, W.kbar), at<uint32_t>(ws, W.amax_v), at<float>(ws, W.mu_k),
-                        at<float>(ws, W.dv), at<bf16_t>(ws, W.eye), s);
+                        at<float>(ws, W.dv), (const bf16_t*)proj_w, at<bf16_t>(ws, W.wfrag), s);
 }
 
 }  // namespace
@@ -156,14 +156,13 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
 
   mark(s, rec, 0);
-  run_stats(q, k, v, p, ws, W, s);
+  run_stats(q, k, v, proj_w, p, ws, W, s);
   mark(s, rec, 1);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
   launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
-  const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, true, lin,
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   mark(s, rec, 3);
   if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
@@ -246,8 +245,8 @@ int sla_sparse_attn_fwd(const void* q, const void* k, const void* v, const int32
   if ((st = check_ws(workspace, workspace_bytes, Wmin.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
-  run_stats(q, k, v, p, ws, Wmin, s);
-  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<float>(ws, Wmin.dv), at<bf16_t>(ws, Wmin.eye), 0, true,
+  run_stats(q, k, v, nullptr, p, ws, Wmin, s);
+  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<float>(ws, Wmin.dv), at<bf16_t>(ws, Wmin.wfrag), 0, true,
                  false, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8), at<float>(ws, Wmin.dk), nullptr, s);
   launch_sparse_fwd(q, p, crit_idx, n_crit, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8),
                     at<float>(ws, Wmin.dq), at<float>(ws, Wmin.dk), at<float>(ws, Wmin.dv), nullptr, nullptr, 0,
@@ -268,9 +267,8 @@ int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
-  run_stats(q, k, v, p, ws, W, s);
-  const bf16_t* w = proj_w ? (const bf16_t*)proj_w : at<bf16_t>(ws, W.eye);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), w, phi_kind, false, true, nullptr,
+  run_stats(q, k, v, proj_w, p, ws, W, s);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true, nullptr,
                  nullptr, nullptr, at<bf16_t>(ws, W.hz), s);
   launch_marginal_bits(p, mask, at<uint32_t>(ws, W.m0), s);
   launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
@@ -298,8 +296,8 @@ int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
-  run_stats(k, k, v, p, ws, W, s);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.eye), 0, true, false,
+  run_stats(k, k, v, nullptr, p, ws, W, s);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), 0, true, false,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), nullptr, s);
   launch_unfragment_kv(p, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), k_codes, v_codes, s);
   const size_t bhd = (size_t)p.BH * D * 4;

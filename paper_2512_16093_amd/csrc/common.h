@@ -92,7 +92,7 @@ struct Workspace {
   size_t k8, v8;            // [BH,Tk] records of KV_FRAG_BYTES
   size_t hz;                // bf16 [BH,Tk,HZ_ROWS,D]
   size_t HZ;                // bf16 [BH,Tq,HZ_ROWS,D]
-  size_t eye;               // bf16 [D,D] identity (used when no projection is given)
+  size_t wfrag;             // bf16 [D,D]: the projection (identity if none) in the operand order of prep_kv
   size_t total;
 };
 
@@ -118,7 +118,7 @@ inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, siz
   w.v8 = take(BH * Tk * KV_FRAG_BYTES);
   w.hz = take(BH * Tk * HZ_ELEMS * 2);
   w.HZ = take(BH * Tq * HZ_ELEMS * 2);
-  w.eye = take(D * D * 2);
+  w.wfrag = take(D * D * 2);
   w.total = o;
   return w;
 }
@@ -144,12 +144,12 @@ struct Problem {
 void launch_pool_stats(const void* q, const void* k, const void* v, const Problem& p, float* qbar,
                        float* kbar, float* dq, uint32_t* amax_v, hipStream_t stream);
 void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,
-                           float* dv, bf16_t* eye, hipStream_t stream);
+                           float* dv, const bf16_t* proj_w, bf16_t* wfrag, hipStream_t stream);
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores, hipStream_t stream);
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
                    uint32_t* mbits, hipStream_t stream);
 void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
-                    const bf16_t* proj_w, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
+                    const bf16_t* wfrag, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream);
 void launch_marginal_bits(const Problem& p, const int8_t* mask, uint32_t* mbits, hipStream_t stream);
 void launch_lin_accumulate(const Problem& p, const uint32_t* mbits, const bf16_t* hz, bf16_t* HZ,

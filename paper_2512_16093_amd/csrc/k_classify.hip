@@ -122,10 +122,15 @@ __global__ void zero_u32_kernel(uint32_t* p, size_t n) {
 }
 
 // finalize_stats: one workgroup of 1024 threads per (b,h): mu_K[c] = sum_j cnt_j kbar[j][c] / N,
-// delta_V[c] = max|V[:,c]| / 448 (1 if zero).  Workgroup 0 also writes the bf16 identity.
+// delta_V[c] = max|V[:,c]| / 448 (1 if zero).  Workgroup 0 also lays the output projection (the
+// identity if none is given) out in the order in which prep_kv's first product takes it as the B
+// operand of v_mfma_f32_32x32x16_bf16: 16-byte chunk [tile of 32 output channels][step of 16 input
+// channels][lane] = W[32 tile + lane % 32][16 step + 8 (lane / 32) + 0..7], so that a wavefront
+// fetches an operand as one contiguous KiB.
 __global__ void __launch_bounds__(1024) finalize_stats_kernel(
     const float* __restrict__ kbar, const uint32_t* __restrict__ amax_v, int N, int Tk,
-    float* __restrict__ mu_k, float* __restrict__ dv, bf16_t* __restrict__ eye) {
+    float* __restrict__ mu_k, float* __restrict__ dv, const bf16_t* __restrict__ proj_w,
+    bf16_t* __restrict__ wfrag) {
   __shared__ float red[8][D];
   const int bh = blockIdx.x, t = threadIdx.x, c = t & 127, rgrp = t >> 7;
   float s = 0.f;
@@ -144,7 +149,11 @@ __global__ void __launch_bounds__(1024) finalize_stats_kernel(
     dv[(size_t)bh * D + t] = am > 0.f ? am / E4M3_MAX : 1.0f;
   }
   if (bh == 0) {
-    for (int i = t; i < D * D; i += 1024) eye[i] = (i / D == i % D) ? (bf16_t)0x3f80 : (bf16_t)0;
+    for (int idx = t; idx < D * D / 8; idx += 1024) {
+      const int lane = idx & 63, row = 32 * (idx >> 9) + (lane & 31), col = 16 * ((idx >> 6) & 7) + 8 * (lane >> 5);
+      for (int e = 0; e < 8; ++e)
+        wfrag[idx * 8 + e] = proj_w ? proj_w[row * D + col + e] : (row == col + e ? (bf16_t)0x3f80 : (bf16_t)0);
+    }
   }
 }
 
@@ -305,8 +314,8 @@ void launch_pool_stats(const void* q, const void* k, const void* v, const Proble
 }
 
 void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,
-                           float* dv, bf16_t* eye, hipStream_t stream) {
-  finalize_stats_kernel<<<p.BH, 1024, 0, stream>>>(kbar, amax_v, p.N, p.Tk, mu_k, dv, eye);
+                           float* dv, const bf16_t* proj_w, bf16_t* wfrag, hipStream_t stream) {
+  finalize_stats_kernel<<<p.BH, 1024, 0, stream>>>(kbar, amax_v, p.N, p.Tk, mu_k, dv, proj_w, wfrag);
 }
 
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores,

@@ -24,15 +24,16 @@ constexpr int STAGE_STRIDE = 2 * D + 16;  // bytes per staged hz row (padded aga
 template <int PHI>
 __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk, int H, Layout lk, Layout lv,
-    const float* __restrict__ mu_k, const float* __restrict__ dv, const bf16_t* __restrict__ W,
+    const float* __restrict__ mu_k, const float* __restrict__ dv, const bf16_t* __restrict__ wfrag,
     int want_quant, int want_linear, int8_t* __restrict__ k8, uint8_t* __restrict__ v8,
     float* __restrict__ dk, bf16_t* __restrict__ hz) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[128 * STAGE_STRIDE + 4 * D * 4];
   __shared__ float wave_amax[4];
   unsigned char* kq = smem;                       // [8192]  K codes, fragment order
   unsigned char* vq = smem + KV_FRAG_BYTES;       // [8192]  V codes, fragment order
-  unsigned char* phit = smem + 2 * KV_FRAG_BYTES; // [16384] phi(K)^T bf16, B-operand order
-  unsigned char* stage = smem;                    // [128][STAGE_STRIDE] aliases the three above
+  unsigned char* vbf = smem;                      // [64][STAGE_STRIDE] V rows as bf16 (aliases kq / vq, after their last read)
+  unsigned char* phit = smem + BK * STAGE_STRIDE; // [16384] phi(K)^T bf16, B-operand order
+  unsigned char* stage = smem;                    // [128][STAGE_STRIDE] aliases everything above
   float* zred = (float*)(smem + 128 * STAGE_STRIDE);  // [4][128] per-wavefront column sums of phi(K)
 
   const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk;
@@ -42,22 +43,22 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
   const bf16_t* kblk = k + b_ * lk.sb + h_ * lk.sh + (long long)j * BK * lk.sn;
   const bf16_t* vblk = v + b_ * lv.sb + h_ * lv.sh + (long long)j * BK * lv.sn;
 
-  float kf[4][8], vf[4][8];
+  float kf[4][8];
+  uint4 vraw[4];  // V stays packed: it is quantised from these words and staged for product 1 as they are
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int row = 4 * m + r;
-    uint4 xk = make_uint4(0, 0, 0, 0), xv = make_uint4(0, 0, 0, 0);
+    uint4 xk = make_uint4(0, 0, 0, 0);
+    vraw[r] = make_uint4(0, 0, 0, 0);
     if (row < valid) {
       xk = *(const uint4*)(kblk + row * lk.sn + cg * 8);
-      xv = *(const uint4*)(vblk + row * lv.sn + cg * 8);
+      vraw[r] = *(const uint4*)(vblk + row * lv.sn + cg * 8);
     }
-    const uint32_t wk[4] = {xk.x, xk.y, xk.z, xk.w}, wv[4] = {xv.x, xv.y, xv.z, xv.w};
+    const uint32_t wk[4] = {xk.x, xk.y, xk.z, xk.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       kf[r][2 * e] = bf16_lo(wk[e]);
       kf[r][2 * e + 1] = bf16_hi(wk[e]);
-      vf[r][2 * e] = bf16_lo(wv[e]);
-      vf[r][2 * e + 1] = bf16_hi(wv[e]);
     }
   }
 
@@ -111,8 +112,10 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
       for (int r = 0; r < 4; ++r) {
         // quotient by reciprocal + one correction step: the correctly rounded v / delta_V for the
         // magnitudes that occur here, at a third of the cost of the general division sequence
-        float qv = vf[r][e] * rdv[e];
-        qv = __builtin_fmaf(__builtin_fmaf(-qv, dvc[e], vf[r][e]), rdv[e], qv);
+        const uint32_t word = (e >> 1) == 0 ? vraw[r].x : (e >> 1) == 1 ? vraw[r].y : (e >> 1) == 2 ? vraw[r].z : vraw[r].w;
+        const float vf = (e & 1) ? bf16_hi(word) : bf16_lo(word);
+        float qv = vf * rdv[e];
+        qv = __builtin_fmaf(__builtin_fmaf(-qv, dvc[e], vf), rdv[e], qv);
         x[r] = clamp_e4m3(qv);
       }
       int code = cvt_pk_e4m3(x[0], x[1], 0, false);
@@ -174,7 +177,10 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
       zs += __shfl_xor(zs, 32);
       if (lane < 16) zred[w * D + c] = zs;
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) *(uint4*)(vbf + (4 * m + r) * STAGE_STRIDE + cg * 16) = vraw[r];
   }
+  __syncthreads();  // phit, zred and the V rows are complete
 
   // ---- product 1: VW[row][o] for o in this wavefront's tile of 32 output channels
   const int hfl = lane >> 5, l32 = lane & 31;
@@ -182,17 +188,14 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt) {
     d1[rt] = v16f{};
-    const int row = 32 * rt + l32;
-    const bool ok = row < valid;
+    const int row = 32 * rt + l32;  // rows past the end of a ragged block were staged as zeros
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      v8bf a = v8bf{};
-      if (ok) a = *(const v8bf*)(vblk + row * lv.sn + 16 * ks + 8 * hfl);
-      const v8bf b = *(const v8bf*)(W + (size_t)(32 * w + l32) * D + 16 * ks + 8 * hfl);
+      const v8bf a = *(const v8bf*)(vbf + row * STAGE_STRIDE + 32 * ks + 16 * hfl);
+      const v8bf b = *(const v8bf*)(wfrag + ((w * 8 + ks) * 64 + lane) * 8);
       d1[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, d1[rt], 0, 0, 0);
     }
   }
-  __syncthreads();  // phit and zred complete
 
   // ---- product 2: hz[o][c] = sum over rows of VW[row][o] phi[row][c]
   v16f d2[4];
@@ -253,17 +256,17 @@ __global__ void e4m3_encode_kernel(const float* __restrict__ in, uint8_t* __rest
 }
 
 void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
-                    const bf16_t* proj_w, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
+                    const bf16_t* wfrag, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream) {
   const unsigned grid = (unsigned)(p.BH * p.Tk);
   const bf16_t* kk = (const bf16_t*)k;
   const bf16_t* vv = (const bf16_t*)v;
   if (phi_kind == 0)
-    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, wfrag, want_quant, want_linear, k8, v8, dk, hz);
   else if (phi_kind == 1)
-    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, wfrag, want_quant, want_linear, k8, v8, dk, hz);
   else
-    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, proj_w, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, wfrag, want_quant, want_linear, k8, v8, dk, hz);
 }
 
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
