@@ -90,19 +90,20 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     const float delta = amax > 0.f ? amax / 127.0f : 1.0f;
     // K codes by multiplication with the reciprocal: differs from a true division only at
     // rounding ties, where one INT8 step moves a score by delta_Q delta_K (the FP8 V codes, whose
-    // steps are coarse, keep the true division)
+    // steps are coarse, keep the true division).  Adding 1.5 * 2^23 inside the fma rounds the
+    // product to the nearest integer (ties to even) and leaves its two's-complement low byte in
+    // the low byte of the float; |k~ / delta| <= 127 by construction, so no clamp is needed.
     const float inv_delta = 1.0f / delta;
     if (t == 0) dk[(size_t)bh * Tk + j] = delta;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      uint32_t lo = 0, hi = 0;
+      uint32_t b[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float c = __builtin_rintf(kt[r][e] * inv_delta);
-        c = fminf(fmaxf(c, -127.f), 127.f);
-        const uint32_t byte = (uint32_t)((int)c) & 0xffu;
-        if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
-      }
+      for (int e = 0; e < 8; ++e) b[e] = __float_as_uint(__builtin_fmaf(kt[r][e], inv_delta, 12582912.0f));
+      const uint32_t lo = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
+                                                __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);
+      const uint32_t hi = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[7], b[6], 0x0c0c0400u),
+                                                __builtin_amdgcn_perm(b[5], b[4], 0x0c0c0400u), 0x05040100u);
       *(uint2*)(kq + kfrag_offset(4 * m + r, cg * 8)) = make_uint2(lo, hi);
     }
 #pragma unroll
@@ -197,7 +198,8 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     }
   }
 
-  // ---- product 2: hz[o][c] = sum over rows of VW[row][o] phi[row][c]
+  // ---- product 2, transposed: hz^T[c][o] = sum over rows of phi[row][c] VW[row][o], so that a lane
+  // ends up with four consecutive c of one o in consecutive registers (8-byte staging writes)
   v16f d2[4];
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) d2[ct] = v16f{};
@@ -209,7 +211,7 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
       const v8bf b = *(const v8bf*)(phit + ((s2 * 128 + 32 * ct + l32) * 2 + hfl) * 16);
-      d2[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, d2[ct], 0, 0, 0);
+      d2[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, d2[ct], 0, 0, 0);
     }
   }
   float zsum = 0.f;
@@ -221,9 +223,10 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int o = 32 * w + 8 * (r >> 2) + 4 * hfl + (r & 3);
-      *(bf16_t*)(stage + o * STAGE_STRIDE + (32 * ct + l32) * 2) = f32_to_bf16(d2[ct][r]);
+    for (int g = 0; g < 4; ++g) {
+      const v16f& x = d2[ct];
+      *(uint2*)(stage + (32 * w + l32) * STAGE_STRIDE + (32 * ct + 8 * g + 4 * hfl) * 2) =
+          make_uint2(pack_bf16x2(x[4 * g], x[4 * g + 1]), pack_bf16x2(x[4 * g + 2], x[4 * g + 3]));
     }
   __syncthreads();
   bf16_t* dst = hz + ((size_t)bh * Tk + j) * HZ_ELEMS;
