@@ -121,34 +121,34 @@ __global__ void zero_u32_kernel(uint32_t* p, size_t n) {
   if (i < n) p[i] = 0u;
 }
 
-// finalize_stats: one workgroup of 1024 threads per (b,h): mu_K[c] = sum_j cnt_j kbar[j][c] / N,
-// delta_V[c] = max|V[:,c]| / 448 (1 if zero).  Workgroup 0 also lays the output projection (the
-// identity if none is given) out in the order in which prep_kv's first product takes it as the B
-// operand of v_mfma_f32_32x32x16_bf16: 16-byte chunk [tile of 32 output channels][step of 16 input
+// finalize_stats: eight workgroups of 1024 threads per (b,h), each for 16 channels:
+// mu_K[c] = sum_j cnt_j kbar[j][c] / N (summed in a fixed order), delta_V[c] = max|V[:,c]| / 448
+// (1 if zero).  Workgroup 0 also lays the output projection (the identity if none is given) out
+// in the order in which prep_kv's first product takes it as the B operand of
+// v_mfma_f32_32x32x16_bf16: 16-byte chunk [tile of 32 output channels][step of 16 input
 // channels][lane] = W[32 tile + lane % 32][16 step + 8 (lane / 32) + 0..7], so that a wavefront
 // fetches an operand as one contiguous KiB.
 __global__ void __launch_bounds__(1024) finalize_stats_kernel(
     const float* __restrict__ kbar, const uint32_t* __restrict__ amax_v, int N, int Tk,
     float* __restrict__ mu_k, float* __restrict__ dv, const bf16_t* __restrict__ proj_w,
     bf16_t* __restrict__ wfrag) {
-  __shared__ float red[8][D];
-  const int bh = blockIdx.x, t = threadIdx.x, c = t & 127, rgrp = t >> 7;
+  __shared__ float red[64][17];
+  const int bh = blockIdx.x >> 3, c0 = (blockIdx.x & 7) * 16, t = threadIdx.x, cl = t & 15, rgrp = t >> 4;
   float s = 0.f;
-  for (int j = rgrp; j < Tk; j += 8) {
+  for (int j = rgrp; j < Tk; j += 64) {
     const int cnt = min(BK, N - j * BK);
-    s += kbar[((size_t)bh * Tk + j) * D + c] * (float)cnt;
+    s += kbar[((size_t)bh * Tk + j) * D + c0 + cl] * (float)cnt;
   }
-  red[rgrp][c] = s;
+  red[rgrp][cl] = s;
   __syncthreads();
-  if (t < 128) {
+  if (t < 16) {
     float tot = 0.f;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) tot += red[r][t];
-    mu_k[(size_t)bh * D + t] = tot / (float)N;
-    const float am = __uint_as_float(amax_v[(size_t)bh * D + t]);
-    dv[(size_t)bh * D + t] = am > 0.f ? am / E4M3_MAX : 1.0f;
+    for (int r = 0; r < 64; ++r) tot += red[r][t];
+    mu_k[(size_t)bh * D + c0 + t] = tot / (float)N;
+    const float am = __uint_as_float(amax_v[(size_t)bh * D + c0 + t]);
+    dv[(size_t)bh * D + c0 + t] = am > 0.f ? am / E4M3_MAX : 1.0f;
   }
-  if (bh == 0) {
+  if (blockIdx.x == 0) {
     for (int idx = t; idx < D * D / 8; idx += 1024) {
       const int lane = idx & 63, row = 32 * (idx >> 9) + (lane & 31), col = 16 * ((idx >> 6) & 7) + 8 * (lane >> 5);
       for (int e = 0; e < 8; ++e)
@@ -315,7 +315,7 @@ void launch_pool_stats(const void* q, const void* k, const void* v, const Proble
 
 void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,
                            float* dv, const bf16_t* proj_w, bf16_t* wfrag, hipStream_t stream) {
-  finalize_stats_kernel<<<p.BH, 1024, 0, stream>>>(kbar, amax_v, p.N, p.Tk, mu_k, dv, proj_w, wfrag);
+  finalize_stats_kernel<<<p.BH * 8, 1024, 0, stream>>>(kbar, amax_v, p.N, p.Tk, mu_k, dv, proj_w, wfrag);
 }
 
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores,

@@ -23,6 +23,8 @@
 // as they are (n contiguous) and read back with the LDS transposing read of gfx950
 // (ds_read_b64_tr_b16): the contraction index j is the slow index of hz, so one transposition
 // is unavoidable, and this one costs 8 LDS reads per 12 MFMAs and no vector-ALU work.
+#include <type_traits>
+
 #include "common.h"
 
 namespace sla {
@@ -134,7 +136,10 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const 
   const int groups = n_items / chunks;  // (b,h, stripe) pairs; group g runs on XCD g % 8
   for (int it = slot; it < (groups + 7) / 8 * chunks; it += slots) {
   // item = 8 * (it / chunks) ... : groups of `chunks` consecutive items stay on one XCD
-  const int grp = it / chunks, item = (grp * 8 + xcd) * chunks + it % chunks;
+  // (the chunk a slot takes rotates from one round of the slots to the next: a head's last chunk
+  // is usually shorter, and every workgroup should get its share of short ones)
+  const int grp = it / chunks, rot = grp / max(1, slots / chunks);
+  const int item = (grp * 8 + xcd) * chunks + (it % chunks + rot) % chunks;
   if (item >= n_items) continue;  // (uniform)
   const int chunk = item % chunks, stripe = (item / chunks) % STRIPES, bh = item / (chunks * STRIPES);
   const int n0 = stripe * LA_COLS, row0 = chunk * LA_ROWS;
@@ -165,21 +170,29 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const 
     else __builtin_amdgcn_s_waitcnt(0x0F70);
   };
 
-  v16f acc[3][4];
+  // The chunk's row tiles (of 32 query blocks; 12 in a full chunk, fewer in a head's last one)
+  // are dealt to the four wavefronts as evenly as consecutive runs allow, and the loop below is
+  // instantiated for the largest share, so a short last chunk costs its share of MFMAs only.
+  const int tiles_c = min(LA_ROWS / 32, (Tq - row0 + 31) / 32);
+  const int t_base = tiles_c >> 2, t_rem = tiles_c & 3;
+  const int my_tiles = t_base + (w < t_rem ? 1 : 0), wrow = 32 * (w * t_base + min(w, t_rem));
+  auto run_item = [&](auto nmt_tag) {
+  constexpr int NMT = decltype(nmt_tag)::value;
+  v16f acc[NMT][4];
 #pragma unroll
-  for (int a = 0; a < 3; ++a)
+  for (int a = 0; a < NMT; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = v16f{};
 
 #define LA_COMPUTE(KTI, HZS, MWS)                                                                         \
   _Pragma("unroll") for (int sub = 0; sub < LA_KSUB; ++sub) {                                             \
-    uint32_t mw[3];                                                                                       \
+    uint32_t mw[NMT];                                                                                     \
     const bool live = (KTI) * LA_KSUB + sub < KT32; /* uniform: the last tile may be partly past the end */ \
-    _Pragma("unroll") for (int mt = 0; mt < 3; ++mt)                                                      \
-      mw[mt] = live ? MWS[sub * LA_M_ROWS + 96 * w + 32 * mt + l32] : 0u;                                 \
+    _Pragma("unroll") for (int mt = 0; mt < NMT; ++mt)                                                    \
+      mw[mt] = live ? MWS[sub * LA_M_ROWS + wrow + 32 * mt + l32] : 0u;                                   \
     _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                    \
-      v8bf aop[3], bop[4];                                                                                \
-      _Pragma("unroll") for (int mt = 0; mt < 3; ++mt) {                                                  \
+      v8bf aop[NMT], bop[4];                                                                              \
+      _Pragma("unroll") for (int mt = 0; mt < NMT; ++mt) {                                                \
         union { uint4 u; v8bf v; } c;                                                                     \
         c.u = lut[(mw[mt] >> (16 * ks + 8 * hf)) & 0xffu];                                                \
         aop[mt] = c.v;                                                                                    \
@@ -192,7 +205,7 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const 
         u.h[1] = la_read_tr(&HZS[tr_off + (r0 + 4) * LA_B_ROW + (r0 >> 3) * 64 + c0]);                    \
         bop[nt] = u.v;                                                                                    \
       }                                                                                                   \
-      _Pragma("unroll") for (int mt = 0; mt < 3; ++mt)                                                    \
+      _Pragma("unroll") for (int mt = 0; mt < NMT; ++mt)                                                  \
         _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                                  \
           acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[nt], aop[mt], acc[mt][nt], 0, 0, 0);  \
     }                                                                                                     \
@@ -224,10 +237,12 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const 
   // The tiles were accumulated transposed (summary entries along the MFMA rows, query blocks
   // along its columns), so a lane owns ONE query block and runs of 4 consecutive entries of
   // its summary: 8-byte stores, the two lane halves completing 16 contiguous bytes.
+  // (a wavefront with fewer row tiles than NMT has accumulated a neighbour's rows in the spare
+  // tiles; it does not store them)
 #pragma unroll
-  for (int mt = 0; mt < 3; ++mt) {
-    const int i = row0 + 96 * w + 32 * mt + l32;
-    if (i < Tq) {
+  for (int mt = 0; mt < NMT; ++mt) {
+    const int i = row0 + wrow + 32 * mt + l32;
+    if (mt < my_tiles && i < Tq) {
       bf16_t* dst = HZ + ((size_t)bh * Tq + i) * HZ_ELEMS + n0 + 4 * hf;
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
@@ -238,6 +253,11 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const 
         }
     }
   }
+  };  // run_item
+  const int nmt_item = t_base + (t_rem ? 1 : 0);
+  if (nmt_item == 3) run_item(std::integral_constant<int, 3>{});
+  else if (nmt_item == 2) run_item(std::integral_constant<int, 2>{});
+  else run_item(std::integral_constant<int, 1>{});
   }  // work items
 }
 
