@@ -27,6 +27,8 @@ EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspac
            "sla_attention_fwd", "sla_attention_fwd_strided", "sla_classify_blocks", "sla_sparse_attn_fwd",
            "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv",
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
+W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
+                "w8a8_quantize_act", "w8a8_gemm_fwd", "w8a8_debug_unpack")
 N_STAGES = 5
 STAGE_NAMES = ("pool_stats", "scores_select", "prep_kv", "lin_accumulate", "sparse_fwd")
 
@@ -84,6 +86,21 @@ def lib():
         L.sla_profile_reset.argtypes = []
         L.sla_profile_read.restype = c_int
         L.sla_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), c_int, ip]
+        # include/w8a8.h
+        L.w8a8_weight_bytes.restype = c_sz
+        L.w8a8_weight_bytes.argtypes = [c_int, c_int]
+        L.w8a8_workspace_bytes.restype = c_sz
+        L.w8a8_workspace_bytes.argtypes = [c_int, c_int]
+        L.w8a8_quantize_weight.restype = c_int
+        L.w8a8_quantize_weight.argtypes = [c_vp, c_int, c_int, c_vp, c_vp]
+        L.w8a8_linear_fwd.restype = c_int
+        L.w8a8_linear_fwd.argtypes = [c_vp] * 4 + [c_int] * 3 + [c_vp, c_sz, c_vp]
+        L.w8a8_quantize_act.restype = c_int
+        L.w8a8_quantize_act.argtypes = [c_vp, c_int, c_int, c_vp, c_sz, c_vp]
+        L.w8a8_gemm_fwd.restype = c_int
+        L.w8a8_gemm_fwd.argtypes = [c_vp, c_sz, c_vp, c_vp, c_vp] + [c_int] * 3 + [c_vp]
+        L.w8a8_debug_unpack.restype = c_int
+        L.w8a8_debug_unpack.argtypes = [c_vp, c_int, c_int, c_int, c_vp, c_vp, c_vp]
         _lib = L
     return _lib
 
@@ -269,3 +286,76 @@ def sla_profile_read(max_calls):
     n = ctypes.c_int(0)
     _check(lib().sla_profile_read(buf, max_calls, ctypes.byref(n)), "sla_profile_read")
     return [[buf[r * N_STAGES + s] for s in range(N_STAGES)] for r in range(n.value)]
+
+
+# ---------------------------------------------------------------------------
+# include/w8a8.h
+# ---------------------------------------------------------------------------
+def _bf16_2d(t, what):
+    if t.dtype != torch.bfloat16 or not t.is_cuda or t.dim() != 2 or not t.is_contiguous():
+        raise ValueError("%s: expected a contiguous 2-D CUDA bfloat16 tensor" % what)
+    return t.shape
+
+
+def w8a8_weight_bytes(N, K):
+    return lib().w8a8_weight_bytes(N, K)
+
+
+def w8a8_workspace_bytes(M, K):
+    return lib().w8a8_workspace_bytes(M, K)
+
+
+def w8a8_quantize_weight(w):
+    """The quantised weight object (a uint8 tensor) of a bf16 weight [N, K]."""
+    N, K = _bf16_2d(w, "w")
+    nbytes = w8a8_weight_bytes(N, K)
+    if nbytes == 0:
+        raise ValueError("unsupported weight shape [%d, %d]" % (N, K))
+    wq = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    _check(lib().w8a8_quantize_weight(_ptr(w), N, K, _ptr(wq), _stream()), "w8a8_quantize_weight")
+    return wq
+
+
+def w8a8_alloc_workspace(M, K, device="cuda"):
+    nbytes = w8a8_workspace_bytes(M, K)
+    if nbytes == 0:
+        raise ValueError("unsupported activation shape [%d, %d]" % (M, K))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def w8a8_linear_fwd(x, wq, N, bias=None, workspace=None, out=None):
+    """y bf16 [M, N] = W8A8-linear(x bf16 [M, K]) with the weight object `wq` of an [N, K] weight."""
+    M, K = _bf16_2d(x, "x")
+    if workspace is None:
+        workspace = w8a8_alloc_workspace(M, K, x.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x.device)
+    st = lib().w8a8_linear_fwd(_ptr(x), _ptr(wq), _ptr(bias), _ptr(out), M, N, K, _ptr(workspace),
+                               workspace.numel(), _stream())
+    _check(st, "w8a8_linear_fwd")
+    return out
+
+
+def w8a8_quantize_act(x, workspace=None):
+    M, K = _bf16_2d(x, "x")
+    if workspace is None:
+        workspace = w8a8_alloc_workspace(M, K, x.device)
+    _check(lib().w8a8_quantize_act(_ptr(x), M, K, _ptr(workspace), workspace.numel(), _stream()), "w8a8_quantize_act")
+    return workspace
+
+
+def w8a8_gemm_fwd(workspace, wq, M, N, K, bias=None, out=None):
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=workspace.device)
+    st = lib().w8a8_gemm_fwd(_ptr(workspace), workspace.numel(), _ptr(wq), _ptr(bias), _ptr(out), M, N, K, _stream())
+    _check(st, "w8a8_gemm_fwd")
+    return out
+
+
+def w8a8_debug_unpack(q, is_weight, R, K):
+    """(codes int8 [R, K], scales fp32 [ceil(R/128), K/128]) held by a weight object or a filled workspace."""
+    codes = torch.empty((R, K), dtype=torch.int8, device=q.device)
+    scales = torch.empty((-(-R // 128), K // 128), dtype=torch.float32, device=q.device)
+    _check(lib().w8a8_debug_unpack(_ptr(q), 1 if is_weight else 0, R, K, _ptr(codes), _ptr(scales), _stream()),
+           "w8a8_debug_unpack")
+    return codes, scales

@@ -134,3 +134,18 @@ def make_proj(cfg: SLAConfig, seed: int = 0):
 def as_f64(x: torch.Tensor) -> np.ndarray:
     """Exact widening of a bf16 tensor to a float64 numpy array."""
     return x.to(torch.float64).numpy()
+
+
+def make_linear_inputs(M: int, K: int, N: int, seed: int = 0, with_bias: bool = True):
+    """Stand-in for a DiT Linear layer (no trained weights are available): activations
+    X [M, K] ~ N(0, 1) with 1 % of the features carrying 10-30x the amplitude (the outlier
+    channels typical of transformer activations) and a per-token amplitude in [0.5, 2];
+    weights W [N, K] ~ N(0, 1 / K); bias ~ N(0, 0.1).  torch.bfloat16 CPU tensors."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 4242, M, K, N])))
+    X = rng.standard_normal((M, K), dtype=np.float32)
+    out_ch = rng.choice(K, size=max(1, K // 100), replace=False)
+    X[:, out_ch] *= rng.uniform(10.0, 30.0, size=out_ch.size).astype(np.float32)
+    X *= rng.uniform(0.5, 2.0, size=(M, 1)).astype(np.float32)
+    W = rng.standard_normal((N, K), dtype=np.float32) / np.float32(math.sqrt(K))
+    b = _to_bf16(0.1 * rng.standard_normal(N)) if with_bias else None
+    return _to_bf16(X), _to_bf16(W), b

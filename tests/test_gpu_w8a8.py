@@ -1,0 +1,115 @@
+"""GPU parity of the W8A8 Linear layer (through the C ABI) against the CPU oracle:
+the quantiser's codes and scales, the INT8 product with its block-scale accumulation
+given those codes, and the whole layer from bf16 inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import w8a8_oracle as wo
+from paper_2512_16093_amd import binding as sla
+from paper_2512_16093_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+# (M, K, N): one token; ragged token tails; one and many feature blocks; several output tiles
+SHAPES = [(1, 128, 128), (300, 384, 256), (257, 256, 128), (1000, 1024, 512), (640, 2048, 384)]
+
+
+def check_codes(gpu_codes, gpu_scales, A, what):
+    codes, scales = wo.quantize_blockwise(A)
+    # scales: max|block| / 127 evaluated in fp32 on the GPU, in fp64 here
+    assert np.allclose(gpu_scales, scales, rtol=3e-7, atol=0), what
+    diff = np.abs(gpu_codes.astype(np.float64) - codes)
+    # the GPU multiplies by the reciprocal of the fp32 scale: codes can differ by one step where
+    # x / s falls within rounding distance of a tie
+    assert diff.max() <= 1 and (diff != 0).mean() <= 1e-3, (what, diff.max(), (diff != 0).mean())
+
+
+def product_tolerance(ref, sX, sW, K):
+    """bf16 rounding of the result (relative 2^-9, doubled) plus the fp32 accumulation of the block
+    sums.  The kernel adds each block sum together with a constant of about 2^23.4 integer steps
+    (it reads the integer accumulator as a float, see the kernel's header) and removes the
+    constants every fourth block, so a running sum stays below 2^26 steps and every fma rounds by
+    at most 2 steps s_X s_W: at most 2 K / 128 steps in all (a worst case; the errors are random)."""
+    return 2.0 ** -8 * np.abs(ref) + (2.0 * K / 128 + 1.0) * sX.max() * sW.max()
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_quantiser_matches_oracle(M, K, N):
+    x, w, _ = synth.make_linear_inputs(M, K, N)
+    ws = sla.w8a8_quantize_act(x.cuda())
+    xc, xs = sla.w8a8_debug_unpack(ws, False, M, K)
+    check_codes(xc.cpu().numpy(), xs.cpu().numpy(), synth.as_f64(x), "activations %s" % ((M, K),))
+    wq = sla.w8a8_quantize_weight(w.cuda())
+    wc, wsc = sla.w8a8_debug_unpack(wq, True, N, K)
+    check_codes(wc.cpu().numpy(), wsc.cpu().numpy(), synth.as_f64(w), "weights %s" % ((N, K),))
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_product_matches_oracle_on_the_same_codes(M, K, N, with_bias):
+    x, w, b = synth.make_linear_inputs(M, K, N, seed=1, with_bias=with_bias)
+    xd, wd = x.cuda(), w.cuda()
+    bd = None if b is None else b.cuda()
+    wq = sla.w8a8_quantize_weight(wd)
+    ws = sla.w8a8_quantize_act(xd)
+    y = sla.w8a8_gemm_fwd(ws, wq, M, N, K, bias=bd).float().cpu().numpy()
+    xc, xs = (t.cpu().numpy().astype(np.float64) for t in sla.w8a8_debug_unpack(ws, False, M, K))
+    wc, wsc = (t.cpu().numpy().astype(np.float64) for t in sla.w8a8_debug_unpack(wq, True, N, K))
+    ref = wo.linear_from_codes(xc, xs, wc, wsc, None if b is None else synth.as_f64(b))
+    assert np.all(np.abs(y - ref) <= product_tolerance(ref, xs, wsc, K)), np.abs(y - ref).max()
+
+
+@pytest.mark.parametrize("M,K,N", SHAPES)
+def test_whole_layer_matches_oracle(M, K, N):
+    x, w, b = synth.make_linear_inputs(M, K, N, seed=2)
+    wq = sla.w8a8_quantize_weight(w.cuda())
+    y = sla.w8a8_linear_fwd(x.cuda(), wq, N, bias=b.cuda()).float().cpu().numpy()
+    ref, parts = wo.w8a8_linear(synth.as_f64(x), synth.as_f64(w), synth.as_f64(b))
+    # on top of the product's tolerance, a code that differs by one step (at a rounding tie, at most
+    # 0.1 % of them) moves a result by one step times the other operand's code
+    tol = product_tolerance(ref, parts["sX"], parts["sW"], K) + 127.0 * 4 * parts["sX"].max() * parts["sW"].max()
+    assert np.all(np.abs(y - ref) <= tol), np.abs(y - ref).max()
+    assert np.linalg.norm(y - ref) / np.linalg.norm(ref) < 3e-3
+    # and the layer does its job: close to the unquantised product (a block's scale follows its
+    # outlier features, so the other features of the block keep only a few bits: several percent)
+    dense = synth.as_f64(x) @ synth.as_f64(w).T + synth.as_f64(b)
+    assert np.linalg.norm(y - dense) / np.linalg.norm(dense) < 0.15
+
+
+def test_exactly_representable_inputs_lose_only_the_accumulation_steps():
+    """Integer codes times power-of-two scales, every block holding a 127: quantisation is lossless,
+    so the only errors left are the accumulation's (at most 2 steps s_X s_W = 1/8 per block, two
+    blocks here) and the bf16 rounding of the output."""
+    g = np.random.default_rng(3)
+    M, K, N = 300, 256, 256
+    Xi = g.integers(-3, 4, size=(M, K)).astype(np.float32)
+    Wi = g.integers(-2, 3, size=(N, K)).astype(np.float32)
+    Xi[::128, ::128] = 127.0
+    Wi[::128, ::128] = 127.0
+    Xi[::128, 1::128] = 0.0
+    x = torch.from_numpy(Xi * 0.25).to(torch.bfloat16)
+    w = torch.from_numpy(Wi * 0.5).to(torch.bfloat16)
+    xd, wd = x.cuda(), w.cuda()
+    wq = sla.w8a8_quantize_weight(wd)
+    ws = sla.w8a8_quantize_act(xd)
+    xc, xs = sla.w8a8_debug_unpack(ws, False, M, K)
+    wc, wsc = sla.w8a8_debug_unpack(wq, True, N, K)
+    assert np.array_equal(xc.cpu().numpy(), Xi) and np.array_equal(wc.cpu().numpy(), Wi)      # lossless codes
+    assert (xs == 0.25).all() and (wsc == 0.5).all()
+    y = sla.w8a8_linear_fwd(xd, wq, N).float().cpu().numpy()
+    ref = (Xi * 0.25).astype(np.float64) @ (Wi * 0.5).astype(np.float64).T
+    assert np.all(np.abs(y - ref) <= 4 * 0.125 + 2.0 ** -9 * np.abs(ref))
+    assert (y == ref).mean() > 0.5          # and most results are exact
+
+
+def test_deterministic_and_workspace_reuse():
+    x, w, b = synth.make_linear_inputs(500, 512, 256, seed=4)
+    xd, bd = x.cuda(), b.cuda()
+    wq = sla.w8a8_quantize_weight(w.cuda())
+    ws = sla.w8a8_alloc_workspace(500, 512)
+    y1 = sla.w8a8_linear_fwd(xd, wq, 256, bias=bd, workspace=ws).clone()
+    sla.w8a8_linear_fwd(xd[:100].contiguous(), wq, 256, bias=bd, workspace=ws)   # a smaller call in between
+    y2 = sla.w8a8_linear_fwd(xd, wq, 256, bias=bd, workspace=ws)
+    assert torch.equal(y1, y2)
+    assert torch.equal(x, xd.cpu())

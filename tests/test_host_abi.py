@@ -16,10 +16,10 @@ FAKE = ctypes.c_void_p(0x1000)      # non-NULL, never dereferenced: validation f
 WS = ctypes.c_void_p(0x10000)       # 256-byte aligned fake workspace
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "sla.h")).read()
+def _declared(header="sla.h", prefix="sla_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sla_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(%s[a-z0-9_]+)\s*\(" % prefix, text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -29,6 +29,40 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sla.sla_version() >= 100
+    names = _declared("w8a8.h", "w8a8_")
+    assert set(names) == set(sla.W8A8_EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_w8a8_sizes_and_argument_errors():
+    L = sla.lib()
+    # weight object and workspace: one byte per code (activations padded to 256-token tiles) plus scales
+    assert sla.w8a8_weight_bytes(5120, 5120) == 5120 * 5120 + 40 * 40 * 4
+    assert sla.w8a8_weight_bytes(256, 128) == 256 * 128 + 256
+    assert sla.w8a8_workspace_bytes(75600, 5120) == 75776 * 5120 + (592 * 40 * 4 + 255) // 256 * 256
+    assert sla.w8a8_workspace_bytes(1, 128) == 256 * 128 + 256
+    for bad in ((100, 128), (128, 100), (128, 64), (0, 128), (128, 1 << 17)):
+        assert sla.w8a8_weight_bytes(*bad) == 0
+    for bad in ((0, 128), (5, 100), (5, 0), ((1 << 22) + 1, 128)):
+        assert sla.w8a8_workspace_bytes(*bad) == 0
+    big = 1 << 40
+    assert L.w8a8_quantize_weight(None, 128, 128, WS, None) == sla.ERR_NULL
+    assert L.w8a8_quantize_weight(FAKE, 100, 128, WS, None) == sla.ERR_SHAPE
+    assert L.w8a8_quantize_weight(FAKE, 128, 128, ctypes.c_void_p(0x10010), None) == sla.ERR_WORKSPACE
+    assert L.w8a8_quantize_act(None, 5, 128, WS, big, None) == sla.ERR_NULL
+    assert L.w8a8_quantize_act(FAKE, 5, 130, WS, big, None) == sla.ERR_SHAPE
+    assert L.w8a8_quantize_act(FAKE, 5, 128, WS, 16, None) == sla.ERR_WORKSPACE
+    assert L.w8a8_quantize_act(FAKE, 5, 128, None, big, None) == sla.ERR_WORKSPACE
+    assert L.w8a8_gemm_fwd(WS, big, None, None, FAKE, 5, 128, 128, None) == sla.ERR_NULL
+    assert L.w8a8_gemm_fwd(WS, big, WS, None, FAKE, 5, 100, 128, None) == sla.ERR_SHAPE
+    assert L.w8a8_gemm_fwd(WS, 16, WS, None, FAKE, 5, 128, 128, None) == sla.ERR_WORKSPACE
+    assert L.w8a8_gemm_fwd(WS, big, WS, None, ctypes.c_void_p(0x1008), 5, 128, 128, None) == sla.ERR_LAYOUT
+    assert L.w8a8_linear_fwd(FAKE, WS, None, None, 5, 128, 128, WS, big, None) == sla.ERR_NULL
+    assert L.w8a8_linear_fwd(FAKE, WS, None, FAKE, 5, 128, 256 + 64, WS, big, None) == sla.ERR_SHAPE
+    assert L.w8a8_linear_fwd(FAKE, WS, None, FAKE, 5, 128, 128, WS, 100, None) == sla.ERR_WORKSPACE
+    assert L.w8a8_debug_unpack(None, 1, 128, 128, None, None, None) == sla.ERR_NULL
+    assert L.w8a8_debug_unpack(FAKE, 1, 100, 128, None, None, None) == sla.ERR_SHAPE
 
 
 def test_status_strings():
