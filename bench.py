@@ -32,6 +32,11 @@ PEAK_MFMA_8BIT_TOPS = 5000.0   # MI355X dense INT8 (POP/s) and FP8 (PFLOP/s) MFM
 SPARSE_TRAFFIC_BYTES = {4: 17.95e9}
 
 
+# Linear layers of a Wan2.1-14B DiT block (hidden 5120, feed-forward 13824) on the 75600 tokens of a
+# 720P clip: (M, K, N)
+W8A8_SHAPES = {"attn_proj": (75600, 5120, 5120), "ffn_up": (75600, 5120, 13824), "ffn_down": (75600, 13824, 5120)}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -41,6 +46,11 @@ def parse():
     ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
                     help="memory order of q, k, v and out: head-major [B,H,N,d] (default) or token-major "
                          "[B,N,H,d] through the strided entry point")
+    ap.add_argument("--workload", choices=("sla", "w8a8"), default="sla",
+                    help="sla: the SLA forward (the headline, default); w8a8: the W8A8 Linear layer at a Wan-14B "
+                         "shape (a second JSON line of its own metric)")
+    ap.add_argument("--w8a8-shape", choices=tuple(W8A8_SHAPES), default="attn_proj",
+                    help="which Linear layer of a Wan-14B block, on the 75600 tokens of a 720P clip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget for the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -113,12 +123,88 @@ def cpu_baseline(cfg, q, k, v, W, budget_s):
                       % (cfg.H, t_head, len(blocks), Tq, per_block, cfg.B * cfg.H, Tq, t_full)}
 
 
+def main_w8a8(args):
+    """One step = one W8A8 Linear layer: block-wise quantisation of the bf16 activations, then the
+    INT8 product with block-scale accumulation and bias, bf16 out.  Weights are quantised once,
+    outside the timed region (offline in the paper's flow)."""
+    import numpy as np
+    import torch
+    from paper_2512_16093_amd import binding as sla
+    from paper_2512_16093_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    sla.lib()
+    M, K, N = W8A8_SHAPES[args.w8a8_shape]
+    t0 = time.perf_counter()
+    x, w, b = synth.make_linear_inputs(M, K, N)
+    print("[bench] inputs for %s generated in %.1f s" % (args.w8a8_shape, time.perf_counter() - t0), file=sys.stderr, flush=True)
+    xd, wd, bd = x.cuda(), w.cuda(), b.cuda()
+    wq = sla.w8a8_quantize_weight(wd)
+    ws = sla.w8a8_alloc_workspace(M, K)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    for _ in range(args.warmup):
+        sla.w8a8_linear_fwd(xd, wq, N, bias=bd, workspace=ws, out=y)
+    torch.cuda.synchronize()
+    # the launches go to torch's current stream, so its events bracket them
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for e in ev:
+        e[0].record()
+        sla.w8a8_quantize_act(xd, workspace=ws)
+        e[1].record()
+        sla.w8a8_gemm_fwd(ws, wq, M, N, K, bias=bd, out=y)
+        e[2].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    t_quant = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    t_gemm = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ops = 2.0 * M * N * K
+    achieved = ops / (t_gemm * 1e-3) / 1e12
+    result = {
+        "metric": "w8a8_linear_tops", "value": ops / (ms_per_step * 1e-3) / 1e12, "unit": "TOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8 (int32 block sums, fp32 scale accumulation, bf16 out)",
+        "data": "synthetic",
+        "config": {"workload": "w8a8-linear %s: M=%d tokens K=%d N=%d, 128x128 block scales, bias, seed=0"
+                               % (args.w8a8_shape, M, K, N)},
+        "stage_ms": {"quantize_act": round(t_quant, 4), "gemm": round(t_gemm, 4)},
+        "roofline": {"kernel": "w8a8_gemm_kernel", "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_8BIT_TOPS,
+                     "unit": "TOP/s", "frac": achieved / PEAK_MFMA_8BIT_TOPS, "traffic": None,
+                     "launch_ms": t_gemm, "ops_per_launch": ops},
+        "quantize_act_roofline": {"bound": "hbm", "achieved": 3.0 * M * K / (t_quant * 1e-3) / 1e9, "peak": 8000.0,
+                                  "unit": "GB/s", "frac": 3.0 * M * K / (t_quant * 1e-3) / 1e9 / 8000.0},
+        "context": "the paper reports no kernel-level number for its W8A8 Linear layers",
+    }
+    if not args.no_cpu_baseline:
+        from oracle import w8a8_oracle as wo      # cpu_baseline leg: allowed to call the oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        rows, cols = 256, min(N, 1024)
+        Xs, Ws = synth.as_f64(x[:rows]), synth.as_f64(w[:cols])
+        t0 = time.perf_counter()
+        wo.w8a8_linear(Xs, Ws, synth.as_f64(b[:cols]))
+        t = time.perf_counter() - t0
+        full = t * (M / rows) * (N / cols)
+        result["cpu_baseline"] = {"value": ops / full / 1e12, "unit": "TOP/s", "cores": int(cores), "kind": "oracle",
+                                  "sample": "%d tokens x %d outputs x all %d features in %.2f s; extrapolated to "
+                                            "%d x %d = %.0f s" % (rows, cols, K, t, M, N, full)}
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (heads would shard with "
               "no collective); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "w8a8":
+        return main_w8a8(args)
     import torch
     from paper_2512_16093_amd import binding as sla
     from paper_2512_16093_amd import synth

@@ -18,9 +18,10 @@
  *
  *     the inner sums are exact (int32); the outer one is accumulated in fp32 by one fma per
  *     block that reads the integer accumulator as a float (offset by a constant of about
- *     2^23.4 integer steps, taken out again every fourth block), so each block adds an error
- *     of at most 2 steps sX*sW -- far below the rounding of the INT8 codes themselves, which
- *     is half a step per product term.
+ *     2^23.4 integer steps, whose sign alternates from block to block and whose remainder is
+ *     taken out at the end), so each block adds an error of at most 2 steps sX*sW of the
+ *     largest block -- far below the rounding of the INT8 codes themselves, which is half a
+ *     step per product term.
  *
  * General rules (as for sla.h)
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  x, w, y and bias are

@@ -7,9 +7,10 @@
 #include "common.h"
 
 namespace sla {
-void launch_w8a8_quantize(const void* a, int R, int K, int RP, int8_t* codes, float* scales, hipStream_t stream);
-void launch_w8a8_unpack(const int8_t* frag, const float* s, int R, int K, int RP, int8_t* codes, float* scales,
-                        hipStream_t stream);
+void launch_w8a8_quantize(const void* a, int R, int K, int RP, bool negate_odd, int8_t* codes, float* scales,
+                          hipStream_t stream);
+void launch_w8a8_unpack(const int8_t* frag, const float* s, int R, int K, int RP, bool negate_odd, int8_t* codes,
+                        float* scales, hipStream_t stream);
 void launch_w8a8_gemm(const int8_t* x8, const float* sx, int MP, const int8_t* w8, const float* sw,
                       const void* bias, void* y, int M, int N, int K, hipStream_t stream);
 }  // namespace sla
@@ -44,7 +45,7 @@ int w8a8_quantize_weight(const void* w, int N, int K, void* wq, sla_stream_t str
   if (!w || !wq) return SLA_ERR_NULL;
   if (!dims_ok(N, K, true)) return SLA_ERR_SHAPE;
   if ((uintptr_t)wq & 255) return SLA_ERR_WORKSPACE;
-  launch_w8a8_quantize(w, N, K, N, (int8_t*)wq, (float*)((unsigned char*)wq + codes_bytes(N, K)), (hipStream_t)stream);
+  launch_w8a8_quantize(w, N, K, N, true, (int8_t*)wq, (float*)((unsigned char*)wq + codes_bytes(N, K)), (hipStream_t)stream);
   return launch_status();
 }
 
@@ -53,7 +54,7 @@ int w8a8_quantize_act(const void* x, int M, int K, void* workspace, size_t works
   if (!dims_ok(M, K, false)) return SLA_ERR_SHAPE;
   const int MP = padded_rows(M, false);
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < object_bytes(MP, K)) return SLA_ERR_WORKSPACE;
-  launch_w8a8_quantize(x, M, K, MP, (int8_t*)workspace, (float*)((unsigned char*)workspace + codes_bytes(MP, K)),
+  launch_w8a8_quantize(x, M, K, MP, false, (int8_t*)workspace, (float*)((unsigned char*)workspace + codes_bytes(MP, K)),
                        (hipStream_t)stream);
   return launch_status();
 }
@@ -85,8 +86,8 @@ int w8a8_debug_unpack(const void* q, int is_weight, int R, int K, int8_t* codes,
   if (!q) return SLA_ERR_NULL;
   if (!dims_ok(R, K, is_weight != 0)) return SLA_ERR_SHAPE;
   const int RP = padded_rows(R, is_weight != 0);
-  launch_w8a8_unpack((const int8_t*)q, (const float*)((const unsigned char*)q + codes_bytes(RP, K)), R, K, RP, codes,
-                     scales, (hipStream_t)stream);
+  launch_w8a8_unpack((const int8_t*)q, (const float*)((const unsigned char*)q + codes_bytes(RP, K)), R, K, RP,
+                     is_weight != 0, codes, scales, (hipStream_t)stream);
   return launch_status();
 }
 

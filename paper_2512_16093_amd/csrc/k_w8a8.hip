@@ -29,9 +29,11 @@ constexpr int W8_WG_M = 256, W8_WG_N = 128;  // workgroup tile of the product
 // takes as its C operand: a finished accumulator, reinterpreted as fp32, is then exactly
 // W8_C0 + s * 2^-26 for every block sum |s| <= 127 * 127 * 128 (the pattern stays inside the
 // binade [1/8, 1/4)), so scaling and accumulating a block is ONE fma per element, with no
-// int -> float conversion; the constant's share, W8_C0 * (sum of the scales), is uniform over
-// a wavefront's tile and is taken out every fourth block (to keep the fp32 sums small) and at
-// the end.
+// int -> float conversion.  The constant's share must stay small next to the sums it rides on
+// (fp32 rounds at the magnitude of the running total): the weight codes of ODD feature blocks
+// are stored negated and their blocks scaled by -s_X s_W, which leaves the products' share
+// unchanged and makes the constants alternate in sign; what is left of them, W8_C0 * (signed
+// sum of the scales), is uniform over a wavefront's tile and is taken out at the end.
 constexpr int W8_BIAS_I = 0x3E22F983;
 constexpr float W8_C0 = 0.15915494f;         // the float with that bit pattern
 constexpr float W8_STEP_INV = 67108864.0f;   // 2^26
@@ -44,8 +46,10 @@ __host__ __device__ inline size_t w8_chunk(int kb, int RT, int rt, int ks) {
 // Quantisation of one 128 x 128 block per workgroup.  Thread t: columns 8 (t % 16) .. +7 of
 // rows t / 16 + 16 i, i = 0..7.
 // ---------------------------------------------------------------------------
+// negate_odd (weights): the codes of odd feature blocks are stored negated (see W8_BIAS_I).
 __global__ void __launch_bounds__(256) w8a8_quantize_kernel(const bf16_t* __restrict__ a, int R, int K, int RP,
-                                                            int8_t* __restrict__ codes, float* __restrict__ scales) {
+                                                            int negate_odd, int8_t* __restrict__ codes,
+                                                            float* __restrict__ scales) {
   __shared__ uint4 blk[QB * QB / 16];
   __shared__ float wave_amax[4];
   const int KB = K / QB, RB = RP / QB, RT = RP / 32;
@@ -71,7 +75,7 @@ __global__ void __launch_bounds__(256) w8a8_quantize_kernel(const bf16_t* __rest
   // codes by multiplication with the reciprocal of the scale (differs from the division only at
   // rounding ties); adding 1.5 * 2^23 inside the fma rounds to the nearest integer, ties to even,
   // and leaves its two's-complement low byte in the low byte of the float; |x / s| <= 127.
-  const float inv = 1.0f / s;
+  const float inv = (negate_odd && (kb & 1)) ? -1.0f / s : 1.0f / s;
   unsigned char* out = (unsigned char*)blk;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -99,13 +103,14 @@ __global__ void __launch_bounds__(256) w8a8_quantize_kernel(const bf16_t* __rest
 
 // Plain-layout copies of codes and scales (tests only).
 __global__ void w8a8_unpack_kernel(const int8_t* __restrict__ frag, const float* __restrict__ s, int R, int K, int RP,
-                                   int8_t* __restrict__ codes, float* __restrict__ scales) {
+                                   int negate_odd, int8_t* __restrict__ codes, float* __restrict__ scales) {
   const int KB = K / QB, RB = RP / QB, RT = RP / 32;
   const size_t total = (size_t)R * K;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int r = (int)(i / K), k = (int)(i % K);
     const int kb = k / QB, ks = (k % QB) / 32, half = (k % 32) / 16, byte = k % 16;
-    if (codes) codes[i] = frag[(w8_chunk(kb, RT, r / 32, ks) + (r % 32) + 32 * half) * 16 + byte];
+    const int8_t c = frag[(w8_chunk(kb, RT, r / 32, ks) + (r % 32) + 32 * half) * 16 + byte];
+    if (codes) codes[i] = (negate_odd && (kb & 1)) ? (int8_t)-c : c;
   }
   const int rbn = (R + QB - 1) / QB;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; scales && i < (size_t)rbn * KB;
@@ -175,36 +180,43 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
   for (int r = 0; r < 2; ++r)
 #pragma unroll
     for (int c = 0; c < 4; ++c) facc[r][c] = v16f{};
-  v16i bias16;
+  v16i bias16;  // (only the idle value of `pend` below; the chains take the pattern as an inline constant)
 #pragma unroll
   for (int e = 0; e < 16; ++e) bias16[e] = W8_BIAS_I;
-  asm volatile("" : "+v"(bias16));  // kept in registers: the MFMA's C operand
   float csum = 0.f;                 // scales whose constant share is still inside facc
 
-  v4i a[2][4];  // this wavefront's activation operands of the current feature block
+  v4i a0[2][4], a1[2][4];  // this wavefront's activation operands of the current and the next feature block
 
   // One feature block: products against the staged weight tile, then one fma per element.  The
   // product is taken transposed (weights as the A operand) so that a lane owns ONE token and runs
-  // of four consecutive outputs.  The activation operands of the next block are requested as soon
-  // as the last products of this block have been issued (there are no registers for a second
-  // set); the other workgroup of the compute unit covers what is left of their latency.
+  // of four consecutive outputs.
+  // The first product of a chain takes the pattern W8_BIAS_I as an inline constant (0.15915494 is
+  // the assembler's spelling of 1 / (2 pi)); written in assembly because the compiler would keep
+  // the constant in sixteen registers instead.  The following products accumulate in place
+  // (same destination, which the hardware supports back to back).
   auto chain = [&](const v4i (&b)[4], const v4i (&ar)[4]) {
-    v16i acc = bias16;
+    v16i acc;
+    asm("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(acc) : "v"(b[0]), "v"(ar[0]));
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[ks], ar[ks], acc, 0, 0, 0);
+    for (int ks = 1; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[ks], ar[ks], acc, 0, 0, 0);
     return acc;
   };
   auto scale_in = [&](const v16i& acc, float sc, v16f& f) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) f[e] = __builtin_fmaf(__int_as_float(acc[e]), sc, f[e]);
   };
-  // The eight chains of a block (4 output tiles x 2 token tiles) run back to back on the matrix
-  // pipe, each with the fmas of the chain before it next to it for the vector ALU; scheduling
-  // barriers keep the compiler from stretching that window (and the registers it needs).
-  auto compute = [&](int kb) {
-    const float sc = sx[(size_t)kb * RBx + rb] * sw[(size_t)kb * RBw + nt] * W8_STEP_INV;
+  // The chains (4 output tiles x 2 token tiles per feature block) run back to back on the matrix
+  // pipe, each with the fmas of the chain before it interleaved for the vector ALU -- across
+  // feature blocks too: the last chain of a block is scaled in next to the first chain of the
+  // next one.  Scheduling barriers and register anchors keep the compiler from stretching that
+  // window (and the registers it needs).
+  v16i pend = bias16;   // finished chain still to be scaled in (token tile 1, output tile 3); none yet: s = 0
+  float pend_sc = 0.f;
+  auto compute = [&](int kb, const v4i (&a)[2][4]) {
+    const float mag = sx[(size_t)kb * RBx + rb] * sw[(size_t)kb * RBw + nt] * W8_STEP_INV;
+    const float sc = (kb & 1) ? -mag : mag;
     const uint4* st = bst[kb % 3];
-    v16i acc0, acc1;
+    v16i acc0;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
       v4i b[4];
@@ -215,48 +227,48 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
         b[ks] = x.v;
       }
       acc0 = chain(b, a[0]);
-      if (ct > 0) {
-        scale_in(acc1, sc, facc[1][ct - 1]);
-        asm volatile("" : "+v"(facc[1][ct - 1]) : : "memory");  // (the fmas stay in this window)
-      }
+      v16f& ftile = facc[1][(ct + 3) & 3];
+      scale_in(pend, pend_sc, ftile);
+      asm volatile("" : "+v"(ftile) : : "memory");  // (the fmas stay in this window)
       asm volatile("" : "+v"(acc0) : : "memory");
       __builtin_amdgcn_sched_barrier(0);
-      acc1 = chain(b, a[1]);
-      if (ct == 3 && kb + 1 < KB) load_a(kb + 1, a);
+      pend = chain(b, a[1]);
+      pend_sc = sc;
       scale_in(acc0, sc, facc[0][ct]);
       asm volatile("" : "+v"(facc[0][ct]) : : "memory");
-      asm volatile("" : "+v"(acc1) : : "memory");
+      asm volatile("" : "+v"(pend) : : "memory");
       __builtin_amdgcn_sched_barrier(0);
     }
-    scale_in(acc1, sc, facc[1][3]);
-    asm volatile("" : "+v"(facc[1][3]) : : "memory");
     csum += sc;
-    if ((kb & 3) == 3) {
-      const float corr = W8_C0 * csum;
-#pragma unroll
-      for (int r = 0; r < 2; ++r)
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) facc[r][c][e] -= corr;
-      csum = 0.f;
-    }
   };
 
-  // Pipeline.  The weight tiles run two feature blocks ahead of the products (three stages).
-  // At the top of step kb everything this wavefront has requested is waited for: its share of
-  // the weight tiles up to kb + 1 and its own activation operands of block kb (the youngest
-  // request); the barrier then publishes everybody's share of stage kb and retires stage
-  // kb - 1, which the copy of block kb + 2 overwrites.
+  // Pipeline.  The weight tiles run two feature blocks ahead of the products (three LDS stages),
+  // the activation operands one block ahead (two register sets).  At the top of step kb
+  // everything this wavefront has requested is waited for -- all of it was requested at least a
+  // whole block earlier; the barrier then publishes everybody's share of stage kb and retires
+  // stage kb - 1, which the copy of block kb + 2 overwrites.
   fetch_b(0);
   if (KB > 1) fetch_b(1);
-  load_a(0, a);
-  for (int kb = 0; kb < KB; ++kb) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    w8_barrier();
-    if (kb + 2 < KB) fetch_b(kb + 2);
-    compute(kb);
+  load_a(0, a0);
+#define W8_STEP(KBI, ACUR, ANEXT)                       \
+  {                                                     \
+    const int kb_ = (KBI);                              \
+    __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0) */  \
+    w8_barrier();                                       \
+    if (kb_ + 2 < KB) fetch_b(kb_ + 2);                 \
+    if (kb_ + 1 < KB) load_a(kb_ + 1, ANEXT);           \
+    compute(kb_, ACUR);                                 \
   }
+  {
+    int kb = 0;
+    for (; kb + 2 <= KB; kb += 2) {
+      W8_STEP(kb, a0, a1)
+      W8_STEP(kb + 1, a1, a0)
+    }
+    if (kb < KB) W8_STEP(kb, a0, a1)
+  }
+#undef W8_STEP
+  scale_in(pend, pend_sc, facc[1][3]);
 
   // Epilogue: constant share out, bias in, bf16, through LDS so that rows leave as 256 contiguous
   // bytes.  Lane = token 32 rt + l32 of this wavefront; registers 4 g .. 4 g + 3 of tile ct =
@@ -295,14 +307,15 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
 }
 
 // ---------------------------------------------------------------------------
-void launch_w8a8_quantize(const void* a, int R, int K, int RP, int8_t* codes, float* scales, hipStream_t stream) {
+void launch_w8a8_quantize(const void* a, int R, int K, int RP, bool negate_odd, int8_t* codes, float* scales,
+                          hipStream_t stream) {
   const unsigned grid = (unsigned)((RP / QB) * (K / QB));
-  w8a8_quantize_kernel<<<grid, 256, 0, stream>>>((const bf16_t*)a, R, K, RP, codes, scales);
+  w8a8_quantize_kernel<<<grid, 256, 0, stream>>>((const bf16_t*)a, R, K, RP, negate_odd ? 1 : 0, codes, scales);
 }
 
-void launch_w8a8_unpack(const int8_t* frag, const float* s, int R, int K, int RP, int8_t* codes, float* scales,
-                        hipStream_t stream) {
-  w8a8_unpack_kernel<<<2048, 256, 0, stream>>>(frag, s, R, K, RP, codes, scales);
+void launch_w8a8_unpack(const int8_t* frag, const float* s, int R, int K, int RP, bool negate_odd, int8_t* codes,
+                        float* scales, hipStream_t stream) {
+  w8a8_unpack_kernel<<<2048, 256, 0, stream>>>(frag, s, R, K, RP, negate_odd ? 1 : 0, codes, scales);
 }
 
 void launch_w8a8_gemm(const int8_t* x8, const float* sx, int MP, const int8_t* w8, const float* sw,
