@@ -147,11 +147,15 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
   __shared__ uint4 bst[3][QB * W8_WG_N / 16];  // three stages of a 128-feature x 128-output weight tile
   static_assert(4 * 32 * W8_EPI_STRIDE <= (int)sizeof(uint4) * 3 * QB * W8_WG_N / 16, "output staging fits the stages");
   // Workgroup ids are dealt round-robin over the 8 XCDs: XCD x takes the token tiles mt = x, x + 8,
-  // ...; inside an XCD consecutive workgroups sweep the output tiles of one token tile, so the
-  // workgroups that share an L2 share their activation rows and stream the weights once.
+  // ...  Inside an XCD 64 consecutive workgroups -- what its 32 compute units hold at a time --
+  // form a patch of 8 token tiles x 8 output tiles and walk the feature blocks at the same pace,
+  // so each activation and weight tile of a feature block is fetched into that L2 once for
+  // eight users (the patches cover the XCD's tiles row of patches by row of patches).
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int mt = __builtin_amdgcn_readfirstlane((slot / NT) * 8 + xcd), nt = __builtin_amdgcn_readfirstlane(slot % NT);
-  if (mt >= MT) return;
+  const int pcols = (NT + 7) >> 3, patch = slot >> 6, q = slot & 63;
+  const int mt = __builtin_amdgcn_readfirstlane((((patch / pcols) << 3) + (q >> 3)) * 8 + xcd);
+  const int nt = __builtin_amdgcn_readfirstlane(((patch % pcols) << 3) + (q & 7));
+  if (mt >= MT || nt >= NT) return;
   const int t = threadIdx.x, lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6), l32 = lane & 31, hf = lane >> 5;
   const int KB = K / QB;
   const int rt0 = mt * (W8_WG_M / 32) + 2 * w;  // this wavefront's two row tiles (64 tokens)
@@ -321,7 +325,8 @@ void launch_w8a8_unpack(const int8_t* frag, const float* s, int R, int K, int RP
 void launch_w8a8_gemm(const int8_t* x8, const float* sx, int MP, const int8_t* w8, const float* sw,
                       const void* bias, void* y, int M, int N, int K, hipStream_t stream) {
   const int MT = MP / W8_WG_M, NT = N / W8_WG_N;
-  const unsigned grid = (unsigned)(8 * ((MT + 7) / 8) * NT);
+  const int mtx = (MT + 7) / 8;  // token tiles per XCD
+  const unsigned grid = (unsigned)(8 * ((mtx + 7) / 8) * ((NT + 7) / 8) * 64);
   w8a8_gemm_kernel<<<grid, 256, 0, stream>>>(x8, sx, w8, sw, (const bf16_t*)bias, (bf16_t*)y, M, N, K, MP / 32,
                                              MP / QB, N / 32, N / QB, MT, NT);
 }

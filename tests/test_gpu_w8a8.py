@@ -113,3 +113,31 @@ def test_deterministic_and_workspace_reuse():
     y2 = sla.w8a8_linear_fwd(xd, wq, 256, bias=bd, workspace=ws)
     assert torch.equal(y1, y2)
     assert torch.equal(x, xd.cpu())
+
+
+def test_full_size_attention_projection_sampled():
+    """The layer at the size the benchmark times (75600 tokens, 5120 -> 5120): the oracle on whole
+    quantisation row blocks -- the first, one in the middle and the ragged last one (75600 =
+    590 * 128 + 80) -- against all output features."""
+    M, K, N = 75600, 5120, 5120
+    x, w, b = synth.make_linear_inputs(M, K, N)
+    print("running the GPU layer", flush=True)
+    wq = sla.w8a8_quantize_weight(w.cuda())
+    y = sla.w8a8_linear_fwd(x.cuda(), wq, N, bias=b.cuda())
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    print("oracle: quantising the weight", flush=True)
+    W8, sW = wo.quantize_blockwise(synth.as_f64(w))
+    worst = 0.0
+    for rb in (0, 295, 590):
+        rows = slice(rb * 128, min((rb + 1) * 128, M))
+        print("oracle on token block", rb, flush=True)
+        X8, sX = wo.quantize_blockwise(synth.as_f64(x[rows]))
+        ref = wo.linear_from_codes(X8, sX, W8, sW, synth.as_f64(b))
+        got = y[rows].float().cpu().numpy()
+        tol = product_tolerance(ref, sX, sW, K) + 127.0 * 4 * sX.max() * sW.max()
+        assert np.all(np.abs(got - ref) <= tol), (rb, np.abs(got - ref).max())
+        rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        assert rel < 3e-3, (rb, rel)
+        worst = max(worst, rel)
+    print("w8a8 75600 x 5120 -> 5120: worst relative error of a sampled token block %.2e" % worst)
