@@ -157,44 +157,53 @@ __global__ void __launch_bounds__(1024) finalize_stats_kernel(
   }
 }
 
-// scores: s[bh][i][j] = qbar_i . kbar_j / sqrt(d), 64x64 tile per workgroup, fp32 FMA.
-__global__ void __launch_bounds__(256) scores_kernel(const float* __restrict__ qbar,
-                                                     const float* __restrict__ kbar, int Tq, int Tk,
-                                                     float* __restrict__ scores) {
-  __shared__ float sq[64][65];
-  __shared__ float sk[64][65];
-  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
-  float acc[4][4] = {};
-  for (int c0 = 0; c0 < D; c0 += 64) {
-    __syncthreads();
-    for (int e = t; e < 64 * 64; e += 256) {
-      const int r = e >> 6, c = e & 63;
-      sq[r][c] = (i0 + r < Tq) ? qbar[((size_t)bh * Tq + i0 + r) * D + c0 + c] : 0.f;
-      sk[r][c] = (j0 + r < Tk) ? kbar[((size_t)bh * Tk + j0 + r) * D + c0 + c] : 0.f;
-    }
-    __syncthreads();
-#pragma unroll 8
-    for (int c = 0; c < 64; ++c) {
-      float a[4], b[4];
+// scores: s[bh][i][j] = qbar_i . kbar_j / sqrt(d) in fp32 on the matrix pipe
+// (v_mfma_f32_32x32x2_f32: fp32 operands and accumulation, the vector-fp32 rate without its issue
+// limits).  A wavefront owns a 32-row tile of query blocks, whose means it keeps in registers, and
+// sweeps SC_JT 32-column tiles of key blocks; the four wavefronts of a workgroup take four
+// consecutive row tiles over the SAME columns, so three of their four reads of a key tile hit
+// the L1.  The instruction contracts two channels per step, one per lane half; which two is
+// free as long as both operands agree: lane half h holds channels 64 h .. 64 h + 63 of its row
+// (16 contiguous 16-byte loads) and step t contracts channels t and 64 + t.
+constexpr int SC_JT = 4;
+typedef float v16f_sc __attribute__((ext_vector_type(16)));
+__global__ void __launch_bounds__(256, 2) scores_kernel(const float* __restrict__ qbar,
+                                                        const float* __restrict__ kbar, int Tq, int Tk,
+                                                        float* __restrict__ scores) {
+  const int bh = blockIdx.z, lane = threadIdx.x & 63, w = threadIdx.x >> 6, l32 = lane & 31, h = lane >> 5;
+  const int i0 = (blockIdx.y * 4 + w) * 32;
+  if (i0 >= Tq) return;  // (whole wavefront; no barriers in this kernel)
+  const int jt0 = blockIdx.x * SC_JT, jts = (Tk + 31) / 32;
+  float a[64], b[64];
+  {
+    const float4* src = (const float4*)(qbar + ((size_t)bh * Tq + min(i0 + l32, Tq - 1)) * D + 64 * h);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        a[u] = sq[ty * 4 + u][c];
-        b[u] = sk[tx + 16 * u][c];
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int w = 0; w < 4; ++w) acc[u][w] = __builtin_fmaf(a[u], b[w], acc[u][w]);
+    for (int u = 0; u < 16; ++u) {
+      const float4 x = src[u];
+      a[4 * u] = x.x; a[4 * u + 1] = x.y; a[4 * u + 2] = x.z; a[4 * u + 3] = x.w;
     }
   }
+  auto load_b = [&](int jt) {
+    const float4* src = (const float4*)(kbar + ((size_t)bh * Tk + min(jt * 32 + l32, Tk - 1)) * D + 64 * h);
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int i = i0 + ty * 4 + u, j = j0 + tx + 16 * w;
-      if (i < Tq && j < Tk) scores[((size_t)bh * Tq + i) * Tk + j] = acc[u][w] / 11.313708498984761f;
+    for (int u = 0; u < 16; ++u) {
+      const float4 x = src[u];
+      b[4 * u] = x.x; b[4 * u + 1] = x.y; b[4 * u + 2] = x.z; b[4 * u + 3] = x.w;
     }
+  };
+  for (int jt = jt0; jt < min(jt0 + SC_JT, jts); ++jt) {
+    load_b(jt);
+    v16f_sc acc = {};
+#pragma unroll
+    for (int t = 0; t < 64; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
+    // accumulator register r of lane (l32, h): row 8 (r / 4) + 4 h + r % 4, column l32
+    const int j = jt * 32 + l32;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = i0 + 8 * (r >> 2) + 4 * h + (r & 3);
+      if (i < Tq && j < Tk) scores[((size_t)bh * Tq + i) * Tk + j] = acc[r] / 11.313708498984761f;
+    }
+  }
 }
 
 // select: one WAVEFRONT per (b,h,i) row; the row's scores live in registers (KPL per lane,
@@ -320,7 +329,7 @@ void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* 
 
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores,
                    hipStream_t stream) {
-  dim3 grid((p.Tk + 63) / 64, (p.Tq + 63) / 64, p.BH);
+  dim3 grid(((p.Tk + 31) / 32 + SC_JT - 1) / SC_JT, (p.Tq + 127) / 128, p.BH);
   scores_kernel<<<grid, 256, 0, stream>>>(qbar, kbar, p.Tq, p.Tk, scores);
 }
 
