@@ -261,18 +261,28 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
   }
   // k1 / k2: the n_c-th / (n_c+n_m)-th largest key; t1 / t2: how many of the keys equal to
   // it belong to the top n_c / n_c+n_m (>= 1).  Bits below `low` are zero in every key.
+  // A threshold's search stops early once exactly the wanted number of keys reaches the
+  // candidate c: the set is then {key >= c}, which the code below takes as "key > c - 1" with
+  // no ties to rank (with ~1000 distinct keys that happens after about log2(Tk) + 2 bits).
   uint32_t k1 = 0, k2 = 0;
   const int rank2 = n_c + n_m;
-  for (int bit = 31; bit >= low; --bit) {
+  bool open1 = true, open2 = n_m > 0;
+  for (int bit = 31; bit >= low && (open1 || open2); --bit) {
     const uint32_t c1 = k1 | (1u << bit), c2 = k2 | (1u << bit);
     int n1 = 0, n2 = 0;
 #pragma unroll
     for (int m = 0; m < KPL; ++m) {  // (padding keys are 0 and never reach a candidate)
-      n1 += __popcll(__ballot(key[m] >= c1));
-      if (n_m > 0) n2 += __popcll(__ballot(key[m] >= c2));
+      if (open1) n1 += __popcll(__ballot(key[m] >= c1));
+      if (open2) n2 += __popcll(__ballot(key[m] >= c2));
     }
-    if (n1 >= n_c) k1 = c1;
-    if (n2 >= rank2) k2 = c2;
+    if (open1) {
+      if (n1 == n_c) { k1 = c1 - 1u; open1 = false; }
+      else if (n1 > n_c) k1 = c1;
+    }
+    if (open2) {
+      if (n2 == rank2) { k2 = c2 - 1u; open2 = false; }
+      else if (n2 > rank2) k2 = c2;
+    }
   }
   int t1 = n_c, t2 = rank2;
 #pragma unroll
