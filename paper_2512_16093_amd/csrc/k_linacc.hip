@@ -15,11 +15,13 @@
 // bf16 values 0.0 / 1.0 of the bits of b), one 16-byte LDS read per fragment.
 //
 // Workgroup = 4 wavefronts, two workgroups per CU (independent, so the two wavefronts of a
-// SIMD are not in step); wavefront w owns query blocks [96 w, 96 w + 96) x 128 columns
-// (3 x 4 MFMA tiles of 32 x 32, 192 accumulator registers), accumulated transposed (the hz
-// fragment is the MFMA's A operand) so that a lane ends up with runs of consecutive entries
-// of one query block's summary and can store 8 bytes at a time.  Operand tiles for 64 key blocks
-// at a time are copied global -> LDS asynchronously, three stages deep (one barrier per tile).  hz rows are copied
+// SIMD are not in step); in a full chunk wavefront w owns query blocks [96 w, 96 w + 96) x 128
+// columns (3 x 4 MFMA tiles of 32 x 32, 192 accumulator registers); a head's shorter last chunk
+// is dealt to the wavefronts in even runs of row tiles and runs a copy of the loop with fewer
+// tiles per wavefront.  Tiles are accumulated transposed (the hz fragment is the MFMA's A
+// operand) so that a lane ends up with runs of consecutive entries of one query block's
+// summary and can store 8 bytes at a time.  Operand tiles for 64 key blocks at a time are
+// copied global -> LDS asynchronously, three stages deep (one barrier per tile).  hz rows are copied
 // as they are (n contiguous) and read back with the LDS transposing read of gfx950
 // (ds_read_b64_tr_b16): the contraction index j is the slow index of hz, so one transposition
 // is unavoidable, and this one costs 8 LDS reads per 12 MFMAs and no vector-ALU work.
