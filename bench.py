@@ -37,6 +37,11 @@ SPARSE_TRAFFIC_BYTES = {4: 17.96e9}
 W8A8_SHAPES = {"attn_proj": (75600, 5120, 5120), "ffn_up": (75600, 5120, 13824), "ffn_down": (75600, 13824, 5120)}
 
 
+# Bytes moved past L2 per launch of the product kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0), by shape;
+# source: profiles/w8a8_linear_wan14b.md.
+W8A8_TRAFFIC_BYTES = {"attn_proj": 6.49e9}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -172,7 +177,8 @@ def main_w8a8(args):
                                % (args.w8a8_shape, M, K, N)},
         "stage_ms": {"quantize_act": round(t_quant, 4), "gemm": round(t_gemm, 4)},
         "roofline": {"kernel": "w8a8_gemm_kernel", "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_8BIT_TOPS,
-                     "unit": "TOP/s", "frac": achieved / PEAK_MFMA_8BIT_TOPS, "traffic": None,
+                     "unit": "TOP/s", "frac": achieved / PEAK_MFMA_8BIT_TOPS,
+                     "traffic": W8A8_TRAFFIC_BYTES.get(args.w8a8_shape), "traffic_unit": "bytes per launch",
                      "launch_ms": t_gemm, "ops_per_launch": ops},
         "quantize_act_roofline": {"bound": "hbm", "achieved": 3.0 * M * K / (t_quant * 1e-3) / 1e9, "peak": 8000.0,
                                   "unit": "GB/s", "frac": 3.0 * M * K / (t_quant * 1e-3) / 1e9 / 8000.0},
