@@ -134,6 +134,13 @@ inline Layout contiguous_layout(int H, int N) {
   return {(long long)H * N * D, (long long)N * D, (long long)D};
 }
 
+// Order of the 128 x 128 part of a block summary (h'^T, entry [o][c]) in hz and HZ: 16-byte chunk
+// hz_frag_chunk(ot, ks, lane) holds row o = 32 ot + lane % 32, channels
+// 32 (ks / 2) + 16 (lane / 32) + 8 (ks % 2) + 0..7 -- what lane `lane` feeds to
+// v_mfma_f32_32x32x16_bf16 as the A operand for output tile ot and contraction step ks.  The z
+// row follows at element 128 * 128, plain.
+__host__ __device__ inline int hz_frag_chunk(int ot, int ks, int lane) { return (ot * 8 + ks) * 64 + lane; }
+
 struct Problem {
   int B, H, N, block_q;
   int BH, Tq, Tk, n_c, n_m;

@@ -230,9 +230,14 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     }
   __syncthreads();
   bf16_t* dst = hz + ((size_t)bh * Tk + j) * HZ_ELEMS;
-  for (int e = t; e < 128 * 16; e += 256) {
-    const int o = e >> 4, part = e & 15;
-    *(uint4*)(dst + o * D + part * 8) = *(const uint4*)(stage + o * STAGE_STRIDE + part * 16);
+  // h'^T leaves in the order in which the attention kernel's epilogue takes it as the A operand of
+  // v_mfma_f32_32x32x16_bf16 (hz_frag_chunk in common.h); the accumulation over marginal blocks in
+  // between is element-wise and does not care.  16-byte chunk d of the destination = row o,
+  // channels 8 cq .. 8 cq + 7 of the staged tile.
+  for (int d = t; d < 128 * 16; d += 256) {
+    const int ot = d >> 9, ks = (d >> 6) & 7, ln = d & 63;
+    const int o = 32 * ot + (ln & 31), cq = 4 * (ks >> 1) + 2 * (ln >> 5) + (ks & 1);
+    *(uint4*)(dst + d * 8) = *(const uint4*)(stage + o * STAGE_STRIDE + cq * 16);
   }
   if (t < D) dst[D * D + t] = f32_to_bf16(zsum);
 }

@@ -559,7 +559,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       v16f al = v16f{};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const v8bf a = *(const v8bf*)(Hi + (size_t)(32 * ot + l32) * D + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
+        const v8bf a = *(const v8bf*)(Hi + (size_t)hz_frag_chunk(ot, ks, lane) * 8);  // 1 KiB contiguous per wavefront
         al = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[ks], al, 0, 0, 0);
       }
 #pragma unroll
