@@ -196,8 +196,10 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
   // of four consecutive outputs.
   // The first product of a chain takes the pattern W8_BIAS_I as an inline constant (0.15915494 is
   // the assembler's spelling of 1 / (2 pi)); written in assembly because the compiler would keep
-  // the constant in sixteen registers instead.  The following products accumulate in place
-  // (same destination, which the hardware supports back to back).
+  // the constant in sixteen registers instead.  The compiler does not know this statement is an
+  // MFMA and adds no wait states after it: none are needed because the following products
+  // accumulate IN PLACE (destination = C operand, which the hardware forwards); that the register
+  // allocation keeps them in place is checked on the generated assembly by tests/test_build_checks.py.
   auto chain = [&](const v4i (&b)[4], const v4i (&ar)[4]) {
     v16i acc;
     asm("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(acc) : "v"(b[0]), "v"(ar[0]));
