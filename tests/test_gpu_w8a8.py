@@ -115,6 +115,29 @@ def test_deterministic_and_workspace_reuse():
     assert torch.equal(x, xd.cpu())
 
 
+def test_long_contraction_feed_forward_down_shape():
+    """K = 13824 (108 feature blocks, the feed-forward down projection of a Wan-14B block): the
+    longest accumulation of block sums the layer sees, on 1000 tokens."""
+    M, K, N = 1000, 13824, 5120
+    x, w, b = synth.make_linear_inputs(M, K, N, seed=5)
+    wq = sla.w8a8_quantize_weight(w.cuda())
+    ws = sla.w8a8_quantize_act(x.cuda())
+    y = sla.w8a8_gemm_fwd(ws, wq, M, N, K, bias=b.cuda()).float().cpu().numpy()
+    xc, xs = (t.cpu().numpy().astype(np.float64) for t in sla.w8a8_debug_unpack(ws, False, M, K))
+    wc, wsc = (t.cpu().numpy().astype(np.float64) for t in sla.w8a8_debug_unpack(wq, True, N, K))
+    ref = wo.linear_from_codes(xc, xs, wc, wsc, synth.as_f64(b))
+    err = np.abs(y - ref)
+    assert np.all(err <= product_tolerance(ref, xs, wsc, K)), err.max()
+    # what the accumulation adds on top of the bf16 rounding of the output: in steps of the largest
+    # block it stays inside the worst-case bound, and as a relative error it is smaller than the
+    # output rounding itself (both are ~100x below the rounding of the INT8 codes)
+    excess = (err - 2.0 ** -9 * np.abs(ref)).max() / (xs.max() * wsc.max())
+    rel = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    print("w8a8 K=13824: accumulation error beyond output rounding: %.1f steps (bound %d); relative error %.2e"
+          % (max(excess, 0.0), 2 * K // 128 + 1, rel))
+    assert rel < 3e-3
+
+
 def test_full_size_attention_projection_sampled():
     """The layer at the size the benchmark times (75600 tokens, 5120 -> 5120): the oracle on whole
     quantisation row blocks -- the first, one in the middle and the ragged last one (75600 =
