@@ -169,7 +169,8 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   mark(s, rec, 4);
   launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
                     at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
-                    (const bf16_t*)proj_b, phi_kind, lin, out, false, nullptr, s);
+                    (const bf16_t*)proj_b, phi_kind, lin, out, false, nullptr, at<int32_t>(ws, W.pair_list),
+                    at<int32_t>(ws, W.pair_len), s);
   mark(s, rec, 5);
   return launch_status();
 }
@@ -250,7 +251,7 @@ int sla_sparse_attn_fwd(const void* q, const void* k, const void* v, const int32
                  false, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8), at<float>(ws, Wmin.dk), nullptr, s);
   launch_sparse_fwd(q, p, crit_idx, n_crit, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8),
                     at<float>(ws, Wmin.dq), at<float>(ws, Wmin.dk), at<float>(ws, Wmin.dv), nullptr, nullptr, 0,
-                    false, out_s, true, lse, s);
+                    false, out_s, true, lse, nullptr, nullptr, s);
   return launch_status();
 }
 
@@ -275,7 +276,7 @@ int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_
   // the attention kernel with an empty critical list leaves only the linear term
   launch_sparse_fwd(q, p, nullptr, 0, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dq),
                     at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ), (const bf16_t*)proj_b,
-                    phi_kind, true, out_l, true, nullptr, s);
+                    phi_kind, true, out_l, true, nullptr, nullptr, nullptr, s);
   return launch_status();
 }
 

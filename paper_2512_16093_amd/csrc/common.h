@@ -89,6 +89,7 @@ struct Workspace {
   size_t mask;              // int8 [BH,Tq,Tk]
   size_t m0;                // uint32 marginal bit matrix [BH, ceil(Tk/32), Tq rounded up to 384, + 128]: bit e of word (kt, i) = block 32 kt + e marginal for query block i
   size_t crit, marg;        // int32 [BH,Tq,n_c], [BH,Tq,n_m]
+  size_t pair_list, pair_len;  // query blocks of 64: merged critical lists of adjacent pairs, int32 [BH,ceil(Tq/2),2 n_c], and their lengths
   size_t k8, v8;            // [BH,Tk] records of KV_FRAG_BYTES
   size_t hz;                // bf16 [BH,Tk,HZ_ROWS,D]
   size_t HZ;                // bf16 [BH,Tq,HZ_ROWS,D]
@@ -113,6 +114,8 @@ inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, siz
   w.mask = take(BH * Tq * Tk);
   w.m0 = take(BH * ((Tk + 31) / 32) * ((Tq + 383) / 384 * 384 + 128) * 4);
   w.crit = take(BH * Tq * n_c * 4);
+  w.pair_list = take(BH * ((Tq + 1) / 2) * 2 * n_c * 4);
+  w.pair_len = take(BH * ((Tq + 1) / 2) * 4);
   w.marg = take(BH * Tq * (n_m ? n_m : 1) * 4);
   w.k8 = take(BH * Tk * KV_FRAG_BYTES);
   w.v8 = take(BH * Tk * KV_FRAG_BYTES);
@@ -164,7 +167,8 @@ void launch_lin_accumulate(const Problem& p, const uint32_t* mbits, const bf16_t
 void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
                        const uint8_t* v8, const float* dq, const float* dk, const float* dv,
                        const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
-                       void* out, bool out_f32, float* lse, hipStream_t stream);
+                       void* out, bool out_f32, float* lse, int32_t* pair_list, int32_t* pair_len,
+                       hipStream_t stream);
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
                           uint8_t* v_codes, hipStream_t stream);
 void launch_e4m3_encode(const float* in, uint8_t* out, size_t n, hipStream_t stream);

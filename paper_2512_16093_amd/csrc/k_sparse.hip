@@ -30,6 +30,7 @@ namespace sla {
 
 struct SparseDims {
   int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32, H;
+  int TqW, ustride;  // workgroup tiles per (b,h); entries per row of the paired lists (see PAIRED)
   Layout lq, lo;  // of q and out
 };
 // The pointers are separate __restrict__ kernel parameters (not struct members) so the
@@ -49,6 +50,8 @@ struct SparseArgs {
   float* __restrict__ lse;
   int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32, H;
   Layout lq, lo;
+  int TqW, ustride;
+  const int32_t* __restrict__ ulen;
 };
 
 constexpr int EPI_STRIDE = 32 * 4 + 16;         // bytes per staged output row (32 fp32 + pad)
@@ -205,15 +208,24 @@ __device__ __forceinline__ void stage_barrier() {
   asm volatile("" ::: "memory");
 }
 
-template <int NW>
+// PAIRED (query blocks of 64, NW = 4): a workgroup serves TWO adjacent query blocks, wavefronts 0-1
+// the first and 2-3 the second, over the merged list of their critical key blocks (crit_ then
+// holds, per pair, the ascending union; bit 30 / 31 of an entry says that the first / second
+// block of the pair has this key block in its own list; ulen_ holds the lengths).  Every K/V
+// record is fetched once for both blocks and there are two wavefronts per SIMD (a workgroup of
+// two wavefronts per 64 KB of staging rings would leave one).  A wavefront whose block does not
+// have the current key block in its list goes through the step like the others and then drops
+// what it computed: zero codes contribute nothing, the reference level is put back.
+template <int NW, bool PAIRED>
 __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     const bf16_t* __restrict__ q_, const int32_t* __restrict__ crit_, const int8_t* __restrict__ k8_,
     const uint8_t* __restrict__ v8_, const float* __restrict__ dq_, const float* __restrict__ dk_,
     const float* __restrict__ dv_, const bf16_t* __restrict__ HZ_, const bf16_t* __restrict__ bias_,
-    void* __restrict__ out_, float* __restrict__ lse_, const SparseDims dims) {
+    void* __restrict__ out_, float* __restrict__ lse_, const int32_t* __restrict__ ulen_, const SparseDims dims) {
+  static_assert(!PAIRED || NW == 4, "paired mode: four wavefronts, two per query block of 64");
   const SparseArgs A = {q_, crit_, k8_, v8_, dq_, dk_, dv_, HZ_, bias_, out_, lse_, dims.N, dims.Tq, dims.Tk,
                         dims.n_c, dims.total, dims.per_xcd, dims.phi, dims.has_lin, dims.out_f32, dims.H,
-                        dims.lq, dims.lo};
+                        dims.lq, dims.lo, dims.TqW, dims.ustride, ulen_};
   constexpr int NT = NW * 64;
   constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
   constexpr int BQ = NW * 32;
@@ -231,19 +243,23 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   // XCD's L2 are neighbouring query blocks, whose critical sets overlap.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   // (the division runs on the vector ALU; its uniform result goes back to scalar registers)
-  const int bh = __builtin_amdgcn_readfirstlane(slot / A.per_xcd);  // per_xcd = ceil(Tq / 8)
-  const int i = xcd * A.per_xcd + (slot - bh * A.per_xcd);
-  if (i >= A.Tq) return;
-  const int rowid = bh * A.Tq + i;
+  const int bh = __builtin_amdgcn_readfirstlane(slot / A.per_xcd);  // per_xcd = ceil(TqW / 8)
+  const int i = xcd * A.per_xcd + (slot - bh * A.per_xcd);       // workgroup tile (of BQ queries)
+  if (i >= A.TqW) return;
 
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int pair_half = PAIRED ? __builtin_amdgcn_readfirstlane(w >> 1) : 0;
+  // the query block whose scale, summaries and list membership this wavefront uses (an odd block
+  // count leaves the last pair's second half without queries: clamped, nothing of it is stored)
+  const int iq = PAIRED ? min(2 * i + pair_half, A.Tq - 1) : i;
+  const int rowid = bh * A.Tq + iq;
   const int qrow = i * BQ + 32 * w + l32;
   const bool qok = qrow < A.N;
   const int b_ = __builtin_amdgcn_readfirstlane(bh / A.H), h_ = bh - b_ * A.H;
   const bf16_t* qptr = A.q + b_ * A.lq.sb + h_ * A.lq.sh + (qok ? qrow : 0) * A.lq.sn;
 
   // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each)
-  const float dqi = A.dq[(size_t)bh * A.Tq + i];
+  const float dqi = A.dq[(size_t)rowid];
   v4i q8[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
@@ -279,9 +295,13 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   for (int e = 0; e < 16; ++e) bias16[e] = BIAS_I;
   asm volatile("" : "+v"(bias16));  // kept in registers: the C operand of the first score MFMA of every half
 
-  const int n_c = A.n_c;
+  const int listrow = bh * A.TqW + i;
+  const int n_c = PAIRED ? A.ulen[listrow] : A.n_c;
   // the critical list and the K scales are read through the scalar unit (uniform addresses)
-  const int32_t* __restrict__ crow = A.crit + (size_t)rowid * n_c;
+  const int32_t* __restrict__ crow = PAIRED ? A.crit + (size_t)listrow * A.ustride : A.crit + (size_t)rowid * n_c;
+  constexpr int JMASK = PAIRED ? 0x3FFFFFFF : -1;  // an entry's key block index
+  // does this wavefront's query block have entry e in its own list?
+  auto mine = [&](int e) { return !PAIRED || ((e >> (30 + pair_half)) & 1); };
   const float* __restrict__ dkrow = A.dk + (size_t)bh * A.Tk;
   const size_t rec0 = (size_t)bh * A.Tk * KV_FRAG_BYTES;
   // Asynchronous global -> LDS copy of one block's K or V record (no registers in between).
@@ -344,7 +364,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   // last entry of the (ascending) list; it is peeled off the loop so that masking its missing
   // keys costs the other blocks nothing.
   const int last = n_c - 1;
-  const bool has_tail = ragged && n_c > 0 && crow[last] == A.Tk - 1;
+  const bool has_tail = ragged && n_c > 0 && (crow[last] & JMASK) == A.Tk - 1;
   constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4070 : (0x0070 | (2 * CH));  // s_waitcnt vmcnt(2*CH) lgkmcnt(0)
   constexpr int WAIT_ALL = 0x0070;                                            // s_waitcnt vmcnt(0) lgkmcnt(0)
   v16i s0, s1;
@@ -360,7 +380,9 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     read4(VPREV, lane, 0, vfa);                                                                       \
     read4(KNEXT, lane, 0, kfA);                                                                       \
     fetch_rec(k8_bh, j4, KFILL);                                                                       \
-    const int jn_ = crow[min(b_ + 5, last)];                                                          \
+    const int jn_ = crow[min(b_ + 5, last)] & JMASK;                                                  \
+    const int eb_ = PAIRED ? crow[b_] : 0;                                                            \
+    const float rk_ = r;                                                                              \
     const float dn_ = dk_of(j4);                                                                      \
     const BlockConsts bc_ = block_consts(cq * d0);                                                    \
     SB s1 = qk_step(kfB[0], q8[0], bias16);                                                           \
@@ -393,7 +415,10 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     SB pv_tile(vfb[2], vfb[3], PBP, sc_prev, acc[3]);                                                 \
     SB PBN[7] = codes_quad<false>(s1, 3, 32, hf, bc_.c2s, offsB_, 0, PBN[7]);                                     \
     SB pv_rowsum(ones, PBP, sc_prev, accl);                                                           \
-    SB const float rsel_ = hf ? r : rA_;   /* level of this lane's half of the new codes */           \
+    if constexpr (PAIRED) {                                                                           \
+      if (!mine(eb_)) { PBN = v8i{}; r = rk_; }                                                       \
+    }                                                                                                 \
+    SB const float rsel_ = (PAIRED && !mine(eb_)) ? rk_ : (hf ? r : rA_);   /* level of this lane's half of the new codes */ \
     j2 = j3; j3 = j4; j4 = jn_;                                                                       \
     d0 = d1; d1 = d2; d2 = d3; d3 = dn_;                                                              \
     /* anchor: keeps every piece inside this step */                                                  \
@@ -409,8 +434,8 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     // step 0 has no previous block: it multiplies all-zero P codes with this all-zero V slot
     for (int e = t; e < KV_FRAG_BYTES / 16; e += NT) vst3[e] = make_uint4(0, 0, 0, 0);
     // indices of blocks 0..4 and K scales of blocks 0..3 (clamped to the list)
-    const int j0 = crow[0], j1 = crow[min(1, last)];
-    int j2 = crow[min(2, last)], j3 = crow[min(3, last)], j4 = crow[min(4, last)];
+    const int j0 = crow[0] & JMASK, j1 = crow[min(1, last)] & JMASK;
+    int j2 = crow[min(2, last)] & JMASK, j3 = crow[min(3, last)] & JMASK, j4 = crow[min(4, last)] & JMASK;
     float d0 = dk_of(j0), d1 = dk_of(j1), d2 = dk_of(j2), d3 = dk_of(j3);
     // three groups of copies, in the order the steps will wait for them
     fetch_rec(k8_bh, j0, kst0);
@@ -464,6 +489,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
       pv_tile(vfb[0], vfb[1], pb_b, sc_prev, acc[2]);
       pv_tile(vfb[2], vfb[3], pb_b, sc_prev, acc[3]);
       pv_rowsum(ones, pb_b, sc_prev, accl);
+      const float rkt = r;
       const int mAt = half_max<true>(s0, 0, hf, kvalid_last);
       const float offsAt = new_reference(mAt, bct, pos_inf, r);
       const float rAt = r;
@@ -475,8 +501,11 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
 #pragma unroll
       for (int g = 0; g < 4; ++g) pb_t[4 + g] = codes_quad<true>(s1, g, 32, hf, bct.c2s, offsBt, kvalid_last, pb_t[4 + g]);
       pb_b = pb_t;
+      if constexpr (PAIRED) {
+        if (!mine(crow[last])) { pb_b = v8i{}; r = rkt; }
+      }
       if (__any(r - R > 64.f)) renormalise(r, R, Rm127, acc, accl);
-      sc_prev = level_scale(hf ? r : rAt, Rm127);
+      sc_prev = level_scale((PAIRED && !mine(crow[last])) ? rkt : (hf ? r : rAt), Rm127);
     }
     {  // P.V of the last block
       const int sl = last & 3;
@@ -602,29 +631,86 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   }
 }
 
+// Paired mode (query blocks of 64): per pair of adjacent query blocks, the ascending union of
+// their critical lists; bit 30 / 31 of an entry = the first / second block of the pair has it.
+// One workgroup of 256 threads per pair; thread t owns key blocks 32 t .. 32 t + 31 (Tk <= 8192).
+__global__ void __launch_bounds__(256) pair_union_kernel(const int32_t* __restrict__ crit, int Tq, int n_c, int TqW,
+                                                         int ustride, int32_t* __restrict__ ulist,
+                                                         int32_t* __restrict__ ulen) {
+  __shared__ uint32_t bm[2][256];
+  __shared__ int wave_cnt[4];
+  const int row = blockIdx.x, bh = row / TqW, i = row - bh * TqW, t = threadIdx.x;
+  bm[0][t] = 0u;
+  bm[1][t] = 0u;
+  __syncthreads();
+  const int32_t* ra = crit + ((size_t)bh * Tq + 2 * i) * n_c;
+  const bool has_b = 2 * i + 1 < Tq;
+  for (int idx = t; idx < n_c; idx += 256) {
+    const int a = ra[idx];
+    atomicOr(&bm[0][a >> 5], 1u << (a & 31));
+    if (has_b) {
+      const int b = ra[n_c + idx];
+      atomicOr(&bm[1][b >> 5], 1u << (b & 31));
+    }
+  }
+  __syncthreads();
+  const uint32_t wa = bm[0][t], wb = bm[1][t];
+  uint32_t u = wa | wb;
+  const int cnt = __popc(u);
+  // exclusive prefix sum of cnt over the 256 threads
+  int incl = cnt;
+  for (int o = 1; o < 64; o <<= 1) {
+    const int v = __shfl_up(incl, o);
+    if ((t & 63) >= o) incl += v;
+  }
+  if ((t & 63) == 63) wave_cnt[t >> 6] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int k = 0; k < (t >> 6); ++k) base += wave_cnt[k];
+  int pos = base + incl - cnt;
+  int32_t* dst = ulist + (size_t)row * ustride;
+  while (u) {
+    const int bit = __ffs(u) - 1;
+    u &= u - 1;
+    dst[pos++] = (32 * t + bit) | (int)(((wa >> bit) & 1u) << 30) | (int)(((wb >> bit) & 1u) << 31);
+  }
+  if (t == 255) ulen[row] = base + incl;
+}
+
 void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
                        const uint8_t* v8, const float* dq, const float* dk, const float* dv,
                        const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
-                       void* out, bool out_f32, float* lse, hipStream_t stream) {
+                       void* out, bool out_f32, float* lse, int32_t* pair_list, int32_t* pair_len,
+                       hipStream_t stream) {
   SparseDims dm;
   dm.N = p.N;
   dm.Tq = p.Tq;
   dm.Tk = p.Tk;
   dm.n_c = n_c;
   dm.total = p.BH * p.Tq;
-  dm.per_xcd = (p.Tq + 7) / 8;  // query blocks of one head per XCD
   dm.phi = phi_kind;
   dm.has_lin = has_linear ? 1 : 0;
   dm.out_f32 = out_f32 ? 1 : 0;
   dm.H = p.H;
   dm.lq = p.lq;
   dm.lo = p.lo;
+  const bool paired = p.block_q == 64 && n_c > 0 && pair_list && pair_len;
+  dm.TqW = paired ? (p.Tq + 1) / 2 : p.Tq;
+  dm.ustride = 2 * n_c;
+  dm.per_xcd = (dm.TqW + 7) / 8;  // workgroup tiles of one head per XCD
   const bf16_t* bias = has_linear ? proj_b : nullptr;
   const unsigned grid = (unsigned)(8 * dm.per_xcd * p.BH);
-  if (p.block_q == 128) {
-    sparse_fwd_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse, dm);
+  if (paired) {
+    pair_union_kernel<<<(unsigned)(p.BH * dm.TqW), 256, 0, stream>>>(crit, p.Tq, n_c, dm.TqW, dm.ustride, pair_list,
+                                                                     pair_len);
+    sparse_fwd_kernel<4, true><<<grid, 256, 0, stream>>>((const bf16_t*)q, pair_list, k8, v8, dq, dk, dv, HZ, bias, out,
+                                                         lse, pair_len, dm);
+  } else if (p.block_q == 128) {
+    sparse_fwd_kernel<4, false><<<grid, 256, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse,
+                                                          nullptr, dm);
   } else {
-    sparse_fwd_kernel<2><<<grid, 128, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse, dm);
+    sparse_fwd_kernel<2, false><<<grid, 128, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse,
+                                                          nullptr, dm);
   }
 }
 
