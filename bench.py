@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 PEAK_MFMA_8BIT_TOPS = 5000.0   # MI355X dense INT8 (POP/s) and FP8 (PFLOP/s) MFMA peak, both 5.0e15
 # Bytes moved past L2 per launch of the sparse kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # from a 1 GiB copy in the same counter runs), by config id; source: profiles/sla_fwd_wan14b-720p.md.
-SPARSE_TRAFFIC_BYTES = {4: 17.95e9}
+SPARSE_TRAFFIC_BYTES = {4: 18.00e9}
 
 
 # Linear layers of a Wan2.1-14B DiT block (hidden 5120, feed-forward 13824) on the 75600 tokens of a
