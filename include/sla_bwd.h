@@ -1,0 +1,63 @@
+/*
+ * sla_bwd.h -- C ABI of the backward pass of Sparse-Linear Attention on MI355X (gfx950),
+ * part of libsla.so.
+ *
+ * The paper's training stage (Section 1.2) replaces full attention by SLA and finetunes the
+ * model; inference (Section 1.3) then swaps in the low-bit core.  So the function that is
+ * differentiated here is the UNQUANTISED SLA forward pass,
+ *
+ *     O = O^s + O^l W^T (+ b)
+ *     O^s[n] = sum_{t in the critical key blocks of n's query block} softmax_t(Q[n].K[t]/sqrt(d)) V[t]
+ *     O^l[n] = phi(Q[n]) H_i / (phi(Q[n]) . Z_i),   H_i = sum_{j marginal for i} phi(K_j)^T V_j,
+ *                                                  Z_i = sum_{j marginal for i} sum_t phi(K_j[t]),
+ *
+ * with the block mask computed exactly as in sla_attention_fwd (pooled scores, Top-K) and held
+ * fixed: it is piecewise constant in Q and K and passes no gradient.  The paper gives no
+ * backward formula; the result is the gradient of the function above, computed in bf16 on the
+ * matrix cores with fp32 accumulation (softmax statistics, delta = dO . O^s and the row
+ * normalisers in fp32).
+ *
+ * Rules as in sla.h: every tensor pointer is a DEVICE pointer owned by the caller; the library
+ * allocates nothing and never synchronises; work is enqueued on `stream`; scratch lives in
+ * `workspace` (256-byte aligned, at least sla_bwd_workspace_bytes(...) bytes, contents undefined
+ * before and after); inputs are never written; outputs must not alias inputs or the workspace.
+ * Returns SLA_OK or a negative sla_status; argument errors are found on the host before any launch.
+ * Supported: what sla_attention_fwd supports for shapes, blocks and ratios; contiguous [B,H,N,d]
+ * tensors; phi_kind == SLA_PHI_SOFTMAX (else SLA_ERR_UNSUPPORTED).
+ */
+#ifndef SLA_BWD_H_
+#define SLA_BWD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "sla.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Host-only.  Workspace bytes of sla_attention_bwd; 0 if the arguments are not supported. */
+size_t sla_bwd_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k, double topk_ratio,
+                               double marginal_ratio);
+
+/* Gradients of the SLA forward pass defined above.
+ *   q, k, v   in   bf16 [B,H,N,d]
+ *   dout      in   bf16 [B,H,N,d]   gradient of the loss with respect to O
+ *   proj_w    in   bf16 [d,d] (row = output channel) or NULL = identity, as in sla_attention_fwd
+ *   dq,dk,dv  out  bf16 [B,H,N,d]
+ *   dproj_w   out  fp32 [d,d]  sum over all (b,h,n) of dout[n]^T O^l[n]; NULL = not wanted.
+ *                  Summed with floating-point atomics: the order of the additions, hence the
+ *                  last bits, can differ from run to run.  Zero when there is no marginal block.
+ *   dproj_b   out  fp32 [d]    sum over all (b,h,n) of dout[n] (the bias gradient); NULL = not
+ *                  wanted; same remark.  Zero when there is no marginal block (the forward pass
+ *                  then adds no bias). */
+int sla_attention_bwd(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
+                      void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
+                      int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
+                      void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLA_BWD_H_ */

@@ -29,6 +29,7 @@ EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspac
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
 W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
                 "w8a8_quantize_act", "w8a8_gemm_fwd", "w8a8_debug_unpack")
+BWD_EXPORTS = ("sla_bwd_workspace_bytes", "sla_attention_bwd")
 N_STAGES = 5
 STAGE_NAMES = ("pool_stats", "scores_select", "prep_kv", "lin_accumulate", "sparse_fwd")
 
@@ -86,6 +87,11 @@ def lib():
         L.sla_profile_reset.argtypes = []
         L.sla_profile_read.restype = c_int
         L.sla_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), c_int, ip]
+        # include/sla_bwd.h
+        L.sla_bwd_workspace_bytes.restype = c_sz
+        L.sla_bwd_workspace_bytes.argtypes = [c_int] * 6 + [c_dbl, c_dbl]
+        L.sla_attention_bwd.restype = c_int
+        L.sla_attention_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_dbl, c_dbl, c_int, c_vp, c_sz, c_vp]
         # include/w8a8.h
         L.w8a8_weight_bytes.restype = c_sz
         L.w8a8_weight_bytes.argtypes = [c_int, c_int]
@@ -166,6 +172,34 @@ def sla_attention_fwd(q, k, v, block_q, block_k, topk_ratio, marginal_ratio, pro
                                  _ptr(workspace), workspace.numel(), _stream())
     _check(st, "sla_attention_fwd")
     return out
+
+
+def sla_bwd_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio):
+    return lib().sla_bwd_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio)
+
+
+def alloc_bwd_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, device="cuda"):
+    nbytes = sla_bwd_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio)
+    if nbytes == 0:
+        raise ValueError("invalid problem for sla_bwd_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def sla_attention_bwd(q, k, v, dout, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None, want_dw=False,
+                      want_db=False, phi_kind=PHI_SOFTMAX, workspace=None, grads=None):
+    """Returns (dq, dk, dv, dproj_w or None, dproj_b or None); dq, dk, dv bf16 [B,H,N,d], the others fp32.
+    `grads` may hand in preallocated (dq, dk, dv)."""
+    B, H, N, d = _bf16_4d(q, k, v, dout)
+    if workspace is None:
+        workspace = alloc_bwd_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    dq, dk, dv = grads if grads is not None else (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
+    dw = torch.empty((d, d), dtype=torch.float32, device=q.device) if want_dw else None
+    db = torch.empty((d,), dtype=torch.float32, device=q.device) if want_db else None
+    st = lib().sla_attention_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(proj_w), _ptr(dq), _ptr(dk), _ptr(dv),
+                                 _ptr(dw), _ptr(db), B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio,
+                                 phi_kind, _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_attention_bwd")
+    return dq, dk, dv, dw, db
 
 
 def _strides_of(t, what):

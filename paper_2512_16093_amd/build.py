@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsla.so")
-SOURCES = ["api.hip", "api_w8a8.hip", "k_classify.hip", "k_prep.hip", "k_linacc.hip", "k_sparse.hip", "k_w8a8.hip"]
+SOURCES = ["api.hip", "api_w8a8.hip", "k_classify.hip", "k_prep.hip", "k_linacc.hip", "k_sparse.hip", "k_w8a8.hip", "k_bwd.hip", "k_bwd_lin.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
          "-Wno-inline-asm"]  # (the asynchronous-copy helpers name m0 in their clobber lists on purpose)

@@ -2,6 +2,7 @@
 // launch sequence.  See include/sla.h for the contract of every entry point.
 #pragma GCC visibility push(default)
 #include "../../include/sla.h"
+#include "../../include/sla_bwd.h"
 #pragma GCC visibility pop
 
 #include <math.h>
@@ -85,6 +86,38 @@ void run_stats(const void* q, const void* k, const void* v, const void* proj_w, 
                     at<uint32_t>(ws, W.amax_v), s);
   launch_finalize_stats(p, at<float>(ws, W.kbar), at<uint32_t>(ws, W.amax_v), at<float>(ws, W.mu_k),
                         at<float>(ws, W.dv), (const bf16_t*)proj_w, at<bf16_t>(ws, W.wfrag), s);
+}
+
+// Scratch of the backward pass, laid out after the forward pass's workspace map.
+struct BwdWorkspace {
+  size_t qn, qt, don, dot;   // records of Q and dO: [BH, T32q, 8 KiB]
+  size_t kn, kt, vn, vt;     // records of K and V:  [BH, T32k, 8 KiB]
+  size_t lse2, delta;        // fp32 [BH, 32 T32q]
+  size_t dql, dkl, dvl;      // fp32 [BH, N, D]: the linear branch's share of dQ, dK, dV
+  size_t dHZ;                // bf16 [BH, Tq, HZ_ROWS, D]: per query block dH^T and dZ
+  size_t mbits_t;            // transposed marginal bit matrix
+  size_t wt;                 // bf16 [D, D]: W^T
+  size_t dw_scratch;         // fp32 [D, D]: stands in for dproj_w when only dproj_b is wanted
+  size_t total;
+};
+
+BwdWorkspace make_bwd_workspace(const Problem& p, const Workspace& W) {
+  BwdWorkspace b;
+  size_t o = W.total;
+  auto take = [&](size_t bytes) { size_t r = o; o = align256(o + bytes); return r; };
+  const size_t BH = p.BH, T32q = (size_t)p.Tq * (p.block_q / 32), T32k = (size_t)p.Tk * 2, rec = 8192;
+  b.qn = take(BH * T32q * rec); b.qt = take(BH * T32q * rec); b.don = take(BH * T32q * rec); b.dot = take(BH * T32q * rec);
+  b.kn = take(BH * T32k * rec); b.kt = take(BH * T32k * rec); b.vn = take(BH * T32k * rec); b.vt = take(BH * T32k * rec);
+  b.lse2 = take(BH * T32q * 32 * 4); b.delta = take(BH * T32q * 32 * 4);
+  const bool lin = p.n_m > 0;
+  const size_t grad = lin ? BH * (size_t)p.N * D * 4 : 0;
+  b.dql = take(grad); b.dkl = take(grad); b.dvl = take(grad);
+  b.dHZ = take(lin ? BH * (size_t)p.Tq * HZ_ELEMS * 2 : 0);
+  b.mbits_t = take(lin ? marginal_bits_t_bytes(p) : 0);
+  b.wt = take(D * D * 2);
+  b.dw_scratch = take(D * D * 4);
+  b.total = o;
+  return b;
 }
 
 }  // namespace
@@ -305,6 +338,73 @@ int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int
   if (k_scale && hipMemcpyAsync(k_scale, at<float>(ws, W.dk), (size_t)p.BH * p.Tk * 4, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
   if (k_mean && hipMemcpyAsync(k_mean, at<float>(ws, W.mu_k), bhd, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
   if (v_scale && hipMemcpyAsync(v_scale, at<float>(ws, W.dv), bhd, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
+  return launch_status();
+}
+
+size_t sla_bwd_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k, double topk_ratio,
+                               double marginal_ratio) {
+  Problem p;
+  if (make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p) != SLA_OK) return 0;
+  return make_bwd_workspace(p, make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m)).total;
+}
+
+int sla_attention_bwd(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
+                      void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
+                      int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
+                      void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  if (!q || !k || !v || !dout || !dq || !dk || !dv) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  if (phi_kind != SLA_PHI_SOFTMAX) return SLA_ERR_UNSUPPORTED;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  const BwdWorkspace X = make_bwd_workspace(p, W);
+  if ((st = check_ws(workspace, workspace_bytes, X.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  const bool lin = p.n_m > 0;
+  const int T32q = p.Tq * (p.block_q / 32), T32k = p.Tk * 2;
+
+  // the block mask, exactly as the forward pass finds it
+  run_stats(q, k, v, nullptr, p, ws, W, s);   // (no projection folded into the summaries here)
+  launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
+  launch_select(p, at<float>(ws, W.scores), at<int8_t>(ws, W.mask), at<int32_t>(ws, W.crit), nullptr,
+                lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
+  // operands in matrix-core order
+  launch_bwd_pack(q, p.lq, p, T32q, at<uint4>(ws, X.qn), at<uint4>(ws, X.qt), s);
+  launch_bwd_pack(dout, p.lq, p, T32q, at<uint4>(ws, X.don), at<uint4>(ws, X.dot), s);
+  launch_bwd_pack(k, p.lk, p, T32k, at<uint4>(ws, X.kn), at<uint4>(ws, X.kt), s);
+  launch_bwd_pack(v, p.lv, p, T32k, at<uint4>(ws, X.vn), at<uint4>(ws, X.vt), s);
+  launch_bwd_stats(p, at<uint4>(ws, X.qn), at<uint4>(ws, X.kn), at<uint4>(ws, X.vt), dout, at<int32_t>(ws, W.crit),
+                   at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
+  float* dw_eff = dproj_w ? dproj_w : (dproj_b ? at<float>(ws, X.dw_scratch) : nullptr);
+  if (dproj_w) launch_zero_u32((uint32_t*)dproj_w, (size_t)D * D, s);
+  if (dproj_b) launch_zero_u32((uint32_t*)dproj_b, (size_t)D, s);
+  if (lin) {
+    // H_i, Z_i of the forward pass (unprojected), then the linear branch's gradients
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
+                   at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+    launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+    launch_bwd_wt((const bf16_t*)proj_w, at<bf16_t>(ws, X.wt), s);
+    if (launch_bwd_lin_q(p, q, dout, at<bf16_t>(ws, W.HZ), at<bf16_t>(ws, X.wt), at<float>(ws, X.dql),
+                         at<bf16_t>(ws, X.dHZ), dw_eff, dproj_b, s) != 0)
+      return SLA_ERR_HIP;
+    // G_j = sum of dH_i over the query blocks that hold key block j as marginal: the forward's
+    // accumulation kernel on the transposed mask (its output reuses the per-key-block summaries' buffer)
+    Problem pt = p;
+    pt.Tq = p.Tk;
+    pt.Tk = p.Tq;
+    launch_marginal_bits_t(p, at<int8_t>(ws, W.mask), at<uint32_t>(ws, X.mbits_t), s);
+    launch_lin_accumulate(pt, at<uint32_t>(ws, X.mbits_t), at<bf16_t>(ws, X.dHZ), at<bf16_t>(ws, W.hz), s);
+    launch_bwd_lin_k(p, k, v, at<bf16_t>(ws, W.hz), at<float>(ws, X.dkl), at<float>(ws, X.dvl), s);
+  }
+  launch_bwd_dq(p, at<uint4>(ws, X.qn), at<uint4>(ws, X.don), at<uint4>(ws, X.kn), at<uint4>(ws, X.kt),
+                at<uint4>(ws, X.vn), at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta),
+                lin ? at<float>(ws, X.dql) : nullptr, dq, s);
+  launch_bwd_dkv(p, at<uint4>(ws, X.qn), at<uint4>(ws, X.qt), at<uint4>(ws, X.don), at<uint4>(ws, X.dot),
+                 at<uint4>(ws, X.kn), at<uint4>(ws, X.vn), at<int8_t>(ws, W.mask), at<float>(ws, X.lse2),
+                 at<float>(ws, X.delta), lin ? at<float>(ws, X.dkl) : nullptr, lin ? at<float>(ws, X.dvl) : nullptr, dk,
+                 dv, s);
   return launch_status();
 }
 

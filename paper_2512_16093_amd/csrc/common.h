@@ -169,6 +169,25 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
                        const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
                        void* out, bool out_f32, float* lse, int32_t* pair_list, int32_t* pair_len,
                        hipStream_t stream);
+// Backward pass (k_bwd.hip, k_bwd_lin.hip; the transposed bit matrix lives with lin_accumulate).
+size_t marginal_bits_t_bytes(const Problem& p);
+void launch_marginal_bits_t(const Problem& p, const int8_t* mask, uint32_t* mbits_t, hipStream_t stream);
+void launch_bwd_pack(const void* x, const Layout& L, const Problem& p, int T32, uint4* nrec, uint4* trec,
+                     hipStream_t stream);
+void launch_bwd_stats(const Problem& p, const uint4* qn, const uint4* kn, const uint4* vt, const void* dout,
+                      const int32_t* crit, float* lse2, float* delta, hipStream_t stream);
+void launch_bwd_dq(const Problem& p, const uint4* qn, const uint4* don, const uint4* kn, const uint4* ktr,
+                   const uint4* vn, const int32_t* crit, const float* lse2, const float* delta, const float* dq_lin,
+                   void* dq, hipStream_t stream);
+void launch_bwd_dkv(const Problem& p, const uint4* qn, const uint4* qtr, const uint4* don, const uint4* dotr,
+                    const uint4* kn, const uint4* vn, const int8_t* mask, const float* lse2, const float* delta,
+                    const float* dk_lin, const float* dv_lin, void* dk, void* dv, hipStream_t stream);
+void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
+int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
+                     float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream);
+void launch_bwd_lin_k(const Problem& p, const void* k, const void* v, const bf16_t* G, float* dk_lin, float* dv_lin,
+                      hipStream_t stream);
+void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream);
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
                           uint8_t* v_codes, hipStream_t stream);
 void launch_e4m3_encode(const float* in, uint8_t* out, size_t n, hipStream_t stream);

@@ -1,0 +1,422 @@
+// Backward pass of SLA, linear branch and projection (Section 1.2; the forward pass it differentiates:
+//     a = phi(Q[n]),  num = a H_i,  den = a . Z_i,  O^l[n] = num / den,   O += O^l W^T + b,
+//     H_i = sum_{j marginal for i} phi(K_j)^T V_j,   Z_i = sum_{j marginal for i} sum_t phi(K_j[t]),
+// phi = softmax over the channels).
+//
+//   bwd_lin_q_kernel   per query block i (a workgroup walks over several and keeps dW, db in
+//                      registers): dO^l = dO W, dnum = dO^l / den, dden = -(dO^l . O^l) / den,
+//                      d phi(Q) = dnum H_i^T + dden Z_i -> dQ (softmax backward), and the block's
+//                      dH_i = a^T dnum, dZ_i = a^T dden, written in the summaries' storage order so
+//                      that the forward's accumulation kernel can sum them over the transposed mask.
+//   bwd_lin_k_kernel   per key block j, with G_j = sum_{i : j marginal for i} dH_i (and the dZ sum):
+//                      d phi(K) = V G_j^T + dZ -> dK (softmax backward),  dV = phi(K) G_j.
+//
+// As in the sparse-branch kernels a wavefront owns 32 tokens, one per lane pair, and every product
+// is formed with the tokens as accumulator columns, so per-token reductions stay in a lane pair.
+#include "common.h"
+
+namespace sla {
+
+namespace {
+
+constexpr int LP = 136;  // row pitch (elements) of the bf16 LDS matrices: 272 bytes, 16-byte aligned, bank-skewed
+
+__device__ __forceinline__ v16f mfma_bf16(const uint4& a, const uint4& b, const v16f& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ uint4 lds_frag(const bf16_t* m, int row, int k0) { return *(const uint4*)(m + row * LP + k0); }
+
+// Where entry [o][c .. c+3] (c a multiple of 4) of a 128 x 128 summary sits in the storage order of
+// hz / HZ (hz_frag_chunk): element offset of the 4-element run.
+__device__ __forceinline__ int hz_run_offset(int o, int c) {
+  const int G = c >> 3, ks = 2 * (G >> 2) + (G & 1), lanep = (o & 31) + 32 * ((G >> 1) & 1);
+  return hz_frag_chunk(o >> 5, ks, lanep) * 8 + (c & 7);
+}
+
+// Softmax over the 128 channels of this lane pair's token; x holds the lane's 64 channels.
+// Returns the row maximum and 1 / sum(exp) through the references; x becomes exp(x - max).
+__device__ __forceinline__ void softmax_stats(float (&x)[64], float& mx, float& rsum) {
+  mx = x[0];
+#pragma unroll
+  for (int e = 1; e < 64; ++e) mx = fmaxf(mx, x[e]);
+  mx = fmaxf(mx, partner_f32(mx));
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 64; ++e) {
+    x[e] = __builtin_amdgcn_exp2f((x[e] - mx) * LOG2E);
+    s += x[e];
+  }
+  s += partner_f32(s);
+  rsum = 1.0f / s;
+}
+
+__device__ __forceinline__ void unpack8(const uint4& v, float* out) {
+  out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x); out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+  out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z); out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
+}
+__device__ __forceinline__ uint4 pack8(const float* x) {
+  return uint4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+}
+
+}  // namespace
+
+// wt[c][r] = W[r][c] (identity when there is no projection): the A operand of dO^l = dO W.
+__global__ void __launch_bounds__(256) bwd_wt_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt) {
+  for (int x = blockIdx.x * 256 + threadIdx.x; x < D * D; x += gridDim.x * 256) {
+    const int c = x >> 7, r = x & 127;
+    wt[x] = w ? w[r * D + c] : (bf16_t)(r == c ? 0x3F80 : 0);
+  }
+}
+
+template <int NW>
+__global__ void __launch_bounds__(NW * 64, 1)
+    bwd_lin_q_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ HZ,
+                     const bf16_t* __restrict__ wt, float* __restrict__ dq_lin, bf16_t* __restrict__ dHZ,
+                     float* __restrict__ dW, float* __restrict__ db, int N, int Tq) {
+  constexpr int BQ = 32 * NW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Wt = (bf16_t*)smem;              // [c'][r]
+  bf16_t* R1 = Wt + 128 * LP;              // Hn[o][c]            -> dnum[n][o]
+  bf16_t* R2 = R1 + 128 * LP;              // Ht[c][o]            -> aT[c][n]   -> gT[r][n]
+  bf16_t* R3 = R2 + 128 * LP;              // dnumT[o][n]         -> OlT[c][n]
+  float* zv = (float*)(R3 + 128 * LP);     // Z[c]
+  float* dden_s = zv + 128;                // dden[n]
+  const int bh = blockIdx.y, t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int nl = 32 * w + l32;             // this lane pair's token within the query block
+
+  for (int x = t; x < 128 * 16; x += NW * 64) *(uint4*)(Wt + (x >> 4) * LP + (x & 15) * 8) = *(const uint4*)(wt + x * 8);
+
+  constexpr int RT = 4 / NW;               // row tiles of dW per wavefront
+  v16f dwacc[RT][4];
+#pragma unroll
+  for (int a = 0; a < RT; ++a)
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) dwacc[a][ct] = v16f{};
+  float dbacc = 0.f;
+
+  for (int i = blockIdx.x; i < Tq; i += gridDim.x) {
+    // ---- stage H_i twice ([o][c] and [c][o]) and Z_i
+    const bf16_t* hz = HZ + ((size_t)bh * Tq + i) * HZ_ELEMS;
+    for (int x = t; x < 2048; x += NW * 64) {
+      const int ln = x & 63, ks = (x >> 6) & 7, ot = x >> 9;
+      const int o = 32 * ot + (ln & 31), c0 = 32 * (ks >> 1) + 16 * (ln >> 5) + 8 * (ks & 1);
+      const uint4 v = *(const uint4*)(hz + (size_t)x * 8);
+      *(uint4*)(R1 + o * LP + c0) = v;
+      const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) R2[(c0 + e) * LP + o] = (bf16_t)(e & 1 ? wv[e >> 1] >> 16 : wv[e >> 1] & 0xffffu);
+    }
+    if (t < 128) zv[t] = bf16_to_f32(hz[128 * 128 + t]);
+    __syncthreads();
+
+    // ---- this wavefront's 32 tokens
+    const long long n = (long long)i * BQ + nl;
+    const bool ok = n < N;
+    const size_t row = ((size_t)bh * N + (ok ? n : 0)) * D;
+    float av[64];                // a = phi(Q[n]) at channels 16 ks + 8 hf + kk  (index 8 ks + kk)
+    uint4 af[8], gf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      uint4 qv = uint4{0u, 0u, 0u, 0u};
+      gf[ks] = qv;
+      if (ok) {
+        qv = *(const uint4*)(q + row + 16 * ks + 8 * hf);
+        gf[ks] = *(const uint4*)(dout + row + 16 * ks + 8 * hf);
+      }
+      unpack8(qv, &av[8 * ks]);
+    }
+    float qmax, rsum;
+    softmax_stats(av, qmax, rsum);
+    if (!ok) rsum = 0.f;         // rows beyond the sequence take no part in dH, dZ, dW
+    float den = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        av[8 * ks + kk] *= rsum;
+        den += av[8 * ks + kk] * zv[16 * ks + 8 * hf + kk];
+      }
+      af[ks] = pack8(&av[8 * ks]);
+    }
+    den += partner_f32(den);
+    const float rden = den > 0.f ? 1.0f / den : 0.f;
+
+    // numT[o][n] = sum_c H[c][o] a[n][c]  ->  O^l;   glT[c'][n] = sum_r W[r][c'] dO[n][r]
+    v16f ol[4], gl[4];
+#pragma unroll
+    for (int ot = 0; ot < 4; ++ot) {
+      ol[ot] = v16f{};
+      gl[ot] = v16f{};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        ol[ot] = mfma_bf16(lds_frag(R1, 32 * ot + l32, 16 * ks + 8 * hf), af[ks], ol[ot]);
+        gl[ot] = mfma_bf16(lds_frag(Wt, 32 * ot + l32, 16 * ks + 8 * hf), gf[ks], gl[ot]);
+      }
+    }
+    float dden = 0.f;
+#pragma unroll
+    for (int ot = 0; ot < 4; ++ot)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        ol[ot][r] *= rden;
+        dden += gl[ot][r] * ol[ot][r];
+        gl[ot][r] *= rden;       // dnum
+      }
+    dden += partner_f32(dden);
+    dden *= -rden;
+    __syncthreads();             // every wavefront is done with Hn
+
+    // ---- d phi(Q) = dnum H^T + dden Z, then through the softmax
+#pragma unroll
+    for (int ot = 0; ot < 4; ++ot)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *(uint2*)(R1 + nl * LP + 32 * ot + 8 * g + 4 * hf) =
+            uint2{pack_bf16x2(gl[ot][4 * g], gl[ot][4 * g + 1]), pack_bf16x2(gl[ot][4 * g + 2], gl[ot][4 * g + 3])};
+    // (own rows only: written and read back by this wavefront, in program order)
+    v16f da[4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      da[ct] = v16f{};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        da[ct] = mfma_bf16(lds_frag(R2, 32 * ct + l32, 16 * ks + 8 * hf), lds_frag(R1, nl, 16 * ks + 8 * hf), da[ct]);
+    }
+    float ad[4][16];             // a at the accumulator's channels 32 ct + 8 g + 4 hf + e
+    float sdot = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c0 = 32 * ct + 8 * g + 4 * hf;
+        uint2 qv = uint2{0u, 0u};
+        if (ok) qv = *(const uint2*)(q + row + c0);
+        const float xq[4] = {bf16_lo(qv.x), bf16_hi(qv.x), bf16_lo(qv.y), bf16_hi(qv.y)};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float a = __builtin_amdgcn_exp2f((xq[e] - qmax) * LOG2E) * rsum;
+          ad[ct][4 * g + e] = a;
+          da[ct][4 * g + e] += zv[c0 + e] * dden;
+          sdot += a * da[ct][4 * g + e];
+        }
+      }
+    sdot += partner_f32(sdot);
+    if (ok) {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float4 o4;
+          o4.x = ad[ct][4 * g] * (da[ct][4 * g] - sdot);
+          o4.y = ad[ct][4 * g + 1] * (da[ct][4 * g + 1] - sdot);
+          o4.z = ad[ct][4 * g + 2] * (da[ct][4 * g + 2] - sdot);
+          o4.w = ad[ct][4 * g + 3] * (da[ct][4 * g + 3] - sdot);
+          *(float4*)(dq_lin + row + 32 * ct + 8 * g + 4 * hf) = o4;
+        }
+    }
+    __syncthreads();             // every wavefront is done with Ht (and with its dnum rows)
+
+    // ---- dH_i^T[o][c] = sum_n dnum[n][o] a[n][c], dZ_i[c] = sum_n a[n][c] dden[n]: transposed copies with the tokens contiguous
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) R2[(16 * ks + 8 * hf + kk) * LP + nl] = f32_to_bf16(av[8 * ks + kk]);
+#pragma unroll
+    for (int ot = 0; ot < 4; ++ot)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) R3[(32 * ot + 8 * (r >> 2) + 4 * hf + (r & 3)) * LP + nl] = f32_to_bf16(gl[ot][r]);
+    if (hf == 0) dden_s[nl] = dden;
+    __syncthreads();
+    bf16_t* dst = dHZ + ((size_t)bh * Tq + i) * HZ_ELEMS;
+    for (int ct = w; ct < 4; ct += NW) {
+      v16f acc[4];
+#pragma unroll
+      for (int ot = 0; ot < 4; ++ot) {
+        acc[ot] = v16f{};
+#pragma unroll
+        for (int ks = 0; ks < BQ / 16; ++ks)
+          acc[ot] = mfma_bf16(lds_frag(R2, 32 * ct + l32, 16 * ks + 8 * hf), lds_frag(R3, 32 * ot + l32, 16 * ks + 8 * hf), acc[ot]);
+        // lane: o = 32 ot + l32; registers: c = 32 ct + 8 g + 4 hf + e
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *(uint2*)(dst + hz_run_offset(32 * ot + l32, 32 * ct + 8 * g + 4 * hf)) =
+              uint2{pack_bf16x2(acc[ot][4 * g], acc[ot][4 * g + 1]), pack_bf16x2(acc[ot][4 * g + 2], acc[ot][4 * g + 3])};
+      }
+    }
+    if (t < 128) {
+      float s = 0.f;
+      for (int m = 0; m < BQ; ++m) s += bf16_to_f32(R2[t * LP + m]) * dden_s[m];
+      dst[128 * 128 + t] = f32_to_bf16(s);
+    }
+    __syncthreads();             // aT and dnumT are consumed
+
+    // ---- dW[r][c] += sum_n dO[n][r] O^l[n][c],  db[r] += sum_n dO[n][r]
+    if (dW) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const uint32_t gw[4] = {gf[ks].x, gf[ks].y, gf[ks].z, gf[ks].w};
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+          R2[(16 * ks + 8 * hf + kk) * LP + nl] = (bf16_t)(kk & 1 ? gw[kk >> 1] >> 16 : gw[kk >> 1] & 0xffffu);
+      }
+#pragma unroll
+      for (int ot = 0; ot < 4; ++ot)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) R3[(32 * ot + 8 * (r >> 2) + 4 * hf + (r & 3)) * LP + nl] = f32_to_bf16(ol[ot][r]);
+      __syncthreads();
+#pragma unroll
+      for (int a = 0; a < RT; ++a) {
+        const int rt = w + a * NW;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int ks = 0; ks < BQ / 16; ++ks)
+            dwacc[a][ct] = mfma_bf16(lds_frag(R2, 32 * rt + l32, 16 * ks + 8 * hf), lds_frag(R3, 32 * ct + l32, 16 * ks + 8 * hf),
+                                     dwacc[a][ct]);
+      }
+      if (t < 128) {
+        float s = 0.f;
+        for (int m = 0; m < BQ; ++m) s += bf16_to_f32(R2[t * LP + m]);
+        dbacc += s;
+      }
+      __syncthreads();
+    }
+  }
+  if (dW) {
+#pragma unroll
+    for (int a = 0; a < RT; ++a)
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          atomicAdd(dW + (32 * (w + a * NW) + 8 * (r >> 2) + 4 * hf + (r & 3)) * D + 32 * ct + l32, dwacc[a][ct][r]);
+    if (db && t < 128) atomicAdd(db + t, dbacc);
+  }
+}
+
+__global__ void __launch_bounds__(128) bwd_lin_k_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                                                        const bf16_t* __restrict__ G, float* __restrict__ dk_lin,
+                                                        float* __restrict__ dv_lin, int N, int Tk) {
+  __shared__ __attribute__((aligned(16))) bf16_t Gc[128 * LP];  // G[c][o], o contiguous
+  __shared__ float gz[128];
+  const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const bf16_t* rec = G + ((size_t)bh * Tk + j) * HZ_ELEMS;
+  for (int x = t; x < 2048; x += 128) {
+    const int ln = x & 63, ks = (x >> 6) & 7, ot = x >> 9;
+    const int o = 32 * ot + (ln & 31), c0 = 32 * (ks >> 1) + 16 * (ln >> 5) + 8 * (ks & 1);
+    const uint4 val = *(const uint4*)(rec + (size_t)x * 8);
+    const uint32_t wv[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) Gc[(c0 + e) * LP + o] = (bf16_t)(e & 1 ? wv[e >> 1] >> 16 : wv[e >> 1] & 0xffffu);
+  }
+  gz[t] = bf16_to_f32(rec[128 * 128 + t]);
+  __syncthreads();
+
+  const long long n = 64ll * j + 32 * w + l32;
+  const bool ok = n < N;
+  const size_t row = ((size_t)bh * N + (ok ? n : 0)) * D;
+  // phi(K[n]) at the channels the summaries' storage order feeds per step: 32 (ks/2) + 16 hf + 8 (ks%2) + kk
+  float cv[64];
+  uint4 cf[8], vf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    uint4 kv = uint4{0u, 0u, 0u, 0u};
+    vf[ks] = kv;
+    if (ok) {
+      kv = *(const uint4*)(k + row + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
+      vf[ks] = *(const uint4*)(v + row + 16 * ks + 8 * hf);
+    }
+    unpack8(kv, &cv[8 * ks]);
+  }
+  float kmax, rsum;
+  softmax_stats(cv, kmax, rsum);
+  if (!ok) rsum = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) cv[8 * ks + kk] *= rsum;
+    cf[ks] = pack8(&cv[8 * ks]);
+  }
+  // dV^T[o][n] = sum_c G[c][o] phi(K)[n][c]: the stored chunks are this product's A operand as they are
+  v16f dvt[4], dct[4];
+#pragma unroll
+  for (int ot = 0; ot < 4; ++ot) {
+    dvt[ot] = v16f{};
+    dct[ot] = v16f{};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      dvt[ot] = mfma_bf16(*(const uint4*)(rec + (size_t)hz_frag_chunk(ot, ks, lane) * 8), cf[ks], dvt[ot]);
+      // d phi(K)^T[c][n] = sum_o G[c][o] V[n][o]
+      dct[ot] = mfma_bf16(lds_frag(Gc, 32 * ot + l32, 16 * ks + 8 * hf), vf[ks], dct[ot]);
+    }
+  }
+  float cd[4][16];
+  float sdot = 0.f;
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int c0 = 32 * ct + 8 * g + 4 * hf;
+      uint2 kv = uint2{0u, 0u};
+      if (ok) kv = *(const uint2*)(k + row + c0);
+      const float xk[4] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float c = __builtin_amdgcn_exp2f((xk[e] - kmax) * LOG2E) * rsum;
+        cd[ct][4 * g + e] = c;
+        dct[ct][4 * g + e] += gz[c0 + e];
+        sdot += c * dct[ct][4 * g + e];
+      }
+    }
+  sdot += partner_f32(sdot);
+  if (ok) {
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int c0 = 32 * ct + 8 * g + 4 * hf;
+        float4 a, b;
+        a.x = cd[ct][4 * g] * (dct[ct][4 * g] - sdot);
+        a.y = cd[ct][4 * g + 1] * (dct[ct][4 * g + 1] - sdot);
+        a.z = cd[ct][4 * g + 2] * (dct[ct][4 * g + 2] - sdot);
+        a.w = cd[ct][4 * g + 3] * (dct[ct][4 * g + 3] - sdot);
+        b.x = dvt[ct][4 * g]; b.y = dvt[ct][4 * g + 1]; b.z = dvt[ct][4 * g + 2]; b.w = dvt[ct][4 * g + 3];
+        *(float4*)(dk_lin + row + c0) = a;
+        *(float4*)(dv_lin + row + c0) = b;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream) {
+  bwd_wt_kernel<<<64, 256, 0, stream>>>(proj_w, wt);
+}
+
+size_t bwd_lin_q_lds_bytes() { return (size_t)4 * 128 * LP * 2 + 128 * 4 + 128 * 4; }
+
+int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
+                     float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
+  const int chunks = p.Tq < 16 ? p.Tq : 16;
+  const dim3 grid((unsigned)chunks, (unsigned)p.BH);
+  const size_t lds = bwd_lin_q_lds_bytes();
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)bwd_lin_q_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void*)bwd_lin_q_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+      return -1;
+    attr_set = true;
+  }
+  if (p.block_q == 128)
+    bwd_lin_q_kernel<4><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
+  else
+    bwd_lin_q_kernel<2><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
+  return 0;
+}
+
+void launch_bwd_lin_k(const Problem& p, const void* k, const void* v, const bf16_t* G, float* dk_lin, float* dv_lin,
+                      hipStream_t stream) {
+  bwd_lin_k_kernel<<<dim3((unsigned)p.Tk, (unsigned)p.BH), 128, 0, stream>>>((const bf16_t*)k, (const bf16_t*)v, G, dk_lin,
+                                                                           dv_lin, p.N, p.Tk);
+}
+
+}  // namespace sla

@@ -321,6 +321,10 @@ __global__ void __launch_bounds__(256) select_kernel(const float* __restrict__ s
 }
 
 // ---------------------------------------------------------------------------
+void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream) {
+  zero_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(p, n);
+}
+
 void launch_pool_stats(const void* q, const void* k, const void* v, const Problem& p, float* qbar,
                        float* kbar, float* dq, uint32_t* amax_v, hipStream_t stream) {
   const size_t n = (size_t)p.BH * D;

@@ -263,6 +263,35 @@ __global__ void __launch_bounds__(LA_WAVES * 64, 2) lin_accumulate_kernel(const 
   }  // work items
 }
 
+// The same bit matrix for the transposed mask (backward pass: sums over the query blocks that hold a
+// key block as marginal): mbits_t[bh][qt][j] (qt < ceil(Tq/32), j < la_rows_padded(Tk)): bit e = 1 where
+// key block j is marginal for query block 32 qt + e.
+__global__ void marginal_bits_t_kernel(const int8_t* __restrict__ mask, int Tq, int Tk, int BH,
+                                       uint32_t* __restrict__ mbits_t) {
+  const int QT = la_k_tiles(Tq), TkP = la_rows_padded(Tk);
+  const size_t total = (size_t)BH * QT * Tk;
+  for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < total; x += (size_t)gridDim.x * blockDim.x) {
+    const int j = (int)(x % Tk), qt = (int)((x / Tk) % QT), bh = (int)(x / ((size_t)Tk * QT));
+    uint32_t w = 0;
+    for (int e = 0; e < 32; ++e) {
+      const int i = qt * 32 + e;
+      if (i < Tq && mask[((size_t)bh * Tq + i) * Tk + j] == 0) w |= 1u << e;
+    }
+    mbits_t[((size_t)bh * QT + qt) * TkP + j] = w;
+  }
+}
+
+size_t marginal_bits_t_bytes(const Problem& p) {
+  return (size_t)p.BH * la_k_tiles(p.Tq) * la_rows_padded(p.Tk) * 4;
+}
+
+void launch_marginal_bits_t(const Problem& p, const int8_t* mask, uint32_t* mbits_t, hipStream_t stream) {
+  const size_t total = (size_t)p.BH * la_k_tiles(p.Tq) * p.Tk;
+  const size_t want = (total + 255) / 256;
+  const unsigned grid = (unsigned)(want < 1048560 ? want : 1048560);
+  marginal_bits_t_kernel<<<grid, 256, 0, stream>>>(mask, p.Tq, p.Tk, p.BH, mbits_t);
+}
+
 size_t marginal_bits_bytes(const Problem& p) {
   return (size_t)p.BH * la_k_tiles(p.Tk) * la_rows_padded(p.Tq) * 4;
 }

@@ -1,0 +1,88 @@
+"""GPU parity of the SLA backward pass: sla_attention_bwd (through the C ABI) against the float64
+gradient oracle, element by element, on seeded synthetic inputs that span several tiles and ragged
+tails.  The block mask is the library's own (its agreement with the oracle's classification is the
+subject of the forward parity tests), so ties in the Top-K choice play no role here.
+
+Tolerance.  The path computes in bf16 with fp32 accumulation: inputs are bf16 already; P, dS, the
+per-block summaries H, Z, their gradients and the outputs are each rounded to bf16 once (relative
+step 2^-9), the softmax statistics, delta and the normalisers stay in fp32.  A handful of
+independent roundings of relative size 2^-9 per contribution, averaged over long sums, give a
+relative Frobenius error well under 1e-2; single elements are held to 3e-2 of the largest
+reference entry, and the direction (cosine) to 0.999 as for the forward pass."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sla_bwd_oracle as bo
+from paper_2512_16093_amd import binding as sla
+from paper_2512_16093_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+REL_FRO, REL_MAX, COS_MIN = 1e-2, 3e-2, 0.999
+
+CASES = [
+    # (H, grid, block_q, rc, rm, proj)
+    (2, (5, 10, 20), 128, 0.25, 0.0, False),   # sparse branch alone, N = 1000 (ragged in both block sizes)
+    (2, (5, 10, 20), 64, 0.2, 0.0, False),
+    (2, (5, 10, 20), 128, 0.25, 0.5, True),    # both branches with projection and bias gradient
+    (2, (5, 10, 20), 64, 0.2, 0.4, True),
+    (1, (3, 27, 27), 128, 0.1, 0.2, False),    # N = 2187 = 17*128 + 11, no projection (identity)
+    (1, (1, 9, 9), 128, 0.5, 0.5, True),       # N = 81: one ragged query block, two key blocks
+    (1, (1, 5, 5), 64, 1.0, 0.0, False),       # N = 25: a single short block, dense attention
+    (1, (4, 16, 16), 64, 0.15, 0.85, True),    # N = 1024: whole blocks, no negligible block
+]
+
+
+def _compare(name, got, ref):
+    got, ref = got.astype(np.float64), ref.astype(np.float64)
+    scale = np.abs(ref).max()
+    assert np.isfinite(got).all(), name
+    if scale == 0.0:
+        assert not got.any(), name
+        return
+    err = np.abs(got - ref).max()
+    fro = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    cos = float((got * ref).sum() / np.linalg.norm(got) / np.linalg.norm(ref))
+    assert err <= REL_MAX * scale and fro <= REL_FRO and cos >= COS_MIN, (name, err / scale, fro, cos)
+
+
+@pytest.mark.parametrize("H,grid,bq,rc,rm,proj", CASES)
+def test_backward_matches_gradient_oracle(H, grid, bq, rc, rm, proj):
+    cfg = synth.custom_config(1, H, grid, block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=proj, cfg_id=300)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=7)[2]          # a V-like tensor as the upstream gradient
+    W = synth.make_proj(cfg) if proj else None
+    dev = torch.device("cuda:0")
+    qd, kd, vd, dd = (t.to(dev) for t in (q, k, v, dout))
+    Wd = W.to(dev) if proj else None
+    print("case", H, grid, bq, rc, rm, proj, flush=True)
+    mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
+    dq, dk, dv, dw, db = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=proj, want_db=proj)
+    torch.cuda.synchronize()
+    sums_w = np.zeros((cfg.d, cfg.d))
+    sums_b = np.zeros(cfg.d)
+    for h in range(H):
+        r = bo.sla_backward_head(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
+                                 synth.as_f64(dout[0, h]), mask[0, h], bq, 64,
+                                 proj_w=synth.as_f64(W) if proj else None, has_bias=proj)
+        _compare("dq", dq[0, h].float().cpu().numpy(), r["dQ"])
+        _compare("dk", dk[0, h].float().cpu().numpy(), r["dK"])
+        _compare("dv", dv[0, h].float().cpu().numpy(), r["dV"])
+        if proj:
+            sums_w += r["dW"]
+            sums_b += r["db"]
+    if proj:
+        _compare("dproj_w", dw.cpu().numpy(), sums_w)
+        _compare("dproj_b", db.cpu().numpy(), sums_b)
+
+
+def test_backward_argument_errors():
+    dev = torch.device("cuda:0")
+    x = torch.zeros((1, 1, 128, 128), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(sla.SLAError) as e:
+        sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, phi_kind=sla.PHI_ELU1)
+    assert e.value.status == sla.ERR_UNSUPPORTED
+    with pytest.raises(sla.SLAError) as e:
+        sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, workspace=torch.empty(256, dtype=torch.uint8, device=dev))
+    assert e.value.status == sla.ERR_WORKSPACE

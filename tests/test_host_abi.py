@@ -33,6 +33,33 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(sla.W8A8_EXPORTS)
     for n in names:
         assert hasattr(L, n), n
+    names = [n for n in _declared("sla_bwd.h") if n not in sla.EXPORTS]   # (its comments name forward entry points)
+    assert set(names) == set(sla.BWD_EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_backward_sizes_and_argument_errors():
+    L = sla.lib()
+    fwd = sla.sla_workspace_bytes(1, 2, 1000, 128, 128, 64, 0.25, 0.5)
+    bwd = sla.sla_bwd_workspace_bytes(1, 2, 1000, 128, 128, 64, 0.25, 0.5)
+    # the forward map plus eight sets of operand records and three fp32 gradient partials
+    assert bwd > fwd + 4 * 2 * 32 * 8192 + 4 * 2 * 32 * 8192 + 3 * 2 * 1000 * 128 * 4
+    assert sla.sla_bwd_workspace_bytes(1, 2, 1000, 64, 128, 64, 0.25, 0.5) == 0
+    assert sla.sla_bwd_workspace_bytes(1, 2, 1000, 128, 96, 64, 0.25, 0.5) == 0
+    big = 1 << 44
+    args = lambda **kw: [kw.get("q", FAKE), FAKE, FAKE, kw.get("dout", FAKE), None, FAKE, FAKE, kw.get("dv", FAKE), None, None,
+                         1, 2, kw.get("N", 1000), kw.get("d", 128), kw.get("bq", 128), 64, kw.get("rc", 0.25), 0.5,
+                         kw.get("phi", 0), kw.get("ws", WS), kw.get("bytes", big), None]
+    assert L.sla_attention_bwd(*args(q=None)) == sla.ERR_NULL
+    assert L.sla_attention_bwd(*args(dout=None)) == sla.ERR_NULL
+    assert L.sla_attention_bwd(*args(dv=None)) == sla.ERR_NULL
+    assert L.sla_attention_bwd(*args(d=64)) == sla.ERR_SHAPE
+    assert L.sla_attention_bwd(*args(bq=32)) == sla.ERR_BLOCK
+    assert L.sla_attention_bwd(*args(rc=0.0)) == sla.ERR_RATIO
+    assert L.sla_attention_bwd(*args(phi=1)) == sla.ERR_UNSUPPORTED
+    assert L.sla_attention_bwd(*args(ws=None)) == sla.ERR_WORKSPACE
+    assert L.sla_attention_bwd(*args(bytes=bwd - 1)) == sla.ERR_WORKSPACE
 
 
 def test_w8a8_sizes_and_argument_errors():
