@@ -40,6 +40,8 @@ W8A8_SHAPES = {"attn_proj": (75600, 5120, 5120), "ffn_up": (75600, 5120, 13824),
 # Bytes moved past L2 per launch of the product kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0), by shape;
 # source: profiles/w8a8_linear_wan14b.md.
 W8A8_TRAFFIC_BYTES = {"attn_proj": 6.49e9}
+# The backward pass's dominant kernel, by (config, kernel); source: profiles/sla_bwd_wan14b-720p.md.
+BWD_TRAFFIC_BYTES = {}
 
 
 def parse():
@@ -51,9 +53,9 @@ def parse():
     ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
                     help="memory order of q, k, v and out: head-major [B,H,N,d] (default) or token-major "
                          "[B,N,H,d] through the strided entry point")
-    ap.add_argument("--workload", choices=("sla", "w8a8"), default="sla",
+    ap.add_argument("--workload", choices=("sla", "w8a8", "sla_bwd"), default="sla",
                     help="sla: the SLA forward (the headline, default); w8a8: the W8A8 Linear layer at a Wan-14B "
-                         "shape (a second JSON line of its own metric)")
+                         "shape; sla_bwd: the SLA backward pass (each a JSON line of its own metric)")
     ap.add_argument("--w8a8-shape", choices=tuple(W8A8_SHAPES), default="attn_proj",
                     help="which Linear layer of a Wan-14B block, on the 75600 tokens of a 720P clip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -215,6 +217,108 @@ def main_w8a8(args):
     print(json.dumps(result))
 
 
+BWD_STAGE_NAMES = ("mask_and_records", "softmax_stats", "linear_branch", "dq", "dkv")
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+
+
+def main_bwd(args):
+    """One step = one backward pass of SLA (sla_attention_bwd): block mask, operand records, softmax
+    statistics, linear-branch and projection gradients, dQ, dK and dV, for the same seeded inputs as
+    the forward benchmark and a seeded upstream gradient."""
+    import numpy as np
+    import torch
+    from paper_2512_16093_amd import binding as sla
+    from paper_2512_16093_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    sla.lib()
+    cfg = synth.CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    t0 = time.perf_counter()
+    q, k, v = make_inputs(cfg, synth, torch)
+    W = synth.make_proj(cfg)
+    # the upstream gradient: the V tensor of another seed (same generator, same statistics)
+    g = torch.Generator().manual_seed(11)
+    dout = v[:, torch.randperm(cfg.H, generator=g)].flip(2).contiguous()
+    print("[bench] inputs for %s generated in %.1f s" % (cfg.name, time.perf_counter() - t0), file=sys.stderr, flush=True)
+    qd, kd, vd, dd = q.to(dev), k.to(dev), v.to(dev), dout.to(dev)
+    Wd = None if W is None else W.to(dev)
+    ws = sla.alloc_bwd_workspace(cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio,
+                                 cfg.marginal_ratio, dev)
+    grads = tuple(torch.empty_like(qd) for _ in range(3))
+    Tq, Tk, n_c, n_m = sla.sla_block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+
+    def step():
+        return sla.sla_attention_bwd(qd, kd, vd, dd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                                     proj_w=Wd, want_dw=Wd is not None, want_db=Wd is not None, workspace=ws, grads=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sla.sla_profile_enable(args.steps)
+    sla.sla_profile_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = sla.sla_profile_read(args.steps)
+    sla.sla_profile_enable(0)
+    ms_per_step = dt / args.steps * 1e3
+    stage_ms = [sum(r[s] for r in stages) / len(stages) for s in range(sla.N_STAGES)]
+    # dense attention's backward is 2.5x its forward (five N x N x d products against two)
+    flops = 10.0 * cfg.B * cfg.H * float(cfg.N) ** 2 * cfg.d
+    pairs = cfg.B * cfg.H * Tq * n_c
+    tile = 2.0 * cfg.block_q * cfg.block_k * cfg.d
+    kernels = {"dkv": (4, stage_ms[4], "bwd_dkv_kernel"), "dq": (3, stage_ms[3], "bwd_dq_kernel")}
+    dom = max(kernels, key=lambda n: kernels[n][1])
+    n_prod, t_dom, kname = kernels[dom]
+    ops = n_prod * tile * pairs
+    achieved = ops / (t_dom * 1e-3) / 1e12
+    result = {
+        "metric": "sla_bwd_dense_equiv_tflops", "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 (fp32 accumulate and statistics)", "data": "synthetic",
+        "config": {"workload": "%s backward: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0"
+                               % (cfg.name, cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio,
+                                  cfg.marginal_ratio),
+                   "n_crit": n_c, "n_marg": n_m, "Tq": Tq, "Tk": Tk},
+        "stage_ms": dict(zip(BWD_STAGE_NAMES, [round(x, 4) for x in stage_ms])),
+        "roofline": {"kernel": kname, "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_BF16_TFLOPS,
+                     "traffic": BWD_TRAFFIC_BYTES.get((cfg.cfg_id, kname)), "traffic_unit": "bytes per launch",
+                     "launch_ms": t_dom, "ops_per_launch": ops},
+        "context": "the paper reports no number for its finetuning stage",
+    }
+    if not args.no_cpu_baseline:
+        from oracle import sla_bwd_oracle as bo   # cpu_baseline leg: allowed to call the oracle
+        from oracle import sla_oracle as so
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        # the oracle works head by head on the whole sequence; a shorter sequence of the same
+        # statistics (the first Ns tokens of head 0) is timed and scaled by the dense-equivalent work
+        Ns = 4096
+        Qs, Ks, Vs, Ds = (synth.as_f64(t[0, 0, :Ns]) for t in (q, k, v, dout))
+        Tq_s, Tk_s, nc_s, nm_s = so.block_counts(Ns, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+        mask = so.classify(so.pooled_scores(Qs, Ks, cfg.block_q, cfg.block_k), nc_s, nm_s)
+        t0 = time.perf_counter()
+        bo.sla_backward_head(Qs, Ks, Vs, Ds, mask, cfg.block_q, cfg.block_k,
+                             proj_w=None if W is None else synth.as_f64(W), has_bias=W is not None)
+        t = time.perf_counter() - t0
+        full = t * cfg.B * cfg.H * (cfg.N / Ns) ** 2
+        result["cpu_baseline"] = {"value": flops / full / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": int(cores),
+                                  "kind": "oracle",
+                                  "sample": "one head of %d tokens (the first %d of head 0) in %.2f s; scaled by "
+                                            "heads x (N / %d)^2 = %.0f s" % (Ns, Ns, t, Ns, full)}
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -223,6 +327,8 @@ def main():
         sys.exit(2)
     if args.workload == "w8a8":
         return main_w8a8(args)
+    if args.workload == "sla_bwd":
+        return main_bwd(args)
     import torch
     from paper_2512_16093_amd import binding as sla
     from paper_2512_16093_amd import synth

@@ -51,7 +51,11 @@ size_t sla_bwd_workspace_bytes(int B, int H, int N, int d, int block_q, int bloc
  *                  last bits, can differ from run to run.  Zero when there is no marginal block.
  *   dproj_b   out  fp32 [d]    sum over all (b,h,n) of dout[n] (the bias gradient); NULL = not
  *                  wanted; same remark.  Zero when there is no marginal block (the forward pass
- *                  then adds no bias). */
+ *                  then adds no bias).
+ * With sla_profile_enable (sla.h) a call records the same number of stage events as a forward
+ * call; the stages are: 0 block mask + operand records, 1 softmax statistics (lse, delta),
+ * 2 linear branch and projection (summaries, dQ share, transposed accumulation, dK / dV shares),
+ * 3 dQ, 4 dK and dV. */
 int sla_attention_bwd(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
                       void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
                       int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,

@@ -90,8 +90,6 @@ void run_stats(const void* q, const void* k, const void* v, const void* proj_w, 
 
 // Scratch of the backward pass, laid out after the forward pass's workspace map.
 struct BwdWorkspace {
-  size_t qn, qt, don, dot;   // records of Q and dO: [BH, T32q, 8 KiB]
-  size_t kn, kt, vn, vt;     // records of K and V:  [BH, T32k, 8 KiB]
   size_t lse2, delta;        // fp32 [BH, 32 T32q]
   size_t dql, dkl, dvl;      // fp32 [BH, N, D]: the linear branch's share of dQ, dK, dV
   size_t dHZ;                // bf16 [BH, Tq, HZ_ROWS, D]: per query block dH^T and dZ
@@ -105,9 +103,7 @@ BwdWorkspace make_bwd_workspace(const Problem& p, const Workspace& W) {
   BwdWorkspace b;
   size_t o = W.total;
   auto take = [&](size_t bytes) { size_t r = o; o = align256(o + bytes); return r; };
-  const size_t BH = p.BH, T32q = (size_t)p.Tq * (p.block_q / 32), T32k = (size_t)p.Tk * 2, rec = 8192;
-  b.qn = take(BH * T32q * rec); b.qt = take(BH * T32q * rec); b.don = take(BH * T32q * rec); b.dot = take(BH * T32q * rec);
-  b.kn = take(BH * T32k * rec); b.kt = take(BH * T32k * rec); b.vn = take(BH * T32k * rec); b.vt = take(BH * T32k * rec);
+  const size_t BH = p.BH, T32q = (size_t)p.Tq * (p.block_q / 32);
   b.lse2 = take(BH * T32q * 32 * 4); b.delta = take(BH * T32q * 32 * 4);
   const bool lin = p.n_m > 0;
   const size_t grad = lin ? BH * (size_t)p.N * D * 4 : 0;
@@ -363,20 +359,17 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   const bool lin = p.n_m > 0;
-  const int T32q = p.Tq * (p.block_q / 32), T32k = p.Tk * 2;
+  const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
+  mark(s, rec, 0);
 
   // the block mask, exactly as the forward pass finds it
   run_stats(q, k, v, nullptr, p, ws, W, s);   // (no projection folded into the summaries here)
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
   launch_select(p, at<float>(ws, W.scores), at<int8_t>(ws, W.mask), at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
-  // operands in matrix-core order
-  launch_bwd_pack(q, p.lq, p, T32q, at<uint4>(ws, X.qn), at<uint4>(ws, X.qt), s);
-  launch_bwd_pack(dout, p.lq, p, T32q, at<uint4>(ws, X.don), at<uint4>(ws, X.dot), s);
-  launch_bwd_pack(k, p.lk, p, T32k, at<uint4>(ws, X.kn), at<uint4>(ws, X.kt), s);
-  launch_bwd_pack(v, p.lv, p, T32k, at<uint4>(ws, X.vn), at<uint4>(ws, X.vt), s);
-  launch_bwd_stats(p, at<uint4>(ws, X.qn), at<uint4>(ws, X.kn), at<uint4>(ws, X.vt), dout, at<int32_t>(ws, W.crit),
-                   at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
+  mark(s, rec, 1);
+  launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
+  mark(s, rec, 2);
   float* dw_eff = dproj_w ? dproj_w : (dproj_b ? at<float>(ws, X.dw_scratch) : nullptr);
   if (dproj_w) launch_zero_u32((uint32_t*)dproj_w, (size_t)D * D, s);
   if (dproj_b) launch_zero_u32((uint32_t*)dproj_b, (size_t)D, s);
@@ -398,13 +391,13 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
     launch_lin_accumulate(pt, at<uint32_t>(ws, X.mbits_t), at<bf16_t>(ws, X.dHZ), at<bf16_t>(ws, W.hz), s);
     launch_bwd_lin_k(p, k, v, at<bf16_t>(ws, W.hz), at<float>(ws, X.dkl), at<float>(ws, X.dvl), s);
   }
-  launch_bwd_dq(p, at<uint4>(ws, X.qn), at<uint4>(ws, X.don), at<uint4>(ws, X.kn), at<uint4>(ws, X.kt),
-                at<uint4>(ws, X.vn), at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta),
+  mark(s, rec, 3);
+  launch_bwd_dq(p, q, dout, k, v, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta),
                 lin ? at<float>(ws, X.dql) : nullptr, dq, s);
-  launch_bwd_dkv(p, at<uint4>(ws, X.qn), at<uint4>(ws, X.qt), at<uint4>(ws, X.don), at<uint4>(ws, X.dot),
-                 at<uint4>(ws, X.kn), at<uint4>(ws, X.vn), at<int8_t>(ws, W.mask), at<float>(ws, X.lse2),
-                 at<float>(ws, X.delta), lin ? at<float>(ws, X.dkl) : nullptr, lin ? at<float>(ws, X.dvl) : nullptr, dk,
-                 dv, s);
+  mark(s, rec, 4);
+  launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), at<float>(ws, X.lse2), at<float>(ws, X.delta),
+                 lin ? at<float>(ws, X.dkl) : nullptr, lin ? at<float>(ws, X.dvl) : nullptr, dk, dv, s);
+  mark(s, rec, 5);
   return launch_status();
 }
 

@@ -172,16 +172,13 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
 // Backward pass (k_bwd.hip, k_bwd_lin.hip; the transposed bit matrix lives with lin_accumulate).
 size_t marginal_bits_t_bytes(const Problem& p);
 void launch_marginal_bits_t(const Problem& p, const int8_t* mask, uint32_t* mbits_t, hipStream_t stream);
-void launch_bwd_pack(const void* x, const Layout& L, const Problem& p, int T32, uint4* nrec, uint4* trec,
-                     hipStream_t stream);
-void launch_bwd_stats(const Problem& p, const uint4* qn, const uint4* kn, const uint4* vt, const void* dout,
+void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
                       const int32_t* crit, float* lse2, float* delta, hipStream_t stream);
-void launch_bwd_dq(const Problem& p, const uint4* qn, const uint4* don, const uint4* kn, const uint4* ktr,
-                   const uint4* vn, const int32_t* crit, const float* lse2, const float* delta, const float* dq_lin,
-                   void* dq, hipStream_t stream);
-void launch_bwd_dkv(const Problem& p, const uint4* qn, const uint4* qtr, const uint4* don, const uint4* dotr,
-                    const uint4* kn, const uint4* vn, const int8_t* mask, const float* lse2, const float* delta,
-                    const float* dk_lin, const float* dv_lin, void* dk, void* dv, hipStream_t stream);
+void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
+                   const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);
+void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+                    const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
+                    hipStream_t stream);
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
                      float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream);

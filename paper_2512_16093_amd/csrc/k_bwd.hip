@@ -3,9 +3,6 @@
 //     O^s[n] = sum_{t in critical blocks of n's query block} softmax_t(Q[n].K[t] / sqrt(d)) V[t]
 // with respect to Q, K and V, in bf16 on the matrix cores with fp32 accumulation.
 //
-//   bwd_pack_kernel     Q, K, V, dO -> per 32-token tile, two 8 KiB records in MFMA operand order:
-//                       the n-record (contraction over channels) and the t-record (contraction
-//                       over the tile's tokens).
 //   bwd_stats_kernel    per query block: online-softmax pass over its critical key blocks ->
 //                       lse (base-2 log-sum-exp of the scaled scores) and delta = dO . O^s per token.
 //   bwd_dq_kernel       per query block, over its critical key blocks:
@@ -17,11 +14,15 @@
 // lane (two lanes per token, each with half of the rows of an accumulator tile), so row statistics
 // stay inside a lane pair, and an accumulator tile converted to bf16 is directly the B operand of
 // the next product (its contraction index = the accumulator's rows).
+//
+// Operand tiles (32 tokens x 128 channels) are staged in LDS row-major as they are in memory.  A
+// product that contracts over the channels reads its operand with one 16-byte read per step; a
+// product that contracts over the tile's tokens reads the same tile with the transposing LDS read
+// of gfx950 (ds_read_b64_tr_b16), so no transposed copy of any tensor is ever made.
 #include "common.h"
 
 namespace sla {
 
-constexpr int REC_CHUNKS = 512;                          // 16-byte chunks per 32-token record
 constexpr float QK_LOG2 = LOG2E / 11.313708498984761f;   // log2(e) / sqrt(d)
 constexpr float INV_SQRT_D = 1.0f / 11.313708498984761f;
 
@@ -31,117 +32,133 @@ __device__ __forceinline__ v16f mfma_bf16(const uint4& a, const uint4& b, const 
 }
 // Accumulator registers 8 s .. 8 s + 7 of a tile as a bf16 operand: contraction step s (16 rows) of
 // the product that contracts over the tile's rows.  Row of element kk for lane half hf:
-// 16 s + 8 (kk / 4) + 4 hf + kk % 4 -- the order the t-records are written in.
+// 16 s + 8 (kk / 4) + 4 hf + kk % 4 -- the order t_op (below) reads a staged tile's rows in.
 __device__ __forceinline__ uint4 acc_operand(const v16f& a, int s) {
   return uint4{pack_bf16x2(a[8 * s], a[8 * s + 1]), pack_bf16x2(a[8 * s + 2], a[8 * s + 3]),
                pack_bf16x2(a[8 * s + 4], a[8 * s + 5]), pack_bf16x2(a[8 * s + 6], a[8 * s + 7])};
 }
 
-// ---------------------------------------------------------------------------------------------
-// Records.  Tile T of a [N, 128] tensor X (rows 32 T .. 32 T + 31, zero beyond N):
-//   n-record  chunk ks * 64 + lane           = X[32 T + lane % 32][16 ks + 8 (lane / 32) + 0..7]
-//   t-record  chunk (ct * 2 + s) * 64 + lane = X[32 T + 16 s + 8 (kk / 4) + 4 (lane / 32) + kk % 4][32 ct + lane % 32], kk = 0..7
-// One wavefront per tile.
-__global__ void __launch_bounds__(64) bwd_pack_kernel(const bf16_t* __restrict__ x, Layout L, int H, int N, int T32,
-                                                      uint4* __restrict__ nrec, uint4* __restrict__ trec) {
-  __shared__ __attribute__((aligned(16))) bf16_t tile[32][136];
-  const int T = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x, l32 = lane & 31, hf = lane >> 5;
-  const int b = bh / H, h = bh - b * H;
-  const bf16_t* src = x + b * L.sb + h * L.sh;
+constexpr int TP = 272;             // bytes per staged row: 256 of data + 16 of skew
+constexpr int TILE_B = 32 * TP;     // one 32-token tile
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4s read_tr(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)p);
+}
+// Operand for a contraction over the channels: token (row) l32 of the tile, channels 16 ks + 8 hf + 0..7.
+__device__ __forceinline__ uint4 n_op(const unsigned char* tile, int l32, int hf, int ks) {
+  return *(const uint4*)(tile + l32 * TP + ks * 32 + hf * 16);
+}
+// This lane's address inside a 4-row x 16-column patch for the transposing read: in every group of
+// 16 lanes, lane i receives element i of rows 0..3 of the patch that the group's lanes address
+// (lane s: row s / 4, columns 4 (s % 4) .. + 3).  Lane group g = lane / 16 serves channels
+// 16 (g % 2) .. + 15 of a 32-channel tile and the token rows of lane half g / 2.
+__device__ __forceinline__ int tr_lane_offset(int lane) {
+  return (4 * (lane >> 5) + ((lane & 15) >> 2)) * TP + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+}
+// Operand for a contraction over the tile's tokens, step s (16 tokens), channel tile ct: channel
+// 32 ct + l32, tokens 16 s + 8 (kk / 4) + 4 hf + kk % 4 for kk = 0..7 -- the order in which
+// acc_operand hands over the rows of an accumulator tile.
+__device__ __forceinline__ uint4 t_op(const unsigned char* tile, int tr_off, int ct, int s) {
+  union { v4s h[2]; uint4 v; } u;
+  u.h[0] = read_tr(tile + tr_off + (16 * s) * TP + ct * 64);
+  u.h[1] = read_tr(tile + tr_off + (16 * s + 8) * TP + ct * 64);
+  return u.v;
+}
+// The same operand as n_op straight from memory (a workgroup's own rows, read once).
+__device__ __forceinline__ void own_rows(const bf16_t* x, long long row, int N, int hf, uint4 (&f)[8]) {
 #pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int c = it * 64 + lane, row = c >> 4, cc = c & 15;
-    const long long r = 32ll * T + row;
-    uint4 v = uint4{0u, 0u, 0u, 0u};
-    if (r < N) v = *(const uint4*)(src + r * L.sn + cc * 8);
-    *(uint4*)&tile[row][cc * 8] = v;
-  }
-  __syncthreads();
-  const size_t base = ((size_t)bh * T32 + T) * REC_CHUNKS;
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) nrec[base + ks * 64 + lane] = *(const uint4*)&tile[l32][16 * ks + 8 * hf];
-#pragma unroll
-  for (int ct = 0; ct < 4; ++ct) {
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      uint32_t w[4];
-#pragma unroll
-      for (int kk = 0; kk < 8; kk += 2) {
-        const int r0 = 16 * s + 8 * (kk >> 2) + 4 * hf + (kk & 3);
-        w[kk >> 1] = (uint32_t)tile[r0][32 * ct + l32] | ((uint32_t)tile[r0 + 1][32 * ct + l32] << 16);
-      }
-      trec[base + (ct * 2 + s) * 64 + lane] = uint4{w[0], w[1], w[2], w[3]};
-    }
-  }
+  for (int ks = 0; ks < 8; ++ks) f[ks] = row < N ? *(const uint4*)(x + row * D + 16 * ks + 8 * hf) : uint4{0u, 0u, 0u, 0u};
 }
 
-// Shared skeleton of the two per-query-block kernels: NW wavefronts, wavefront w owns tile
-// T = i NW + w of query block i; per critical key block, NREC records of 1024 chunks (the block's
-// two key tiles) are staged in LDS through registers, one block ahead.
-template <int NW, int NREC>
-struct KeyStage {
-  static constexpr int PER = NREC * 2 * REC_CHUNKS / (NW * 64);  // chunks per thread per key block
+// ROWS consecutive token rows of a [N, 128] tensor -> LDS tile(s), through registers (loaded one
+// step ahead); rows beyond N are zero.  NT threads take part.
+template <int NT, int ROWS>
+struct RowStage {
+  static constexpr int PER = ROWS * 16 / NT;
   uint4 pf[PER];
-  __device__ __forceinline__ void load(const uint4* const (&src)[NREC], size_t rec0, int t) {
+  __device__ __forceinline__ void load(const bf16_t* x, long long r0, int N, int t) {
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-      const int c = u * NW * 64 + t;                 // chunk of the staged step
-      const int which = c / (2 * REC_CHUNKS);        // (compile-time per u: NW * 64 divides 1024)
-      pf[u] = src[which][rec0 + (c - which * 2 * REC_CHUNKS)];
+      const int c = u * NT + t;
+      const long long r = r0 + (c >> 4);
+      pf[u] = r < N ? *(const uint4*)(x + r * D + (c & 15) * 8) : uint4{0u, 0u, 0u, 0u};
     }
   }
-  __device__ __forceinline__ void store(uint4* lds, int t) const {
+  __device__ __forceinline__ void store(unsigned char* lds, int t) const {
 #pragma unroll
-    for (int u = 0; u < PER; ++u) lds[u * NW * 64 + t] = pf[u];
+    for (int u = 0; u < PER; ++u) {
+      const int c = u * NT + t;
+      *(uint4*)(lds + (c >> 4) * TP + (c & 15) * 16) = pf[u];
+    }
   }
 };
 
 struct BwdDims {
-  int N, Tq, Tk, n_c, T32q, T32k;
+  int N, Tq, Tk, n_c, T32q;
 };
 
-// Scaled scores of one key tile, transposed: lane = query, registers = keys.
-__device__ __forceinline__ v16f score_tile(const uint4* kn_tile, const uint4 (&qf)[8], int lane) {
+// Workgroup -> (block, head) for a 1-D grid of 8 * ceil(T / 8) * BH workgroups.  Consecutive workgroup
+// ids go to the 8 XCDs in turn; this order gives each XCD a contiguous run of a head's blocks, so
+// the workgroups resident on one XCD at a time work on neighbouring blocks.  Returns false for the padding.
+__device__ __forceinline__ bool xcd_block(int T, int& block, int& bh) {
+  const int per_xcd = (T + 7) >> 3, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  bh = slot / per_xcd;
+  block = xcd * per_xcd + (slot - bh * per_xcd);
+  return block < T;
+}
+
+// Scores of one key tile, transposed: lane = query, registers = keys.
+__device__ __forceinline__ v16f score_tile(const unsigned char* ktile, const uint4 (&qf)[8], int l32, int hf) {
   v16f s = v16f{};
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) s = mfma_bf16(kn_tile[ks * 64 + lane], qf[ks], s);
+  for (int ks = 0; ks < 8; ++ks) s = mfma_bf16(n_op(ktile, l32, hf, ks), qf[ks], s);
   return s;
 }
 
 // lse2[bh][32 T + r], delta[bh][32 T + r] for every token row of every query tile (rows beyond N:
 // lse2 = +inf, delta = 0, so that their P is exactly 0 wherever they are used).
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) bwd_stats_kernel(const uint4* __restrict__ qn, const uint4* __restrict__ kn,
-                                                            const uint4* __restrict__ vt, const bf16_t* __restrict__ dout,
+__global__ void __launch_bounds__(NW * 64) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                            const bf16_t* __restrict__ v, const bf16_t* __restrict__ dout,
                                                             const int32_t* __restrict__ crit, float* __restrict__ lse2,
                                                             float* __restrict__ delta, BwdDims dm) {
-  __shared__ uint4 lds[2 * 2 * REC_CHUNKS];  // Kn then Vt of the current key block
-  const int i = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE_B];  // K (2 tiles) then V (2 tiles) of the current key block
+  int i, bh;
+  if (!xcd_block(dm.Tq, i, bh)) return;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tr_off = tr_lane_offset(lane);
   const int T = i * NW + w;
-  const long long q = 32ll * T + l32;
-  const bool qok = q < dm.N;
+  const long long qrow = 32ll * T + l32;
+  const bool qok = qrow < dm.N;
+  const size_t head = (size_t)bh * dm.N * D;
   uint4 qf[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) qf[ks] = qn[((size_t)bh * dm.T32q + T) * REC_CHUNKS + ks * 64 + lane];
+  own_rows(q + head, qrow, dm.N, hf, qf);
   const int32_t* crow = crit + ((size_t)bh * dm.Tq + i) * dm.n_c;
-  const uint4* const srcs[2] = {kn, vt};
-  KeyStage<NW, 2> st;
+  RowStage<NW * 64, 64> sk, sv;
   v16f o[4];
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) o[ct] = v16f{};
   float m = -INFINITY, lsum = 0.f;
-  if (dm.n_c > 0) st.load(srcs, ((size_t)bh * dm.T32k + 2 * crow[0]) * REC_CHUNKS, t);
+  if (dm.n_c > 0) {
+    sk.load(k + head, 64ll * crow[0], dm.N, t);
+    sv.load(v + head, 64ll * crow[0], dm.N, t);
+  }
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
     __syncthreads();
-    st.store(lds, t);
+    sk.store(lds, t);
+    sv.store(lds + 2 * TILE_B, t);
     __syncthreads();
-    if (b + 1 < dm.n_c) st.load(srcs, ((size_t)bh * dm.T32k + 2 * crow[b + 1]) * REC_CHUNKS, t);
+    if (b + 1 < dm.n_c) {
+      sk.load(k + head, 64ll * crow[b + 1], dm.N, t);
+      sv.load(v + head, 64ll * crow[b + 1], dm.N, t);
+    }
     v16f s[2];
     float mx = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
-      s[kt] = score_tile(lds + kt * REC_CHUNKS, qf, lane);
+      s[kt] = score_tile(lds + kt * TILE_B, qf, l32, hf);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -166,21 +183,19 @@ __global__ void __launch_bounds__(NW * 64) bwd_stats_kernel(const uint4* __restr
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[ct][r] *= alpha;
-    const uint4* vtl = lds + 2 * REC_CHUNKS;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int sidx = 0; sidx < 2; ++sidx) {
-        const uint4 pb = acc_operand(s[kt], sidx);
+      for (int sx = 0; sx < 2; ++sx) {
+        const uint4 pb = acc_operand(s[kt], sx);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-          o[ct] = mfma_bf16(vtl[kt * REC_CHUNKS + (ct * 2 + sidx) * 64 + lane], pb, o[ct]);
+        for (int ct = 0; ct < 4; ++ct) o[ct] = mfma_bf16(t_op(lds + (2 + kt) * TILE_B, tr_off, ct, sx), pb, o[ct]);
       }
   }
   const float l = lsum + partner_f32(lsum);
   float dl = 0.f;
   if (qok && dm.n_c > 0) {
-    const bf16_t* drow = dout + ((size_t)bh * dm.N + q) * D;
+    const bf16_t* drow = dout + head + qrow * D;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -209,46 +224,51 @@ __device__ __forceinline__ void store_grad4(bf16_t* dst, const float* lin, float
 }
 
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) bwd_dq_kernel(const uint4* __restrict__ qn, const uint4* __restrict__ don,
-                                                         const uint4* __restrict__ kn, const uint4* __restrict__ ktr,
-                                                         const uint4* __restrict__ vn, const int32_t* __restrict__ crit,
-                                                         const float* __restrict__ lse2, const float* __restrict__ delta,
-                                                         const float* __restrict__ dq_lin, bf16_t* __restrict__ dq,
-                                                         BwdDims dm) {
-  __shared__ uint4 lds[3 * 2 * REC_CHUNKS];  // Kn, Kt, Vn of the current key block
-  const int i = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+__global__ void __launch_bounds__(NW * 64) bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
+                                                         const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+                                                         const int32_t* __restrict__ crit, const float* __restrict__ lse2,
+                                                         const float* __restrict__ delta, const float* __restrict__ dq_lin,
+                                                         bf16_t* __restrict__ dq, BwdDims dm) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE_B];  // K (2 tiles) then V (2 tiles) of the current key block
+  int i, bh;
+  if (!xcd_block(dm.Tq, i, bh)) return;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tr_off = tr_lane_offset(lane);
   const int T = i * NW + w;
-  const long long q = 32ll * T + l32;
+  const long long qrow = 32ll * T + l32;
+  const size_t head = (size_t)bh * dm.N * D;
   uint4 qf[8], dof[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    qf[ks] = qn[((size_t)bh * dm.T32q + T) * REC_CHUNKS + ks * 64 + lane];
-    dof[ks] = don[((size_t)bh * dm.T32q + T) * REC_CHUNKS + ks * 64 + lane];
-  }
+  own_rows(q + head, qrow, dm.N, hf, qf);
+  own_rows(dout + head, qrow, dm.N, hf, dof);
   const size_t sidx = (size_t)bh * dm.T32q * 32 + 32 * T + l32;
   const float lse_q = lse2[sidx], delta_q = delta[sidx];
   const int32_t* crow = crit + ((size_t)bh * dm.Tq + i) * dm.n_c;
-  const uint4* const srcs[3] = {kn, ktr, vn};
-  KeyStage<NW, 3> st;
+  RowStage<NW * 64, 64> sk, sv;
   v16f acc[4];
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
-  if (dm.n_c > 0) st.load(srcs, ((size_t)bh * dm.T32k + 2 * crow[0]) * REC_CHUNKS, t);
+  if (dm.n_c > 0) {
+    sk.load(k + head, 64ll * crow[0], dm.N, t);
+    sv.load(v + head, 64ll * crow[0], dm.N, t);
+  }
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
     __syncthreads();
-    st.store(lds, t);
+    sk.store(lds, t);
+    sv.store(lds + 2 * TILE_B, t);
     __syncthreads();
-    if (b + 1 < dm.n_c) st.load(srcs, ((size_t)bh * dm.T32k + 2 * crow[b + 1]) * REC_CHUNKS, t);
-    const uint4* knl = lds;
-    const uint4* ktl = lds + 2 * REC_CHUNKS;
-    const uint4* vnl = lds + 4 * REC_CHUNKS;
+    if (b + 1 < dm.n_c) {
+      sk.load(k + head, 64ll * crow[b + 1], dm.N, t);
+      sv.load(v + head, 64ll * crow[b + 1], dm.N, t);
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
-      v16f s = score_tile(knl + kt * REC_CHUNKS, qf, lane);
+      const unsigned char* ktile = lds + kt * TILE_B;
+      const unsigned char* vtile = lds + (2 + kt) * TILE_B;
+      v16f s = score_tile(ktile, qf, l32, hf);
       v16f dp = v16f{};
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) dp = mfma_bf16(vnl[kt * REC_CHUNKS + ks * 64 + lane], dof[ks], dp);
+      for (int ks = 0; ks < 8; ++ks) dp = mfma_bf16(n_op(vtile, l32, hf, ks), dof[ks], dp);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -259,13 +279,12 @@ __global__ void __launch_bounds__(NW * 64) bwd_dq_kernel(const uint4* __restrict
       for (int sx = 0; sx < 2; ++sx) {
         const uint4 dsb = acc_operand(s, sx);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-          acc[ct] = mfma_bf16(ktl[kt * REC_CHUNKS + (ct * 2 + sx) * 64 + lane], dsb, acc[ct]);
+        for (int ct = 0; ct < 4; ++ct) acc[ct] = mfma_bf16(t_op(ktile, tr_off, ct, sx), dsb, acc[ct]);
       }
     }
   }
-  if (q < dm.N) {
-    const size_t row = ((size_t)bh * dm.N + q) * D;
+  if (qrow < dm.N) {
+    const size_t row = head + qrow * D;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -277,43 +296,51 @@ __global__ void __launch_bounds__(NW * 64) bwd_dq_kernel(const uint4* __restrict
   }
 }
 
-// One workgroup of two wavefronts per key block; wavefront w owns key tile 2 j + w (one key per
-// lane pair).  The query blocks that hold block j as critical are found from the mask column.
-constexpr int DKV_MAX_TQ = 8192;
-__global__ void __launch_bounds__(128) bwd_dkv_kernel(const uint4* __restrict__ qn, const uint4* __restrict__ qtr,
-                                                      const uint4* __restrict__ don, const uint4* __restrict__ dotr,
-                                                      const uint4* __restrict__ kn, const uint4* __restrict__ vn,
+// One workgroup of four wavefronts per PAIR of adjacent key blocks (2 J, 2 J + 1): wavefronts 0, 1
+// own the two key tiles of the first block, wavefronts 2, 3 those of the second (one key per lane
+// pair).  The workgroup walks over the query blocks that hold either block as critical (found from
+// the two mask columns; two flag bits per entry), staging each query tile's Q and dO once for both;
+// a wavefront whose block is not critical for the current query block sits the step out.
+__global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
+                                                      const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
                                                       const float* __restrict__ delta, const float* __restrict__ dk_lin,
                                                       const float* __restrict__ dv_lin, bf16_t* __restrict__ dk,
                                                       bf16_t* __restrict__ dv, int tiles_per_qblock, BwdDims dm) {
-  __shared__ uint4 lds[4 * REC_CHUNKS];  // Qn, Qt, dOn, dOt of the current query tile
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TILE_B];  // Q then dO of the current query tile
   __shared__ __attribute__((aligned(16))) float stat[2][32];
-  __shared__ unsigned short qlist[DKV_MAX_TQ];
-  __shared__ int wcnt[2];
-  const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
-  // ---- the query blocks of this key block, ascending
+  __shared__ unsigned short qlist[8192];
+  __shared__ int wcnt[4];
+  int J, bh;
+  if (!xcd_block((dm.Tk + 1) >> 1, J, bh)) return;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
+  const int tr_off = tr_lane_offset(lane);
+  const int half = w >> 1;
+  // ---- the query blocks of the two key blocks, ascending; bit 14 / 15 = first / second block has it
   int nq = 0;
-  for (int base = 0; base < dm.Tq; base += 128) {
+  const bool has2 = 2 * J + 1 < dm.Tk;
+  for (int base = 0; base < dm.Tq; base += 256) {
     const int i = base + t;
-    const bool hit = i < dm.Tq && mask[((size_t)bh * dm.Tq + i) * dm.Tk + j] == 1;
-    const unsigned long long bal = __ballot(hit);
+    int fl = 0;
+    if (i < dm.Tq) {
+      const int8_t* mrow = mask + ((size_t)bh * dm.Tq + i) * dm.Tk + 2 * J;
+      fl = (mrow[0] == 1 ? 1 : 0) | (has2 && mrow[1] == 1 ? 2 : 0);
+    }
+    const unsigned long long bal = __ballot(fl != 0);
     if (lane == 0) wcnt[w] = __popcll(bal);
     __syncthreads();
-    const int off = nq + (w ? wcnt[0] : 0) + __popcll(bal & ((1ull << lane) - 1ull));
-    if (hit) qlist[off] = (unsigned short)i;
-    nq += wcnt[0] + wcnt[1];
+    int off = nq + __popcll(bal & ((1ull << lane) - 1ull));
+    for (int x = 0; x < w; ++x) off += wcnt[x];
+    if (fl) qlist[off] = (unsigned short)(i | (fl << 14));
+    nq += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
     __syncthreads();
   }
-  const int Tkey = 2 * j + w;
-  const long long key = 32ll * Tkey + l32;
+  const size_t head = (size_t)bh * dm.N * D;
+  const long long key = 64ll * (2 * J + half) + 32 * (w & 1) + l32;
   const bool kok = key < dm.N;
   uint4 kf[8], vf[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    kf[ks] = kn[((size_t)bh * dm.T32k + Tkey) * REC_CHUNKS + ks * 64 + lane];
-    vf[ks] = vn[((size_t)bh * dm.T32k + Tkey) * REC_CHUNKS + ks * 64 + lane];
-  }
+  own_rows(k + head, key, dm.N, hf, kf);
+  own_rows(v + head, key, dm.N, hf, vf);
   v16f dkt[4], dvt[4];
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) {
@@ -321,33 +348,45 @@ __global__ void __launch_bounds__(128) bwd_dkv_kernel(const uint4* __restrict__ 
     dvt[ct] = v16f{};
   }
   const int steps = nq * tiles_per_qblock;
-  const uint4* const srcs[4] = {qn, qtr, don, dotr};
-  uint4 pf[16];
+  RowStage<256, 32> sq, sd;
   float pstat = 0.f;
-  auto load = [&](int step) {
-    const int T = qlist[step / tiles_per_qblock] * tiles_per_qblock + step % tiles_per_qblock;
-    const size_t rec0 = ((size_t)bh * dm.T32q + T) * REC_CHUNKS;
-#pragma unroll
-    for (int u = 0; u < 16; ++u) pf[u] = srcs[u >> 2][rec0 + (u & 3) * 128 + t];
-    if (t < 64) pstat = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T + (t & 31)];
-  };
-  if (steps > 0) load(0);
+  int T_next = 0, fl_next = 0;
+  if (steps > 0) {
+    const int e = qlist[0];
+    fl_next = e >> 14;
+    T_next = (e & 0x3fff) * tiles_per_qblock;
+    sq.load(q + head, 32ll * T_next, dm.N, t);
+    sd.load(dout + head, 32ll * T_next, dm.N, t);
+    if (t < 64) pstat = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T_next + (t & 31)];
+  }
+  int u_in = 0, e_idx = 0;  // tile within the query block, entry of the list (of the staged step)
   for (int step = 0; step < steps; ++step) {
+    const int fl = fl_next;
     __syncthreads();
-#pragma unroll
-    for (int u = 0; u < 16; ++u) lds[(u >> 2) * REC_CHUNKS + (u & 3) * 128 + t] = pf[u];
+    sq.store(lds, t);
+    sd.store(lds + TILE_B, t);
     if (t < 64) stat[t >> 5][t & 31] = pstat;
     __syncthreads();
-    if (step + 1 < steps) load(step + 1);
-    const uint4* qnl = lds;
-    const uint4* qtl = lds + REC_CHUNKS;
-    const uint4* donl = lds + 2 * REC_CHUNKS;
-    const uint4* dotl = lds + 3 * REC_CHUNKS;
+    if (step + 1 < steps) {
+      if (++u_in == tiles_per_qblock) {
+        u_in = 0;
+        ++e_idx;
+      }
+      const int e = qlist[e_idx];
+      fl_next = e >> 14;
+      T_next = (e & 0x3fff) * tiles_per_qblock + u_in;
+      sq.load(q + head, 32ll * T_next, dm.N, t);
+      sd.load(dout + head, 32ll * T_next, dm.N, t);
+      if (t < 64) pstat = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T_next + (t & 31)];
+    }
+    if (!((fl >> half) & 1)) continue;  // (wave-uniform; the barriers are at the top of the loop)
+    const unsigned char* qtile = lds;
+    const unsigned char* dtile = lds + TILE_B;
     v16f s = v16f{}, dp = v16f{};
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      s = mfma_bf16(qnl[ks * 64 + lane], kf[ks], s);
-      dp = mfma_bf16(donl[ks * 64 + lane], vf[ks], dp);
+      s = mfma_bf16(n_op(qtile, l32, hf, ks), kf[ks], s);
+      dp = mfma_bf16(n_op(dtile, l32, hf, ks), vf[ks], dp);
     }
     v16f p;
 #pragma unroll
@@ -367,13 +406,13 @@ __global__ void __launch_bounds__(128) bwd_dkv_kernel(const uint4* __restrict__ 
       const uint4 pb = acc_operand(p, sx), dsb = acc_operand(s, sx);
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        dvt[ct] = mfma_bf16(dotl[(ct * 2 + sx) * 64 + lane], pb, dvt[ct]);
-        dkt[ct] = mfma_bf16(qtl[(ct * 2 + sx) * 64 + lane], dsb, dkt[ct]);
+        dvt[ct] = mfma_bf16(t_op(dtile, tr_off, ct, sx), pb, dvt[ct]);
+        dkt[ct] = mfma_bf16(t_op(qtile, tr_off, ct, sx), dsb, dkt[ct]);
       }
     }
   }
   if (kok) {
-    const size_t row = ((size_t)bh * dm.N + key) * D;
+    const size_t row = head + key * D;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -388,40 +427,37 @@ __global__ void __launch_bounds__(128) bwd_dkv_kernel(const uint4* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-void launch_bwd_pack(const void* x, const Layout& L, const Problem& p, int T32, uint4* nrec, uint4* trec,
-                     hipStream_t stream) {
-  bwd_pack_kernel<<<dim3((unsigned)T32, (unsigned)p.BH), 64, 0, stream>>>((const bf16_t*)x, L, p.H, p.N, T32, nrec, trec);
-}
+static BwdDims bwd_dims(const Problem& p) { return BwdDims{p.N, p.Tq, p.Tk, p.n_c, p.Tq * (p.block_q / 32)}; }
 
-static BwdDims bwd_dims(const Problem& p) {
-  return BwdDims{p.N, p.Tq, p.Tk, p.n_c, p.Tq * (p.block_q / 32), p.Tk * 2};
-}
-
-void launch_bwd_stats(const Problem& p, const uint4* qn, const uint4* kn, const uint4* vt, const void* dout,
+void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
                       const int32_t* crit, float* lse2, float* delta, hipStream_t stream) {
-  const dim3 grid((unsigned)p.Tq, (unsigned)p.BH);
+  const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   if (p.block_q == 128)
-    bwd_stats_kernel<4><<<grid, 256, 0, stream>>>(qn, kn, vt, (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p));
+    bwd_stats_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
+                                                   crit, lse2, delta, bwd_dims(p));
   else
-    bwd_stats_kernel<2><<<grid, 128, 0, stream>>>(qn, kn, vt, (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p));
+    bwd_stats_kernel<2><<<grid, 128, 0, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
+                                                   crit, lse2, delta, bwd_dims(p));
 }
 
-void launch_bwd_dq(const Problem& p, const uint4* qn, const uint4* don, const uint4* kn, const uint4* ktr,
-                   const uint4* vn, const int32_t* crit, const float* lse2, const float* delta, const float* dq_lin,
-                   void* dq, hipStream_t stream) {
-  const dim3 grid((unsigned)p.Tq, (unsigned)p.BH);
+void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
+                   const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream) {
+  const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   if (p.block_q == 128)
-    bwd_dq_kernel<4><<<grid, 256, 0, stream>>>(qn, don, kn, ktr, vn, crit, lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
+    bwd_dq_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
+                                                lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
   else
-    bwd_dq_kernel<2><<<grid, 128, 0, stream>>>(qn, don, kn, ktr, vn, crit, lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
+    bwd_dq_kernel<2><<<grid, 128, 0, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
+                                                lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
 }
 
-void launch_bwd_dkv(const Problem& p, const uint4* qn, const uint4* qtr, const uint4* don, const uint4* dotr,
-                    const uint4* kn, const uint4* vn, const int8_t* mask, const float* lse2, const float* delta,
-                    const float* dk_lin, const float* dv_lin, void* dk, void* dv, hipStream_t stream) {
-  bwd_dkv_kernel<<<dim3((unsigned)p.Tk, (unsigned)p.BH), 128, 0, stream>>>(qn, qtr, don, dotr, kn, vn, mask, lse2, delta,
-                                                                         dk_lin, dv_lin, (bf16_t*)dk, (bf16_t*)dv,
-                                                                         p.block_q / 32, bwd_dims(p));
+void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+                    const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
+                    hipStream_t stream) {
+  const int pairs = (p.Tk + 1) / 2;
+  bwd_dkv_kernel<<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, 0, stream>>>(
+      (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
+      (bf16_t*)dk, (bf16_t*)dv, p.block_q / 32, bwd_dims(p));
 }
 
 }  // namespace sla
