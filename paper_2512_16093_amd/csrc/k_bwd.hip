@@ -119,7 +119,7 @@ __device__ __forceinline__ v16f score_tile(const unsigned char* ktile, const uin
 // lse2[bh][32 T + r], delta[bh][32 T + r] for every token row of every query tile (rows beyond N:
 // lse2 = +inf, delta = 0, so that their P is exactly 0 wherever they are used).
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, const bf16_t* __restrict__ dout,
                                                             const int32_t* __restrict__ crit, float* __restrict__ lse2,
                                                             float* __restrict__ delta, BwdDims dm) {
@@ -224,7 +224,7 @@ __device__ __forceinline__ void store_grad4(bf16_t* dst, const float* lin, float
 }
 
 template <int NW>
-__global__ void __launch_bounds__(NW * 64) bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
+__global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
                                                          const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                          const int32_t* __restrict__ crit, const float* __restrict__ lse2,
                                                          const float* __restrict__ delta, const float* __restrict__ dq_lin,
@@ -306,9 +306,9 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
                                                       const float* __restrict__ delta, const float* __restrict__ dk_lin,
                                                       const float* __restrict__ dv_lin, bf16_t* __restrict__ dk,
-                                                      bf16_t* __restrict__ dv, int tiles_per_qblock, BwdDims dm) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * TILE_B];  // Q then dO of the current query tile
-  __shared__ __attribute__((aligned(16))) float stat[2][32];
+                                                      bf16_t* __restrict__ dv, int tile_shift, BwdDims dm) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * 2 * TILE_B];  // two buffers of: Q then dO of a query tile
+  __shared__ __attribute__((aligned(16))) float stat[2][2][32];             // and its lse, delta
   __shared__ unsigned short qlist[8192];
   __shared__ int wcnt[4];
   int J, bh;
@@ -347,41 +347,30 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
     dkt[ct] = v16f{};
     dvt[ct] = v16f{};
   }
-  const int steps = nq * tiles_per_qblock;
-  RowStage<256, 32> sq, sd;
-  float pstat = 0.f;
-  int T_next = 0, fl_next = 0;
-  if (steps > 0) {
-    const int e = qlist[0];
-    fl_next = e >> 14;
-    T_next = (e & 0x3fff) * tiles_per_qblock;
-    sq.load(q + head, 32ll * T_next, dm.N, t);
-    sd.load(dout + head, 32ll * T_next, dm.N, t);
-    if (t < 64) pstat = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T_next + (t & 31)];
+  // Steps = (list entry, tile of its query block).  Tiles travel memory -> registers -> LDS two steps
+  // ahead: while step s is computed from one LDS buffer, step s + 1 waits in registers for the other
+  // buffer and step s + 2 is being loaded; one barrier per step.
+  const int steps = nq << tile_shift, tile_mask = (1 << tile_shift) - 1;
+  RowStage<256, 32> sqa, sda, sqb, sdb;
+  float psa = 0.f, psb = 0.f;
+  auto tile_of = [&](int step) { return ((qlist[step >> tile_shift] & 0x3fff) << tile_shift) + (step & tile_mask); };
+#define DKV_LOAD(SQ, SD, PS, STEP)                                                                   \
+  if ((STEP) < steps) {                                                                              \
+    const int T_ = tile_of(STEP);                                                                    \
+    SQ.load(q + head, 32ll * T_, dm.N, t);                                                           \
+    SD.load(dout + head, 32ll * T_, dm.N, t);                                                        \
+    if (t < 64) PS = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T_ + (t & 31)];        \
   }
-  int u_in = 0, e_idx = 0;  // tile within the query block, entry of the list (of the staged step)
-  for (int step = 0; step < steps; ++step) {
-    const int fl = fl_next;
-    __syncthreads();
-    sq.store(lds, t);
-    sd.store(lds + TILE_B, t);
-    if (t < 64) stat[t >> 5][t & 31] = pstat;
-    __syncthreads();
-    if (step + 1 < steps) {
-      if (++u_in == tiles_per_qblock) {
-        u_in = 0;
-        ++e_idx;
-      }
-      const int e = qlist[e_idx];
-      fl_next = e >> 14;
-      T_next = (e & 0x3fff) * tiles_per_qblock + u_in;
-      sq.load(q + head, 32ll * T_next, dm.N, t);
-      sd.load(dout + head, 32ll * T_next, dm.N, t);
-      if (t < 64) pstat = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T_next + (t & 31)];
-    }
-    if (!((fl >> half) & 1)) continue;  // (wave-uniform; the barriers are at the top of the loop)
-    const unsigned char* qtile = lds;
-    const unsigned char* dtile = lds + TILE_B;
+#define DKV_STORE(SQ, SD, PS, BUF)                                                                   \
+  {                                                                                                  \
+    SQ.store(lds + (BUF) * 2 * TILE_B, t);                                                           \
+    SD.store(lds + (BUF) * 2 * TILE_B + TILE_B, t);                                                  \
+    if (t < 64) stat[BUF][t >> 5][t & 31] = PS;                                                      \
+  }
+  auto compute = [&](int step, int buf) {
+    if (!((qlist[step >> tile_shift] >> (14 + half)) & 1)) return;  // (wave-uniform)
+    const unsigned char* qtile = lds + buf * 2 * TILE_B;
+    const unsigned char* dtile = qtile + TILE_B;
     v16f s = v16f{}, dp = v16f{};
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
@@ -391,8 +380,8 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
     v16f p;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const float4 ls = *(const float4*)&stat[0][8 * g + 4 * hf];
-      const float4 dl = *(const float4*)&stat[1][8 * g + 4 * hf];
+      const float4 ls = *(const float4*)&stat[buf][0][8 * g + 4 * hf];
+      const float4 dl = *(const float4*)&stat[buf][1][8 * g + 4 * hf];
       const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -410,7 +399,24 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
         dkt[ct] = mfma_bf16(t_op(qtile, tr_off, ct, sx), dsb, dkt[ct]);
       }
     }
+  };
+  DKV_LOAD(sqa, sda, psa, 0)
+  DKV_LOAD(sqb, sdb, psb, 1)
+  if (steps > 0) DKV_STORE(sqa, sda, psa, 0)
+  __syncthreads();
+  for (int step = 0; step < steps; step += 2) {
+    DKV_LOAD(sqa, sda, psa, step + 2)
+    compute(step, 0);
+    if (step + 1 < steps) DKV_STORE(sqb, sdb, psb, 1)
+    __syncthreads();
+    if (step + 1 >= steps) break;  // (uniform over the workgroup)
+    DKV_LOAD(sqb, sdb, psb, step + 3)
+    compute(step + 1, 1);
+    if (step + 2 < steps) DKV_STORE(sqa, sda, psa, 0)
+    __syncthreads();
   }
+#undef DKV_LOAD
+#undef DKV_STORE
   if (kok) {
     const size_t row = head + key * D;
 #pragma unroll
@@ -457,7 +463,7 @@ void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const voi
   const int pairs = (p.Tk + 1) / 2;
   bwd_dkv_kernel<<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, 0, stream>>>(
       (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
-      (bf16_t*)dk, (bf16_t*)dv, p.block_q / 32, bwd_dims(p));
+      (bf16_t*)dk, (bf16_t*)dv, p.block_q == 128 ? 2 : 1, bwd_dims(p));
 }
 
 }  // namespace sla
