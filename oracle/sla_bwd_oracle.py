@@ -41,16 +41,44 @@ def feature_map_grad(X, PX, dP, kind="softmax"):
     raise ValueError(kind)
 
 
-def sparse_branch_grad(Q, K, V, dO, mask, block_q, block_k):
+def _sample_plan(mask, value, q_blocks, k_blocks):
+    """Which query blocks a sampled evaluation has to visit: those asked for, plus every one whose
+    mask row holds `value` at one of the key blocks asked for.  None, None = all of them."""
+    if q_blocks is None and k_blocks is None:
+        return None
+    need = set(int(i) for i in (q_blocks or []))
+    for j in (k_blocks or []):
+        need.update(int(i) for i in np.flatnonzero(mask[:, j] == value))
+    return need
+
+
+def _keep_sampled(dQ, dK, dV, q_blocks, k_blocks, qs, ks):
+    """NaN everywhere except the sampled rows (a partial sum elsewhere is not a gradient)."""
+    keep_q, keep_k = np.zeros(dQ.shape[0], bool), np.zeros(dK.shape[0], bool)
+    for i in (q_blocks or []):
+        keep_q[qs[i]] = True
+    for j in (k_blocks or []):
+        keep_k[ks[j]] = True
+    dQ[~keep_q] = np.nan
+    dK[~keep_k] = np.nan
+    dV[~keep_k] = np.nan
+
+
+def sparse_branch_grad(Q, K, V, dO, mask, block_q, block_k, q_blocks=None, k_blocks=None):
     """Gradient of sparse_branch_exact: (dQ, dK, dV, lse, delta) with
     lse[n] = log sum_t exp(Q[n].K[t]/sqrt(d)) over the critical keys of n and
-    delta[n] = dO[n] . O^s[n] (the two per-row statistics a tiled backward keeps)."""
+    delta[n] = dO[n] . O^s[n] (the two per-row statistics a tiled backward keeps).
+    With q_blocks / k_blocks (lists) only dQ of those query blocks and dK, dV of those key blocks
+    are evaluated (the same steps, over the query blocks that contribute to them); the rest is NaN."""
     N, d = Q.shape
     qs, ks = so.block_slices(N, block_q), so.block_slices(N, block_k)
     dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
     lse, delta = np.full(N, -np.inf), np.zeros(N)
     scale = 1.0 / math.sqrt(d)
+    plan = _sample_plan(mask, 1, q_blocks, k_blocks)
     for i, rows in enumerate(qs):
+        if plan is not None and i not in plan:
+            continue
         crit = np.flatnonzero(mask[i] == 1)
         if crit.size == 0:
             continue
@@ -68,18 +96,24 @@ def sparse_branch_grad(Q, K, V, dO, mask, block_q, block_k):
         dQ[rows] += dS @ K[keys] * scale              # S = Q K^T / sqrt(d)
         np.add.at(dK, keys, dS.T @ Q[rows] * scale)
         np.add.at(dV, keys, P.T @ dO[rows])
+    if plan is not None:
+        _keep_sampled(dQ, dK, dV, q_blocks, k_blocks, qs, ks)
     return dQ, dK, dV, lse, delta
 
 
-def linear_branch_grad(Q, K, V, dOl, mask, block_q, block_k, phi="softmax"):
-    """Gradient of linear_branch for an upstream gradient dOl = dLoss/dO^l: (dQ, dK, dV)."""
+def linear_branch_grad(Q, K, V, dOl, mask, block_q, block_k, phi="softmax", q_blocks=None, k_blocks=None):
+    """Gradient of linear_branch for an upstream gradient dOl = dLoss/dO^l: (dQ, dK, dV);
+    q_blocks / k_blocks as in sparse_branch_grad."""
     N, d = Q.shape
     qs, ks = so.block_slices(N, block_q), so.block_slices(N, block_k)
     PQ, PK = so.feature_map(Q, phi), so.feature_map(K, phi)
     h, z = so.linear_summaries(K, V, block_k, phi)
     dh, dz = np.zeros_like(h), np.zeros_like(z)
     dPQ = np.zeros_like(PQ)
+    plan = _sample_plan(mask, 0, q_blocks, k_blocks)
     for i, rows in enumerate(qs):
+        if plan is not None and i not in plan:
+            continue
         marg = np.flatnonzero(mask[i] == 0)
         if marg.size == 0:
             continue                                   # O^l is the constant 0 there
@@ -98,31 +132,36 @@ def linear_branch_grad(Q, K, V, dOl, mask, block_q, block_k, phi="softmax"):
         dPK[rows] = V[rows] @ dh[j].T + dz[j][None, :]  # h_j = phi(K_j)^T V_j, z_j = column sums of phi(K_j)
         dV[rows] = PK[rows] @ dh[j]
     dK = feature_map_grad(K, PK, dPK, phi)
+    if plan is not None:
+        _keep_sampled(dQ, dK, dV, q_blocks, k_blocks, qs, ks)
     return dQ, dK, dV
 
 
 def sla_backward_head(Q, K, V, dO, mask, block_q, block_k, proj_w=None, has_bias=False, phi="softmax",
-                      linear=True):
+                      linear=True, q_blocks=None, k_blocks=None):
     """Backward of sla_forward_head(..., quant="none", mask=mask) for one (batch, head) slice.
 
     Returns a dict: dQ, dK, dV [N, d]; dW [d, d] and db [d] (zeros when the linear term is absent;
     dW is None when proj_w is None, db is None unless has_bias); lse, delta (sparse-branch row
-    statistics); o_linear (what dW contracts dO with)."""
+    statistics); o_linear (what dW contracts dO with).  With q_blocks / k_blocks: dQ of those query
+    blocks and dK, dV of those key blocks only (NaN elsewhere), no dW, db."""
     N, d = Q.shape
-    dQ, dK, dV, lse, delta = sparse_branch_grad(Q, K, V, dO, mask, block_q, block_k)
+    sampled = q_blocks is not None or k_blocks is not None
+    dQ, dK, dV, lse, delta = sparse_branch_grad(Q, K, V, dO, mask, block_q, block_k, q_blocks, k_blocks)
     out = {"lse": lse, "delta": delta, "dW": None, "db": None, "o_linear": None}
     if linear and bool((mask == 0).any()):
-        Ol = so.linear_branch(Q, K, V, mask, block_q, block_k, phi)
         W = None if proj_w is None else np.asarray(proj_w, dtype=np.float64)
         dOl = dO if W is None else dO @ W              # term = O^l W^T (+ b)
-        if W is not None:
-            out["dW"] = dO.T @ Ol
-        if has_bias:
-            out["db"] = dO.sum(axis=0)
-        lq, lk, lv = linear_branch_grad(Q, K, V, dOl, mask, block_q, block_k, phi)
+        if not sampled:
+            Ol = so.linear_branch(Q, K, V, mask, block_q, block_k, phi)
+            if W is not None:
+                out["dW"] = dO.T @ Ol
+            if has_bias:
+                out["db"] = dO.sum(axis=0)
+            out["o_linear"] = Ol
+        lq, lk, lv = linear_branch_grad(Q, K, V, dOl, mask, block_q, block_k, phi, q_blocks, k_blocks)
         dQ, dK, dV = dQ + lq, dK + lk, dV + lv
-        out["o_linear"] = Ol
-    else:
+    elif not sampled:
         if proj_w is not None:
             out["dW"] = np.zeros((d, d))
         if has_bias:

@@ -50,3 +50,51 @@ def test_named_config_sampled_parity(cfg_id, heads):
             err, cos = pu.check_output(oh[rows], r["out"][rows], "%s head %d block %d" % (cfg.name, h, i))
             worst, cmin = max(worst, err), min(cmin, cos)
     print("%s: sampled max-abs %.3e, min cosine %.6f, tie-excused mask entries %d" % (cfg.name, worst, cmin, nbad))
+
+
+@pytest.mark.parametrize("cfg_id,head", [(1, 7), (4, 23), (6, 2)])
+def test_named_config_backward_sampled_parity(cfg_id, head):
+    """sla_attention_bwd at the full size the benchmark times: dQ of sampled query blocks and dK, dV of
+    sampled key blocks (first, middle, ragged last) of one head against the gradient oracle's sampled
+    evaluation on the library's own mask; every output finite.  Tolerances as in test_gpu_bwd.py."""
+    from oracle import sla_bwd_oracle as bo
+    cfg = synth.CONFIGS[cfg_id]
+    print("config", cfg.name, "generating inputs", flush=True)
+    q, k, v = pu.make_qkv_threaded(cfg)
+    dout = v.flip(1).flip(2).contiguous()            # an upstream gradient with V's statistics
+    W = synth.make_proj(cfg)
+    qd, kd, vd, dd = pu.to_dev(q, k, v, dout)
+    Wd = None if W is None else W.cuda()
+    print("running GPU backward", flush=True)
+    dq, dk, dv, dw, db = sla.sla_attention_bwd(qd, kd, vd, dd, cfg.block_q, cfg.block_k, cfg.topk_ratio,
+                                               cfg.marginal_ratio, proj_w=Wd, want_dw=Wd is not None,
+                                               want_db=Wd is not None)
+    mask = sla.sla_classify_blocks(qd, kd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                                   want_scores=False)[0][0, head].cpu().numpy()
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv, dw, db):
+        assert t is None or torch.isfinite(t.float()).all()
+    if db is not None and cfg.marginal_ratio > 0:    # the bias gradient has a closed form: the sum of dO
+        ref_b = dout.double().sum(dim=(0, 1, 2)).numpy()
+        assert np.abs(db.cpu().numpy() - ref_b).max() <= 1e-3 * np.abs(ref_b).max() + 1e-2
+    Tq, Tk, n_c, n_m = so.block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+    qb, kb = sorted({0, Tq // 2, Tq - 1}), sorted({0, Tk // 2, Tk - 1})
+    print("oracle on head", head, flush=True)
+    r = bo.sla_backward_head(synth.as_f64(q[0, head]), synth.as_f64(k[0, head]), synth.as_f64(v[0, head]),
+                             synth.as_f64(dout[0, head]), mask, cfg.block_q, cfg.block_k,
+                             proj_w=None if W is None else synth.as_f64(W), has_bias=W is not None,
+                             q_blocks=qb, k_blocks=kb)
+    worst = 0.0
+    for name, got, blocks, size in (("dQ", dq, qb, cfg.block_q), ("dK", dk, kb, cfg.block_k), ("dV", dv, kb, cfg.block_k)):
+        g = got[0, head].float().cpu().numpy().astype(np.float64)
+        scale = np.nanmax(np.abs(r[name]))
+        for i in blocks:
+            rows = slice(i * size, min((i + 1) * size, cfg.N))
+            ref = r[name][rows]
+            assert np.isfinite(ref).all()
+            err = np.abs(g[rows] - ref).max() / scale
+            fro = np.linalg.norm(g[rows] - ref) / np.linalg.norm(ref)
+            cos = float((g[rows] * ref).sum() / np.linalg.norm(g[rows]) / np.linalg.norm(ref))
+            worst = max(worst, fro)
+            assert err <= 3e-2 and fro <= 1e-2 and cos >= 0.999, (cfg.name, name, i, err, fro, cos)
+    print("%s backward: worst sampled relative Frobenius error %.3e" % (cfg.name, worst))

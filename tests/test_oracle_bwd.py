@@ -174,3 +174,24 @@ def test_a_planted_mistake_is_caught():
         P /= P.sum(axis=1, keepdims=True)
         bad[rows] = (P * (dO[rows] @ V[keys].T)) @ K[keys] / math.sqrt(d)
     assert abs(fd - (bad * p).sum()) > 1e-3 * max(1.0, abs(fd))
+
+
+def test_sampled_evaluation_equals_the_full_one_on_the_sampled_blocks():
+    N, d, bq, bk = 90, 8, 8, 4
+    Q, K, V, dO, mask, W, b = _case(N, d, bq, bk, 0.25, 0.5, 8)
+    full = bo.sla_backward_head(Q, K, V, dO, mask, bq, bk, proj_w=W, has_bias=True)
+    qb, kb = [1, 7, 11], [0, 9, 22]                      # 11 and 22: the ragged last blocks
+    part = bo.sla_backward_head(Q, K, V, dO, mask, bq, bk, proj_w=W, has_bias=True, q_blocks=qb, k_blocks=kb)
+    qs, ks = so.block_slices(N, bq), so.block_slices(N, bk)
+    for i in range(len(qs)):
+        if i in qb:
+            assert np.allclose(part["dQ"][qs[i]], full["dQ"][qs[i]], rtol=1e-12, atol=1e-14)
+        else:
+            assert np.isnan(part["dQ"][qs[i]]).all()
+    for j in range(len(ks)):
+        for name in ("dK", "dV"):
+            if j in kb:
+                assert np.allclose(part[name][ks[j]], full[name][ks[j]], rtol=1e-12, atol=1e-14)
+            else:
+                assert np.isnan(part[name][ks[j]]).all()
+    assert part["dW"] is None and part["db"] is None
