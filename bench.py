@@ -66,6 +66,17 @@ def parse():
     return ap.parse_args()
 
 
+def copy_calibration(torch, dev):
+    """Three plain 1 GiB device copies (1 GiB read, 1 GiB written each): a kernel of known traffic
+    for scaling the FETCH_SIZE / WRITE_SIZE counters of the same run."""
+    a = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    del a, b
+
+
 def make_inputs(cfg, synth, torch):
     """All heads of the seeded config, generated on the host (threaded over heads), then uploaded."""
     shape = (cfg.B, cfg.H, cfg.N, cfg.d)
@@ -254,6 +265,8 @@ def main_bwd(args):
         return sla.sla_attention_bwd(qd, kd, vd, dd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
                                      proj_w=Wd, want_dw=Wd is not None, want_db=Wd is not None, workspace=ws, grads=grads)
 
+    if args.copy_calibration:
+        copy_calibration(torch, dev)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -303,14 +316,19 @@ def main_bwd(args):
             cores = os.cpu_count() or 1
         # the oracle works head by head on the whole sequence; a shorter sequence of the same
         # statistics (the first Ns tokens of head 0) is timed and scaled by the dense-equivalent work
-        Ns = 4096
-        Qs, Ks, Vs, Ds = (synth.as_f64(t[0, 0, :Ns]) for t in (q, k, v, dout))
-        Tq_s, Tk_s, nc_s, nm_s = so.block_counts(Ns, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
-        mask = so.classify(so.pooled_scores(Qs, Ks, cfg.block_q, cfg.block_k), nc_s, nm_s)
-        t0 = time.perf_counter()
-        bo.sla_backward_head(Qs, Ks, Vs, Ds, mask, cfg.block_q, cfg.block_k,
-                             proj_w=None if W is None else synth.as_f64(W), has_bias=W is not None)
-        t = time.perf_counter() - t0
+        # (a short probe first, then a length that fills the time budget)
+        def run(Ns):
+            Qs, Ks, Vs, Ds = (synth.as_f64(t[0, 0, :Ns]) for t in (q, k, v, dout))
+            Tq_s, Tk_s, nc_s, nm_s = so.block_counts(Ns, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+            mask = so.classify(so.pooled_scores(Qs, Ks, cfg.block_q, cfg.block_k), nc_s, nm_s)
+            t0 = time.perf_counter()
+            bo.sla_backward_head(Qs, Ks, Vs, Ds, mask, cfg.block_q, cfg.block_k,
+                                 proj_w=None if W is None else synth.as_f64(W), has_bias=W is not None)
+            return time.perf_counter() - t0
+
+        t_probe = run(4096)
+        Ns = int(min(cfg.N, 4096 * max(1.0, args.cpu_seconds / max(t_probe, 1e-3)) ** 0.5)) // 128 * 128
+        t = run(Ns)
         full = t * cfg.B * cfg.H * (cfg.N / Ns) ** 2
         result["cpu_baseline"] = {"value": flops / full / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": int(cores),
                                   "kind": "oracle",
@@ -363,12 +381,7 @@ def main():
                                   proj_w=Wd, workspace=ws, out=out)
 
     if args.copy_calibration:
-        a = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        del a, b
+        copy_calibration(torch, dev)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

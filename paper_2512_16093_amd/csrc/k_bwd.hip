@@ -347,12 +347,13 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
     dkt[ct] = v16f{};
     dvt[ct] = v16f{};
   }
-  // Steps = (list entry, tile of its query block).  Tiles travel memory -> registers -> LDS two steps
-  // ahead: while step s is computed from one LDS buffer, step s + 1 waits in registers for the other
-  // buffer and step s + 2 is being loaded; one barrier per step.
+  // Steps = (list entry, tile of its query block).  Tiles travel memory -> registers -> LDS: while
+  // step s is computed from one LDS buffer, step s + 1 is moved from registers to the other buffer,
+  // and steps s + 2, s + 3 are on their way from memory in two more register sets (four sets in
+  // rotation); one barrier per step.
   const int steps = nq << tile_shift, tile_mask = (1 << tile_shift) - 1;
-  RowStage<256, 32> sqa, sda, sqb, sdb;
-  float psa = 0.f, psb = 0.f;
+  RowStage<256, 32> sq0, sd0, sq1, sd1, sq2, sd2, sq3, sd3;
+  float ps0 = 0.f, ps1 = 0.f, ps2 = 0.f, ps3 = 0.f;
   auto tile_of = [&](int step) { return ((qlist[step >> tile_shift] & 0x3fff) << tile_shift) + (step & tile_mask); };
 #define DKV_LOAD(SQ, SD, PS, STEP)                                                                   \
   if ((STEP) < steps) {                                                                              \
@@ -400,21 +401,25 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
       }
     }
   };
-  DKV_LOAD(sqa, sda, psa, 0)
-  DKV_LOAD(sqb, sdb, psb, 1)
-  if (steps > 0) DKV_STORE(sqa, sda, psa, 0)
+  DKV_LOAD(sq0, sd0, ps0, 0)
+  DKV_LOAD(sq1, sd1, ps1, 1)
+  DKV_LOAD(sq2, sd2, ps2, 2)
+  if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
   __syncthreads();
-  for (int step = 0; step < steps; step += 2) {
-    DKV_LOAD(sqa, sda, psa, step + 2)
-    compute(step, 0);
-    if (step + 1 < steps) DKV_STORE(sqb, sdb, psb, 1)
-    __syncthreads();
-    if (step + 1 >= steps) break;  // (uniform over the workgroup)
-    DKV_LOAD(sqb, sdb, psb, step + 3)
-    compute(step + 1, 1);
-    if (step + 2 < steps) DKV_STORE(sqa, sda, psa, 0)
-    __syncthreads();
+  // one step: load step S + 3 into the set that step S - 1 has left, compute S, publish S + 1
+#define DKV_STEP(S, BUF, SQL, SDL, PSL, SQN, SDN, PSN)  \
+  if ((S) >= steps) break;                              \
+  DKV_LOAD(SQL, SDL, PSL, (S) + 3)                      \
+  compute((S), BUF);                                    \
+  if ((S) + 1 < steps) DKV_STORE(SQN, SDN, PSN, 1 - (BUF)) \
+  __syncthreads();
+  for (int step = 0;; step += 4) {  // (every exit test is uniform over the workgroup)
+    DKV_STEP(step, 0, sq3, sd3, ps3, sq1, sd1, ps1)
+    DKV_STEP(step + 1, 1, sq0, sd0, ps0, sq2, sd2, ps2)
+    DKV_STEP(step + 2, 0, sq1, sd1, ps1, sq3, sd3, ps3)
+    DKV_STEP(step + 3, 1, sq2, sd2, ps2, sq0, sd0, ps0)
   }
+#undef DKV_STEP
 #undef DKV_LOAD
 #undef DKV_STORE
   if (kok) {
