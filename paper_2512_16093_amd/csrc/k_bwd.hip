@@ -38,7 +38,8 @@ __device__ __forceinline__ uint4 acc_operand(const v16f& a, int s) {
                pack_bf16x2(a[8 * s + 4], a[8 * s + 5]), pack_bf16x2(a[8 * s + 6], a[8 * s + 7])};
 }
 
-constexpr int TP = 272;             // bytes per staged row: 256 of data + 16 of skew
+constexpr int TP = 304;             // bytes per staged row: 256 of data + 48 of skew (76 dwords: within a group of 16 lanes neither
+                                    // the 16-byte operand reads nor the transposing reads collide)
 constexpr int TILE_B = 32 * TP;     // one 32-token tile
 
 typedef short v4s __attribute__((ext_vector_type(4)));
