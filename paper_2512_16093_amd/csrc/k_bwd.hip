@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
                                                             const bf16_t* __restrict__ v, const bf16_t* __restrict__ dout,
                                                             const int32_t* __restrict__ crit, float* __restrict__ lse2,
                                                             float* __restrict__ delta, BwdDims dm) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE_B];  // K (2 tiles) then V (2 tiles) of the current key block
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];  // two buffers of: K (2 tiles) then V (2 tiles) of a key block
   int i, bh;
   if (!xcd_block(dm.Tq, i, bh)) return;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
@@ -141,16 +141,19 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) o[ct] = v16f{};
   float m = -INFINITY, lsum = 0.f;
+  // key blocks travel memory -> registers -> LDS one step ahead, into the buffer the step before
+  // last has left: one barrier per step
   if (dm.n_c > 0) {
     sk.load(k + head, 64ll * crow[0], dm.N, t);
     sv.load(v + head, 64ll * crow[0], dm.N, t);
+    sk.store(lds_all, t);
+    sv.store(lds_all + 2 * TILE_B, t);
   }
+  __syncthreads();
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
-    __syncthreads();
-    sk.store(lds, t);
-    sv.store(lds + 2 * TILE_B, t);
-    __syncthreads();
+    const unsigned char* lds = lds_all + (b & 1) * 4 * TILE_B;
+    unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
     if (b + 1 < dm.n_c) {
       sk.load(k + head, 64ll * crow[b + 1], dm.N, t);
       sv.load(v + head, 64ll * crow[b + 1], dm.N, t);
@@ -192,6 +195,11 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) o[ct] = mfma_bf16(t_op(lds + (2 + kt) * TILE_B, tr_off, ct, sx), pb, o[ct]);
       }
+    if (b + 1 < dm.n_c) {
+      sk.store(lds_next, t);
+      sv.store(lds_next + 2 * TILE_B, t);
+    }
+    __syncthreads();
   }
   const float l = lsum + partner_f32(lsum);
   float dl = 0.f;
@@ -230,7 +238,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
                                                          const int32_t* __restrict__ crit, const float* __restrict__ lse2,
                                                          const float* __restrict__ delta, const float* __restrict__ dq_lin,
                                                          bf16_t* __restrict__ dq, BwdDims dm) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[4 * TILE_B];  // K (2 tiles) then V (2 tiles) of the current key block
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];  // two buffers of: K (2 tiles) then V (2 tiles) of a key block
   int i, bh;
   if (!xcd_block(dm.Tq, i, bh)) return;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
@@ -251,13 +259,14 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
   if (dm.n_c > 0) {
     sk.load(k + head, 64ll * crow[0], dm.N, t);
     sv.load(v + head, 64ll * crow[0], dm.N, t);
+    sk.store(lds_all, t);
+    sv.store(lds_all + 2 * TILE_B, t);
   }
+  __syncthreads();
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
-    __syncthreads();
-    sk.store(lds, t);
-    sv.store(lds + 2 * TILE_B, t);
-    __syncthreads();
+    const unsigned char* lds = lds_all + (b & 1) * 4 * TILE_B;
+    unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
     if (b + 1 < dm.n_c) {
       sk.load(k + head, 64ll * crow[b + 1], dm.N, t);
       sv.load(v + head, 64ll * crow[b + 1], dm.N, t);
@@ -283,6 +292,11 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
         for (int ct = 0; ct < 4; ++ct) acc[ct] = mfma_bf16(t_op(ktile, tr_off, ct, sx), dsb, acc[ct]);
       }
     }
+    if (b + 1 < dm.n_c) {
+      sk.store(lds_next, t);
+      sv.store(lds_next + 2 * TILE_B, t);
+    }
+    __syncthreads();
   }
   if (qrow < dm.N) {
     const size_t row = head + qrow * D;
@@ -439,27 +453,37 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
+constexpr int KV_STAGE_BYTES = 2 * 4 * TILE_B;  // dynamic LDS of the two per-query-block kernels
+template <class K>
+static bool allow_lds(K kernel) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KV_STAGE_BYTES) == hipSuccess;
+}
+
 static BwdDims bwd_dims(const Problem& p) { return BwdDims{p.N, p.Tq, p.Tk, p.n_c, p.Tq * (p.block_q / 32)}; }
 
 void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
                       const int32_t* crit, float* lse2, float* delta, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
+  static const bool ok = allow_lds(bwd_stats_kernel<4>) && allow_lds(bwd_stats_kernel<2>);
+  if (!ok) return;  // (the launch below would fail the same way and be reported by the caller's status check)
   if (p.block_q == 128)
-    bwd_stats_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
+    bwd_stats_kernel<4><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
                                                    crit, lse2, delta, bwd_dims(p));
   else
-    bwd_stats_kernel<2><<<grid, 128, 0, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
+    bwd_stats_kernel<2><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
                                                    crit, lse2, delta, bwd_dims(p));
 }
 
 void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
+  static const bool ok = allow_lds(bwd_dq_kernel<4>) && allow_lds(bwd_dq_kernel<2>);
+  if (!ok) return;
   if (p.block_q == 128)
-    bwd_dq_kernel<4><<<grid, 256, 0, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
+    bwd_dq_kernel<4><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
   else
-    bwd_dq_kernel<2><<<grid, 128, 0, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
+    bwd_dq_kernel<2><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
 }
 
