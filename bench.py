@@ -58,6 +58,9 @@ def parse():
                          "shape; sla_bwd: the SLA backward pass (each a JSON line of its own metric)")
     ap.add_argument("--w8a8-shape", choices=tuple(W8A8_SHAPES), default="attn_proj",
                     help="which Linear layer of a Wan-14B block, on the 75600 tokens of a 720P clip")
+    ap.add_argument("--quant", choices=("int8fp8", "none"), default="int8fp8",
+                    help="sla workload: the paper's low-bit inference path (default) or the unquantised bf16 forward "
+                         "(plain SLA, the training-time operator)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget for the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -372,13 +375,16 @@ def main():
     ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, dev)
     Tq, Tk, n_c, n_m = sla.sla_block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
 
+    low_bit = args.quant == "int8fp8"
+    qmode = sla.QUANT_QK_INT8_PV_FP8 if low_bit else sla.QUANT_NONE
+
     def step():
         if args.layout == "bnhd":
             sla.sla_attention_fwd_strided(qd, kd, vd, out, cfg.block_q, cfg.block_k, cfg.topk_ratio,
-                                          cfg.marginal_ratio, proj_w=Wd, workspace=ws)
+                                          cfg.marginal_ratio, proj_w=Wd, workspace=ws, quant_mode=qmode)
         else:
             sla.sla_attention_fwd(qd, kd, vd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
-                                  proj_w=Wd, workspace=ws, out=out)
+                                  proj_w=Wd, workspace=ws, out=out, quant_mode=qmode)
 
     if args.copy_calibration:
         copy_calibration(torch, dev)
@@ -405,19 +411,22 @@ def main():
     ops = 2.0 * (2.0 * cfg.block_q * cfg.block_k * cfg.d) * pairs
     t_sparse = stage_ms[4] * 1e-3
     achieved = ops / t_sparse / 1e12
+    peak = PEAK_MFMA_8BIT_TOPS if low_bit else PEAK_MFMA_BF16_TFLOPS
     result = {
         "metric": "sla_fwd_dense_equiv_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int8/fp8-e4m3 (fp32 accumulate; bf16 linear branch)",
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8/fp8-e4m3 (fp32 accumulate; bf16 linear branch)" if low_bit else "bf16 (fp32 accumulate and softmax)",
         "data": "synthetic",
-        "config": {"workload": "%s: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0 layout=%s"
-                               % (cfg.name, cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio,
-                                  cfg.marginal_ratio, "[B,H,N,d]" if args.layout == "bhnd" else "[B,N,H,d]"),
+        "config": {"workload": "%s%s: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0 layout=%s"
+                               % (cfg.name, "" if low_bit else " unquantised", cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q,
+                                  cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                                  "[B,H,N,d]" if args.layout == "bhnd" else "[B,N,H,d]"),
                    "n_crit": n_c, "n_marg": n_m, "Tq": Tq, "Tk": Tk},
         "stage_ms": dict(zip(sla.STAGE_NAMES, [round(x, 4) for x in stage_ms])),
-        "roofline": {"kernel": "sparse_fwd_kernel", "bound": "mfma", "achieved": achieved,
-                     "peak": PEAK_MFMA_8BIT_TOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_8BIT_TOPS,
-                     "traffic": SPARSE_TRAFFIC_BYTES.get(cfg.cfg_id), "traffic_unit": "bytes per launch",
+        "roofline": {"kernel": "sparse_fwd_kernel" if low_bit else "bwd_stats_kernel<NW, true> (bf16 forward)",
+                     "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": SPARSE_TRAFFIC_BYTES.get(cfg.cfg_id) if low_bit else None, "traffic_unit": "bytes per launch",
                      "launch_ms": stage_ms[4], "ops_per_launch": ops},
         "context": "paper: 100-200x end-to-end, 184 s -> 1.9 s on one RTX 5090 (whole pipeline; no kernel-level number)",
     }

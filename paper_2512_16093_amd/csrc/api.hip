@@ -146,7 +146,7 @@ int sla_block_counts(int N, int block_q, int block_k, double topk_ratio, double 
 size_t sla_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k, double topk_ratio,
                            double marginal_ratio, int quant_mode) {
   Problem p;
-  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return 0;
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8 && quant_mode != SLA_QUANT_NONE) return 0;
   if (make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p) != SLA_OK) return 0;
   // the stage entry points take caller-chosen lists (up to every block critical or marginal)
   return make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m).total;
@@ -176,13 +176,37 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   if ((st = make_layout(v, v_strides, H, N, &p.lv)) != SLA_OK) return st;
   if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
-  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8 && quant_mode != SLA_QUANT_NONE) return SLA_ERR_UNSUPPORTED;
+  if (quant_mode == SLA_QUANT_NONE) {  // the 16-bit path takes contiguous [B,H,N,d] tensors only
+    const Layout c = contiguous_layout(H, N);
+    for (const Layout* L : {&p.lq, &p.lk, &p.lv, &p.lo})
+      if (L->sb != c.sb || L->sh != c.sh || L->sn != c.sn) return SLA_ERR_LAYOUT;
+  }
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   const bool lin = p.n_m > 0;
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
+  if (quant_mode == SLA_QUANT_NONE) {
+    mark(s, rec, 0);
+    run_stats(q, k, v, proj_w, p, ws, W, s);
+    mark(s, rec, 1);
+    launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
+    launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
+                  lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
+    mark(s, rec, 2);
+    if (lin)
+      launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
+                     at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+    mark(s, rec, 3);
+    if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+    mark(s, rec, 4);
+    launch_fwd_bf16(p, q, k, v, at<int32_t>(ws, W.crit), lin ? at<bf16_t>(ws, W.HZ) : nullptr, (const bf16_t*)proj_b,
+                    phi_kind, out, s);
+    mark(s, rec, 5);
+    return launch_status();
+  }
 
   mark(s, rec, 0);
   run_stats(q, k, v, proj_w, p, ws, W, s);

@@ -119,11 +119,21 @@ __device__ __forceinline__ v16f score_tile(const unsigned char* ktile, const uin
 
 // lse2[bh][32 T + r], delta[bh][32 T + r] for every token row of every query tile (rows beyond N:
 // lse2 = +inf, delta = 0, so that their P is exactly 0 wherever they are used).
-template <int NW>
+//
+// With FWD the same pass is the unquantised SLA forward (Section 1.2's training-time operator):
+// instead of the statistics it writes O = O^s + (phi(Q) H'_i) / (phi(Q) . Z_i) (+ b) in bf16, H'_i
+// being the projected summaries the forward pass accumulates.
+struct FwdEpilogue {
+  const bf16_t* HZ;    // [BH, Tq, HZ_ROWS, D] or nullptr (no marginal block: no linear term)
+  const bf16_t* bias;  // [D] or nullptr
+  bf16_t* out;         // [BH, N, D]
+  int phi;
+};
+template <int NW, bool FWD>
 __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, const bf16_t* __restrict__ dout,
                                                             const int32_t* __restrict__ crit, float* __restrict__ lse2,
-                                                            float* __restrict__ delta, BwdDims dm) {
+                                                            float* __restrict__ delta, BwdDims dm, FwdEpilogue fe) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];  // two buffers of: K (2 tiles) then V (2 tiles) of a key block
   int i, bh;
   if (!xcd_block(dm.Tq, i, bh)) return;
@@ -202,6 +212,87 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     __syncthreads();
   }
   const float l = lsum + partner_f32(lsum);
+  if constexpr (FWD) {
+    const float inv_l = dm.n_c > 0 ? 1.0f / l : 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[ct][r] *= inv_l;
+    if (fe.HZ) {
+      // linear term, transposed like everything else: O_l^T[o][n] = sum_c H'[c][o] phi(Q)[n][c]; the
+      // stored chunks of H' are this product's A operand, phi(Q) follows their channel order
+      const bf16_t* Hi = fe.HZ + ((size_t)bh * dm.Tq + i) * HZ_ELEMS;
+      float x[64];
+      uint4 bq[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const int c0 = 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1);
+        const uint4 qv = qok ? *(const uint4*)(q + head + qrow * D + c0) : uint4{0u, 0u, 0u, 0u};
+        x[8 * ks] = bf16_lo(qv.x); x[8 * ks + 1] = bf16_hi(qv.x); x[8 * ks + 2] = bf16_lo(qv.y); x[8 * ks + 3] = bf16_hi(qv.y);
+        x[8 * ks + 4] = bf16_lo(qv.z); x[8 * ks + 5] = bf16_hi(qv.z); x[8 * ks + 6] = bf16_lo(qv.w); x[8 * ks + 7] = bf16_hi(qv.w);
+      }
+      if (fe.phi == 0) {
+        float mx = x[0];
+#pragma unroll
+        for (int e = 1; e < 64; ++e) mx = fmaxf(mx, x[e]);
+        mx = fmaxf(mx, partner_f32(mx));
+        float sum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 64; ++e) {
+          x[e] = __builtin_amdgcn_exp2f((x[e] - mx) * LOG2E);
+          sum += x[e];
+        }
+        sum += partner_f32(sum);
+        const float inv = 1.0f / sum;
+#pragma unroll
+        for (int e = 0; e < 64; ++e) x[e] *= inv;
+      } else if (fe.phi == 1) {
+#pragma unroll
+        for (int e = 0; e < 64; ++e) x[e] = x[e] > 0.f ? x[e] + 1.0f : __builtin_amdgcn_exp2f(x[e] * LOG2E);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 64; ++e) x[e] = fmaxf(x[e], 0.f);
+      }
+      float den = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const int c0 = 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1);
+        const uint4 zv = *(const uint4*)(Hi + D * D + c0);
+        const float z[8] = {bf16_lo(zv.x), bf16_hi(zv.x), bf16_lo(zv.y), bf16_hi(zv.y),
+                            bf16_lo(zv.z), bf16_hi(zv.z), bf16_lo(zv.w), bf16_hi(zv.w)};
+        bq[ks] = uint4{pack_bf16x2(x[8 * ks], x[8 * ks + 1]), pack_bf16x2(x[8 * ks + 2], x[8 * ks + 3]),
+                       pack_bf16x2(x[8 * ks + 4], x[8 * ks + 5]), pack_bf16x2(x[8 * ks + 6], x[8 * ks + 7])};
+        const uint32_t bw[4] = {bq[ks].x, bq[ks].y, bq[ks].z, bq[ks].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) den = __builtin_fmaf(e & 1 ? bf16_hi(bw[e >> 1]) : bf16_lo(bw[e >> 1]), z[e], den);
+      }
+      den += partner_f32(den);
+      const float inv_den = den != 0.f ? 1.0f / den : 0.f;  // no marginal block: no linear term
+#pragma unroll
+      for (int ot = 0; ot < 4; ++ot) {
+        v16f al = v16f{};
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) al = mfma_bf16(*(const uint4*)(Hi + (size_t)hz_frag_chunk(ot, ks, lane) * 8), bq[ks], al);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[ot][r] = __builtin_fmaf(al[r], inv_den, o[ot][r]);
+      }
+      if (fe.bias) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[ct][r] += bf16_to_f32(fe.bias[32 * ct + 8 * (r >> 2) + 4 * hf + (r & 3)]);
+      }
+    }
+    if (qok) {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *(uint2*)(fe.out + head + qrow * D + 32 * ct + 8 * g + 4 * hf) =
+              uint2{pack_bf16x2(o[ct][4 * g], o[ct][4 * g + 1]), pack_bf16x2(o[ct][4 * g + 2], o[ct][4 * g + 3])};
+    }
+    return;
+  }
   float dl = 0.f;
   if (qok && dm.n_c > 0) {
     const bf16_t* drow = dout + head + qrow * D;
@@ -464,14 +555,30 @@ static BwdDims bwd_dims(const Problem& p) { return BwdDims{p.N, p.Tq, p.Tk, p.n_
 void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
                       const int32_t* crit, float* lse2, float* delta, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
-  static const bool ok = allow_lds(bwd_stats_kernel<4>) && allow_lds(bwd_stats_kernel<2>);
+  static const bool ok = allow_lds(bwd_stats_kernel<4, false>) && allow_lds(bwd_stats_kernel<2, false>);
   if (!ok) return;  // (the launch below would fail the same way and be reported by the caller's status check)
+  const FwdEpilogue none{nullptr, nullptr, nullptr, 0};
   if (p.block_q == 128)
-    bwd_stats_kernel<4><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
-                                                   crit, lse2, delta, bwd_dims(p));
+    bwd_stats_kernel<4, false><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                      (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
   else
-    bwd_stats_kernel<2><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout,
-                                                   crit, lse2, delta, bwd_dims(p));
+    bwd_stats_kernel<2, false><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
+                                                                      (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
+}
+
+// The unquantised forward pass: the same kernel with the output epilogue.
+void launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
+                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, hipStream_t stream) {
+  const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
+  static const bool ok = allow_lds(bwd_stats_kernel<4, true>) && allow_lds(bwd_stats_kernel<2, true>);
+  if (!ok) return;
+  const FwdEpilogue fe{HZ, HZ ? proj_b : nullptr, (bf16_t*)out, phi_kind};
+  if (p.block_q == 128)
+    bwd_stats_kernel<4, true><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr,
+                                                                     crit, nullptr, nullptr, bwd_dims(p), fe);
+  else
+    bwd_stats_kernel<2, true><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr,
+                                                                     crit, nullptr, nullptr, bwd_dims(p), fe);
 }
 
 void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,

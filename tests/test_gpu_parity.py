@@ -231,3 +231,45 @@ def test_token_major_and_packed_layouts_give_the_same_bits(case):
     assert torch.equal(wide[:, :, 1].permute(0, 2, 1, 3), ref)
     assert (wide[:, :, 0] == 7.0).all()
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("H,grid,bq,rc,rm,proj,phi", [
+    (2, (5, 10, 20), 128, 0.25, 0.5, True, "softmax"),     # N = 1000, ragged in both block sizes
+    (2, (5, 10, 20), 64, 0.2, 0.4, True, "elu1"),
+    (1, (3, 27, 27), 128, 0.1, 0.2, False, "relu"),        # N = 2187, identity projection
+    (1, (1, 9, 9), 128, 0.5, 0.5, True, "softmax"),        # N = 81: one ragged query block
+    (1, (1, 5, 5), 64, 1.0, 0.0, False, "softmax"),        # N = 25: dense attention, no linear term
+])
+def test_unquantised_forward_matches_oracle(H, grid, bq, rc, rm, proj, phi):
+    """quant_mode SLA_QUANT_NONE (the operator the backward pass differentiates): bf16 products with
+    fp32 accumulation against the oracle's exact branch, on the library's own mask.  The bar of the
+    low-bit path (max-abs 2e-2, cosine 0.999) applies; the only roundings here are P, the summaries
+    and the output to bf16 (relative step 2^-9: up to 8e-3 on outputs of magnitude 4, which the bias
+    brings about), so the relative Frobenius error is asserted too, at 5e-3."""
+    cfg = _cfg(H, grid, bq, rc, rm, proj=proj, cid=400)
+    q, k, v = synth.make_qkv(cfg)
+    W = synth.make_proj(cfg) if proj else None
+    bias = synth.make_qkv(cfg, seed=3)[0][0, 0, 0].contiguous() if proj else None   # 128 bf16 values
+    qd, kd, vd, Wd, bd = pu.to_dev(q, k, v, W, bias)
+    kind = {"softmax": sla.PHI_SOFTMAX, "elu1": sla.PHI_ELU1, "relu": sla.PHI_RELU}[phi]
+    out = sla.sla_attention_fwd(qd, kd, vd, bq, 64, rc, rm, proj_w=Wd, proj_b=bd, phi_kind=kind,
+                                quant_mode=sla.QUANT_NONE)
+    mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
+    torch.cuda.synchronize()
+    for h in range(H):
+        r = so.sla_forward_head(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]), bq, 64, rc, rm,
+                                proj_w=None if W is None else synth.as_f64(W),
+                                proj_b=None if bias is None else synth.as_f64(bias), phi=phi,
+                                quant=so.QUANT_NONE, mask=mask[0, h])
+        got = out[0, h].float().cpu().numpy().astype(np.float64)
+        pu.check_output(got, r["out"], "unquantised forward head %d" % h)
+        assert np.linalg.norm(got - r["out"]) / np.linalg.norm(r["out"]) <= 5e-3
+
+
+def test_unquantised_forward_rejects_strided_layouts():
+    cfg = _cfg(2, (1, 9, 9), 128, 0.5, 0.5)            # two heads: token-major memory differs from head-major
+    q, k, v = pu.to_dev(*synth.make_qkv(cfg))
+    qt = q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)          # token-major memory
+    with pytest.raises(sla.SLAError) as e:
+        sla.sla_attention_fwd_strided(qt, k, v, torch.empty_like(q), 128, 64, 0.5, 0.5, quant_mode=sla.QUANT_NONE)
+    assert e.value.status == sla.ERR_LAYOUT

@@ -134,7 +134,8 @@ def test_workspace_bytes():
     for bad in ((0, 2, 1024, 128, 64, 64, 0.2, 0.4), (1, 2, 1024, 64, 64, 64, 0.2, 0.4),
                 (1, 2, 1024, 128, 96, 64, 0.2, 0.4), (1, 2, 1024, 128, 64, 64, 0.0, 0.4)):
         assert sla.sla_workspace_bytes(*bad) == 0
-    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_NONE) == 0
+    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_NONE) == w0   # the 16-bit path: same map
+    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_QK_INT8) == 0
 
 
 def _fwd(q=FAKE, k=FAKE, v=FAKE, out=FAKE, B=1, H=2, N=1024, d=128, bq=64, bk=64, rc=0.2, rm=0.4,
@@ -149,8 +150,9 @@ def test_attention_fwd_argument_errors_are_found_before_any_launch():
     assert _fwd(H=70000) == sla.ERR_SHAPE
     assert _fwd(bq=32) == sla.ERR_BLOCK and _fwd(bk=32) == sla.ERR_BLOCK
     assert _fwd(rc=0.0) == sla.ERR_RATIO and _fwd(rc=0.8, rm=0.4) == sla.ERR_RATIO
-    assert _fwd(phi=7) == sla.ERR_UNSUPPORTED and _fwd(quant=0) == sla.ERR_UNSUPPORTED
+    assert _fwd(phi=7) == sla.ERR_UNSUPPORTED and _fwd(quant=3) == sla.ERR_UNSUPPORTED
     assert _fwd(quant=1) == sla.ERR_UNSUPPORTED
+    assert _fwd(quant=0, ws=None) == sla.ERR_WORKSPACE   # the 16-bit path checks its arguments the same way
     assert _fwd(ws=None) == sla.ERR_WORKSPACE
     assert _fwd(ws=ctypes.c_void_p(0x10010)) == sla.ERR_WORKSPACE          # misaligned
     need = sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4)
