@@ -231,12 +231,12 @@ def main_w8a8(args):
     print(json.dumps(result))
 
 
-BWD_STAGE_NAMES = ("mask_and_records", "softmax_stats", "linear_branch", "dq", "dkv")
+BWD_STAGE_NAMES = ("block_mask", "softmax_stats", "linear_branch", "dq", "dkv")
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 
 
 def main_bwd(args):
-    """One step = one backward pass of SLA (sla_attention_bwd): block mask, operand records, softmax
+    """One step = one backward pass of SLA (sla_attention_bwd): block mask, softmax
     statistics, linear-branch and projection gradients, dQ, dK and dV, for the same seeded inputs as
     the forward benchmark and a seeded upstream gradient."""
     import numpy as np

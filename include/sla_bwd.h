@@ -53,7 +53,7 @@ size_t sla_bwd_workspace_bytes(int B, int H, int N, int d, int block_q, int bloc
  *                  wanted; same remark.  Zero when there is no marginal block (the forward pass
  *                  then adds no bias).
  * With sla_profile_enable (sla.h) a call records the same number of stage events as a forward
- * call; the stages are: 0 block mask + operand records, 1 softmax statistics (lse, delta),
+ * call; the stages are: 0 block mask, 1 softmax statistics (lse, delta),
  * 2 linear branch and projection (summaries, dQ share, transposed accumulation, dK / dV shares),
  * 3 dQ, 4 dK and dV. */
 int sla_attention_bwd(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
