@@ -412,9 +412,10 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
                                                       const float* __restrict__ delta, const float* __restrict__ dk_lin,
                                                       const float* __restrict__ dv_lin, bf16_t* __restrict__ dk,
-                                                      bf16_t* __restrict__ dv, int tile_shift, BwdDims dm) {
-  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * 2 * TILE_B];  // two buffers of: Q then dO of a query tile
-  __shared__ __attribute__((aligned(16))) float stat[2][2][32];             // and its lse, delta
+                                                      bf16_t* __restrict__ dv, int pair_shift, BwdDims dm) {
+  // two buffers of: Q (2 tiles) then dO (2 tiles) of 64 consecutive query rows; then their lse, delta
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  float (*stat)[2][64] = (float (*)[2][64])(lds + 2 * 4 * TILE_B);
   __shared__ unsigned short qlist[8192];
   __shared__ int wcnt[4];
   int J, bh;
@@ -453,77 +454,103 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
     dkt[ct] = v16f{};
     dvt[ct] = v16f{};
   }
-  // Steps = (list entry, tile of its query block).  Tiles travel memory -> registers -> LDS: while
-  // step s is computed from one LDS buffer, step s + 1 is moved from registers to the other buffer,
-  // and steps s + 2, s + 3 are on their way from memory in two more register sets (four sets in
-  // rotation); one barrier per step.
-  const int steps = nq << tile_shift, tile_mask = (1 << tile_shift) - 1;
-  RowStage<256, 32> sq0, sd0, sq1, sd1, sq2, sd2, sq3, sd3;
-  float ps0 = 0.f, ps1 = 0.f, ps2 = 0.f, ps3 = 0.f;
-  auto tile_of = [&](int step) { return ((qlist[step >> tile_shift] & 0x3fff) << tile_shift) + (step & tile_mask); };
+  // Steps = (list entry, pair of tiles of its query block): 64 query rows at a time.  They travel
+  // memory -> registers -> LDS: while step s is computed from one LDS buffer, step s + 1 is moved from
+  // registers to the other buffer and step s + 2 is on its way from memory (two register sets in
+  // rotation); one barrier per step.  Within a step the two tiles are independent, which lets the
+  // matrix products of one run under the exponentials of the other.
+  const int steps = nq << pair_shift, pair_mask = (1 << pair_shift) - 1;
+  RowStage<256, 64> sq0, sd0, sq1, sd1;
+  float ps0 = 0.f, ps1 = 0.f;
+  auto rows_of = [&](int step) { return 64 * (((qlist[step >> pair_shift] & 0x3fff) << pair_shift) + (step & pair_mask)); };
 #define DKV_LOAD(SQ, SD, PS, STEP)                                                                   \
   if ((STEP) < steps) {                                                                              \
-    const int T_ = tile_of(STEP);                                                                    \
-    SQ.load(q + head, 32ll * T_, dm.N, t);                                                           \
-    SD.load(dout + head, 32ll * T_, dm.N, t);                                                        \
-    if (t < 64) PS = (t < 32 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + 32 * T_ + (t & 31)];        \
+    const long long r_ = rows_of(STEP);                                                              \
+    SQ.load(q + head, r_, dm.N, t);                                                                  \
+    SD.load(dout + head, r_, dm.N, t);                                                               \
+    if (t < 128) PS = (t < 64 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + r_ + (t & 63)];            \
   }
 #define DKV_STORE(SQ, SD, PS, BUF)                                                                   \
   {                                                                                                  \
-    SQ.store(lds + (BUF) * 2 * TILE_B, t);                                                           \
-    SD.store(lds + (BUF) * 2 * TILE_B + TILE_B, t);                                                  \
-    if (t < 64) stat[BUF][t >> 5][t & 31] = PS;                                                      \
+    SQ.store(lds + (BUF) * 4 * TILE_B, t);                                                           \
+    SD.store(lds + (BUF) * 4 * TILE_B + 2 * TILE_B, t);                                              \
+    if (t < 128) stat[BUF][t >> 6][t & 63] = PS;                                                     \
   }
-  auto compute = [&](int step, int buf) {
-    if (!((qlist[step >> tile_shift] >> (14 + half)) & 1)) return;  // (wave-uniform)
-    const unsigned char* qtile = lds + buf * 2 * TILE_B;
-    const unsigned char* dtile = qtile + TILE_B;
-    v16f s = v16f{}, dp = v16f{};
+  auto compute = [&](int step, int buf) __attribute__((always_inline)) {
+    if (!((qlist[step >> pair_shift] >> (14 + half)) & 1)) return;  // (wave-uniform)
+    const unsigned char* qt0 = lds + buf * 4 * TILE_B;
+    const unsigned char* dt0 = qt0 + 2 * TILE_B;
+    v16f s[2], dp[2], p[2];
+    // Operand reads are grouped ahead of the matrix products that use them (the compiler would
+    // otherwise issue each read right before its product and wait for it every time).
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      s = mfma_bf16(n_op(qtile, l32, hf, ks), kf[ks], s);
-      dp = mfma_bf16(n_op(dtile, l32, hf, ks), vf[ks], dp);
+    for (int u = 0; u < 2; ++u) {
+      uint4 aq[8], ad[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        aq[ks] = n_op(qt0 + u * TILE_B, l32, hf, ks);
+        ad[ks] = n_op(dt0 + u * TILE_B, l32, hf, ks);
+      }
+      s[u] = v16f{};
+      dp[u] = v16f{};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        s[u] = mfma_bf16(aq[ks], kf[ks], s[u]);
+        dp[u] = mfma_bf16(ad[ks], vf[ks], dp[u]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);  // 16 LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // then 16 matrix products
     }
-    v16f p;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const float4 ls = *(const float4*)&stat[buf][0][8 * g + 4 * hf];
-      const float4 dl = *(const float4*)&stat[buf][1][8 * g + 4 * hf];
-      const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float pe = kok ? __builtin_amdgcn_exp2f(s[4 * g + e] * QK_LOG2 - lsv[e]) : 0.f;
-        p[4 * g + e] = pe;
-        s[4 * g + e] = pe * (dp[4 * g + e] - dlv[e]);
+      for (int g = 0; g < 4; ++g) {
+        const float4 ls = *(const float4*)&stat[buf][0][32 * u + 8 * g + 4 * hf];
+        const float4 dl = *(const float4*)&stat[buf][1][32 * u + 8 * g + 4 * hf];
+        const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float pe = kok ? __builtin_amdgcn_exp2f(s[u][4 * g + e] * QK_LOG2 - lsv[e]) : 0.f;
+          p[u][4 * g + e] = pe;
+          s[u][4 * g + e] = pe * (dp[u][4 * g + e] - dlv[e]);
+        }
       }
     }
 #pragma unroll
-    for (int sx = 0; sx < 2; ++sx) {
-      const uint4 pb = acc_operand(p, sx), dsb = acc_operand(s, sx);
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
-        dvt[ct] = mfma_bf16(t_op(dtile, tr_off, ct, sx), pb, dvt[ct]);
-        dkt[ct] = mfma_bf16(t_op(qtile, tr_off, ct, sx), dsb, dkt[ct]);
+      for (int sx = 0; sx < 2; ++sx) {
+        const uint4 pb = acc_operand(p[u], sx), dsb = acc_operand(s[u], sx);
+        uint4 td[4], tq[4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          td[ct] = t_op(dt0 + u * TILE_B, tr_off, ct, sx);
+          tq[ct] = t_op(qt0 + u * TILE_B, tr_off, ct, sx);
+        }
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          dvt[ct] = mfma_bf16(td[ct], pb, dvt[ct]);
+          dkt[ct] = mfma_bf16(tq[ct], dsb, dkt[ct]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);  // 16 transposing LDS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);   // then 8 matrix products
       }
     }
   };
+  // one step: load step S + 2 into the set that step S has left, compute S, publish S + 1
+#define DKV_STEP(S, BUF, SQL, SDL, PSL, SQN, SDN, PSN)       \
+  if ((S) >= steps) break;                                   \
+  DKV_LOAD(SQL, SDL, PSL, (S) + 2)                           \
+  compute((S), BUF);                                         \
+  if ((S) + 1 < steps) DKV_STORE(SQN, SDN, PSN, 1 - (BUF))   \
+  __syncthreads();
   DKV_LOAD(sq0, sd0, ps0, 0)
   DKV_LOAD(sq1, sd1, ps1, 1)
-  DKV_LOAD(sq2, sd2, ps2, 2)
   if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
   __syncthreads();
-  // one step: load step S + 3 into the set that step S - 1 has left, compute S, publish S + 1
-#define DKV_STEP(S, BUF, SQL, SDL, PSL, SQN, SDN, PSN)  \
-  if ((S) >= steps) break;                              \
-  DKV_LOAD(SQL, SDL, PSL, (S) + 3)                      \
-  compute((S), BUF);                                    \
-  if ((S) + 1 < steps) DKV_STORE(SQN, SDN, PSN, 1 - (BUF)) \
-  __syncthreads();
-  for (int step = 0;; step += 4) {  // (every exit test is uniform over the workgroup)
-    DKV_STEP(step, 0, sq3, sd3, ps3, sq1, sd1, ps1)
-    DKV_STEP(step + 1, 1, sq0, sd0, ps0, sq2, sd2, ps2)
-    DKV_STEP(step + 2, 0, sq1, sd1, ps1, sq3, sd3, ps3)
-    DKV_STEP(step + 3, 1, sq2, sd2, ps2, sq0, sd0, ps0)
+  for (int step = 0;; step += 2) {  // (every exit test is uniform over the workgroup)
+    DKV_STEP(step, 0, sq0, sd0, ps0, sq1, sd1, ps1)
+    DKV_STEP(step + 1, 1, sq1, sd1, ps1, sq0, sd0, ps0)
   }
 #undef DKV_STEP
 #undef DKV_LOAD
@@ -598,9 +625,14 @@ void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const voi
                     const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
                     hipStream_t stream) {
   const int pairs = (p.Tk + 1) / 2;
-  bwd_dkv_kernel<<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, 0, stream>>>(
+  constexpr int lds_bytes = 2 * 4 * TILE_B + 2 * 2 * 64 * 4;
+  static const bool ok =
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) == hipSuccess;
+  if (!ok) return;
+  // (a query block is 2 or 4 tiles = 1 or 2 steps of 64 rows)
+  bwd_dkv_kernel<<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds_bytes, stream>>>(
       (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
-      (bf16_t*)dk, (bf16_t*)dv, p.block_q == 128 ? 2 : 1, bwd_dims(p));
+      (bf16_t*)dk, (bf16_t*)dv, p.block_q == 128 ? 1 : 0, bwd_dims(p));
 }
 
 }  // namespace sla
