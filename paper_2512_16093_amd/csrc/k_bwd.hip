@@ -486,10 +486,16 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       uint4 aq[8], ad[8];
+      float4 ls[4], dl[4];
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         aq[ks] = n_op(qt0 + u * TILE_B, l32, hf, ks);
         ad[ks] = n_op(dt0 + u * TILE_B, l32, hf, ks);
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        ls[g] = *(const float4*)&stat[buf][0][32 * u + 8 * g + 4 * hf];
+        dl[g] = *(const float4*)&stat[buf][1][32 * u + 8 * g + 4 * hf];
       }
       s[u] = v16f{};
       dp[u] = v16f{};
@@ -498,16 +504,11 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
         s[u] = mfma_bf16(aq[ks], kf[ks], s[u]);
         dp[u] = mfma_bf16(ad[ks], vf[ks], dp[u]);
       }
-      __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);  // 16 LDS reads
+      __builtin_amdgcn_sched_group_barrier(0x100, 24, 0);  // 24 LDS reads (operands, then lse and delta)
       __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // then 16 matrix products
-    }
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 ls = *(const float4*)&stat[buf][0][32 * u + 8 * g + 4 * hf];
-        const float4 dl = *(const float4*)&stat[buf][1][32 * u + 8 * g + 4 * hf];
-        const float lsv[4] = {ls.x, ls.y, ls.z, ls.w}, dlv[4] = {dl.x, dl.y, dl.z, dl.w};
+        const float lsv[4] = {ls[g].x, ls[g].y, ls[g].z, ls[g].w}, dlv[4] = {dl[g].x, dl[g].y, dl[g].z, dl[g].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float pe = kok ? __builtin_amdgcn_exp2f(s[u][4 * g + e] * QK_LOG2 - lsv[e]) : 0.f;
