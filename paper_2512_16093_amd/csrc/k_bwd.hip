@@ -172,7 +172,14 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     float mx = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
-      s[kt] = score_tile(lds + kt * TILE_B, qf, l32, hf);
+      uint4 ak[8];  // operand reads grouped ahead of the matrix products that use them
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) ak[ks] = n_op(lds + kt * TILE_B, l32, hf, ks);
+      s[kt] = v16f{};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) s[kt] = mfma_bf16(ak[ks], qf[ks], s[kt]);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -202,8 +209,13 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
       for (int sx = 0; sx < 2; ++sx) {
         const uint4 pb = acc_operand(s[kt], sx);
+        uint4 tv[4];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) o[ct] = mfma_bf16(t_op(lds + (2 + kt) * TILE_B, tr_off, ct, sx), pb, o[ct]);
+        for (int ct = 0; ct < 4; ++ct) tv[ct] = t_op(lds + (2 + kt) * TILE_B, tr_off, ct, sx);
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) o[ct] = mfma_bf16(tv[ct], pb, o[ct]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
     if (b + 1 < dm.n_c) {
       sk.store(lds_next, t);
@@ -366,10 +378,26 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
     for (int kt = 0; kt < 2; ++kt) {
       const unsigned char* ktile = lds + kt * TILE_B;
       const unsigned char* vtile = lds + (2 + kt) * TILE_B;
-      v16f s = score_tile(ktile, qf, l32, hf);
-      v16f dp = v16f{};
+      // operand reads grouped ahead of the matrix products that use them
+      uint4 ak[8], av[8];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) dp = mfma_bf16(n_op(vtile, l32, hf, ks), dof[ks], dp);
+      for (int ks = 0; ks < 8; ++ks) {
+        ak[ks] = n_op(ktile, l32, hf, ks);
+        av[ks] = n_op(vtile, l32, hf, ks);
+      }
+      v16f s = v16f{}, dp = v16f{};
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) s = mfma_bf16(ak[ks], qf[ks], s);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) dp = mfma_bf16(av[ks], dof[ks], dp);
+      // K reads; the score products, one V read behind each; the dO V^T products
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
@@ -379,8 +407,13 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
 #pragma unroll
       for (int sx = 0; sx < 2; ++sx) {
         const uint4 dsb = acc_operand(s, sx);
+        uint4 tk[4];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) acc[ct] = mfma_bf16(t_op(ktile, tr_off, ct, sx), dsb, acc[ct]);
+        for (int ct = 0; ct < 4; ++ct) tk[ct] = t_op(ktile, tr_off, ct, sx);
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) acc[ct] = mfma_bf16(tk[ct], dsb, acc[ct]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
     }
     if (b + 1 < dm.n_c) {
