@@ -79,11 +79,19 @@ struct RowStage {
   static constexpr int PER = ROWS * 16 / NT;
   uint4 pf[PER];
   __device__ __forceinline__ void load(const bf16_t* x, long long r0, int N, int t) {
+    if (r0 + ROWS <= N) {  // (uniform) every row exists: no per-row test
 #pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int c = u * NT + t;
-      const long long r = r0 + (c >> 4);
-      pf[u] = r < N ? *(const uint4*)(x + r * D + (c & 15) * 8) : uint4{0u, 0u, 0u, 0u};
+      for (int u = 0; u < PER; ++u) {
+        const int c = u * NT + t;
+        pf[u] = *(const uint4*)(x + (r0 + (c >> 4)) * D + (c & 15) * 8);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < PER; ++u) {
+        const int c = u * NT + t;
+        const long long r = r0 + (c >> 4);
+        pf[u] = r < N ? *(const uint4*)(x + r * D + (c & 15) * 8) : uint4{0u, 0u, 0u, 0u};
+      }
     }
   }
   __device__ __forceinline__ void store(unsigned char* lds, int t) const {
@@ -180,11 +188,19 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
       for (int ks = 0; ks < 8; ++ks) s[kt] = mfma_bf16(ak[ks], qf[ks], s[kt]);
       __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      if (64 * j + 64 <= dm.N) {  // (uniform) only the sequence's last key block can hold keys that do not exist
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
-        s[kt][r] = key < dm.N ? s[kt][r] * QK_LOG2 : -INFINITY;
-        mx = fmaxf(mx, s[kt][r]);
+        for (int r = 0; r < 16; ++r) {
+          s[kt][r] *= QK_LOG2;
+          mx = fmaxf(mx, s[kt][r]);
+        }
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
+          s[kt][r] = key < dm.N ? s[kt][r] * QK_LOG2 : -INFINITY;
+          mx = fmaxf(mx, s[kt][r]);
+        }
       }
     }
     mx = fmaxf(mx, partner_f32(mx));
@@ -398,11 +414,16 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      if (64 * j + 64 <= dm.N) {  // (uniform) only the sequence's last key block can hold keys that do not exist
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
-        const float p = key < dm.N ? __builtin_amdgcn_exp2f(s[r] * QK_LOG2 - lse_q) : 0.f;
-        s[r] = p * (dp[r] - delta_q);
+        for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(s[r] * QK_LOG2 - lse_q) * (dp[r] - delta_q);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
+          const float p = key < dm.N ? __builtin_amdgcn_exp2f(s[r] * QK_LOG2 - lse_q) : 0.f;
+          s[r] = p * (dp[r] - delta_q);
+        }
       }
 #pragma unroll
       for (int sx = 0; sx < 2; ++sx) {
