@@ -22,7 +22,7 @@ pytestmark = pytest.mark.gpu
 REL_FRO, REL_MAX, COS_MIN = 1e-2, 3e-2, 0.999
 
 CASES = [
-    # (H, grid, block_q, rc, rm, proj)
+    # (H, grid, block_q, rc, rm, proj)  -- batch 1; a batch of 2 is in test_backward_batch_of_two
     (2, (5, 10, 20), 128, 0.25, 0.0, False),   # sparse branch alone, N = 1000 (ragged in both block sizes)
     (2, (5, 10, 20), 64, 0.2, 0.0, False),
     (2, (5, 10, 20), 128, 0.25, 0.5, True),    # both branches with projection and bias gradient
@@ -75,6 +75,34 @@ def test_backward_matches_gradient_oracle(H, grid, bq, rc, rm, proj):
     if proj:
         _compare("dproj_w", dw.cpu().numpy(), sums_w)
         _compare("dproj_b", db.cpu().numpy(), sums_b)
+
+
+def test_backward_batch_of_two():
+    """Two batch entries with different contents: every (b, h) slice matches the oracle, and the
+    projection gradients sum over both."""
+    H, grid, bq, rc, rm = 2, (3, 9, 11), 128, 0.3, 0.5          # N = 297: ragged, Tq = 3 (odd), Tk = 5 (odd)
+    cfg = synth.custom_config(2, H, grid, block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=True, cfg_id=301)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=9)[2]
+    W = synth.make_proj(cfg)
+    dev = torch.device("cuda:0")
+    qd, kd, vd, dd, Wd = (t.to(dev) for t in (q, k, v, dout, W))
+    assert not torch.equal(q[0], q[1])
+    mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
+    dq, dk, dv, dw, db = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True)
+    torch.cuda.synchronize()
+    sums_w, sums_b = np.zeros((cfg.d, cfg.d)), np.zeros(cfg.d)
+    for b in range(2):
+        for h in range(H):
+            r = bo.sla_backward_head(synth.as_f64(q[b, h]), synth.as_f64(k[b, h]), synth.as_f64(v[b, h]),
+                                     synth.as_f64(dout[b, h]), mask[b, h], bq, 64, proj_w=synth.as_f64(W), has_bias=True)
+            _compare("dq", dq[b, h].float().cpu().numpy(), r["dQ"])
+            _compare("dk", dk[b, h].float().cpu().numpy(), r["dK"])
+            _compare("dv", dv[b, h].float().cpu().numpy(), r["dV"])
+            sums_w += r["dW"]
+            sums_b += r["db"]
+    _compare("dproj_w", dw.cpu().numpy(), sums_w)
+    _compare("dproj_b", db.cpu().numpy(), sums_b)
 
 
 def test_backward_argument_errors():
