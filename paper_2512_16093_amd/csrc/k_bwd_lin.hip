@@ -143,15 +143,25 @@ __global__ void __launch_bounds__(NW * 64, 1)
 
     // numT[o][n] = sum_c H[c][o] a[n][c]  ->  O^l;   glT[c'][n] = sum_r W[r][c'] dO[n][r]
     v16f ol[4], gl[4];
+    // (here and below: the LDS operand reads of a tile are grouped ahead of its matrix products;
+    // left alone the compiler issues each read right before its product and waits for it every time)
 #pragma unroll
     for (int ot = 0; ot < 4; ++ot) {
+      uint4 ah[8], aw[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        ah[ks] = lds_frag(R1, 32 * ot + l32, 16 * ks + 8 * hf);
+        aw[ks] = lds_frag(Wt, 32 * ot + l32, 16 * ks + 8 * hf);
+      }
       ol[ot] = v16f{};
       gl[ot] = v16f{};
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        ol[ot] = mfma_bf16(lds_frag(R1, 32 * ot + l32, 16 * ks + 8 * hf), af[ks], ol[ot]);
-        gl[ot] = mfma_bf16(lds_frag(Wt, 32 * ot + l32, 16 * ks + 8 * hf), gf[ks], gl[ot]);
+        ol[ot] = mfma_bf16(ah[ks], af[ks], ol[ot]);
+        gl[ot] = mfma_bf16(aw[ks], gf[ks], gl[ot]);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
     }
     float dden = 0.f;
 #pragma unroll
@@ -175,12 +185,20 @@ __global__ void __launch_bounds__(NW * 64, 1)
             uint2{pack_bf16x2(gl[ot][4 * g], gl[ot][4 * g + 1]), pack_bf16x2(gl[ot][4 * g + 2], gl[ot][4 * g + 3])};
     // (own rows only: written and read back by this wavefront, in program order)
     v16f da[4];
+    uint4 bn[8];                 // this token's dnum row: the B operand of all four tiles
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) bn[ks] = lds_frag(R1, nl, 16 * ks + 8 * hf);
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) {
+      uint4 ah[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) ah[ks] = lds_frag(R2, 32 * ct + l32, 16 * ks + 8 * hf);
       da[ct] = v16f{};
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        da[ct] = mfma_bf16(lds_frag(R2, 32 * ct + l32, 16 * ks + 8 * hf), lds_frag(R1, nl, 16 * ks + 8 * hf), da[ct]);
+      for (int ks = 0; ks < 8; ++ks) da[ct] = mfma_bf16(ah[ks], bn[ks], da[ct]);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
     float ad[4][16];             // a at the accumulator's channels 32 ct + 8 g + 4 hf + e
     float sdot = 0.f;
@@ -233,9 +251,16 @@ __global__ void __launch_bounds__(NW * 64, 1)
 #pragma unroll
       for (int ot = 0; ot < 4; ++ot) {
         acc[ot] = v16f{};
+        uint4 aa[BQ / 16], bb[BQ / 16];
 #pragma unroll
-        for (int ks = 0; ks < BQ / 16; ++ks)
-          acc[ot] = mfma_bf16(lds_frag(R2, 32 * ct + l32, 16 * ks + 8 * hf), lds_frag(R3, 32 * ot + l32, 16 * ks + 8 * hf), acc[ot]);
+        for (int ks = 0; ks < BQ / 16; ++ks) {
+          aa[ks] = lds_frag(R2, 32 * ct + l32, 16 * ks + 8 * hf);
+          bb[ks] = lds_frag(R3, 32 * ot + l32, 16 * ks + 8 * hf);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BQ / 16; ++ks) acc[ot] = mfma_bf16(aa[ks], bb[ks], acc[ot]);
+        __builtin_amdgcn_sched_group_barrier(0x100, BQ / 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, BQ / 16, 0);
         // lane: o = 32 ot + l32; registers: c = 32 ct + 8 g + 4 hf + e
 #pragma unroll
         for (int g = 0; g < 4; ++g)
@@ -243,9 +268,15 @@ __global__ void __launch_bounds__(NW * 64, 1)
               uint2{pack_bf16x2(acc[ot][4 * g], acc[ot][4 * g + 1]), pack_bf16x2(acc[ot][4 * g + 2], acc[ot][4 * g + 3])};
       }
     }
-    if (t < 128) {
+    if (t < 128) {  // dZ_i[c = t] = sum_n a[n][c] dden[n], eight tokens per read
       float s = 0.f;
-      for (int m = 0; m < BQ; ++m) s += bf16_to_f32(R2[t * LP + m]) * dden_s[m];
+#pragma unroll
+      for (int m = 0; m < BQ; m += 8) {
+        float a8[8];
+        unpack8(*(const uint4*)(R2 + t * LP + m), a8);
+        const float4 d0 = *(const float4*)(dden_s + m), d1 = *(const float4*)(dden_s + m + 4);
+        s += a8[0] * d0.x + a8[1] * d0.y + a8[2] * d0.z + a8[3] * d0.w + a8[4] * d1.x + a8[5] * d1.y + a8[6] * d1.z + a8[7] * d1.w;
+      }
       dst[128 * 128 + t] = f32_to_bf16(s);
     }
     __syncthreads();             // aT and dnumT are consumed
@@ -267,16 +298,29 @@ __global__ void __launch_bounds__(NW * 64, 1)
 #pragma unroll
       for (int a = 0; a < RT; ++a) {
         const int rt = w + a * NW;
+        uint4 ag[BQ / 16];       // this row tile of dO^T: the A operand of all four column tiles
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ks = 0; ks < BQ / 16; ++ks) ag[ks] = lds_frag(R2, 32 * rt + l32, 16 * ks + 8 * hf);
+        __builtin_amdgcn_sched_group_barrier(0x100, BQ / 16, 0);
 #pragma unroll
-          for (int ks = 0; ks < BQ / 16; ++ks)
-            dwacc[a][ct] = mfma_bf16(lds_frag(R2, 32 * rt + l32, 16 * ks + 8 * hf), lds_frag(R3, 32 * ct + l32, 16 * ks + 8 * hf),
-                                     dwacc[a][ct]);
+        for (int ct = 0; ct < 4; ++ct) {
+          uint4 bo[BQ / 16];
+#pragma unroll
+          for (int ks = 0; ks < BQ / 16; ++ks) bo[ks] = lds_frag(R3, 32 * ct + l32, 16 * ks + 8 * hf);
+#pragma unroll
+          for (int ks = 0; ks < BQ / 16; ++ks) dwacc[a][ct] = mfma_bf16(ag[ks], bo[ks], dwacc[a][ct]);
+          __builtin_amdgcn_sched_group_barrier(0x100, BQ / 16, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, BQ / 16, 0);
+        }
       }
-      if (t < 128) {
+      if (t < 128) {  // db[r = t] += sum_n dO[n][r]
         float s = 0.f;
-        for (int m = 0; m < BQ; ++m) s += bf16_to_f32(R2[t * LP + m]);
+#pragma unroll
+        for (int m = 0; m < BQ; m += 8) {
+          float g8[8];
+          unpack8(*(const uint4*)(R2 + t * LP + m), g8);
+          s += ((g8[0] + g8[1]) + (g8[2] + g8[3])) + ((g8[4] + g8[5]) + (g8[6] + g8[7]));
+        }
         dbacc += s;
       }
       __syncthreads();
@@ -341,14 +385,23 @@ __global__ void __launch_bounds__(128) bwd_lin_k_kernel(const bf16_t* __restrict
   v16f dvt[4], dct[4];
 #pragma unroll
   for (int ot = 0; ot < 4; ++ot) {
+    uint4 ag[8], ac[8];  // operand reads grouped ahead of the matrix products
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      ag[ks] = *(const uint4*)(rec + (size_t)hz_frag_chunk(ot, ks, lane) * 8);
+      ac[ks] = lds_frag(Gc, 32 * ot + l32, 16 * ks + 8 * hf);
+    }
     dvt[ot] = v16f{};
     dct[ot] = v16f{};
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      dvt[ot] = mfma_bf16(*(const uint4*)(rec + (size_t)hz_frag_chunk(ot, ks, lane) * 8), cf[ks], dvt[ot]);
+      dvt[ot] = mfma_bf16(ag[ks], cf[ks], dvt[ot]);
       // d phi(K)^T[c][n] = sum_o G[c][o] V[n][o]
-      dct[ot] = mfma_bf16(lds_frag(Gc, 32 * ot + l32, 16 * ks + 8 * hf), vf[ks], dct[ot]);
+      dct[ot] = mfma_bf16(ac[ks], vf[ks], dct[ot]);
     }
+    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);   // 8 global reads
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);   // 8 LDS reads
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // 16 matrix products
   }
   float cd[4][16];
   float sdot = 0.f;
