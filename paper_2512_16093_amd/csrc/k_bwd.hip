@@ -461,30 +461,36 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
 // pair).  The workgroup walks over the query blocks that hold either block as critical (found from
 // the two mask columns; two flag bits per entry), staging each query tile's Q and dO once for both;
 // a wavefront whose block is not critical for the current query block sits the step out.
-__global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
+// (KB = 2, 64 query rows per step.)  With KB = 1 a workgroup of two wavefronts serves one key block
+// over its own list, 32 query rows per step, and two workgroups share a compute unit: every
+// staged tile then serves one key block only, but no wavefront ever sits out.
+template <int KB, int TILES>
+__global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
                                                       const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
                                                       const float* __restrict__ delta, const float* __restrict__ dk_lin,
                                                       const float* __restrict__ dv_lin, bf16_t* __restrict__ dk,
                                                       bf16_t* __restrict__ dv, int pair_shift, BwdDims dm) {
-  // two buffers of: Q (2 tiles) then dO (2 tiles) of 64 consecutive query rows; then their lse, delta
+  constexpr int NT = 128 * KB, ROWS = 32 * TILES;  // threads; query rows per step
+  // two buffers of: Q (TILES tiles) then dO (TILES tiles) of ROWS consecutive query rows; then their lse, delta
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  float (*stat)[2][64] = (float (*)[2][64])(lds + 2 * 4 * TILE_B);
+  constexpr int BUF_B = 2 * TILES * TILE_B;
+  float (*stat)[2][ROWS] = (float (*)[2][ROWS])(lds + 2 * BUF_B);
   __shared__ unsigned short qlist[8192];
   __shared__ int wcnt[4];
   int J, bh;
-  if (!xcd_block((dm.Tk + 1) >> 1, J, bh)) return;
+  if (!xcd_block((dm.Tk + KB - 1) / KB, J, bh)) return;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
   const int tr_off = tr_lane_offset(lane);
-  const int half = w >> 1;
+  const int half = KB == 2 ? w >> 1 : 0;
   // ---- the query blocks of the two key blocks, ascending; bit 14 / 15 = first / second block has it
   int nq = 0;
-  const bool has2 = 2 * J + 1 < dm.Tk;
-  for (int base = 0; base < dm.Tq; base += 256) {
+  const bool has2 = KB == 2 && 2 * J + 1 < dm.Tk;
+  for (int base = 0; base < dm.Tq; base += NT) {
     const int i = base + t;
     int fl = 0;
     if (i < dm.Tq) {
-      const int8_t* mrow = mask + ((size_t)bh * dm.Tq + i) * dm.Tk + 2 * J;
+      const int8_t* mrow = mask + ((size_t)bh * dm.Tq + i) * dm.Tk + KB * J;
       fl = (mrow[0] == 1 ? 1 : 0) | (has2 && mrow[1] == 1 ? 2 : 0);
     }
     const unsigned long long bal = __ballot(fl != 0);
@@ -493,11 +499,12 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
     int off = nq + __popcll(bal & ((1ull << lane) - 1ull));
     for (int x = 0; x < w; ++x) off += wcnt[x];
     if (fl) qlist[off] = (unsigned short)(i | (fl << 14));
-    nq += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+#pragma unroll
+    for (int x = 0; x < NT / 64; ++x) nq += wcnt[x];
     __syncthreads();
   }
   const size_t head = (size_t)bh * dm.N * D;
-  const long long key = 64ll * (2 * J + half) + 32 * (w & 1) + l32;
+  const long long key = 64ll * (KB * J + half) + 32 * (w & 1) + l32;
   const bool kok = key < dm.N;
   uint4 kf[8], vf[8];
   own_rows(k + head, key, dm.N, hf, kf);
@@ -514,31 +521,31 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
   // rotation); one barrier per step.  Within a step the two tiles are independent, which lets the
   // matrix products of one run under the exponentials of the other.
   const int steps = nq << pair_shift, pair_mask = (1 << pair_shift) - 1;
-  RowStage<256, 64> sq0, sd0, sq1, sd1;
+  RowStage<NT, ROWS> sq0, sd0, sq1, sd1;
   float ps0 = 0.f, ps1 = 0.f;
-  auto rows_of = [&](int step) { return 64 * (((qlist[step >> pair_shift] & 0x3fff) << pair_shift) + (step & pair_mask)); };
+  auto rows_of = [&](int step) { return ROWS * (((qlist[step >> pair_shift] & 0x3fff) << pair_shift) + (step & pair_mask)); };
 #define DKV_LOAD(SQ, SD, PS, STEP)                                                                   \
   if ((STEP) < steps) {                                                                              \
     const long long r_ = rows_of(STEP);                                                              \
     SQ.load(q + head, r_, dm.N, t);                                                                  \
     SD.load(dout + head, r_, dm.N, t);                                                               \
-    if (t < 128) PS = (t < 64 ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + r_ + (t & 63)];            \
+    if (t < 2 * ROWS) PS = (t < ROWS ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + r_ + (t & (ROWS - 1))]; \
   }
 #define DKV_STORE(SQ, SD, PS, BUF)                                                                   \
   {                                                                                                  \
-    SQ.store(lds + (BUF) * 4 * TILE_B, t);                                                           \
-    SD.store(lds + (BUF) * 4 * TILE_B + 2 * TILE_B, t);                                              \
-    if (t < 128) stat[BUF][t >> 6][t & 63] = PS;                                                     \
+    SQ.store(lds + (BUF) * BUF_B, t);                                                                \
+    SD.store(lds + (BUF) * BUF_B + TILES * TILE_B, t);                                               \
+    if (t < 2 * ROWS) stat[BUF][t / ROWS][t & (ROWS - 1)] = PS;                                      \
   }
   auto compute = [&](int step, int buf) __attribute__((always_inline)) {
-    if (!((qlist[step >> pair_shift] >> (14 + half)) & 1)) return;  // (wave-uniform)
-    const unsigned char* qt0 = lds + buf * 4 * TILE_B;
-    const unsigned char* dt0 = qt0 + 2 * TILE_B;
-    v16f s[2], dp[2], p[2];
+    if (!((qlist[step >> pair_shift] >> (14 + half)) & 1)) return;  // (wave-uniform; always set when KB == 1)
+    const unsigned char* qt0 = lds + buf * BUF_B;
+    const unsigned char* dt0 = qt0 + TILES * TILE_B;
+    v16f s[TILES], dp[TILES], p[TILES];
     // Operand reads are grouped ahead of the matrix products that use them (the compiler would
     // otherwise issue each read right before its product and wait for it every time).
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < TILES; ++u) {
       uint4 aq[8], ad[8];
       float4 ls[4], dl[4];
 #pragma unroll
@@ -572,7 +579,7 @@ __global__ void __launch_bounds__(256) bwd_dkv_kernel(const bf16_t* __restrict__
       }
     }
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < TILES; ++u) {
 #pragma unroll
       for (int sx = 0; sx < 2; ++sx) {
         const uint4 pb = acc_operand(p[u], sx), dsb = acc_operand(s[u], sx);
@@ -679,15 +686,23 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
                     hipStream_t stream) {
-  const int pairs = (p.Tk + 1) / 2;
-  constexpr int lds_bytes = 2 * 4 * TILE_B + 2 * 2 * 64 * 4;
+  constexpr int lds2 = 2 * 4 * TILE_B + 2 * 2 * 64 * 4, lds1 = 2 * 2 * TILE_B + 2 * 2 * 32 * 4;
   static const bool ok =
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) == hipSuccess;
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds2) == hipSuccess &&
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds1) == hipSuccess;
   if (!ok) return;
-  // (a query block is 2 or 4 tiles = 1 or 2 steps of 64 rows)
-  bwd_dkv_kernel<<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds_bytes, stream>>>(
-      (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
-      (bf16_t*)dk, (bf16_t*)dv, p.block_q == 128 ? 1 : 0, bwd_dims(p));
+  const int tiles = p.block_q / 32;  // of a query block: 2 or 4
+  const bool paired = false;
+  if (paired) {
+    const int pairs = (p.Tk + 1) / 2;
+    bwd_dkv_kernel<2, 2><<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds2, stream>>>(
+        (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
+        (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 1 : 0, bwd_dims(p));
+  } else {
+    bwd_dkv_kernel<1, 1><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
+        (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
+        (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 2 : 1, bwd_dims(p));
+  }
 }
 
 }  // namespace sla
