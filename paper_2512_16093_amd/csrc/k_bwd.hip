@@ -476,7 +476,7 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   constexpr int BUF_B = 2 * TILES * TILE_B;
   float (*stat)[2][ROWS] = (float (*)[2][ROWS])(lds + 2 * BUF_B);
-  __shared__ unsigned short qlist[8192];
+  unsigned short* qlist = (unsigned short*)(lds + 2 * BUF_B + 2 * 2 * ROWS * 4);  // [Tq]
   __shared__ int wcnt[4];
   int J, bh;
   if (!xcd_block((dm.Tk + KB - 1) / KB, J, bh)) return;
@@ -600,19 +600,28 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
     }
   };
   // one step: load step S + 2 into the set that step S has left, compute S, publish S + 1
-#define DKV_STEP(S, BUF, SQL, SDL, PSL, SQN, SDN, PSN)       \
-  if ((S) >= steps) break;                                   \
-  DKV_LOAD(SQL, SDL, PSL, (S) + 2)                           \
-  compute((S), BUF);                                         \
-  if ((S) + 1 < steps) DKV_STORE(SQN, SDN, PSN, 1 - (BUF))   \
+#define DKV_STEP(S, AHEAD, BUF, SQL, SDL, PSL, SQN, SDN, PSN)  \
+  if ((S) >= steps) break;                                     \
+  DKV_LOAD(SQL, SDL, PSL, (S) + (AHEAD))                       \
+  compute((S), BUF);                                           \
+  if ((S) + 1 < steps) DKV_STORE(SQN, SDN, PSN, 1 - (BUF))     \
   __syncthreads();
   DKV_LOAD(sq0, sd0, ps0, 0)
-  DKV_LOAD(sq1, sd1, ps1, 1)
-  if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
-  __syncthreads();
-  for (int step = 0;; step += 2) {  // (every exit test is uniform over the workgroup)
-    DKV_STEP(step, 0, sq0, sd0, ps0, sq1, sd1, ps1)
-    DKV_STEP(step + 1, 1, sq1, sd1, ps1, sq0, sd0, ps0)
+  if constexpr (NT * 2 >= ROWS * 8) {  // two register sets in rotation, two steps in flight
+    DKV_LOAD(sq1, sd1, ps1, 1)
+    if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
+    __syncthreads();
+    for (int step = 0;; step += 2) {  // (every exit test is uniform over the workgroup)
+      DKV_STEP(step, 2, 0, sq0, sd0, ps0, sq1, sd1, ps1)
+      DKV_STEP(step + 1, 2, 1, sq1, sd1, ps1, sq0, sd0, ps0)
+    }
+  } else {                             // (a set is 64 registers here) one set, one step ahead
+    if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
+    __syncthreads();
+    for (int step = 0;; step += 2) {
+      DKV_STEP(step, 1, 0, sq0, sd0, ps0, sq0, sd0, ps0)
+      DKV_STEP(step + 1, 1, 1, sq0, sd0, ps0, sq0, sd0, ps0)
+    }
   }
 #undef DKV_STEP
 #undef DKV_LOAD
@@ -683,13 +692,17 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
 }
 
+constexpr int DKV1_TILES = 1;  // tiles per step of the one-key-block variant (2 measured the same and needs 80 KB of LDS per workgroup)
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
                     hipStream_t stream) {
-  constexpr int lds2 = 2 * 4 * TILE_B + 2 * 2 * 64 * 4, lds1 = 2 * 2 * TILE_B + 2 * 2 * 32 * 4;
+  // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
+  const int list_bytes = (2 * p.Tq + 15) & ~15;
+  const int lds2 = 2 * 4 * TILE_B + 2 * 2 * 64 * 4 + list_bytes;
+  const int lds1 = 2 * 2 * DKV1_TILES * TILE_B + 2 * 2 * 32 * DKV1_TILES * 4 + list_bytes;
   static const bool ok =
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, lds2) == hipSuccess &&
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, lds1) == hipSuccess;
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess &&
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
   if (!ok) return;
   const int tiles = p.block_q / 32;  // of a query block: 2 or 4
   const bool paired = false;
@@ -699,9 +712,9 @@ void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const voi
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
         (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 1 : 0, bwd_dims(p));
   } else {
-    bwd_dkv_kernel<1, 1><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
+    bwd_dkv_kernel<1, DKV1_TILES><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
-        (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 2 : 1, bwd_dims(p));
+        (bf16_t*)dk, (bf16_t*)dv, (tiles == 4 ? 2 : 1) - (DKV1_TILES == 2 ? 1 : 0), bwd_dims(p));
   }
 }
 
