@@ -174,6 +174,12 @@ __global__ void __launch_bounds__(NW * 64, 1)
       }
     dden += partner_f32(dden);
     dden *= -rden;
+    uint2 olp[4][4];             // O^l rounded to bf16 (all that is used of it from here on: the dW product)
+#pragma unroll
+    for (int ot = 0; ot < 4; ++ot)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        olp[ot][g] = uint2{pack_bf16x2(ol[ot][4 * g], ol[ot][4 * g + 1]), pack_bf16x2(ol[ot][4 * g + 2], ol[ot][4 * g + 3])};
     __syncthreads();             // every wavefront is done with Hn
 
     // ---- d phi(Q) = dnum H^T + dden Z, then through the softmax
@@ -200,20 +206,20 @@ __global__ void __launch_bounds__(NW * 64, 1)
       __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
     }
-    float ad[4][16];             // a at the accumulator's channels 32 ct + 8 g + 4 hf + e
+    // a at the accumulator's channels 32 ct + 8 g + 4 hf + e: from Q again (its words are kept, a
+    // itself is formed twice rather than held in 64 registers)
+    uint2 qw[4][4];
     float sdot = 0.f;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int c0 = 32 * ct + 8 * g + 4 * hf;
-        uint2 qv = uint2{0u, 0u};
-        if (ok) qv = *(const uint2*)(q + row + c0);
-        const float xq[4] = {bf16_lo(qv.x), bf16_hi(qv.x), bf16_lo(qv.y), bf16_hi(qv.y)};
+        qw[ct][g] = ok ? *(const uint2*)(q + row + c0) : uint2{0u, 0u};
+        const float xq[4] = {bf16_lo(qw[ct][g].x), bf16_hi(qw[ct][g].x), bf16_lo(qw[ct][g].y), bf16_hi(qw[ct][g].y)};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float a = __builtin_amdgcn_exp2f((xq[e] - qmax) * LOG2E) * rsum;
-          ad[ct][4 * g + e] = a;
           da[ct][4 * g + e] += zv[c0 + e] * dden;
           sdot += a * da[ct][4 * g + e];
         }
@@ -224,25 +230,32 @@ __global__ void __launch_bounds__(NW * 64, 1)
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          float4 o4;
-          o4.x = ad[ct][4 * g] * (da[ct][4 * g] - sdot);
-          o4.y = ad[ct][4 * g + 1] * (da[ct][4 * g + 1] - sdot);
-          o4.z = ad[ct][4 * g + 2] * (da[ct][4 * g + 2] - sdot);
-          o4.w = ad[ct][4 * g + 3] * (da[ct][4 * g + 3] - sdot);
-          *(float4*)(dq_lin + row + 32 * ct + 8 * g + 4 * hf) = o4;
+          const float xq[4] = {bf16_lo(qw[ct][g].x), bf16_hi(qw[ct][g].x), bf16_lo(qw[ct][g].y), bf16_hi(qw[ct][g].y)};
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            o[e] = __builtin_amdgcn_exp2f((xq[e] - qmax) * LOG2E) * rsum * (da[ct][4 * g + e] - sdot);
+          *(float4*)(dq_lin + row + 32 * ct + 8 * g + 4 * hf) = float4{o[0], o[1], o[2], o[3]};
         }
     }
     __syncthreads();             // every wavefront is done with Ht (and with its dnum rows)
 
     // ---- dH_i^T[o][c] = sum_n dnum[n][o] a[n][c], dZ_i[c] = sum_n a[n][c] dden[n]: transposed copies with the tokens contiguous
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < 8; ++ks) {
+      const uint32_t aw[4] = {af[ks].x, af[ks].y, af[ks].z, af[ks].w};
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) R2[(16 * ks + 8 * hf + kk) * LP + nl] = f32_to_bf16(av[8 * ks + kk]);
+      for (int kk = 0; kk < 8; ++kk)
+        R2[(16 * ks + 8 * hf + kk) * LP + nl] = (bf16_t)(kk & 1 ? aw[kk >> 1] >> 16 : aw[kk >> 1] & 0xffffu);
+    }
 #pragma unroll
-    for (int ot = 0; ot < 4; ++ot)
+    for (int ks = 0; ks < 8; ++ks) {  // dnum: this token's row of R1 again (written above), not 64 registers held since
+      const uint4 dv = lds_frag(R1, nl, 16 * ks + 8 * hf);
+      const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w};
 #pragma unroll
-      for (int r = 0; r < 16; ++r) R3[(32 * ot + 8 * (r >> 2) + 4 * hf + (r & 3)) * LP + nl] = f32_to_bf16(gl[ot][r]);
+      for (int kk = 0; kk < 8; ++kk)
+        R3[(16 * ks + 8 * hf + kk) * LP + nl] = (bf16_t)(kk & 1 ? dw[kk >> 1] >> 16 : dw[kk >> 1] & 0xffffu);
+    }
     if (hf == 0) dden_s[nl] = dden;
     __syncthreads();
     bf16_t* dst = dHZ + ((size_t)bh * Tq + i) * HZ_ELEMS;
@@ -293,7 +306,13 @@ __global__ void __launch_bounds__(NW * 64, 1)
 #pragma unroll
       for (int ot = 0; ot < 4; ++ot)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) R3[(32 * ot + 8 * (r >> 2) + 4 * hf + (r & 3)) * LP + nl] = f32_to_bf16(ol[ot][r]);
+        for (int g = 0; g < 4; ++g) {
+          const int c0 = 32 * ot + 8 * g + 4 * hf;
+          R3[(c0 + 0) * LP + nl] = (bf16_t)(olp[ot][g].x & 0xffffu);
+          R3[(c0 + 1) * LP + nl] = (bf16_t)(olp[ot][g].x >> 16);
+          R3[(c0 + 2) * LP + nl] = (bf16_t)(olp[ot][g].y & 0xffffu);
+          R3[(c0 + 3) * LP + nl] = (bf16_t)(olp[ot][g].y >> 16);
+        }
       __syncthreads();
 #pragma unroll
       for (int a = 0; a < RT; ++a) {
