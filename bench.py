@@ -61,6 +61,9 @@ def parse():
     ap.add_argument("--quant", choices=("int8fp8", "none"), default="int8fp8",
                     help="sla workload: the paper's low-bit inference path (default) or the unquantised bf16 forward "
                          "(plain SLA, the training-time operator)")
+    ap.add_argument("--saved-state", action="store_true",
+                    help="sla_bwd workload: hand the backward pass the statistics of a training forward pass "
+                         "(sla_attention_fwd_train, run once outside the timed region) instead of recomputing them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget for the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -264,9 +267,16 @@ def main_bwd(args):
     grads = tuple(torch.empty_like(qd) for _ in range(3))
     Tq, Tk, n_c, n_m = sla.sla_block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
 
+    saved = None
+    if args.saved_state:
+        saved = sla.sla_attention_fwd_train(qd, kd, vd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                                            proj_w=Wd, workspace=ws, out=grads[0])[1]
+        torch.cuda.synchronize()
+
     def step():
         return sla.sla_attention_bwd(qd, kd, vd, dd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
-                                     proj_w=Wd, want_dw=Wd is not None, want_db=Wd is not None, workspace=ws, grads=grads)
+                                     proj_w=Wd, want_dw=Wd is not None, want_db=Wd is not None, workspace=ws, grads=grads,
+                                     saved=saved)
 
     if args.copy_calibration:
         copy_calibration(torch, dev)
@@ -298,9 +308,9 @@ def main_bwd(args):
         "metric": "sla_bwd_dense_equiv_tflops", "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16 (fp32 accumulate and statistics)", "data": "synthetic",
-        "config": {"workload": "%s backward: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0"
-                               % (cfg.name, cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio,
-                                  cfg.marginal_ratio),
+        "config": {"workload": "%s backward%s: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0"
+                               % (cfg.name, " (statistics from the forward pass)" if args.saved_state else "", cfg.B, cfg.H,
+                                  cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio),
                    "n_crit": n_c, "n_marg": n_m, "Tq": Tq, "Tk": Tk},
         "stage_ms": dict(zip(BWD_STAGE_NAMES, [round(x, 4) for x in stage_ms])),
         "roofline": {"kernel": kname, "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS,

@@ -61,6 +61,30 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
                       int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
                       void* workspace, size_t workspace_bytes, sla_stream_t stream);
 
+/* ---- Handing the forward pass's statistics over (a training step: forward, then backward) ----
+ *
+ * sla_attention_fwd_train is sla_attention_fwd with SLA_QUANT_NONE (contiguous tensors; all
+ * three feature maps) that also fills `saved` with what the backward pass would otherwise compute
+ * again: every row's log-sum-exp over its critical keys and O^s.  sla_attention_bwd_saved is
+ * sla_attention_bwd without its statistics pass: it takes them from `saved`, which must come from
+ * sla_attention_fwd_train on the same q, k, v, sizes, blocks and ratios (delta = dO . O^s is then
+ * formed from the bf16 O^s, a difference far below the tolerance of the result).
+ *   saved   device, 256-byte aligned, sla_saved_bytes(...) bytes; opaque; written by the forward
+ *           entry point, read by the backward one; NULL in sla_attention_bwd_saved = recompute
+ *           (exactly sla_attention_bwd). */
+size_t sla_saved_bytes(int B, int H, int N, int d, int block_q);
+
+int sla_attention_fwd_train(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,
+                            int block_q, int block_k, double topk_ratio, double marginal_ratio, const void* proj_w,
+                            const void* proj_b, int phi_kind, void* saved, size_t saved_bytes, void* workspace,
+                            size_t workspace_bytes, sla_stream_t stream);
+
+int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
+                            void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
+                            int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
+                            const void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes,
+                            sla_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,8 @@ EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspac
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
 W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
                 "w8a8_quantize_act", "w8a8_gemm_fwd", "w8a8_debug_unpack")
-BWD_EXPORTS = ("sla_bwd_workspace_bytes", "sla_attention_bwd")
+BWD_EXPORTS = ("sla_bwd_workspace_bytes", "sla_attention_bwd", "sla_saved_bytes", "sla_attention_fwd_train",
+               "sla_attention_bwd_saved")
 N_STAGES = 5
 STAGE_NAMES = ("pool_stats", "scores_select", "prep_kv", "lin_accumulate", "sparse_fwd")
 
@@ -92,6 +93,14 @@ def lib():
         L.sla_bwd_workspace_bytes.argtypes = [c_int] * 6 + [c_dbl, c_dbl]
         L.sla_attention_bwd.restype = c_int
         L.sla_attention_bwd.argtypes = [c_vp] * 10 + [c_int] * 6 + [c_dbl, c_dbl, c_int, c_vp, c_sz, c_vp]
+        L.sla_saved_bytes.restype = c_sz
+        L.sla_saved_bytes.argtypes = [c_int] * 5
+        L.sla_attention_fwd_train.restype = c_int
+        L.sla_attention_fwd_train.argtypes = ([c_vp] * 4 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_vp, c_int, c_vp, c_sz,
+                                              c_vp, c_sz, c_vp])
+        L.sla_attention_bwd_saved.restype = c_int
+        L.sla_attention_bwd_saved.argtypes = ([c_vp] * 10 + [c_int] * 6 + [c_dbl, c_dbl, c_int, c_vp, c_sz, c_vp, c_sz,
+                                              c_vp])
         # include/w8a8.h
         L.w8a8_weight_bytes.restype = c_sz
         L.w8a8_weight_bytes.argtypes = [c_int, c_int]
@@ -185,19 +194,47 @@ def alloc_bwd_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
+def sla_saved_bytes(B, H, N, d, block_q):
+    return lib().sla_saved_bytes(B, H, N, d, block_q)
+
+
+def sla_attention_fwd_train(q, k, v, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None, proj_b=None,
+                            phi_kind=PHI_SOFTMAX, workspace=None, out=None, saved=None):
+    """The unquantised forward pass that also keeps what the backward pass needs: returns (out, saved)."""
+    B, H, N, d = _bf16_4d(q, k, v)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    if out is None:
+        out = torch.empty_like(q)
+    if saved is None:
+        saved = torch.empty(sla_saved_bytes(B, H, N, d, block_q), dtype=torch.uint8, device=q.device)
+    st = lib().sla_attention_fwd_train(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, N, d, block_q, block_k, topk_ratio,
+                                       marginal_ratio, _ptr(proj_w), _ptr(proj_b), phi_kind, _ptr(saved), saved.numel(),
+                                       _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_attention_fwd_train")
+    return out, saved
+
+
 def sla_attention_bwd(q, k, v, dout, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None, want_dw=False,
-                      want_db=False, phi_kind=PHI_SOFTMAX, workspace=None, grads=None):
+                      want_db=False, phi_kind=PHI_SOFTMAX, workspace=None, grads=None, saved=None):
     """Returns (dq, dk, dv, dproj_w or None, dproj_b or None); dq, dk, dv bf16 [B,H,N,d], the others fp32.
-    `grads` may hand in preallocated (dq, dk, dv)."""
+    `grads` may hand in preallocated (dq, dk, dv); `saved` is the state sla_attention_fwd_train returned
+    for the same inputs (the statistics pass is then skipped)."""
     B, H, N, d = _bf16_4d(q, k, v, dout)
     if workspace is None:
         workspace = alloc_bwd_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
     dq, dk, dv = grads if grads is not None else (torch.empty_like(q), torch.empty_like(k), torch.empty_like(v))
     dw = torch.empty((d, d), dtype=torch.float32, device=q.device) if want_dw else None
     db = torch.empty((d,), dtype=torch.float32, device=q.device) if want_db else None
-    st = lib().sla_attention_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(proj_w), _ptr(dq), _ptr(dk), _ptr(dv),
-                                 _ptr(dw), _ptr(db), B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio,
-                                 phi_kind, _ptr(workspace), workspace.numel(), _stream())
+    if saved is None:
+        st = lib().sla_attention_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(proj_w), _ptr(dq), _ptr(dk), _ptr(dv),
+                                     _ptr(dw), _ptr(db), B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio,
+                                     phi_kind, _ptr(workspace), workspace.numel(), _stream())
+    else:
+        st = lib().sla_attention_bwd_saved(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(proj_w), _ptr(dq), _ptr(dk),
+                                           _ptr(dv), _ptr(dw), _ptr(db), B, H, N, d, block_q, block_k, topk_ratio,
+                                           marginal_ratio, phi_kind, _ptr(saved), saved.numel(), _ptr(workspace),
+                                           workspace.numel(), _stream())
     _check(st, "sla_attention_bwd")
     return dq, dk, dv, dw, db
 

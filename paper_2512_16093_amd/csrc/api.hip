@@ -88,6 +88,44 @@ void run_stats(const void* q, const void* k, const void* v, const void* proj_w, 
                         at<float>(ws, W.dv), (const bf16_t*)proj_w, at<bf16_t>(ws, W.wfrag), s);
 }
 
+// The unquantised forward pass (bf16 products): the launch sequence of sla_attention_fwd with
+// SLA_QUANT_NONE; save_lse2 / save_os, if given, receive what a backward pass can reuse.
+int fwd_bf16(const void* q, const void* k, const void* v, void* out, const Problem& p, const void* proj_w,
+             const void* proj_b, int phi_kind, void* ws, const Workspace& W, hipStream_t s, int rec, float* save_lse2,
+             void* save_os) {
+  const bool lin = p.n_m > 0;
+  mark(s, rec, 0);
+  run_stats(q, k, v, proj_w, p, ws, W, s);
+  mark(s, rec, 1);
+  launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
+  launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
+                lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
+  mark(s, rec, 2);
+  if (lin)
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
+                   at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+  mark(s, rec, 3);
+  if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+  mark(s, rec, 4);
+  launch_fwd_bf16(p, q, k, v, at<int32_t>(ws, W.crit), lin ? at<bf16_t>(ws, W.HZ) : nullptr, (const bf16_t*)proj_b,
+                  phi_kind, out, save_lse2, save_os, s);
+  mark(s, rec, 5);
+  return launch_status();
+}
+
+// What sla_attention_fwd_train hands to sla_attention_bwd_saved: the rows' base-2 log-sum-exp
+// (fp32, padded to whole query blocks), then O^s (bf16 [BH, N, D]).
+struct SavedState {
+  size_t lse2, os, total;
+};
+SavedState make_saved(const Problem& p) {
+  SavedState v;
+  v.lse2 = 0;
+  v.os = align256((size_t)p.BH * p.Tq * p.block_q * 4);
+  v.total = v.os + align256((size_t)p.BH * p.N * D * 2);
+  return v;
+}
+
 // Scratch of the backward pass, laid out after the forward pass's workspace map.
 struct BwdWorkspace {
   size_t lse2, delta;        // fp32 [BH, 32 T32q]
@@ -188,26 +226,8 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   void* ws = workspace;
   const bool lin = p.n_m > 0;
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
-  if (quant_mode == SLA_QUANT_NONE) {
-    mark(s, rec, 0);
-    run_stats(q, k, v, proj_w, p, ws, W, s);
-    mark(s, rec, 1);
-    launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
-    launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
-                  lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
-    mark(s, rec, 2);
-    if (lin)
-      launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
-                     at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
-    mark(s, rec, 3);
-    if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
-    mark(s, rec, 4);
-    launch_fwd_bf16(p, q, k, v, at<int32_t>(ws, W.crit), lin ? at<bf16_t>(ws, W.HZ) : nullptr, (const bf16_t*)proj_b,
-                    phi_kind, out, s);
-    mark(s, rec, 5);
-    return launch_status();
-  }
-
+  if (quant_mode == SLA_QUANT_NONE)
+    return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, ws, W, s, rec, nullptr, nullptr);
   mark(s, rec, 0);
   run_stats(q, k, v, proj_w, p, ws, W, s);
   mark(s, rec, 1);
@@ -368,15 +388,50 @@ size_t sla_bwd_workspace_bytes(int B, int H, int N, int d, int block_q, int bloc
   return make_bwd_workspace(p, make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m)).total;
 }
 
+size_t sla_saved_bytes(int B, int H, int N, int d, int block_q) {
+  Problem p;
+  if (make_problem(B, H, N, d, block_q, BK, 1.0, 0.0, &p) != SLA_OK) return 0;
+  return make_saved(p).total;
+}
+
+int sla_attention_fwd_train(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,
+                            int block_q, int block_k, double topk_ratio, double marginal_ratio, const void* proj_w,
+                            const void* proj_b, int phi_kind, void* saved, size_t saved_bytes, void* workspace,
+                            size_t workspace_bytes, sla_stream_t stream) {
+  if (!q || !k || !v || !out || !saved) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  const SavedState V = make_saved(p);
+  if ((st = check_ws(saved, saved_bytes, V.total)) != SLA_OK) return st;
+  const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
+  return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, workspace, W, (hipStream_t)stream, rec,
+                  at<float>(saved, V.lse2), at<bf16_t>(saved, V.os));
+}
+
 int sla_attention_bwd(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
                       void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
                       int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
                       void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  return sla_attention_bwd_saved(q, k, v, dout, proj_w, dq, dk, dv, dproj_w, dproj_b, B, H, N, d, block_q, block_k,
+                                 topk_ratio, marginal_ratio, phi_kind, nullptr, 0, workspace, workspace_bytes, stream);
+}
+
+int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
+                            void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
+                            int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
+                            const void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes,
+                            sla_stream_t stream) {
   if (!q || !k || !v || !dout || !dq || !dk || !dv) return SLA_ERR_NULL;
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
   if (phi_kind != SLA_PHI_SOFTMAX) return SLA_ERR_UNSUPPORTED;
+  const SavedState V = make_saved(p);
+  if (saved && (st = check_ws(saved, saved_bytes, V.total)) != SLA_OK) return st;
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
   const BwdWorkspace X = make_bwd_workspace(p, W);
   if ((st = check_ws(workspace, workspace_bytes, X.total)) != SLA_OK) return st;
@@ -392,7 +447,13 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
   launch_select(p, at<float>(ws, W.scores), at<int8_t>(ws, W.mask), at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 1);
-  launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
+  const float* lse2 = at<float>(ws, X.lse2);
+  if (saved) {  // the forward pass's statistics: only delta = dO . O^s is left to do
+    lse2 = (const float*)((const unsigned char*)saved + V.lse2);
+    launch_bwd_delta(p, dout, (const unsigned char*)saved + V.os, at<float>(ws, X.delta), s);
+  } else {
+    launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
+  }
   mark(s, rec, 2);
   float* dw_eff = dproj_w ? dproj_w : (dproj_b ? at<float>(ws, X.dw_scratch) : nullptr);
   if (dproj_w) launch_zero_u32((uint32_t*)dproj_w, (size_t)D * D, s);
@@ -416,10 +477,10 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
     launch_bwd_lin_k(p, k, v, at<bf16_t>(ws, W.hz), at<float>(ws, X.dkl), at<float>(ws, X.dvl), s);
   }
   mark(s, rec, 3);
-  launch_bwd_dq(p, q, dout, k, v, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta),
+  launch_bwd_dq(p, q, dout, k, v, at<int32_t>(ws, W.crit), lse2, at<float>(ws, X.delta),
                 lin ? at<float>(ws, X.dql) : nullptr, dq, s);
   mark(s, rec, 4);
-  launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), at<float>(ws, X.lse2), at<float>(ws, X.delta),
+  launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), lse2, at<float>(ws, X.delta),
                  lin ? at<float>(ws, X.dkl) : nullptr, lin ? at<float>(ws, X.dvl) : nullptr, dk, dv, s);
   mark(s, rec, 5);
   return launch_status();

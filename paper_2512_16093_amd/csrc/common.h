@@ -175,7 +175,9 @@ void launch_marginal_bits_t(const Problem& p, const int8_t* mask, uint32_t* mbit
 void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
                       const int32_t* crit, float* lse2, float* delta, hipStream_t stream);
 void launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
-                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, hipStream_t stream);
+                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
+                     hipStream_t stream);
+void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float* delta, hipStream_t stream);
 void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,

@@ -136,6 +136,8 @@ struct FwdEpilogue {
   const bf16_t* bias;  // [D] or nullptr
   bf16_t* out;         // [BH, N, D]
   int phi;
+  float* save_lse2;    // [BH, 32 T32q] or nullptr: the rows' log-sum-exp (base 2), as bwd_stats_kernel<.., false> writes it
+  bf16_t* save_os;     // [BH, N, D] or nullptr: O^s alone (for delta = dO . O^s of a later backward pass)
 };
 template <int NW, bool FWD>
 __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
@@ -246,6 +248,17 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[ct][r] *= inv_l;
+    if (fe.save_lse2) {  // what a backward pass needs of this one
+      if (hf == 0) fe.save_lse2[(size_t)bh * dm.T32q * 32 + 32 * T + l32] = (qok && dm.n_c > 0) ? m + __builtin_amdgcn_logf(l) : INFINITY;
+      if (qok) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            *(uint2*)(fe.save_os + head + qrow * D + 32 * ct + 8 * g + 4 * hf) =
+                uint2{pack_bf16x2(o[ct][4 * g], o[ct][4 * g + 1]), pack_bf16x2(o[ct][4 * g + 2], o[ct][4 * g + 3])};
+      }
+    }
     if (fe.HZ) {
       // linear term, transposed like everything else: O_l^T[o][n] = sum_c H'[c][o] phi(Q)[n][c]; the
       // stored chunks of H' are this product's A operand, phi(Q) follows their channel order
@@ -655,7 +668,7 @@ void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   static const bool ok = allow_lds(bwd_stats_kernel<4, false>) && allow_lds(bwd_stats_kernel<2, false>);
   if (!ok) return;  // (the launch below would fail the same way and be reported by the caller's status check)
-  const FwdEpilogue none{nullptr, nullptr, nullptr, 0};
+  const FwdEpilogue none{nullptr, nullptr, nullptr, 0, nullptr, nullptr};
   if (p.block_q == 128)
     bwd_stats_kernel<4, false><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
                                                                       (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
@@ -666,17 +679,47 @@ void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void
 
 // The unquantised forward pass: the same kernel with the output epilogue.
 void launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
-                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, hipStream_t stream) {
+                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
+                     hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   static const bool ok = allow_lds(bwd_stats_kernel<4, true>) && allow_lds(bwd_stats_kernel<2, true>);
   if (!ok) return;
-  const FwdEpilogue fe{HZ, HZ ? proj_b : nullptr, (bf16_t*)out, phi_kind};
+  const FwdEpilogue fe{HZ, HZ ? proj_b : nullptr, (bf16_t*)out, phi_kind, save_lse2, (bf16_t*)save_os};
   if (p.block_q == 128)
     bwd_stats_kernel<4, true><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr,
                                                                      crit, nullptr, nullptr, bwd_dims(p), fe);
   else
     bwd_stats_kernel<2, true><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr,
                                                                      crit, nullptr, nullptr, bwd_dims(p), fe);
+}
+
+// delta[bh][row] = dO[row] . O^s[row] from a saved O^s (rows beyond N: 0); one wavefront per 8 rows.
+__global__ void __launch_bounds__(256) bwd_delta_kernel(const bf16_t* __restrict__ dout, const bf16_t* __restrict__ os,
+                                                        float* __restrict__ delta, int N, int rows_padded, int BH) {
+  const long long gr = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);  // padded row index over all heads
+  if (gr >= (long long)BH * rows_padded) return;
+  const int bh = (int)(gr / rows_padded), row = (int)(gr - (long long)bh * rows_padded), part = threadIdx.x & 7;
+  float s = 0.f;
+  if (row < N) {
+    const size_t off = ((size_t)bh * N + row) * D + 16 * part;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint4 a = *(const uint4*)(dout + off + 8 * h), b = *(const uint4*)(os + off + 8 * h);
+      s += bf16_lo(a.x) * bf16_lo(b.x) + bf16_hi(a.x) * bf16_hi(b.x) + bf16_lo(a.y) * bf16_lo(b.y) + bf16_hi(a.y) * bf16_hi(b.y) +
+           bf16_lo(a.z) * bf16_lo(b.z) + bf16_hi(a.z) * bf16_hi(b.z) + bf16_lo(a.w) * bf16_lo(b.w) + bf16_hi(a.w) * bf16_hi(b.w);
+    }
+  }
+  s += __shfl_xor(s, 1);
+  s += __shfl_xor(s, 2);
+  s += __shfl_xor(s, 4);
+  if (part == 0) delta[gr] = s;
+}
+
+void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float* delta, hipStream_t stream) {
+  const int rows_padded = p.Tq * p.block_q;
+  const long long total = (long long)p.BH * rows_padded;
+  bwd_delta_kernel<<<(unsigned)((total + 31) / 32), 256, 0, stream>>>((const bf16_t*)dout, (const bf16_t*)os, delta, p.N,
+                                                                     rows_padded, p.BH);
 }
 
 void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,

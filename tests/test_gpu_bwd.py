@@ -105,6 +105,34 @@ def test_backward_batch_of_two():
     _compare("dproj_b", db.cpu().numpy(), sums_b)
 
 
+@pytest.mark.parametrize("H,grid,bq,rc,rm", [(2, (5, 10, 20), 128, 0.25, 0.5), (2, (3, 9, 11), 64, 0.3, 0.4)])
+def test_backward_from_the_forward_pass_saved_state(H, grid, bq, rc, rm):
+    """sla_attention_fwd_train gives the same output as the unquantised forward and a state with which
+    sla_attention_bwd_saved matches the oracle to the same bar as the self-contained backward (and
+    agrees with it closely: the only difference is delta formed from the bf16 O^s)."""
+    cfg = synth.custom_config(1, H, grid, block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=True, cfg_id=302)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=5)[2]
+    W = synth.make_proj(cfg)
+    dev = torch.device("cuda:0")
+    qd, kd, vd, dd, Wd = (t.to(dev) for t in (q, k, v, dout, W))
+    out, saved = sla.sla_attention_fwd_train(qd, kd, vd, bq, 64, rc, rm, proj_w=Wd)
+    ref_out = sla.sla_attention_fwd(qd, kd, vd, bq, 64, rc, rm, proj_w=Wd, quant_mode=sla.QUANT_NONE)
+    assert torch.equal(out, ref_out)
+    mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
+    a = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True, saved=saved)
+    b = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a[:3], b[:3]):
+        x, y = x.float(), y.float()
+        assert (x - y).abs().max() <= 2e-2 * y.abs().max()
+    for h in range(H):
+        r = bo.sla_backward_head(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
+                                 synth.as_f64(dout[0, h]), mask[0, h], bq, 64, proj_w=synth.as_f64(W), has_bias=True)
+        for name, got in (("dQ", a[0]), ("dK", a[1]), ("dV", a[2])):
+            _compare(name, got[0, h].float().cpu().numpy(), r[name])
+
+
 def test_backward_argument_errors():
     dev = torch.device("cuda:0")
     x = torch.zeros((1, 1, 128, 128), dtype=torch.bfloat16, device=dev)

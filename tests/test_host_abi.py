@@ -60,6 +60,18 @@ def test_backward_sizes_and_argument_errors():
     assert L.sla_attention_bwd(*args(phi=1)) == sla.ERR_UNSUPPORTED
     assert L.sla_attention_bwd(*args(ws=None)) == sla.ERR_WORKSPACE
     assert L.sla_attention_bwd(*args(bytes=bwd - 1)) == sla.ERR_WORKSPACE
+    # the saved state: padded per-row statistics plus a bf16 copy of O^s
+    sv = sla.sla_saved_bytes(1, 2, 1000, 128, 128)
+    assert sv == (2 * 1024 * 4 + 255) // 256 * 256 + (2 * 1000 * 128 * 2 + 255) // 256 * 256
+    assert sla.sla_saved_bytes(1, 2, 1000, 64, 128) == 0 and sla.sla_saved_bytes(1, 2, 1000, 128, 96) == 0
+    a = args()
+    assert L.sla_attention_bwd_saved(*a[:19], WS, sv - 1, *a[19:]) == sla.ERR_WORKSPACE
+    assert L.sla_attention_bwd_saved(*a[:19], ctypes.c_void_p(0x10010), sv, *a[19:]) == sla.ERR_WORKSPACE
+    f = [FAKE, FAKE, FAKE, FAKE, 1, 2, 1000, 128, 128, 64, 0.25, 0.5, None, None, 0]
+    assert L.sla_attention_fwd_train(*f, None, sv, WS, big, None) == sla.ERR_NULL
+    assert L.sla_attention_fwd_train(*f, WS, sv - 1, WS, big, None) == sla.ERR_WORKSPACE
+    assert L.sla_attention_fwd_train(*f, WS, sv, WS, 16, None) == sla.ERR_WORKSPACE
+    assert L.sla_attention_fwd_train(*(f[:14] + [9]), WS, sv, WS, big, None) == sla.ERR_UNSUPPORTED
 
 
 def test_w8a8_sizes_and_argument_errors():
