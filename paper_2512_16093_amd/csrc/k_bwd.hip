@@ -160,7 +160,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
   v16f o[4];
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) o[ct] = v16f{};
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY;
+  v16f lacc = v16f{};  // register 0: the running sum of P over the keys (see the ones operand below)
   // key blocks travel memory -> registers -> LDS one step ahead, into the buffer the step before
   // last has left: one barrier per step
   if (dm.n_c > 0) {
@@ -192,36 +193,36 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
       __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
       if (64 * j + 64 <= dm.N) {  // (uniform) only the sequence's last key block can hold keys that do not exist
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          s[kt][r] *= QK_LOG2;
-          mx = fmaxf(mx, s[kt][r]);
-        }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
       } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = 64 * j + 32 * kt + 8 * (r >> 2) + 4 * hf + (r & 3);
-          s[kt][r] = key < dm.N ? s[kt][r] * QK_LOG2 : -INFINITY;
+          if (key >= dm.N) s[kt][r] = -INFINITY;
           mx = fmaxf(mx, s[kt][r]);
         }
       }
     }
-    mx = fmaxf(mx, partner_f32(mx));
-    const float m_new = fmaxf(m, mx);           // finite: a block holds at least one valid key
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-    m = m_new;
-    float rs = 0.f;
+    // The reference m moves only when the block's maximum exceeds it by more than 2^8: P then stays
+    // below 2^8 (harmless in bf16 and fp32) and the accumulators are rescaled a few times per row
+    // instead of every step.  (mx is finite: a block holds at least one valid key.)
+    mx = fmaxf(mx, partner_f32(mx)) * QK_LOG2;
+    const bool moves = mx > m + 8.0f;
+    if (__any(moves)) {
+      const float m_new = moves ? mx : m;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      m = m_new;
+      lacc[0] *= alpha;
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[ct][r] *= alpha;
+    }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        s[kt][r] = __builtin_amdgcn_exp2f(s[kt][r] - m_new);
-        rs += s[kt][r];
-      }
-    lsum = lsum * alpha + rs;
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[ct][r] *= alpha;
+      for (int r = 0; r < 16; ++r) s[kt][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], QK_LOG2, -m));
+    const uint4 ones = uint4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};  // bf16 1.0: sums P over the keys
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -232,8 +233,9 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
         for (int ct = 0; ct < 4; ++ct) tv[ct] = t_op(lds + (2 + kt) * TILE_B, tr_off, ct, sx);
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) o[ct] = mfma_bf16(tv[ct], pb, o[ct]);
+        lacc = mfma_bf16(ones, pb, lacc);  // every row of this tile = the key sum of P (as rounded for the product above)
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 5, 0);
       }
     if (b + 1 < dm.n_c) {
       sk.store(lds_next, t);
@@ -241,7 +243,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     }
     __syncthreads();
   }
-  const float l = lsum + partner_f32(lsum);
+  const float l = lacc[0];
   if constexpr (FWD) {
     const float inv_l = dm.n_c > 0 ? 1.0f / l : 0.f;
 #pragma unroll
