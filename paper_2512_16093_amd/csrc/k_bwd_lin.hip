@@ -468,7 +468,21 @@ size_t bwd_lin_q_lds_bytes() { return (size_t)4 * 128 * LP * 2 + 128 * 4 + 128 *
 
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
                      float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
-  const int chunks = p.Tq < 16 ? p.Tq : 16;
+  // workgroups per head: enough of them to fill the compute units a whole number of times where
+  // that is possible (one workgroup per unit), few enough that the dW, db atomics stay cheap
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    n_cu = v;
+  }
+  int chunks = 16;
+  for (int c = 16; c <= 64; ++c)
+    if ((long long)c * p.BH % n_cu == 0) {
+      chunks = c;
+      break;
+    }
+  if (chunks > p.Tq) chunks = p.Tq;
   const dim3 grid((unsigned)chunks, (unsigned)p.BH);
   const size_t lds = bwd_lin_q_lds_bytes();
   static bool attr_set = false;
