@@ -129,7 +129,7 @@ SavedState make_saved(const Problem& p) {
 // Scratch of the backward pass, laid out after the forward pass's workspace map.
 struct BwdWorkspace {
   size_t lse2, delta;        // fp32 [BH, 32 T32q]
-  size_t dql, dkl, dvl;      // fp32 [BH, N, D]: the linear branch's share of dQ, dK, dV
+  size_t dql;                // fp32 [BH, N, D]: the linear branch's share of dQ
   size_t dHZ;                // bf16 [BH, Tq, HZ_ROWS, D]: per query block dH^T and dZ
   size_t mbits_t;            // transposed marginal bit matrix
   size_t wt;                 // bf16 [D, D]: W^T
@@ -145,7 +145,7 @@ BwdWorkspace make_bwd_workspace(const Problem& p, const Workspace& W) {
   b.lse2 = take(BH * T32q * 32 * 4); b.delta = take(BH * T32q * 32 * 4);
   const bool lin = p.n_m > 0;
   const size_t grad = lin ? BH * (size_t)p.N * D * 4 : 0;
-  b.dql = take(grad); b.dkl = take(grad); b.dvl = take(grad);
+  b.dql = take(grad);
   b.dHZ = take(lin ? BH * (size_t)p.Tq * HZ_ELEMS * 2 : 0);
   b.mbits_t = take(lin ? marginal_bits_t_bytes(p) : 0);
   b.wt = take(D * D * 2);
@@ -474,14 +474,13 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
     pt.Tk = p.Tq;
     launch_marginal_bits_t(p, at<int8_t>(ws, W.mask), at<uint32_t>(ws, X.mbits_t), s);
     launch_lin_accumulate(pt, at<uint32_t>(ws, X.mbits_t), at<bf16_t>(ws, X.dHZ), at<bf16_t>(ws, W.hz), s);
-    launch_bwd_lin_k(p, k, v, at<bf16_t>(ws, W.hz), at<float>(ws, X.dkl), at<float>(ws, X.dvl), s);
   }
   mark(s, rec, 3);
   launch_bwd_dq(p, q, dout, k, v, at<int32_t>(ws, W.crit), lse2, at<float>(ws, X.delta),
                 lin ? at<float>(ws, X.dql) : nullptr, dq, s);
   mark(s, rec, 4);
   launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), lse2, at<float>(ws, X.delta),
-                 lin ? at<float>(ws, X.dkl) : nullptr, lin ? at<float>(ws, X.dvl) : nullptr, dk, dv, s);
+                 lin ? at<bf16_t>(ws, W.hz) : nullptr, dk, dv, s);
   mark(s, rec, 5);
   return launch_status();
 }

@@ -181,13 +181,10 @@ void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float*
 void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
-                    const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
-                    hipStream_t stream);
+                    const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream);
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
                      float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream);
-void launch_bwd_lin_k(const Problem& p, const void* k, const void* v, const bf16_t* G, float* dk_lin, float* dv_lin,
-                      hipStream_t stream);
 void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream);
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
                           uint8_t* v_codes, hipStream_t stream);

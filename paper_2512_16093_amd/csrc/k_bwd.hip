@@ -471,6 +471,112 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
   }
 }
 
+// The linear branch's share of dK and dV for the 32 keys of a wavefront (Section 1.2's operator:
+// h_j = phi(K_j)^T V_j, z_j = column sums of phi(K_j), phi = softmax over the channels), given
+// G_j = the sum of dH_i over the query blocks that hold key block j as marginal, and the same sum
+// of dZ_i, in the summaries' storage order (hz_frag_chunk):
+//     d phi(K)^T[c][n] = sum_o G[c][o] V[n][o] + dZ[c]   ->  dK[n] = phi o (d phi - phi . d phi)
+//     dV^T[o][n]       = sum_c G[c][o] phi(K)[n][c]
+// Called by every thread of the workgroup (NT of them): G_j is staged in LDS transposed (gc,
+// 128 rows of GP elements; gz, 128 floats); both barriers are inside.  Results in the accumulator
+// layout of the sparse-branch kernels (lane = key, registers = channels).
+constexpr int GP = 136;  // row pitch of the staged G (elements)
+template <int NT>
+__device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, size_t row,
+                                                bool ok, const bf16_t* __restrict__ rec, bf16_t* gc, float* gz, int t,
+                                                int lane, v16f (&dk_share)[4], v16f (&dv_share)[4]) {
+  const int l32 = lane & 31, hf = lane >> 5;
+  for (int x = t; x < 2048; x += NT) {
+    const int ln = x & 63, ks = (x >> 6) & 7, ot = x >> 9;
+    const int o = 32 * ot + (ln & 31), c0 = 32 * (ks >> 1) + 16 * (ln >> 5) + 8 * (ks & 1);
+    const uint4 val = *(const uint4*)(rec + (size_t)x * 8);
+    const uint32_t wv[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) gc[(c0 + e) * GP + o] = (bf16_t)(e & 1 ? wv[e >> 1] >> 16 : wv[e >> 1] & 0xffffu);
+  }
+  if (t < 128) gz[t] = bf16_to_f32(rec[128 * 128 + t]);
+  __syncthreads();
+  // phi(K[n]) at the channels the storage order feeds per step: 32 (ks / 2) + 16 hf + 8 (ks % 2) + kk
+  float cv[64];
+  uint4 cf[8], vf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    uint4 kv = uint4{0u, 0u, 0u, 0u};
+    vf[ks] = kv;
+    if (ok) {
+      kv = *(const uint4*)(k + row + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
+      vf[ks] = *(const uint4*)(v + row + 16 * ks + 8 * hf);
+    }
+    cv[8 * ks] = bf16_lo(kv.x); cv[8 * ks + 1] = bf16_hi(kv.x); cv[8 * ks + 2] = bf16_lo(kv.y); cv[8 * ks + 3] = bf16_hi(kv.y);
+    cv[8 * ks + 4] = bf16_lo(kv.z); cv[8 * ks + 5] = bf16_hi(kv.z); cv[8 * ks + 6] = bf16_lo(kv.w); cv[8 * ks + 7] = bf16_hi(kv.w);
+  }
+  float kmax = cv[0];
+#pragma unroll
+  for (int e = 1; e < 64; ++e) kmax = fmaxf(kmax, cv[e]);
+  kmax = fmaxf(kmax, partner_f32(kmax));
+  float sum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 64; ++e) {
+    cv[e] = __builtin_amdgcn_exp2f((cv[e] - kmax) * LOG2E);
+    sum += cv[e];
+  }
+  sum += partner_f32(sum);
+  const float rsum = ok ? 1.0f / sum : 0.f;  // keys beyond the sequence take no part
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) cv[8 * ks + kk] *= rsum;
+    cf[ks] = uint4{pack_bf16x2(cv[8 * ks], cv[8 * ks + 1]), pack_bf16x2(cv[8 * ks + 2], cv[8 * ks + 3]),
+                   pack_bf16x2(cv[8 * ks + 4], cv[8 * ks + 5]), pack_bf16x2(cv[8 * ks + 6], cv[8 * ks + 7])};
+  }
+#pragma unroll
+  for (int ot = 0; ot < 4; ++ot) {
+    uint4 ag[8], ac[8];  // operand reads grouped ahead of the matrix products
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      ag[ks] = *(const uint4*)(rec + (size_t)hz_frag_chunk(ot, ks, lane) * 8);  // the stored chunks are this product's A operand as they are
+      ac[ks] = *(const uint4*)(gc + (32 * ot + l32) * GP + 16 * ks + 8 * hf);
+    }
+    dv_share[ot] = v16f{};
+    dk_share[ot] = v16f{};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      dv_share[ot] = mfma_bf16(ag[ks], cf[ks], dv_share[ot]);
+      dk_share[ot] = mfma_bf16(ac[ks], vf[ks], dk_share[ot]);  // d phi(K)^T for now
+    }
+    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+  }
+  // through the softmax: phi at the accumulator's channels 32 ct + 8 g + 4 hf + e, from K again
+  float sdot = 0.f;
+  uint2 kw[4][4];
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int c0 = 32 * ct + 8 * g + 4 * hf;
+      kw[ct][g] = ok ? *(const uint2*)(k + row + c0) : uint2{0u, 0u};
+      const float xk[4] = {bf16_lo(kw[ct][g].x), bf16_hi(kw[ct][g].x), bf16_lo(kw[ct][g].y), bf16_hi(kw[ct][g].y)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        dk_share[ct][4 * g + e] += gz[c0 + e];
+        sdot += __builtin_amdgcn_exp2f((xk[e] - kmax) * LOG2E) * rsum * dk_share[ct][4 * g + e];
+      }
+    }
+  sdot += partner_f32(sdot);
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float xk[4] = {bf16_lo(kw[ct][g].x), bf16_hi(kw[ct][g].x), bf16_lo(kw[ct][g].y), bf16_hi(kw[ct][g].y)};
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        dk_share[ct][4 * g + e] = __builtin_amdgcn_exp2f((xk[e] - kmax) * LOG2E) * rsum * (dk_share[ct][4 * g + e] - sdot);
+    }
+  __syncthreads();  // the staged G is consumed: the caller may reuse the LDS
+}
+
 // One workgroup of four wavefronts per PAIR of adjacent key blocks (2 J, 2 J + 1): wavefronts 0, 1
 // own the two key tiles of the first block, wavefronts 2, 3 those of the second (one key per lane
 // pair).  The workgroup walks over the query blocks that hold either block as critical (found from
@@ -483,9 +589,9 @@ template <int KB, int TILES>
 __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
                                                       const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
-                                                      const float* __restrict__ delta, const float* __restrict__ dk_lin,
-                                                      const float* __restrict__ dv_lin, bf16_t* __restrict__ dk,
-                                                      bf16_t* __restrict__ dv, int pair_shift, BwdDims dm) {
+                                                      const float* __restrict__ delta, const bf16_t* __restrict__ G,
+                                                      bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, int pair_shift,
+                                                      BwdDims dm) {
   constexpr int NT = 128 * KB, ROWS = 32 * TILES;  // threads; query rows per step
   // two buffers of: Q (TILES tiles) then dO (TILES tiles) of ROWS consecutive query rows; then their lse, delta
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -524,11 +630,26 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
   uint4 kf[8], vf[8];
   own_rows(k + head, key, dm.N, hf, kf);
   own_rows(v + head, key, dm.N, hf, vf);
+  // the accumulators start from the linear branch's share (G = nullptr: there is none); dK is scaled
+  // by 1 / sqrt(d) at the end, so its share goes in multiplied by sqrt(d)
   v16f dkt[4], dvt[4];
+  if (G) {
+    // each key block's two wavefronts stage its G_j in their own part of the (still unused) staging buffers
+    constexpr int LIN_B = 128 * GP * 2 + 128 * 4;
+    static_assert(KB * LIN_B <= 2 * BUF_B, "the staged G fits in the staging buffers");
+    const int jb = min(KB * J + half, dm.Tk - 1);  // (the missing second block of an odd last pair: its keys do not exist)
+    linear_kv_share<128>(k + head, v + head, (size_t)(kok ? key : 0) * D, kok, G + ((size_t)bh * dm.Tk + jb) * HZ_ELEMS,
+                         (bf16_t*)(lds + half * LIN_B), (float*)(lds + half * LIN_B + 128 * GP * 2), t & 127, lane, dkt, dvt);
 #pragma unroll
-  for (int ct = 0; ct < 4; ++ct) {
-    dkt[ct] = v16f{};
-    dvt[ct] = v16f{};
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dkt[ct][r] *= 11.313708498984761f;
+  } else {
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+      dkt[ct] = v16f{};
+      dvt[ct] = v16f{};
+    }
   }
   // Steps = (list entry, pair of tiles of its query block): 64 query rows at a time.  They travel
   // memory -> registers -> LDS: while step s is computed from one LDS buffer, step s + 1 is moved from
@@ -648,10 +769,9 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int ch = 32 * ct + 8 * g + 4 * hf;
-        store_grad4(dk + row + ch, dk_lin ? dk_lin + row + ch : nullptr, dkt[ct][4 * g] * INV_SQRT_D,
-                    dkt[ct][4 * g + 1] * INV_SQRT_D, dkt[ct][4 * g + 2] * INV_SQRT_D, dkt[ct][4 * g + 3] * INV_SQRT_D);
-        store_grad4(dv + row + ch, dv_lin ? dv_lin + row + ch : nullptr, dvt[ct][4 * g], dvt[ct][4 * g + 1],
-                    dvt[ct][4 * g + 2], dvt[ct][4 * g + 3]);
+        store_grad4(dk + row + ch, nullptr, dkt[ct][4 * g] * INV_SQRT_D, dkt[ct][4 * g + 1] * INV_SQRT_D,
+                    dkt[ct][4 * g + 2] * INV_SQRT_D, dkt[ct][4 * g + 3] * INV_SQRT_D);
+        store_grad4(dv + row + ch, nullptr, dvt[ct][4 * g], dvt[ct][4 * g + 1], dvt[ct][4 * g + 2], dvt[ct][4 * g + 3]);
       }
   }
 }
@@ -739,8 +859,7 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
 
 constexpr int DKV1_TILES = 1;  // tiles per step of the one-key-block variant (2 measured the same and needs 80 KB of LDS per workgroup)
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
-                    const float* lse2, const float* delta, const float* dk_lin, const float* dv_lin, void* dk, void* dv,
-                    hipStream_t stream) {
+                    const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
   // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
   const int list_bytes = (2 * p.Tq + 15) & ~15;
   const int lds2 = 2 * 4 * TILE_B + 2 * 2 * 64 * 4 + list_bytes;
@@ -750,15 +869,18 @@ void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const voi
       hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
   if (!ok) return;
   const int tiles = p.block_q / 32;  // of a query block: 2 or 4
-  const bool paired = false;
+  // Two key blocks per workgroup halve the bytes streamed where their lists coincide and idle half
+  // a workgroup where they do not: worth it only when most blocks are critical (at the paper's
+  // 10-15 % the lists of neighbours share 60 % and one key block per workgroup is 25 % faster).
+  const bool paired = 2 * p.n_c > p.Tk;
   if (paired) {
     const int pairs = (p.Tk + 1) / 2;
     bwd_dkv_kernel<2, 2><<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds2, stream>>>(
-        (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
+        (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 1 : 0, bwd_dims(p));
   } else {
     bwd_dkv_kernel<1, DKV1_TILES><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
-        (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, dk_lin, dv_lin,
+        (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, (tiles == 4 ? 2 : 1) - (DKV1_TILES == 2 ? 1 : 0), bwd_dims(p));
   }
 }

@@ -8,8 +8,8 @@
 //                      d phi(Q) = dnum H_i^T + dden Z_i -> dQ (softmax backward), and the block's
 //                      dH_i = a^T dnum, dZ_i = a^T dden, written in the summaries' storage order so
 //                      that the forward's accumulation kernel can sum them over the transposed mask.
-//   bwd_lin_k_kernel   per key block j, with G_j = sum_{i : j marginal for i} dH_i (and the dZ sum):
-//                      d phi(K) = V G_j^T + dZ -> dK (softmax backward),  dV = phi(K) G_j.
+//   (the key side -- per key block j, with G_j = sum_{i : j marginal for i} dH_i and the dZ sum:
+//   d phi(K) = V G_j^T + dZ -> dK, dV = phi(K) G_j -- is the prologue of the dK/dV kernel, k_bwd.hip)
 //
 // As in the sparse-branch kernels a wavefront owns 32 tokens, one per lane pair, and every product
 // is formed with the tokens as accumulator columns, so per-token reductions stay in a lane pair.
@@ -357,108 +357,6 @@ __global__ void __launch_bounds__(NW * 64, 1)
   }
 }
 
-__global__ void __launch_bounds__(128) bwd_lin_k_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
-                                                        const bf16_t* __restrict__ G, float* __restrict__ dk_lin,
-                                                        float* __restrict__ dv_lin, int N, int Tk) {
-  __shared__ __attribute__((aligned(16))) bf16_t Gc[128 * LP];  // G[c][o], o contiguous
-  __shared__ float gz[128];
-  const int j = blockIdx.x, bh = blockIdx.y, t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
-  const bf16_t* rec = G + ((size_t)bh * Tk + j) * HZ_ELEMS;
-  for (int x = t; x < 2048; x += 128) {
-    const int ln = x & 63, ks = (x >> 6) & 7, ot = x >> 9;
-    const int o = 32 * ot + (ln & 31), c0 = 32 * (ks >> 1) + 16 * (ln >> 5) + 8 * (ks & 1);
-    const uint4 val = *(const uint4*)(rec + (size_t)x * 8);
-    const uint32_t wv[4] = {val.x, val.y, val.z, val.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) Gc[(c0 + e) * LP + o] = (bf16_t)(e & 1 ? wv[e >> 1] >> 16 : wv[e >> 1] & 0xffffu);
-  }
-  gz[t] = bf16_to_f32(rec[128 * 128 + t]);
-  __syncthreads();
-
-  const long long n = 64ll * j + 32 * w + l32;
-  const bool ok = n < N;
-  const size_t row = ((size_t)bh * N + (ok ? n : 0)) * D;
-  // phi(K[n]) at the channels the summaries' storage order feeds per step: 32 (ks/2) + 16 hf + 8 (ks%2) + kk
-  float cv[64];
-  uint4 cf[8], vf[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    uint4 kv = uint4{0u, 0u, 0u, 0u};
-    vf[ks] = kv;
-    if (ok) {
-      kv = *(const uint4*)(k + row + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
-      vf[ks] = *(const uint4*)(v + row + 16 * ks + 8 * hf);
-    }
-    unpack8(kv, &cv[8 * ks]);
-  }
-  float kmax, rsum;
-  softmax_stats(cv, kmax, rsum);
-  if (!ok) rsum = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) cv[8 * ks + kk] *= rsum;
-    cf[ks] = pack8(&cv[8 * ks]);
-  }
-  // dV^T[o][n] = sum_c G[c][o] phi(K)[n][c]: the stored chunks are this product's A operand as they are
-  v16f dvt[4], dct[4];
-#pragma unroll
-  for (int ot = 0; ot < 4; ++ot) {
-    uint4 ag[8], ac[8];  // operand reads grouped ahead of the matrix products
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      ag[ks] = *(const uint4*)(rec + (size_t)hz_frag_chunk(ot, ks, lane) * 8);
-      ac[ks] = lds_frag(Gc, 32 * ot + l32, 16 * ks + 8 * hf);
-    }
-    dvt[ot] = v16f{};
-    dct[ot] = v16f{};
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      dvt[ot] = mfma_bf16(ag[ks], cf[ks], dvt[ot]);
-      // d phi(K)^T[c][n] = sum_o G[c][o] V[n][o]
-      dct[ot] = mfma_bf16(ac[ks], vf[ks], dct[ot]);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);   // 8 global reads
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);   // 8 LDS reads
-    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);  // 16 matrix products
-  }
-  float cd[4][16];
-  float sdot = 0.f;
-#pragma unroll
-  for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int c0 = 32 * ct + 8 * g + 4 * hf;
-      uint2 kv = uint2{0u, 0u};
-      if (ok) kv = *(const uint2*)(k + row + c0);
-      const float xk[4] = {bf16_lo(kv.x), bf16_hi(kv.x), bf16_lo(kv.y), bf16_hi(kv.y)};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float c = __builtin_amdgcn_exp2f((xk[e] - kmax) * LOG2E) * rsum;
-        cd[ct][4 * g + e] = c;
-        dct[ct][4 * g + e] += gz[c0 + e];
-        sdot += c * dct[ct][4 * g + e];
-      }
-    }
-  sdot += partner_f32(sdot);
-  if (ok) {
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int c0 = 32 * ct + 8 * g + 4 * hf;
-        float4 a, b;
-        a.x = cd[ct][4 * g] * (dct[ct][4 * g] - sdot);
-        a.y = cd[ct][4 * g + 1] * (dct[ct][4 * g + 1] - sdot);
-        a.z = cd[ct][4 * g + 2] * (dct[ct][4 * g + 2] - sdot);
-        a.w = cd[ct][4 * g + 3] * (dct[ct][4 * g + 3] - sdot);
-        b.x = dvt[ct][4 * g]; b.y = dvt[ct][4 * g + 1]; b.z = dvt[ct][4 * g + 2]; b.w = dvt[ct][4 * g + 3];
-        *(float4*)(dk_lin + row + c0) = a;
-        *(float4*)(dv_lin + row + c0) = b;
-      }
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream) {
   bwd_wt_kernel<<<64, 256, 0, stream>>>(proj_w, wt);
@@ -497,12 +395,6 @@ int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf
   else
     bwd_lin_q_kernel<2><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
   return 0;
-}
-
-void launch_bwd_lin_k(const Problem& p, const void* k, const void* v, const bf16_t* G, float* dk_lin, float* dv_lin,
-                      hipStream_t stream) {
-  bwd_lin_k_kernel<<<dim3((unsigned)p.Tk, (unsigned)p.BH), 128, 0, stream>>>((const bf16_t*)k, (const bf16_t*)v, G, dk_lin,
-                                                                           dv_lin, p.N, p.Tk);
 }
 
 }  // namespace sla

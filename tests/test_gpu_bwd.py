@@ -31,6 +31,8 @@ CASES = [
     (1, (1, 9, 9), 128, 0.5, 0.5, True),       # N = 81: one ragged query block, two key blocks
     (1, (1, 5, 5), 64, 1.0, 0.0, False),       # N = 25: a single short block, dense attention
     (1, (4, 16, 16), 64, 0.15, 0.85, True),    # N = 1024: whole blocks, no negligible block
+    (2, (5, 10, 20), 128, 0.75, 0.25, True),   # most blocks critical: the dK/dV kernel's two-key-block variant
+    (1, (3, 27, 27), 64, 0.6, 0.0, False),     # the same with an odd number of key blocks (35) and no linear term
 ]
 
 
