@@ -97,7 +97,7 @@ def make_inputs(cfg, synth, torch):
     return q, k, v
 
 
-def cpu_baseline(cfg, q, k, v, W, budget_s):
+def cpu_baseline(cfg, q, k, v, W, budget_s, low_bit=True):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload:
     head 0 in full for the per-head work (pooling, scores, classification, quantisation,
     linear summaries) and as many query blocks as the budget allows for the per-block work;
@@ -117,9 +117,11 @@ def cpu_baseline(cfg, q, k, v, W, budget_s):
     t0 = time.perf_counter()
     scores = so.pooled_scores(Q, K, cfg.block_q, cfg.block_k)
     mask = so.classify(scores, n_c, n_m)
-    so.quantize_q(Q, cfg.block_q)
-    so.quantize_k(K, cfg.block_k)
-    so.quantize_v(V)
+    if low_bit:
+        so.quantize_q(Q, cfg.block_q)
+        so.quantize_k(K, cfg.block_k)
+        so.quantize_v(V)
+    quant = so.QUANT_QK_INT8_PV_FP8 if low_bit else so.QUANT_NONE
     if n_m:
         so.linear_summaries(K, V, cfg.block_k)
     t_head = time.perf_counter() - t0
@@ -127,7 +129,7 @@ def cpu_baseline(cfg, q, k, v, W, budget_s):
     # one call on 1 block and one on 1 + nb blocks and take the difference
     t0 = time.perf_counter()
     so.sla_forward_head(Q, K, V, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, proj_w=Wd,
-                        q_blocks=[0], mask=mask)
+                        q_blocks=[0], mask=mask, quant=quant)
     t_one = time.perf_counter() - t0
     per_block_guess = max(t_one - t_head, 1e-3)
     nb = int(max(2, min(Tq - 1, budget_s / per_block_guess)))
@@ -135,7 +137,7 @@ def cpu_baseline(cfg, q, k, v, W, budget_s):
     blocks = sorted(set(blocks))
     t0 = time.perf_counter()
     so.sla_forward_head(Q, K, V, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, proj_w=Wd,
-                        q_blocks=blocks, mask=mask)
+                        q_blocks=blocks, mask=mask, quant=quant)
     t_many = time.perf_counter() - t0
     per_block = max(t_many - t_one, 1e-9) / max(len(blocks) - 1, 1)
     t_full = cfg.B * cfg.H * (t_head + Tq * per_block)
@@ -442,7 +444,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle sample ...", file=sys.stderr, flush=True)
-        result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, W, args.cpu_seconds)
+        result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, W, args.cpu_seconds, low_bit)
     print(json.dumps(result))
 
 
