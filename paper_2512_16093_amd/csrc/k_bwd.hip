@@ -94,6 +94,16 @@ struct RowStage {
       }
     }
   }
+  // The same with rows beyond N replaced by row N - 1 and no branch: for callers that give such rows
+  // a weight of exactly zero and want every call to issue the same loads (N > 0).
+  __device__ __forceinline__ void load_clamped(const bf16_t* x, int r0, int N, int t) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int c = u * NT + t;
+      const uint4 got = *(const uint4*)(x + (size_t)min(r0 + (c >> 4), N - 1) * D + (c & 15) * 8);
+      pf[u] = got;  // (through a named value: assigning the dereferenced pointer straight to the member left the arrays in scratch memory)
+    }
+  }
   __device__ __forceinline__ void store(unsigned char* lds, int t) const {
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
@@ -661,11 +671,11 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
   float ps0 = 0.f, ps1 = 0.f;
   auto rows_of = [&](int step) { return ROWS * (((qlist[step >> pair_shift] & 0x3fff) << pair_shift) + (step & pair_mask)); };
 #define DKV_LOAD(SQ, SD, PS, STEP)                                                                   \
-  if ((STEP) < steps) {                                                                              \
-    const long long r_ = rows_of(STEP);                                                              \
-    SQ.load(q + head, r_, dm.N, t);                                                                  \
-    SD.load(dout + head, r_, dm.N, t);                                                               \
-    if (t < 2 * ROWS) PS = (t < ROWS ? lse2 : delta)[(size_t)bh * dm.T32q * 32 + r_ + (t & (ROWS - 1))]; \
+  {                                                                                                  \
+    const int r_ = rows_of(min((STEP), steps - 1));                                                  \
+    SQ.load_clamped(q + head, r_, dm.N, t);                                                          \
+    SD.load_clamped(dout + head, r_, dm.N, t);                                                       \
+    PS = ((t & ROWS) ? delta : lse2)[(size_t)bh * dm.T32q * 32 + r_ + (t & (ROWS - 1))];             \
   }
 #define DKV_STORE(SQ, SD, PS, BUF)                                                                   \
   {                                                                                                  \
@@ -735,28 +745,37 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
       }
     }
   };
-  // one step: load step S + 2 into the set that step S has left, compute S, publish S + 1
+  // One step: load step S + 2 into the set that step S has left, compute S, publish S + 1.  Every
+  // step issues the same loads and stores whatever the step number (past the end the last step is
+  // loaded again and a stale set is published to the buffer nobody reads any more; rows beyond N
+  // come as row N - 1, their lse = +inf makes their P and dS exactly 0): with nothing conditional
+  // the compiler can count the loads in flight and waits for those of step S + 1 only -- with the
+  // loads under "if (step < steps)" it waited for everything, the loads just issued included,
+  // before every publish, and again in the middle of the first group of products.
 #define DKV_STEP(S, AHEAD, BUF, SQL, SDL, PSL, SQN, SDN, PSN)  \
   if ((S) >= steps) break;                                     \
   DKV_LOAD(SQL, SDL, PSL, (S) + (AHEAD))                       \
   compute((S), BUF);                                           \
-  if ((S) + 1 < steps) DKV_STORE(SQN, SDN, PSN, 1 - (BUF))     \
+  DKV_STORE(SQN, SDN, PSN, 1 - (BUF))                          \
   __syncthreads();
-  DKV_LOAD(sq0, sd0, ps0, 0)
-  if constexpr (NT * 2 >= ROWS * 8) {  // two register sets in rotation, two steps in flight
-    DKV_LOAD(sq1, sd1, ps1, 1)
-    if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
-    __syncthreads();
-    for (int step = 0;; step += 2) {  // (every exit test is uniform over the workgroup)
-      DKV_STEP(step, 2, 0, sq0, sd0, ps0, sq1, sd1, ps1)
-      DKV_STEP(step + 1, 2, 1, sq1, sd1, ps1, sq0, sd0, ps0)
-    }
-  } else {                             // (a set is 64 registers here) one set, one step ahead
-    if (steps > 0) DKV_STORE(sq0, sd0, ps0, 0)
-    __syncthreads();
-    for (int step = 0;; step += 2) {
-      DKV_STEP(step, 1, 0, sq0, sd0, ps0, sq0, sd0, ps0)
-      DKV_STEP(step + 1, 1, 1, sq0, sd0, ps0, sq0, sd0, ps0)
+  if (steps > 0) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the workgroup's own K, V rows are in (else the loop would wait for them each time round)
+    DKV_LOAD(sq0, sd0, ps0, 0)
+    if constexpr (NT * 2 >= ROWS * 8) {  // two register sets in rotation, two steps in flight
+      DKV_LOAD(sq1, sd1, ps1, 1)
+      DKV_STORE(sq0, sd0, ps0, 0)
+      __syncthreads();
+      for (int step = 0;; step += 2) {  // (every exit test is uniform over the workgroup)
+        DKV_STEP(step, 2, 0, sq0, sd0, ps0, sq1, sd1, ps1)
+        DKV_STEP(step + 1, 2, 1, sq1, sd1, ps1, sq0, sd0, ps0)
+      }
+    } else {                             // (a set is 64 registers here) one set, one step ahead
+      DKV_STORE(sq0, sd0, ps0, 0)
+      __syncthreads();
+      for (int step = 0;; step += 2) {
+        DKV_STEP(step, 1, 0, sq0, sd0, ps0, sq0, sd0, ps0)
+        DKV_STEP(step + 1, 1, 1, sq0, sd0, ps0, sq0, sd0, ps0)
+      }
     }
   }
 #undef DKV_STEP
