@@ -180,14 +180,20 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     sk.store(lds_all, t);
     sv.store(lds_all + 2 * TILE_B, t);
   }
+  // Everything requested so far has to be in before the loop: a load the compiler cannot prove
+  // finished on every path into the loop would be waited for each time round, in the middle of the
+  // products and together with the loads of the next block just issued.  For the same reason the
+  // loop's own loads and stores are unconditional (rows beyond N come as row N - 1; their P is 0).
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
     const unsigned char* lds = lds_all + (b & 1) * 4 * TILE_B;
     unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
-    if (b + 1 < dm.n_c) {
-      sk.load(k + head, 64ll * crow[b + 1], dm.N, t);
-      sv.load(v + head, 64ll * crow[b + 1], dm.N, t);
+    {  // the next block (after the last one: the last one again), the same loads every time round -- see below
+      const int jn = 64 * crow[min(b + 1, dm.n_c - 1)];
+      sk.load_clamped(k + head, jn, dm.N, t);
+      sv.load_clamped(v + head, jn, dm.N, t);
     }
     v16f s[2];
     float mx = -INFINITY;
@@ -247,10 +253,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
         __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, 5, 0);
       }
-    if (b + 1 < dm.n_c) {
-      sk.store(lds_next, t);
-      sv.store(lds_next + 2 * TILE_B, t);
-    }
+    sk.store(lds_next, t);  // (after the last block: into the buffer nobody reads any more)
+    sv.store(lds_next + 2 * TILE_B, t);
     __syncthreads();
   }
   const float l = lacc[0];
@@ -406,14 +410,20 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
     sk.store(lds_all, t);
     sv.store(lds_all + 2 * TILE_B, t);
   }
+  // Everything requested so far has to be in before the loop: a load the compiler cannot prove
+  // finished on every path into the loop would be waited for each time round, in the middle of the
+  // products and together with the loads of the next block just issued.  For the same reason the
+  // loop's own loads and stores are unconditional (rows beyond N come as row N - 1; their P is 0).
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
     const unsigned char* lds = lds_all + (b & 1) * 4 * TILE_B;
     unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
-    if (b + 1 < dm.n_c) {
-      sk.load(k + head, 64ll * crow[b + 1], dm.N, t);
-      sv.load(v + head, 64ll * crow[b + 1], dm.N, t);
+    {  // the next block (after the last one: the last one again), the same loads every time round -- see below
+      const int jn = 64 * crow[min(b + 1, dm.n_c - 1)];
+      sk.load_clamped(k + head, jn, dm.N, t);
+      sv.load_clamped(v + head, jn, dm.N, t);
     }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -462,10 +472,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
     }
-    if (b + 1 < dm.n_c) {
-      sk.store(lds_next, t);
-      sv.store(lds_next + 2 * TILE_B, t);
-    }
+    sk.store(lds_next, t);  // (after the last block: into the buffer nobody reads any more)
+    sv.store(lds_next + 2 * TILE_B, t);
     __syncthreads();
   }
   if (qrow < dm.N) {
