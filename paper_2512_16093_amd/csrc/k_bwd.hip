@@ -753,6 +753,105 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
       }
     }
   };
+  // The same for two tiles per step (one key block per workgroup), laid out so that the vector work of
+  // one tile (exponentials, dS, conversions) is issued between the matrix products of the other: a
+  // lone wavefront per SIMD has nobody else to fill the matrix pipe while it computes exponentials.
+  auto compute_interleaved = [&](int step, int buf) __attribute__((always_inline)) {
+    if (!((qlist[step >> pair_shift] >> (14 + half)) & 1)) return;  // (always set; keeps the compiler from hoisting reads over the step boundary)
+    const unsigned char* qt0 = lds + buf * BUF_B;
+    const unsigned char* dt0 = qt0 + TILES * TILE_B;
+    v16f s[2], dp[2], p[2];
+    float4 ls[4], dl[4];
+    uint4 aq[8], ad[8];
+    auto read_ops = [&](int u) __attribute__((always_inline)) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        aq[ks] = n_op(qt0 + u * TILE_B, l32, hf, ks);
+        ad[ks] = n_op(dt0 + u * TILE_B, l32, hf, ks);
+      }
+    };
+    auto read_stats = [&](int u) __attribute__((always_inline)) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        ls[g] = *(const float4*)&stat[buf][0][32 * u + 8 * g + 4 * hf];
+        dl[g] = *(const float4*)&stat[buf][1][32 * u + 8 * g + 4 * hf];
+      }
+    };
+    auto weight = [&](int u, int r) __attribute__((always_inline)) {  // P and dS of tile u, accumulator register r
+      const float4 l4 = ls[r >> 2], d4 = dl[r >> 2];
+      const float lv = (r & 3) == 0 ? l4.x : (r & 3) == 1 ? l4.y : (r & 3) == 2 ? l4.z : l4.w;
+      const float dv_ = (r & 3) == 0 ? d4.x : (r & 3) == 1 ? d4.y : (r & 3) == 2 ? d4.z : d4.w;
+      const float pe = kok ? __builtin_amdgcn_exp2f(s[u][r] * QK_LOG2 - lv) : 0.f;
+      p[u][r] = pe;
+      s[u][r] = pe * (dp[u][r] - dv_);
+    };
+    // The step as an explicit schedule: every piece ends with a full scheduling fence, so the order
+    // below is the order of issue.  Tile 0's scores; tile 1's scores with tile 0's exponentials
+    // between the products; tile 0's gradient products with tile 1's exponentials between them;
+    // tile 1's gradient products.
+    read_ops(0);
+    __builtin_amdgcn_sched_barrier(0);
+    s[0] = v16f{};
+    dp[0] = v16f{};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      s[0] = mfma_bf16(aq[ks], kf[ks], s[0]);
+      dp[0] = mfma_bf16(ad[ks], vf[ks], dp[0]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    read_ops(1);
+    read_stats(0);
+    __builtin_amdgcn_sched_barrier(0);
+    s[1] = v16f{};
+    dp[1] = v16f{};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      s[1] = mfma_bf16(aq[ks], kf[ks], s[1]);
+      weight(0, 2 * ks);
+      __builtin_amdgcn_sched_barrier(0);
+      dp[1] = mfma_bf16(ad[ks], vf[ks], dp[1]);
+      weight(0, 2 * ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    read_stats(1);
+#pragma unroll
+    for (int sx = 0; sx < 2; ++sx) {
+      const uint4 pb = acc_operand(p[0], sx), dsb = acc_operand(s[0], sx);
+      uint4 td[4], tq[4];
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        td[ct] = t_op(dt0, tr_off, ct, sx);
+        tq[ct] = t_op(qt0, tr_off, ct, sx);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        dvt[ct] = mfma_bf16(td[ct], pb, dvt[ct]);
+        weight(1, 8 * sx + 2 * ct);
+        __builtin_amdgcn_sched_barrier(0);
+        dkt[ct] = mfma_bf16(tq[ct], dsb, dkt[ct]);
+        weight(1, 8 * sx + 2 * ct + 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int sx = 0; sx < 2; ++sx) {
+      const uint4 pb = acc_operand(p[1], sx), dsb = acc_operand(s[1], sx);
+      uint4 td[4], tq[4];
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        td[ct] = t_op(dt0 + TILE_B, tr_off, ct, sx);
+        tq[ct] = t_op(qt0 + TILE_B, tr_off, ct, sx);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        dvt[ct] = mfma_bf16(td[ct], pb, dvt[ct]);
+        dkt[ct] = mfma_bf16(tq[ct], dsb, dkt[ct]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
   // One step: load step S + 2 into the set that step S has left, compute S, publish S + 1.  Every
   // step issues the same loads and stores whatever the step number (past the end the last step is
   // loaded again and a stale set is published to the buffer nobody reads any more; rows beyond N
@@ -763,7 +862,7 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
 #define DKV_STEP(S, AHEAD, BUF, SQL, SDL, PSL, SQN, SDN, PSN)  \
   if ((S) >= steps) break;                                     \
   DKV_LOAD(SQL, SDL, PSL, (S) + (AHEAD))                       \
-  compute((S), BUF);                                           \
+  if constexpr (KB == 1 && TILES == 2) compute_interleaved((S), BUF); else compute((S), BUF); \
   DKV_STORE(SQN, SDN, PSN, 1 - (BUF))                          \
   __syncthreads();
   if (steps > 0) {
@@ -884,7 +983,7 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
 }
 
-constexpr int DKV1_TILES = 1;  // tiles per step of the one-key-block variant (2 measured the same and needs 80 KB of LDS per workgroup)
+constexpr int DKV1_TILES = 2;  // tiles per step of the one-key-block variant (2 measured the same and needs 80 KB of LDS per workgroup)
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
   // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
