@@ -601,7 +601,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
 // the two mask columns; two flag bits per entry), staging each query tile's Q and dO once for both;
 // a wavefront whose block is not critical for the current query block sits the step out.
 // (KB = 2, 64 query rows per step.)  With KB = 1 a workgroup of two wavefronts serves one key block
-// over its own list, 32 query rows per step, and two workgroups share a compute unit: every
+// over its own list, 64 query rows per step as well, and two workgroups share a compute unit: every
 // staged tile then serves one key block only, but no wavefront ever sits out.
 template <int KB, int TILES>
 __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
@@ -671,9 +671,9 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
   }
   // Steps = (list entry, pair of tiles of its query block): 64 query rows at a time.  They travel
   // memory -> registers -> LDS: while step s is computed from one LDS buffer, step s + 1 is moved from
-  // registers to the other buffer and step s + 2 is on its way from memory (two register sets in
-  // rotation); one barrier per step.  Within a step the two tiles are independent, which lets the
-  // matrix products of one run under the exponentials of the other.
+  // registers to the other buffer and, where the registers allow a second set (KB = 2), step s + 2 is
+  // on its way from memory; one barrier per step.  Within a step the two tiles are independent, which
+  // lets the matrix products of one run under the exponentials of the other.
   const int steps = nq << pair_shift, pair_mask = (1 << pair_shift) - 1;
   RowStage<NT, ROWS> sq0, sd0, sq1, sd1;
   float ps0 = 0.f, ps1 = 0.f;
@@ -983,7 +983,7 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
 }
 
-constexpr int DKV1_TILES = 2;  // tiles per step of the one-key-block variant (2 measured the same and needs 80 KB of LDS per workgroup)
+constexpr int DKV1_TILES = 2;  // tiles per step of the one-key-block variant: 2 (78 KB of LDS per workgroup) runs compute_interleaved, 1 the plain step
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
   // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
