@@ -259,6 +259,10 @@ __global__ void __launch_bounds__(NW * 64, 1)
     if (hf == 0) dden_s[nl] = dden;
     __syncthreads();
     bf16_t* dst = dHZ + ((size_t)bh * Tq + i) * HZ_ELEMS;
+    // (the store offsets below are formed from a value the compiler cannot see through: as loop
+    // invariants they were kept in scratch memory, and each reload made its store wait for the one before)
+    int lane_o = l32;
+    asm volatile("" : "+v"(lane_o));
     for (int ct = w; ct < 4; ct += NW) {
       v16f acc[4];
 #pragma unroll
@@ -277,7 +281,7 @@ __global__ void __launch_bounds__(NW * 64, 1)
         // lane: o = 32 ot + l32; registers: c = 32 ct + 8 g + 4 hf + e
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          *(uint2*)(dst + hz_run_offset(32 * ot + l32, 32 * ct + 8 * g + 4 * hf)) =
+          *(uint2*)(dst + hz_run_offset(32 * ot + lane_o, 32 * ct + 8 * g + 4 * hf)) =
               uint2{pack_bf16x2(acc[ot][4 * g], acc[ot][4 * g + 1]), pack_bf16x2(acc[ot][4 * g + 2], acc[ot][4 * g + 3])};
       }
     }
