@@ -788,69 +788,95 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
     // The step as an explicit schedule: every piece ends with a full scheduling fence, so the order
     // below is the order of issue.  Tile 0's scores; tile 1's scores with tile 0's exponentials
     // between the products; tile 0's gradient products with tile 1's exponentials between them;
-    // tile 1's gradient products.
+    // tile 1's gradient products.  The LDS reads of each section are issued one section early, a
+    // pair behind every product that has just consumed its operands (whose registers they take
+    // over), so that no section starts by waiting for its reads.
+#define FENCE __builtin_amdgcn_sched_barrier(0);
+    uint4 bq[8], bd[8];          // tile 1's score operands
+    uint4 td[4], tq[4], te[4], tr[4];  // transposed operands of the gradient products, two sets in turn
     read_ops(0);
-    __builtin_amdgcn_sched_barrier(0);
+    FENCE
     s[0] = v16f{};
     dp[0] = v16f{};
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       s[0] = mfma_bf16(aq[ks], kf[ks], s[0]);
       dp[0] = mfma_bf16(ad[ks], vf[ks], dp[0]);
+      bq[ks] = n_op(qt0 + TILE_B, l32, hf, ks);
+      bd[ks] = n_op(dt0 + TILE_B, l32, hf, ks);
+      FENCE
     }
-    __builtin_amdgcn_sched_barrier(0);
-    read_ops(1);
     read_stats(0);
-    __builtin_amdgcn_sched_barrier(0);
+    FENCE
     s[1] = v16f{};
     dp[1] = v16f{};
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      s[1] = mfma_bf16(aq[ks], kf[ks], s[1]);
+      s[1] = mfma_bf16(bq[ks], kf[ks], s[1]);
       weight(0, 2 * ks);
-      __builtin_amdgcn_sched_barrier(0);
-      dp[1] = mfma_bf16(ad[ks], vf[ks], dp[1]);
+      FENCE
+      dp[1] = mfma_bf16(bd[ks], vf[ks], dp[1]);
       weight(0, 2 * ks + 1);
-      __builtin_amdgcn_sched_barrier(0);
+      if (ks & 1) {
+        td[ks >> 1] = t_op(dt0, tr_off, ks >> 1, 0);
+        tq[ks >> 1] = t_op(qt0, tr_off, ks >> 1, 0);
+      }
+      FENCE
     }
     read_stats(1);
-#pragma unroll
-    for (int sx = 0; sx < 2; ++sx) {
-      const uint4 pb = acc_operand(p[0], sx), dsb = acc_operand(s[0], sx);
-      uint4 td[4], tq[4];
-#pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
-        td[ct] = t_op(dt0, tr_off, ct, sx);
-        tq[ct] = t_op(qt0, tr_off, ct, sx);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+    {
+      const uint4 pb = acc_operand(p[0], 0), dsb = acc_operand(s[0], 0);
+      FENCE
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
         dvt[ct] = mfma_bf16(td[ct], pb, dvt[ct]);
-        weight(1, 8 * sx + 2 * ct);
-        __builtin_amdgcn_sched_barrier(0);
+        weight(1, 2 * ct);
+        FENCE
         dkt[ct] = mfma_bf16(tq[ct], dsb, dkt[ct]);
-        weight(1, 8 * sx + 2 * ct + 1);
-        __builtin_amdgcn_sched_barrier(0);
+        weight(1, 2 * ct + 1);
+        te[ct] = t_op(dt0, tr_off, ct, 1);
+        tr[ct] = t_op(qt0, tr_off, ct, 1);
+        FENCE
       }
     }
-#pragma unroll
-    for (int sx = 0; sx < 2; ++sx) {
-      const uint4 pb = acc_operand(p[1], sx), dsb = acc_operand(s[1], sx);
-      uint4 td[4], tq[4];
+    {
+      const uint4 pb = acc_operand(p[0], 1), dsb = acc_operand(s[0], 1);
+      FENCE
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        td[ct] = t_op(dt0 + TILE_B, tr_off, ct, sx);
-        tq[ct] = t_op(qt0 + TILE_B, tr_off, ct, sx);
+        dvt[ct] = mfma_bf16(te[ct], pb, dvt[ct]);
+        weight(1, 8 + 2 * ct);
+        FENCE
+        dkt[ct] = mfma_bf16(tr[ct], dsb, dkt[ct]);
+        weight(1, 8 + 2 * ct + 1);
+        td[ct] = t_op(dt0 + TILE_B, tr_off, ct, 0);
+        tq[ct] = t_op(qt0 + TILE_B, tr_off, ct, 0);
+        FENCE
       }
-      __builtin_amdgcn_sched_barrier(0);
+    }
+    {
+      const uint4 pb = acc_operand(p[1], 0), dsb = acc_operand(s[1], 0);
+      FENCE
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
         dvt[ct] = mfma_bf16(td[ct], pb, dvt[ct]);
         dkt[ct] = mfma_bf16(tq[ct], dsb, dkt[ct]);
+        te[ct] = t_op(dt0 + TILE_B, tr_off, ct, 1);
+        tr[ct] = t_op(qt0 + TILE_B, tr_off, ct, 1);
+        FENCE
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
+    {
+      const uint4 pb = acc_operand(p[1], 1), dsb = acc_operand(s[1], 1);
+      FENCE
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        dvt[ct] = mfma_bf16(te[ct], pb, dvt[ct]);
+        dkt[ct] = mfma_bf16(tr[ct], dsb, dkt[ct]);
+      }
+      FENCE
+    }
+#undef FENCE
   };
   // One step: load step S + 2 into the set that step S has left, compute S, publish S + 1.  Every
   // step issues the same loads and stores whatever the step number (past the end the last step is
