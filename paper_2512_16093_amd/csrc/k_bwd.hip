@@ -726,7 +726,7 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
         const float lsv[4] = {ls[g].x, ls[g].y, ls[g].z, ls[g].w}, dlv[4] = {dl[g].x, dl[g].y, dl[g].z, dl[g].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float pe = kok ? __builtin_amdgcn_exp2f(s[u][4 * g + e] * QK_LOG2 - lsv[e]) : 0.f;
+          const float pe = __builtin_amdgcn_exp2f(s[u][4 * g + e] * QK_LOG2 - lsv[e]);  // (a key beyond N: a finite value in a column that is never stored)
           p[u][4 * g + e] = pe;
           s[u][4 * g + e] = pe * (dp[u][4 * g + e] - dlv[e]);
         }
@@ -781,7 +781,7 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
       const float4 l4 = ls[r >> 2], d4 = dl[r >> 2];
       const float lv = (r & 3) == 0 ? l4.x : (r & 3) == 1 ? l4.y : (r & 3) == 2 ? l4.z : l4.w;
       const float dv_ = (r & 3) == 0 ? d4.x : (r & 3) == 1 ? d4.y : (r & 3) == 2 ? d4.z : d4.w;
-      const float pe = kok ? __builtin_amdgcn_exp2f(s[u][r] * QK_LOG2 - lv) : 0.f;
+      const float pe = __builtin_amdgcn_exp2f(s[u][r] * QK_LOG2 - lv);  // (a key beyond N: a finite value in a column that is never stored)
       p[u][r] = pe;
       s[u][r] = pe * (dp[u][r] - dv_);
     };
