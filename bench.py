@@ -41,7 +41,7 @@ W8A8_SHAPES = {"attn_proj": (75600, 5120, 5120), "ffn_up": (75600, 5120, 13824),
 # source: profiles/w8a8_linear_wan14b.md.
 W8A8_TRAFFIC_BYTES = {"attn_proj": 6.49e9}
 # The backward pass's dominant kernel, by (config, kernel); source: profiles/sla_bwd_wan14b-720p.md.
-BWD_TRAFFIC_BYTES = {(4, "bwd_dkv_kernel"): 163.4e9}
+BWD_TRAFFIC_BYTES = {(4, "bwd_dkv_kernel"): 164.0e9}
 
 
 def parse():
