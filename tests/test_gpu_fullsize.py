@@ -52,6 +52,38 @@ def test_named_config_sampled_parity(cfg_id, heads):
     print("%s: sampled max-abs %.3e, min cosine %.6f, tie-excused mask entries %d" % (cfg.name, worst, cmin, nbad))
 
 
+@pytest.mark.parametrize("cfg_id,head", [(4, 9), (6, 30)])
+def test_named_config_unquantised_forward_sampled_parity(cfg_id, head):
+    """quant_mode SLA_QUANT_NONE at full size: sampled query blocks (first, middle, ragged last) of
+    one head against the oracle's exact branch on the library's own mask; the bar of the small
+    cases (max-abs 2e-2, cosine 0.999, relative Frobenius 5e-3 per block)."""
+    cfg = synth.CONFIGS[cfg_id]
+    print("config", cfg.name, "generating inputs", flush=True)
+    q, k, v = pu.make_qkv_threaded(cfg)
+    W = synth.make_proj(cfg)
+    qd, kd, vd = pu.to_dev(q, k, v)
+    Wd = None if W is None else W.cuda()
+    print("running GPU forward (unquantised)", flush=True)
+    out = sla.sla_attention_fwd(qd, kd, vd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, proj_w=Wd,
+                                quant_mode=sla.QUANT_NONE)
+    mask = sla.sla_classify_blocks(qd, kd, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                                   want_scores=False)[0]
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    Tq = so.block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)[0]
+    blocks = sorted({0, Tq // 2, Tq - 1})
+    print("oracle on head", head, flush=True)
+    r = so.sla_forward_head(synth.as_f64(q[0, head]), synth.as_f64(k[0, head]), synth.as_f64(v[0, head]), cfg.block_q,
+                            cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
+                            proj_w=None if W is None else synth.as_f64(W), quant=so.QUANT_NONE, q_blocks=blocks,
+                            mask=mask[0, head].cpu().numpy())
+    oh = out[0, head].float().cpu().numpy().astype(np.float64)
+    for i in blocks:
+        rows = slice(i * cfg.block_q, min((i + 1) * cfg.block_q, cfg.N))
+        pu.check_output(oh[rows], r["out"][rows], "%s head %d block %d (unquantised)" % (cfg.name, head, i))
+        assert np.linalg.norm(oh[rows] - r["out"][rows]) / np.linalg.norm(r["out"][rows]) <= 5e-3
+
+
 @pytest.mark.parametrize("cfg_id,head", [(1, 7), (4, 23), (6, 2)])
 def test_named_config_backward_sampled_parity(cfg_id, head):
     """sla_attention_bwd at the full size the benchmark times: dQ of sampled query blocks and dK, dV of
