@@ -23,7 +23,7 @@
  * before and after); inputs are never written; outputs must not alias inputs or the workspace.
  * Returns SLA_OK or a negative sla_status; argument errors are found on the host before any launch.
  * Supported: what sla_attention_fwd supports for shapes, blocks and ratios; contiguous [B,H,N,d]
- * tensors; phi_kind == SLA_PHI_SOFTMAX (else SLA_ERR_UNSUPPORTED).
+ * tensors; phi_kind SLA_PHI_SOFTMAX or SLA_PHI_ELU1 (SLA_PHI_RELU: SLA_ERR_UNSUPPORTED).
  */
 #ifndef SLA_BWD_H_
 #define SLA_BWD_H_

@@ -429,7 +429,7 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
-  if (phi_kind != SLA_PHI_SOFTMAX) return SLA_ERR_UNSUPPORTED;
+  if (phi_kind != SLA_PHI_SOFTMAX && phi_kind != SLA_PHI_ELU1) return SLA_ERR_UNSUPPORTED;  // (relu: forward only)
   const SavedState V = make_saved(p);
   if (saved && (st = check_ws(saved, saved_bytes, V.total)) != SLA_OK) return st;
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
@@ -464,7 +464,7 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
                    at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
     launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
     launch_bwd_wt((const bf16_t*)proj_w, at<bf16_t>(ws, X.wt), s);
-    if (launch_bwd_lin_q(p, q, dout, at<bf16_t>(ws, W.HZ), at<bf16_t>(ws, X.wt), at<float>(ws, X.dql),
+    if (launch_bwd_lin_q(p, q, dout, at<bf16_t>(ws, W.HZ), at<bf16_t>(ws, X.wt), phi_kind, at<float>(ws, X.dql),
                          at<bf16_t>(ws, X.dHZ), dw_eff, dproj_b, s) != 0)
       return SLA_ERR_HIP;
     // G_j = sum of dH_i over the query blocks that hold key block j as marginal: the forward's
@@ -480,7 +480,7 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
                 lin ? at<float>(ws, X.dql) : nullptr, dq, s);
   mark(s, rec, 4);
   launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), lse2, at<float>(ws, X.delta),
-                 lin ? at<bf16_t>(ws, W.hz) : nullptr, dk, dv, s);
+                 lin ? at<bf16_t>(ws, W.hz) : nullptr, phi_kind, dk, dv, s);
   mark(s, rec, 5);
   return launch_status();
 }

@@ -13,6 +13,23 @@ constexpr int KV_FRAG_BYTES = BK * D;  // 8 KiB of INT8 K codes / FP8 V codes pe
 constexpr float E4M3_MAX = 448.0f;
 constexpr float LOG2_448 = 8.807354922057604f;
 constexpr float LOG2E = 1.4426950408889634f;
+
+// The linear branch's feature maps in the element-wise form the backward kernels use
+// (PHI = SLA_PHI_SOFTMAX 0: softmax over the channels, given the row's maximum mx and 1 / sum;
+// 1: elu(x) + 1;  2: relu; for these two mx is unused and scale is 1, or 0 for a row that does not exist).
+template <int PHI>
+__device__ __forceinline__ float phi_value(float x, float mx, float scale) {
+  if constexpr (PHI == 0) return __builtin_amdgcn_exp2f((x - mx) * LOG2E) * scale;
+  else if constexpr (PHI == 1) return (x > 0.f ? x + 1.0f : __builtin_amdgcn_exp2f(x * LOG2E)) * scale;
+  else return fmaxf(x, 0.f) * scale;
+}
+// d loss / d x from a = phi(x), d = d loss / d phi(x) and -- softmax only -- sdot = sum over the row of a d.
+template <int PHI>
+__device__ __forceinline__ float phi_backward(float x, float a, float d, float sdot) {
+  if constexpr (PHI == 0) return a * (d - sdot);
+  else if constexpr (PHI == 1) return x > 0.f ? d : a * d;   // (x <= 0: phi = exp(x) = its own derivative)
+  else return x > 0.f ? d : 0.f;
+}
 constexpr float LN2 = 0.6931471805599453f;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -181,10 +198,10 @@ void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float*
 void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
-                    const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream);
+                    const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream);
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
-                     float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream);
+                     int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream);
 void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream);
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
                           uint8_t* v_codes, hipStream_t stream);

@@ -499,7 +499,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
 // 128 rows of GP elements; gz, 128 floats); both barriers are inside.  Results in the accumulator
 // layout of the sparse-branch kernels (lane = key, registers = channels).
 constexpr int GP = 136;  // row pitch of the staged G (elements)
-template <int NT>
+template <int NT, int PHI>
 __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, size_t row,
                                                 bool ok, const bf16_t* __restrict__ rec, bf16_t* gc, float* gz, int t,
                                                 int lane, v16f (&dk_share)[4], v16f (&dv_share)[4]) {
@@ -528,17 +528,23 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
     cv[8 * ks] = bf16_lo(kv.x); cv[8 * ks + 1] = bf16_hi(kv.x); cv[8 * ks + 2] = bf16_lo(kv.y); cv[8 * ks + 3] = bf16_hi(kv.y);
     cv[8 * ks + 4] = bf16_lo(kv.z); cv[8 * ks + 5] = bf16_hi(kv.z); cv[8 * ks + 6] = bf16_lo(kv.w); cv[8 * ks + 7] = bf16_hi(kv.w);
   }
-  float kmax = cv[0];
+  float kmax = 0.f, sum = 1.0f;
+  if constexpr (PHI == 0) {
+    kmax = cv[0];
 #pragma unroll
-  for (int e = 1; e < 64; ++e) kmax = fmaxf(kmax, cv[e]);
-  kmax = fmaxf(kmax, partner_f32(kmax));
-  float sum = 0.f;
+    for (int e = 1; e < 64; ++e) kmax = fmaxf(kmax, cv[e]);
+    kmax = fmaxf(kmax, partner_f32(kmax));
+    sum = 0.f;
 #pragma unroll
-  for (int e = 0; e < 64; ++e) {
-    cv[e] = __builtin_amdgcn_exp2f((cv[e] - kmax) * LOG2E);
-    sum += cv[e];
+    for (int e = 0; e < 64; ++e) {
+      cv[e] = __builtin_amdgcn_exp2f((cv[e] - kmax) * LOG2E);
+      sum += cv[e];
+    }
+    sum += partner_f32(sum);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 64; ++e) cv[e] = phi_value<PHI>(cv[e], 0.f, 1.0f);
   }
-  sum += partner_f32(sum);
   const float rsum = ok ? 1.0f / sum : 0.f;  // keys beyond the sequence take no part
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
@@ -566,7 +572,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
     __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
   }
-  // through the softmax: phi at the accumulator's channels 32 ct + 8 g + 4 hf + e, from K again
+  // through the feature map: phi at the accumulator's channels 32 ct + 8 g + 4 hf + e, from K again
   float sdot = 0.f;
   uint2 kw[4][4];
 #pragma unroll
@@ -579,7 +585,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         dk_share[ct][4 * g + e] += gz[c0 + e];
-        sdot += __builtin_amdgcn_exp2f((xk[e] - kmax) * LOG2E) * rsum * dk_share[ct][4 * g + e];
+        if constexpr (PHI == 0) sdot += phi_value<0>(xk[e], kmax, rsum) * dk_share[ct][4 * g + e];
       }
     }
   sdot += partner_f32(sdot);
@@ -590,7 +596,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
       const float xk[4] = {bf16_lo(kw[ct][g].x), bf16_hi(kw[ct][g].x), bf16_lo(kw[ct][g].y), bf16_hi(kw[ct][g].y)};
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        dk_share[ct][4 * g + e] = __builtin_amdgcn_exp2f((xk[e] - kmax) * LOG2E) * rsum * (dk_share[ct][4 * g + e] - sdot);
+        dk_share[ct][4 * g + e] = phi_backward<PHI>(xk[e], phi_value<PHI>(xk[e], kmax, rsum), dk_share[ct][4 * g + e], sdot);
     }
   __syncthreads();  // the staged G is consumed: the caller may reuse the LDS
 }
@@ -603,7 +609,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
 // (KB = 2, 64 query rows per step.)  With KB = 1 a workgroup of two wavefronts serves one key block
 // over its own list, 64 query rows per step as well, and two workgroups share a compute unit: every
 // staged tile then serves one key block only, but no wavefront ever sits out.
-template <int KB, int TILES>
+template <int KB, int TILES, int PHI>
 __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
                                                       const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
@@ -656,7 +662,7 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
     constexpr int LIN_B = 128 * GP * 2 + 128 * 4;
     static_assert(KB * LIN_B <= 2 * BUF_B, "the staged G fits in the staging buffers");
     const int jb = min(KB * J + half, dm.Tk - 1);  // (the missing second block of an odd last pair: its keys do not exist)
-    linear_kv_share<128>(k + head, v + head, (size_t)(kok ? key : 0) * D, kok, G + ((size_t)bh * dm.Tk + jb) * HZ_ELEMS,
+    linear_kv_share<128, PHI>(k + head, v + head, (size_t)(kok ? key : 0) * D, kok, G + ((size_t)bh * dm.Tk + jb) * HZ_ELEMS,
                          (bf16_t*)(lds + half * LIN_B), (float*)(lds + half * LIN_B + 128 * GP * 2), t & 127, lane, dkt, dvt);
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
@@ -1010,15 +1016,16 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
 }
 
 constexpr int DKV1_TILES = 2;  // tiles per step of the one-key-block variant: 2 (78 KB of LDS per workgroup) runs compute_interleaved, 1 the plain step
-void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
-                    const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
+template <int PHI>
+static void launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+                               const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
   // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
   const int list_bytes = (2 * p.Tq + 15) & ~15;
   const int lds2 = 2 * 4 * TILE_B + 2 * 2 * 64 * 4 + list_bytes;
   const int lds1 = 2 * 2 * DKV1_TILES * TILE_B + 2 * 2 * 32 * DKV1_TILES * 4 + list_bytes;
   static const bool ok =
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess &&
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess &&
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
   if (!ok) return;
   const int tiles = p.block_q / 32;  // of a query block: 2 or 4
   // Two key blocks per workgroup halve the bytes streamed where their lists coincide and idle half
@@ -1027,14 +1034,21 @@ void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const voi
   const bool paired = 2 * p.n_c > p.Tk;
   if (paired) {
     const int pairs = (p.Tk + 1) / 2;
-    bwd_dkv_kernel<2, 2><<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds2, stream>>>(
+    bwd_dkv_kernel<2, 2, PHI><<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds2, stream>>>(
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 1 : 0, bwd_dims(p));
   } else {
-    bwd_dkv_kernel<1, DKV1_TILES><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
+    bwd_dkv_kernel<1, DKV1_TILES, PHI><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, (tiles == 4 ? 2 : 1) - (DKV1_TILES == 2 ? 1 : 0), bwd_dims(p));
   }
+}
+
+// (the feature map matters to the prologue only -- the linear branch's share -- and only when G is given)
+void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+                    const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream) {
+  if (!G || phi_kind == 0) launch_bwd_dkv_phi<0>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  else launch_bwd_dkv_phi<1>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);  // (the caller admits 0 and 1 only)
 }
 
 }  // namespace sla

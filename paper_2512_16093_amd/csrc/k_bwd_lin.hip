@@ -68,7 +68,7 @@ __global__ void __launch_bounds__(256) bwd_wt_kernel(const bf16_t* __restrict__ 
   }
 }
 
-template <int NW>
+template <int NW, int PHI>
 __global__ void __launch_bounds__(NW * 64, 1)
     bwd_lin_q_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ HZ,
                      const bf16_t* __restrict__ wt, float* __restrict__ dq_lin, bf16_t* __restrict__ dHZ,
@@ -125,8 +125,12 @@ __global__ void __launch_bounds__(NW * 64, 1)
       }
       unpack8(qv, &av[8 * ks]);
     }
-    float qmax, rsum;
-    softmax_stats(av, qmax, rsum);
+    float qmax = 0.f, rsum = 1.0f;
+    if constexpr (PHI == 0) softmax_stats(av, qmax, rsum);
+    else {
+#pragma unroll
+      for (int e = 0; e < 64; ++e) av[e] = phi_value<PHI>(av[e], 0.f, 1.0f);
+    }
     if (!ok) rsum = 0.f;         // rows beyond the sequence take no part in dH, dZ, dW
     float den = 0.f;
 #pragma unroll
@@ -219,9 +223,8 @@ __global__ void __launch_bounds__(NW * 64, 1)
         const float xq[4] = {bf16_lo(qw[ct][g].x), bf16_hi(qw[ct][g].x), bf16_lo(qw[ct][g].y), bf16_hi(qw[ct][g].y)};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float a = __builtin_amdgcn_exp2f((xq[e] - qmax) * LOG2E) * rsum;
           da[ct][4 * g + e] += zv[c0 + e] * dden;
-          sdot += a * da[ct][4 * g + e];
+          if constexpr (PHI == 0) sdot += phi_value<0>(xq[e], qmax, rsum) * da[ct][4 * g + e];
         }
       }
     sdot += partner_f32(sdot);
@@ -234,7 +237,7 @@ __global__ void __launch_bounds__(NW * 64, 1)
           float o[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e)
-            o[e] = __builtin_amdgcn_exp2f((xq[e] - qmax) * LOG2E) * rsum * (da[ct][4 * g + e] - sdot);
+            o[e] = phi_backward<PHI>(xq[e], phi_value<PHI>(xq[e], qmax, rsum), da[ct][4 * g + e], sdot);
           *(float4*)(dq_lin + row + 32 * ct + 8 * g + 4 * hf) = float4{o[0], o[1], o[2], o[3]};
         }
     }
@@ -368,8 +371,9 @@ void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream) {
 
 size_t bwd_lin_q_lds_bytes() { return (size_t)4 * 128 * LP * 2 + 128 * 4 + 128 * 4; }
 
-int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
-                     float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
+template <int PHI>
+static int launch_bwd_lin_q_phi(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
+                                float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
   // workgroups per head: enough of them to fill the compute units a whole number of times where
   // that is possible (one workgroup per unit), few enough that the dW, db atomics stay cheap
   static int n_cu = 0;
@@ -389,16 +393,22 @@ int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf
   const size_t lds = bwd_lin_q_lds_bytes();
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)bwd_lin_q_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
-        hipFuncSetAttribute((const void*)bwd_lin_q_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)bwd_lin_q_kernel<4, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void*)bwd_lin_q_kernel<2, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return -1;
     attr_set = true;
   }
   if (p.block_q == 128)
-    bwd_lin_q_kernel<4><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
+    bwd_lin_q_kernel<4, PHI><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
   else
-    bwd_lin_q_kernel<2><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
+    bwd_lin_q_kernel<2, PHI><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
   return 0;
+}
+
+int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
+                     int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
+  if (phi_kind == 0) return launch_bwd_lin_q_phi<0>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, stream);
+  return launch_bwd_lin_q_phi<1>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, stream);  // (the caller admits 0 and 1 only)
 }
 
 }  // namespace sla

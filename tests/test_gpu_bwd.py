@@ -79,6 +79,35 @@ def test_backward_matches_gradient_oracle(H, grid, bq, rc, rm, proj):
         _compare("dproj_b", db.cpu().numpy(), sums_b)
 
 
+@pytest.mark.parametrize("H,grid,bq,rc,rm", [(2, (5, 10, 20), 128, 0.25, 0.5), (1, (3, 27, 27), 64, 0.1, 0.9),
+                                             (2, (5, 10, 20), 64, 0.75, 0.25)])
+def test_backward_with_the_elu_feature_map(H, grid, bq, rc, rm):
+    """phi = elu + 1 in the linear branch (the forward pass offers it; the oracle's gradient for it is
+    pinned by the same finite-difference and autograd checks as the softmax's): both dK/dV variants."""
+    cfg = synth.custom_config(1, H, grid, block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=True, cfg_id=303)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=11)[2]
+    W = synth.make_proj(cfg)
+    dev = torch.device("cuda:0")
+    qd, kd, vd, dd, Wd = (t.to(dev) for t in (q, k, v, dout, W))
+    mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
+    dq, dk, dv, dw, db = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True,
+                                               phi_kind=sla.PHI_ELU1)
+    torch.cuda.synchronize()
+    sums_w, sums_b = np.zeros((cfg.d, cfg.d)), np.zeros(cfg.d)
+    for h in range(H):
+        r = bo.sla_backward_head(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
+                                 synth.as_f64(dout[0, h]), mask[0, h], bq, 64, proj_w=synth.as_f64(W), has_bias=True,
+                                 phi="elu1")
+        _compare("dq", dq[0, h].float().cpu().numpy(), r["dQ"])
+        _compare("dk", dk[0, h].float().cpu().numpy(), r["dK"])
+        _compare("dv", dv[0, h].float().cpu().numpy(), r["dV"])
+        sums_w += r["dW"]
+        sums_b += r["db"]
+    _compare("dproj_w", dw.cpu().numpy(), sums_w)
+    _compare("dproj_b", db.cpu().numpy(), sums_b)
+
+
 def test_backward_batch_of_two():
     """Two batch entries with different contents: every (b, h) slice matches the oracle, and the
     projection gradients sum over both."""
@@ -139,7 +168,7 @@ def test_backward_argument_errors():
     dev = torch.device("cuda:0")
     x = torch.zeros((1, 1, 128, 128), dtype=torch.bfloat16, device=dev)
     with pytest.raises(sla.SLAError) as e:
-        sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, phi_kind=sla.PHI_ELU1)
+        sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, phi_kind=sla.PHI_RELU)
     assert e.value.status == sla.ERR_UNSUPPORTED
     with pytest.raises(sla.SLAError) as e:
         sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, workspace=torch.empty(256, dtype=torch.uint8, device=dev))
