@@ -14,12 +14,20 @@
  *      ascending j;  n_c = min(Tk, max(1, floor(topk_ratio*Tk + 1e-9))),
  *      n_m = min(Tk - n_c, floor(marginal_ratio*Tk + 1e-9));
  *   3. sparse branch: softmax attention of the block's queries over the keys of
- *      its critical blocks, visited in ascending j with a running row maximum;
- *      K is smoothed (channel mean over all N tokens removed) and quantised to
- *      INT8 with one scale per key block, Q to INT8 with one scale per query
- *      block, V to FP8 E4M3 with one scale per channel, the probabilities to
- *      E4M3 after scaling by 448; both products accumulate exactly (int32) or in
- *      fp32; the row sum uses the unrounded probabilities;
+ *      its critical blocks, in one pass in ascending j.  K is smoothed (channel
+ *      mean over all N tokens removed) and quantised to INT8 with one scale per
+ *      key block, Q to INT8 with one scale per query block, V to FP8 E4M3 with
+ *      one scale per channel.  With t = log2(e) * (Q8.K8) dq dk / sqrt(d) the
+ *      base-2 logit (the integer product is exact), each query keeps a reference
+ *      level r, an INTEGER: after every run of 32 keys r = max(r, ceil(largest t
+ *      of the run)).  The weights of the run are P = 448 * 2^(t - r), at most 448,
+ *      rounded to E4M3 (nearest even); what was gathered before is scaled by the
+ *      power of two 2^(r_old - r), exactly.  The P.V products accumulate in fp32,
+ *      and the row sum is the sum of the ROUNDED weights, so numerator and
+ *      denominator use the same numbers:  O_s = sum(P8 V8) dv / sum(P8).
+ *      (Against the textbook form -- running maximum itself as the reference,
+ *      one refresh per block, row sum of the unrounded weights -- only the points
+ *      at which P is rounded move; without rounding the results coincide.)
  *   4. linear branch: with phi a per-token feature map (softmax over channels by
  *      default) on the ORIGINAL Q and K, O_l = phi(Q) H_i / (phi(Q).Z_i) where
  *      H_i = sum of phi(K_j)^T V_j and Z_i = sum of column sums of phi(K_j) over
@@ -45,7 +53,8 @@
  *     quant_mode SLA_QUANT_QK_INT8_PV_FP8 (the paper's inference path) or
  *     SLA_QUANT_NONE (bf16 products: the training-time operator that
  *     sla_bwd.h differentiates; contiguous [B,H,N,d] tensors only).
- *   - Results are deterministic: no floating-point atomics anywhere.
+ *   - Results of this header's entry points are deterministic: no floating-point
+ *     atomics.  (sla_bwd.h: dQ, dK, dV likewise; see there for dW and db.)
  */
 #ifndef SLA_H_
 #define SLA_H_

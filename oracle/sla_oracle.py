@@ -15,10 +15,15 @@ Conventions: one (batch, head) slice at a time; Q, K, V are float64 arrays
 block_q / block_k tokens, the last one possibly shorter.  No tiling, fusion or
 reordering beyond what the steps state.
 
-Parity unpinned (defined only by the readings, no outside value to check
-against): the quantised sparse branch as a whole (its parts -- formats, integer
-products, online-softmax algebra, the no-quantisation limit -- are pinned), the
-choice of feature map, the meaning of "marginal", and the projection form.
+Pins (tests/test_oracle_sla.py): all-critical + no quantisation against dense
+softmax attention from a library; the exact mode and the low-bit sparse branch
+(both reference rules, both refresh intervals, both row sums, both low-bit
+modes) against the scalar-loop restatement in oracle/brute.py; formats against
+library conversions; closed-form rankings; textbook linear attention;
+invariants.  Parity unpinned by the paper itself (no outside value exists; the
+readings define them): the choice of feature map, the meaning of "marginal",
+the projection form, and which of the equivalent-before-rounding variants of
+the low-bit pass (reference rule, refresh interval, row sum) is "the" scheme.
 """
 from __future__ import annotations
 
@@ -261,14 +266,16 @@ def linear_branch(Q, K, V, mask, block_q, block_k, phi="softmax", q_blocks=None)
 # --------------------------------------------------------------------------
 def sla_forward_head(Q, K, V, block_q, block_k, topk_ratio, marginal_ratio,
                      proj_w=None, proj_b=None, phi="softmax", quant=QUANT_QK_INT8_PV_FP8,
-                     linear=True, q_blocks=None, mask=None, ref_tile=None):
+                     linear=True, q_blocks=None, mask=None, ref_tile=None,
+                     reference="ceil_log2", rowsum_quantized=True):
     """SLA forward of one (batch, head) slice.
 
     O = O^s + O^l W^T (+ b); W = identity when proj_w is None; the linear term
     (and the bias) is absent when there is no marginal block (n_m = 0) or
     linear=False.  Returns a dict with out [N, d] (NaN rows for query blocks
-    outside q_blocks), mask, scores, o_sparse, o_linear.  ref_tile is handed to
-    sparse_branch_quant (how often the running reference is refreshed)."""
+    outside q_blocks), mask, scores, o_sparse, o_linear.  ref_tile, reference and
+    rowsum_quantized are handed to sparse_branch_quant (how often the running
+    reference is refreshed, which reference rule, which row sum)."""
     N, d = Q.shape
     Tq, Tk, n_c, n_m = block_counts(N, block_q, block_k, topk_ratio, marginal_ratio)
     scores = pooled_scores(Q, K, block_q, block_k)
@@ -277,7 +284,8 @@ def sla_forward_head(Q, K, V, block_q, block_k, topk_ratio, marginal_ratio,
     if quant == QUANT_NONE:
         o_s = sparse_branch_exact(Q, K, V, mask, block_q, block_k, q_blocks)
     else:
-        o_s = sparse_branch_quant(Q, K, V, mask, block_q, block_k, quant, q_blocks, ref_tile=ref_tile)
+        o_s = sparse_branch_quant(Q, K, V, mask, block_q, block_k, quant, q_blocks, ref_tile=ref_tile,
+                                  reference=reference, rowsum_quantized=rowsum_quantized)
     out = o_s.copy()
     o_l = None
     if linear and n_m > 0:

@@ -84,6 +84,79 @@ def test_matches_scalar_brute_force(N, d, bq, bk, rc, rm, proj):
     assert np.abs(r["out"] - np.array(ref)).max() < 1e-12
 
 
+# ---- brute force of the low-bit sparse branch --------------------------------
+_QCASES = [(64, 8, 16, 16, 0.25), (100, 8, 32, 16, 0.3), (192, 16, 32, 32, 0.2), (250, 16, 32, 16, 0.1),
+           (90, 8, 16, 32, 0.34), (150, 128, 64, 32, 0.4)]
+
+
+def _quant_case(N, d, bq, bk, rc):
+    rng = np.random.default_rng(7 * N + d)
+    Q, V = (_rand_bf16(rng, (N, d), 1.5) for _ in range(2))
+    K = _rand_bf16(rng, (N, d), 1.5, bias=2 * rng.standard_normal(d))     # outlier channels, as K-smoothing expects
+    Tq, Tk, n_c, n_m = so.block_counts(N, bq, bk, rc, 0.3)
+    mask = so.classify(so.pooled_scores(Q, K, bq, bk), n_c, n_m)
+    return Q, K, V, mask
+
+
+@pytest.mark.parametrize("N,d,bq,bk,rc", _QCASES)
+@pytest.mark.parametrize("reference", ["ceil_log2", "running"])
+@pytest.mark.parametrize("ref_tile", [None, 16])
+def test_quantised_branch_matches_scalar_brute_force(N, d, bq, bk, rc, reference, ref_tile):
+    # Second statement of the whole low-bit branch: token by token, Python round() for the integer
+    # codes, the 8-bit float as the nearest entry of its value table (ties to the even code).
+    Q, K, V, mask = _quant_case(N, d, bq, bk, rc)
+    for mode, fp8 in ((so.QUANT_QK_INT8_PV_FP8, True), (so.QUANT_QK_INT8, False)):
+        for rq in ((True, False) if d <= 16 else (True,)):
+            out, lse = so.sparse_branch_quant(Q, K, V, mask, bq, bk, mode=mode, reference=reference, ref_tile=ref_tile,
+                                              rowsum_quantized=rq, return_lse=True)
+            ref, ref_lse = brute.brute_sparse_quant(Q.tolist(), K.tolist(), V.tolist(), mask.tolist(), bq, bk, pv_fp8=fp8,
+                                                    reference=reference, ref_tile=ref_tile, rowsum_quantized=rq)
+            assert np.abs(out - np.array(ref)).max() < 1e-12
+            assert np.abs(lse - np.array(ref_lse)).max() < 1e-12
+
+
+def test_brute_force_notices_misplaced_rounding(monkeypatch):
+    # The pin has teeth: each of these slips inside the low-bit branch moves the result far
+    # beyond 1e-12 of the scalar restatement (which does not go through oracle.formats).
+    Q, K, V, mask = _quant_case(100, 8, 32, 16, 0.3)
+    ref = np.array(brute.brute_sparse_quant(Q.tolist(), K.tolist(), V.tolist(), mask.tolist(), 32, 16)[0])
+    assert np.abs(so.sparse_branch_quant(Q, K, V, mask, 32, 16) - ref).max() < 1e-12
+    # (a) V used unrounded  (b) P not rounded  (c) truncation instead of nearest-even for the integer codes
+    real_round = formats.e4m3_round
+    calls = {"n": 0}
+
+    def v_unrounded(x):
+        calls["n"] += 1
+        return np.asarray(x, dtype=np.float64) if calls["n"] == 1 else real_round(x)   # first call = V
+    monkeypatch.setattr(formats, "e4m3_round", v_unrounded)
+    assert np.abs(so.sparse_branch_quant(Q, K, V, mask, 32, 16) - ref).max() > 1e-6
+    calls["n"] = 0
+
+    def p_unrounded(x):
+        calls["n"] += 1
+        return real_round(x) if calls["n"] == 1 else np.asarray(x, dtype=np.float64)
+    monkeypatch.setattr(formats, "e4m3_round", p_unrounded)
+    assert np.abs(so.sparse_branch_quant(Q, K, V, mask, 32, 16) - ref).max() > 1e-6
+    monkeypatch.setattr(formats, "e4m3_round", real_round)
+    monkeypatch.setattr(formats, "int8_quantize",
+                        lambda x, delta: np.clip(np.trunc(np.asarray(x) / delta), -127, 127))
+    assert np.abs(so.sparse_branch_quant(Q, K, V, mask, 32, 16) - ref).max() > 1e-6
+
+
+def test_brute_e4m3_is_the_published_format():
+    # every table value survives, midpoints go to the even code, the top saturates
+    vals = brute._E4M3
+    assert len(vals) == 127 and vals[0] == 0.0 and vals[1] == 2.0 ** -9 and vals[8] == 2.0 ** -6 and vals[-1] == 448.0
+    for c, v in enumerate(vals):
+        assert brute.brute_e4m3(v) == v and brute.brute_e4m3(-v) == -v
+    for c in range(126):
+        mid = (vals[c] + vals[c + 1]) / 2
+        assert brute.brute_e4m3(mid) == vals[c if c % 2 == 0 else c + 1]
+    assert brute.brute_e4m3(1e9) == 448.0 and brute.brute_e4m3(-465.0) == -448.0
+    xs = np.random.default_rng(0).uniform(-500, 500, 4000)
+    assert np.array_equal(np.array([brute.brute_e4m3(float(x)) for x in xs]), formats.e4m3_round(xs))
+
+
 # ---- classification ---------------------------------------------------------
 def test_classification_closed_form_ranking():
     # Every key block is a constant multiple c_j of one vector u, every query block
@@ -403,3 +476,24 @@ def test_reference_refresh_tile_changes_only_the_rounding():
     assert eb < 1.25 * ea and ea < 1.25 * eb
     # a tile equal to the block is the default
     assert np.array_equal(a8, so.sparse_branch_quant(Q, K, V, mask, 64, 64, ref_tile=64))
+
+
+def test_the_two_readings_are_equally_close_to_exact():
+    # The kernel-shaped switches (integer reference level, refreshed per 32 keys, row sum of the rounded
+    # weights) against the plain reading (running maximum per 64-key block, unrounded row sum): the two
+    # differ only in where P is rounded to the 8-bit float, so each is as far from the exact branch as the
+    # other, and they are no further from each other than from it.
+    cfg = synth.CONFIGS[0]
+    for h in range(cfg.H):
+        q, k, v = synth.make_head(cfg, 0, h, seed=0)
+        Q, K, V = synth.as_f64(q), synth.as_f64(k), synth.as_f64(v)
+        args = (Q, K, V, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+        a = so.sla_forward_head(*args, ref_tile=32)["out"]
+        b = so.sla_forward_head(*args, reference="running", rowsum_quantized=False, ref_tile=None)["out"]
+        e = so.sla_forward_head(*args, quant=so.QUANT_NONE)["out"]
+        rms = lambda x: float(np.sqrt((x ** 2).mean()))
+        assert 0.85 < rms(a - e) / rms(b - e) < 1.15
+        assert rms(a - b) <= max(rms(a - e), rms(b - e))
+        assert np.abs(a - b).max() <= 3e-2 and np.abs(a - e).max() <= 3.5e-2 and np.abs(b - e).max() <= 3.5e-2
+        cos = (a * b).sum() / np.linalg.norm(a) / np.linalg.norm(b)
+        assert cos >= 0.9999
