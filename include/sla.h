@@ -77,8 +77,9 @@ typedef enum {
   SLA_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or too small */
   SLA_ERR_UNSUPPORTED = -6, /* phi_kind / quant_mode outside what this build implements */
   SLA_ERR_HIP = -7,         /* a kernel launch reported an error */
-  SLA_ERR_LAYOUT = -8       /* strides negative, not multiples of 8 elements, token stride < d, or a
+  SLA_ERR_LAYOUT = -8,      /* strides negative, not multiples of 8 elements, token stride < d, or a
                                base pointer not 16-byte aligned */
+  SLA_ERR_STATIC_LIMIT = -9 /* sla_classify_blocks_static: the problem needs more than SLA_STATIC_SCRATCH_BYTES */
 } sla_status;
 
 typedef enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1, SLA_PHI_RELU = 2 } sla_phi;
@@ -152,6 +153,23 @@ int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d
                         int block_q, int block_k, double topk_ratio, double marginal_ratio,
                         int8_t* mask, int32_t* crit_idx, int32_t* marg_idx, float* pooled_scores,
                         void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
+/* sla_classify_blocks for callers that cannot allocate or hand over device memory beyond inputs and
+ * outputs: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results (bit for bit) as sla_classify_blocks, minus the workspace: the block means,
+ * the statistics and -- when pooled_scores is NULL -- the scores live in an array built into the
+ * library, SLA_STATIC_SCRATCH_BYTES per GPU, held from the library's load until the process ends.
+ * The call allocates and frees nothing and does not synchronise.  It needs
+ *   256-byte-rounded  4 B H (Tq + Tk) d + 4 B H Tq + 4 B H d  (+ 4 B H Tq Tk if pooled_scores is NULL)
+ * bytes (e.g. 37 MiB for H = 40, N = 32760, block_q = 128); a larger problem returns
+ * SLA_ERR_STATIC_LIMIT and launches nothing.  Every call on a GPU uses that GPU's one array: calls
+ * that may overlap on one GPU (different streams, different threads) race and must be ordered by
+ * the caller.  Nothing in the array needs to survive between calls. */
+#define SLA_STATIC_SCRATCH_BYTES (64u << 20)
+int sla_classify_blocks_static(const void* q, const void* k, int B, int H, int N, int d,
+                               int block_q, int block_k, double topk_ratio, double marginal_ratio,
+                               int8_t* mask, int32_t* crit_idx, int32_t* marg_idx, float* pooled_scores,
+                               sla_stream_t stream);
 
 /* Step 3 alone, for a caller-supplied critical list.
  *   crit_idx  in   int32 [B,H,Tq,n_crit]; each row strictly ascending, entries in

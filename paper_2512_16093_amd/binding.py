@@ -22,9 +22,12 @@ QUANT_NONE, QUANT_QK_INT8, QUANT_QK_INT8_PV_FP8 = 0, 1, 2
 SLA_OK = 0
 ERR_NULL, ERR_SHAPE, ERR_BLOCK, ERR_RATIO, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = -1, -2, -3, -4, -5, -6, -7
 ERR_LAYOUT = -8
+ERR_STATIC_LIMIT = -9
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
-           "sla_attention_fwd", "sla_attention_fwd_strided", "sla_classify_blocks", "sla_sparse_attn_fwd",
+           "sla_attention_fwd", "sla_attention_fwd_strided", "sla_classify_blocks", "sla_classify_blocks_static",
+           "sla_sparse_attn_fwd",
            "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv",
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
 W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
@@ -74,6 +77,8 @@ def lib():
                                                 [c_dbl, c_dbl, c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp])
         L.sla_classify_blocks.restype = c_int
         L.sla_classify_blocks.argtypes = [c_vp, c_vp] + [c_int] * 6 + [c_dbl, c_dbl] + [c_vp] * 4 + [c_vp, c_sz, c_vp]
+        L.sla_classify_blocks_static.restype = c_int
+        L.sla_classify_blocks_static.argtypes = [c_vp, c_vp] + [c_int] * 6 + [c_dbl, c_dbl] + [c_vp] * 4 + [c_vp]
         L.sla_sparse_attn_fwd.restype = c_int
         L.sla_sparse_attn_fwd.argtypes = [c_vp] * 4 + [c_int, c_vp, c_vp] + [c_int] * 7 + [c_vp, c_sz, c_vp]
         L.sla_linear_attn_fwd.restype = c_int
@@ -281,6 +286,16 @@ def sla_classify_blocks(q, k, block_q, block_k, topk_ratio, marginal_ratio, want
                                    _ptr(workspace), workspace.numel(), _stream())
     _check(st, "sla_classify_blocks")
     return mask, crit, marg, scores
+
+
+def sla_classify_blocks_static(q, k, block_q, block_k, topk_ratio, marginal_ratio, mask, crit_idx, marg_idx,
+                               pooled_scores=None):
+    """sla_classify_blocks on the library's built-in scratch: the caller passes every output tensor
+    (mask int8 [B,H,Tq,Tk], crit_idx / marg_idx int32, pooled_scores fp32 or None); nothing is allocated."""
+    B, H, N, d = _bf16_4d(q, k)
+    st = lib().sla_classify_blocks_static(_ptr(q), _ptr(k), B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio,
+                                          _ptr(mask), _ptr(crit_idx), _ptr(marg_idx), _ptr(pooled_scores), _stream())
+    _check(st, "sla_classify_blocks_static")
 
 
 def sla_sparse_attn_fwd(q, k, v, crit_idx, block_q, block_k, quant_mode=QUANT_QK_INT8_PV_FP8, want_lse=True,

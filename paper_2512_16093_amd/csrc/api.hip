@@ -9,9 +9,50 @@
 
 #include "common.h"
 
+#include <mutex>
+
 using namespace sla;
 
+// Built-in scratch of sla_classify_blocks_static: one copy per GPU, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; the device address is looked
+// up once per device (static_scratch_ptr) and that pointer is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[SLA_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (nullptr on any HIP error).
+void* static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+// Scratch of the block classification alone: block means, the statistics pass's by-products, scores.
+struct ClassifyScratch {
+  size_t qbar, kbar, dq, amax_v, scores, total;
+};
+ClassifyScratch make_classify_scratch(const Problem& p, bool own_scores) {
+  ClassifyScratch c;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t r = o; o = align256(o + bytes); return r; };
+  c.qbar = take((size_t)p.BH * p.Tq * D * 4);
+  c.kbar = take((size_t)p.BH * p.Tk * D * 4);
+  c.dq = take((size_t)p.BH * p.Tq * 4);
+  c.amax_v = take((size_t)p.BH * D * 4);
+  c.scores = take(own_scores ? (size_t)p.BH * p.Tq * p.Tk * 4 : 0);
+  c.total = o;
+  return c;
+}
 
 int count_blocks(int N, int block_q, int block_k, double rc, double rm, int* Tq, int* Tk, int* nc,
                  int* nm) {
@@ -171,6 +212,7 @@ const char* sla_status_string(int status) {
     case SLA_ERR_WORKSPACE: return "workspace NULL, not 256-byte aligned, or too small";
     case SLA_ERR_UNSUPPORTED: return "phi_kind or quant_mode not implemented";
     case SLA_ERR_HIP: return "a kernel launch failed";
+    case SLA_ERR_STATIC_LIMIT: return "problem needs more scratch than the built-in SLA_STATIC_SCRATCH_BYTES";
     case SLA_ERR_LAYOUT: return "unsupported strides (non-negative multiples of 8 elements, token stride >= d, 16-byte aligned base)";
     default: return "unknown status";
   }
@@ -300,6 +342,27 @@ int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d
                     at<uint32_t>(ws, W.amax_v), s);
   float* sc = pooled_scores ? pooled_scores : at<float>(ws, W.scores);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), sc, s);
+  launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, nullptr, s);
+  return launch_status();
+}
+
+int sla_classify_blocks_static(const void* q, const void* k, int B, int H, int N, int d, int block_q, int block_k,
+                               double topk_ratio, double marginal_ratio, int8_t* mask, int32_t* crit_idx,
+                               int32_t* marg_idx, float* pooled_scores, sla_stream_t stream) {
+  if (!q || !k || !mask) return SLA_ERR_NULL;
+  Problem p;
+  const int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  const ClassifyScratch C = make_classify_scratch(p, pooled_scores == nullptr);
+  if (C.total > (size_t)SLA_STATIC_SCRATCH_BYTES) return SLA_ERR_STATIC_LIMIT;
+  void* ws = static_scratch_ptr();
+  if (!ws) return SLA_ERR_HIP;
+  hipStream_t s = (hipStream_t)stream;
+  // the same kernels as sla_classify_blocks; the statistics pass zeroes what it accumulates into
+  launch_pool_stats(q, k, k, p, at<float>(ws, C.qbar), at<float>(ws, C.kbar), at<float>(ws, C.dq),
+                    at<uint32_t>(ws, C.amax_v), s);
+  float* sc = pooled_scores ? pooled_scores : at<float>(ws, C.scores);
+  launch_scores(p, at<float>(ws, C.qbar), at<float>(ws, C.kbar), sc, s);
   launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, nullptr, s);
   return launch_status();
 }

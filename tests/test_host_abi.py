@@ -74,6 +74,21 @@ def test_backward_sizes_and_argument_errors():
     assert L.sla_attention_fwd_train(*(f[:14] + [9]), WS, sv, WS, big, None) == sla.ERR_UNSUPPORTED
 
 
+def test_static_scratch_entry_point_argument_errors():
+    # sla_classify_blocks_static: every refusal happens on the host, before the GPU is touched
+    L = sla.lib()
+    call = lambda **kw: L.sla_classify_blocks_static(kw.get("q", FAKE), FAKE, 1, kw.get("H", 2), kw.get("N", 1000),
+                                                     kw.get("d", 128), kw.get("bq", 128), 64, kw.get("rc", 0.25), 0.5,
+                                                     kw.get("mask", FAKE), None, None, kw.get("scores"), None)
+    assert call(q=None) == sla.ERR_NULL and call(mask=None) == sla.ERR_NULL
+    assert call(d=64) == sla.ERR_SHAPE and call(bq=32) == sla.ERR_BLOCK and call(rc=1.5) == sla.ERR_RATIO
+    # the Wan-14B-720P shape needs 148 MiB with the scores inside, 36 MiB with the caller holding them
+    assert call(H=40, N=75600) == sla.ERR_STATIC_LIMIT
+    assert call(H=80, N=75600, scores=FAKE) == sla.ERR_STATIC_LIMIT
+    assert sla.STATIC_SCRATCH_BYTES == 64 << 20
+    assert b"SLA_STATIC_SCRATCH_BYTES" in L.sla_status_string(sla.ERR_STATIC_LIMIT)
+
+
 def test_w8a8_sizes_and_argument_errors():
     L = sla.lib()
     # weight object and workspace: one byte per code (activations padded to 256-token tiles) plus scales
