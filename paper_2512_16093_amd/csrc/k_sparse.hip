@@ -367,6 +367,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const bool has_tail = ragged && n_c > 0 && (crow[last] & JMASK) == A.Tk - 1;
   constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4070 : (0x0070 | (2 * CH));  // s_waitcnt vmcnt(2*CH) lgkmcnt(0)
   constexpr int WAIT_ALL = 0x0070;                                            // s_waitcnt vmcnt(0) lgkmcnt(0)
+  constexpr int WAIT_KEEP_ALL_VM = 0xC07F;                                    // s_waitcnt lgkmcnt(0) only (vmcnt 63)
   v16i s0, s1;
   v8i pb_a = {}, pb_b = {};   // P codes of blocks b-1 / b (alternating); all-zero codes contribute nothing
   uint4 kfA[4], kfB[4], vfa[4], vfb[4];
@@ -448,6 +449,11 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     stage_barrier();
     read4(kst0, lane, 0, kfA);
     read4(kst0, lane, 4, kfB);
+    // Step 0 refills K slot 0 right away: every wavefront must have its fragments of block 0 in
+    // registers before any wavefront starts that copy (inside the loop the barrier that ends a step
+    // plays this part for the slot the next step refills).
+    __builtin_amdgcn_s_waitcnt(WAIT_KEEP_ALL_VM);
+    stage_barrier();
     s0 = qk_step(kfA[0], q8[0], bias16);
 #pragma unroll
     for (int u = 1; u < 4; ++u) s0 = qk_step(kfA[u], q8[u], s0);

@@ -24,6 +24,8 @@ RAGGED = [
     (1, (3, 27, 27), 128, 0.1, 0.2),      # N = 2187 = 17*128 + 11 = 34*64 + 11
     (1, (1, 9, 9), 128, 0.5, 0.5),        # N = 81: one ragged query block, two key blocks
     (1, (1, 5, 5), 64, 1.0, 0.0),         # N = 25: a single short block
+    (1, (3, 9, 7), 64, 0.34, 0.66),       # N = 189: three query blocks of 64 (an odd count: the last pair has one)
+    (2, (6, 7, 25), 64, 0.2, 0.4),        # N = 1050: 17 query blocks of 64, ragged
 ]
 
 
@@ -99,7 +101,9 @@ def test_sparse_branch_matches_oracle(case):
     for h in range(cfg.H):
         ref, ref_lse = so.sparse_branch_quant(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
                                               masks[0, h], cfg.block_q, 64, return_lse=True, ref_tile=pu.REF_TILE)
-        pu.check_output(out[0, h], ref, "sparse head %d" % h, max_abs=1e-2)
+        # tighter than the task's 2e-2 where a row's softmax spans several blocks; with a single 64-key block
+        # one weight whose 8-bit rounding falls the other way (fp32 here, fp64 there) moves an output by ~1e-2
+        pu.check_output(out[0, h], ref, "sparse head %d" % h, max_abs=1e-2 if n_c > 1 else pu.MAX_ABS)
         # the row sum is a sum of FP8-rounded terms: a rounding that falls the other way moves it a little
         dl = np.abs(lse[0, h] - ref_lse)
         assert dl.max() < 2e-2 and np.median(dl) < 1e-5
