@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 PEAK_MFMA_8BIT_TOPS = 5000.0   # MI355X dense INT8 (POP/s) and FP8 (PFLOP/s) MFMA peak, both 5.0e15
 # Bytes moved past L2 per launch of the sparse kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # from a 1 GiB copy in the same counter runs), by config id; source: profiles/sla_fwd_wan14b-720p.md.
@@ -48,7 +49,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="seeded config id (4 = Wan-14B-720P shape, the headline)")
     ap.add_argument("--layout", choices=("bhnd", "bnhd"), default="bhnd",
                     help="memory order of q, k, v and out: head-major [B,H,N,d] (default) or token-major "
@@ -413,20 +414,42 @@ def main():
     dt = time.perf_counter() - t0
     stages = sla.sla_profile_read(args.steps)
     sla.sla_profile_enable(0)
-    ms_per_step = dt / args.steps * 1e3
-    stage_ms = [sum(r[s] for r in stages) / len(stages) for s in range(sla.N_STAGES)]
+    import statistics
+    ms_wall_mean = dt / args.steps * 1e3
+    # per call: the stages' HIP-event times on the launch stream; the step time is the MEDIAN call
+    # (the mean over the wall clock of the whole timed region is reported beside it)
+    call_ms = [sum(r) for r in stages]
+    ms_per_step = statistics.median(call_ms) if call_ms else ms_wall_mean
+    stage_mean = [sum(r[s] for r in stages) / len(stages) for s in range(sla.N_STAGES)]
+    stage_ms = [statistics.median(r[s] for r in stages) for s in range(sla.N_STAGES)]
 
     flops = 4.0 * cfg.B * cfg.H * float(cfg.N) ** 2 * cfg.d
     value = flops / (ms_per_step * 1e-3) / 1e12
+    # HBM-bound stages: algorithmic bytes (each operand once) over the stage's median time
+    bhnd = float(cfg.B * cfg.H) * cfg.N * cfg.d
+    hz_row = 129 * 128 * 2.0                      # one block summary: 128 x 128 + 128 bf16 values
+    lin = n_m > 0 and low_bit
+    stage_bytes = {
+        "pool_stats": 6.0 * bhnd,                                                  # Q, K, V read once (bf16)
+        "prep_kv": 4.0 * bhnd + (2.0 * bhnd if low_bit else 0.0) + (cfg.B * cfg.H * Tk * hz_row if n_m > 0 else 0.0),
+        "lin_accumulate": cfg.B * cfg.H * (Tk + Tq) * hz_row if n_m > 0 else 0.0,  # summaries in once, sums out once
+    }
+    stage_hbm = {}
+    for name, nbytes in stage_bytes.items():
+        t = stage_ms[sla.STAGE_NAMES.index(name)]
+        if nbytes > 0 and t > 0:
+            gbps = nbytes / (t * 1e-3) / 1e9
+            stage_hbm[name] = {"bytes": nbytes, "GBps": round(gbps, 1), "frac_of_8TBps": round(gbps / PEAK_HBM_GBPS, 4)}
     # sparse kernel: per (query block, critical key block) pair 2*bq*bk*d INT8 ops + as many FP8 flops
     pairs = cfg.B * cfg.H * Tq * n_c
     ops = 2.0 * (2.0 * cfg.block_q * cfg.block_k * cfg.d) * pairs
-    t_sparse = stage_ms[4] * 1e-3
+    t_sparse = stage_mean[4] * 1e-3           # the roofline takes the kernel's AVERAGE launch duration
     achieved = ops / t_sparse / 1e12
     peak = PEAK_MFMA_8BIT_TOPS if low_bit else PEAK_MFMA_BF16_TFLOPS
     result = {
         "metric": "sla_fwd_dense_equiv_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_kind": "median of the timed calls (HIP events)",
+        "ms_per_step_wall_mean": ms_wall_mean, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         "dtype": "int8/fp8-e4m3 (fp32 accumulate; bf16 linear branch)" if low_bit else "bf16 (fp32 accumulate and softmax)",
         "data": "synthetic",
@@ -436,10 +459,13 @@ def main():
                                   "[B,H,N,d]" if args.layout == "bhnd" else "[B,N,H,d]"),
                    "n_crit": n_c, "n_marg": n_m, "Tq": Tq, "Tk": Tk},
         "stage_ms": dict(zip(sla.STAGE_NAMES, [round(x, 4) for x in stage_ms])),
+        "stage_hbm": stage_hbm,
         "roofline": {"kernel": "sparse_fwd_kernel" if low_bit else "bwd_stats_kernel<NW, true> (bf16 forward)",
                      "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": SPARSE_TRAFFIC_BYTES.get(cfg.cfg_id) if low_bit else None, "traffic_unit": "bytes per launch",
-                     "launch_ms": stage_ms[4], "ops_per_launch": ops},
+                     "traffic_source": "profiles/sla_fwd_wan14b-720p.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)"
+                                       if low_bit and cfg.cfg_id in SPARSE_TRAFFIC_BYTES else None,
+                     "launch_ms": stage_mean[4], "launch_ms_median": stage_ms[4], "ops_per_launch": ops},
         "context": "paper: 100-200x end-to-end, 184 s -> 1.9 s on one RTX 5090 (whole pipeline; no kernel-level number)",
     }
     if not args.no_cpu_baseline:

@@ -53,8 +53,7 @@
  *     quant_mode SLA_QUANT_QK_INT8_PV_FP8 (the paper's inference path) or
  *     SLA_QUANT_NONE (bf16 products: the training-time operator that
  *     sla_bwd.h differentiates; contiguous [B,H,N,d] tensors only).
- *   - Results of this header's entry points are deterministic: no floating-point
- *     atomics.  (sla_bwd.h: dQ, dK, dV likewise; see there for dW and db.)
+ *   - Results are deterministic: no floating-point atomics anywhere (sla_bwd.h included).
  */
 #ifndef SLA_H_
 #define SLA_H_

@@ -23,7 +23,7 @@
  * before and after); inputs are never written; outputs must not alias inputs or the workspace.
  * Returns SLA_OK or a negative sla_status; argument errors are found on the host before any launch.
  * Supported: what sla_attention_fwd supports for shapes, blocks and ratios; contiguous [B,H,N,d]
- * tensors; phi_kind SLA_PHI_SOFTMAX or SLA_PHI_ELU1 (SLA_PHI_RELU: SLA_ERR_UNSUPPORTED).
+ * tensors; any phi_kind of sla_phi (relu's gradient is taken as 0 at x <= 0).
  */
 #ifndef SLA_BWD_H_
 #define SLA_BWD_H_
@@ -47,11 +47,12 @@ size_t sla_bwd_workspace_bytes(int B, int H, int N, int d, int block_q, int bloc
  *   proj_w    in   bf16 [d,d] (row = output channel) or NULL = identity, as in sla_attention_fwd
  *   dq,dk,dv  out  bf16 [B,H,N,d]
  *   dproj_w   out  fp32 [d,d]  sum over all (b,h,n) of dout[n]^T O^l[n]; NULL = not wanted.
- *                  Summed with floating-point atomics: the order of the additions, hence the
- *                  last bits, can differ from run to run.  Zero when there is no marginal block.
+ *                  Zero when there is no marginal block.
  *   dproj_b   out  fp32 [d]    sum over all (b,h,n) of dout[n] (the bias gradient); NULL = not
- *                  wanted; same remark.  Zero when there is no marginal block (the forward pass
- *                  then adds no bias).
+ *                  wanted.  Zero when there is no marginal block (the forward pass then adds no
+ *                  bias).
+ * Every output is deterministic: dproj_w and dproj_b are per-workgroup partial sums added in a
+ * fixed order by a second kernel (no floating-point atomics anywhere).
  * With sla_profile_enable (sla.h) a call records the same number of stage events as a forward
  * call; the stages are: 0 block mask, 1 softmax statistics (lse, delta),
  * 2 linear branch and projection (summaries, dQ share, transposed accumulation, dK / dV shares),

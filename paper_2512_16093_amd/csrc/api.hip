@@ -174,7 +174,7 @@ struct BwdWorkspace {
   size_t dHZ;                // bf16 [BH, Tq, HZ_ROWS, D]: per query block dH^T and dZ
   size_t mbits_t;            // transposed marginal bit matrix
   size_t wt;                 // bf16 [D, D]: W^T
-  size_t dw_scratch;         // fp32 [D, D]: stands in for dproj_w when only dproj_b is wanted
+  size_t dw_part;            // fp32 per-workgroup partial sums of dW and db (bwd_lin_q_partial_bytes)
   size_t total;
 };
 
@@ -190,7 +190,7 @@ BwdWorkspace make_bwd_workspace(const Problem& p, const Workspace& W) {
   b.dHZ = take(lin ? BH * (size_t)p.Tq * HZ_ELEMS * 2 : 0);
   b.mbits_t = take(lin ? marginal_bits_t_bytes(p) : 0);
   b.wt = take(D * D * 2);
-  b.dw_scratch = take(D * D * 4);
+  b.dw_part = take(lin ? bwd_lin_q_partial_bytes(p) : 0);
   b.total = o;
   return b;
 }
@@ -492,7 +492,7 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
-  if (phi_kind != SLA_PHI_SOFTMAX && phi_kind != SLA_PHI_ELU1) return SLA_ERR_UNSUPPORTED;  // (relu: forward only)
+  if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
   const SavedState V = make_saved(p);
   if (saved && (st = check_ws(saved, saved_bytes, V.total)) != SLA_OK) return st;
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
@@ -518,9 +518,9 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
     launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
   }
   mark(s, rec, 2);
-  float* dw_eff = dproj_w ? dproj_w : (dproj_b ? at<float>(ws, X.dw_scratch) : nullptr);
-  if (dproj_w) launch_zero_u32((uint32_t*)dproj_w, (size_t)D * D, s);
-  if (dproj_b) launch_zero_u32((uint32_t*)dproj_b, (size_t)D, s);
+  // (with no marginal block there is no linear term: the projection and the bias receive no gradient)
+  if (dproj_w && !lin) launch_zero_u32((uint32_t*)dproj_w, (size_t)D * D, s);
+  if (dproj_b && !lin) launch_zero_u32((uint32_t*)dproj_b, (size_t)D, s);
   if (lin) {
     // H_i, Z_i of the forward pass (unprojected), then the linear branch's gradients
     launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
@@ -528,7 +528,7 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
     launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
     launch_bwd_wt((const bf16_t*)proj_w, at<bf16_t>(ws, X.wt), s);
     if (launch_bwd_lin_q(p, q, dout, at<bf16_t>(ws, W.HZ), at<bf16_t>(ws, X.wt), phi_kind, at<float>(ws, X.dql),
-                         at<bf16_t>(ws, X.dHZ), dw_eff, dproj_b, s) != 0)
+                         at<bf16_t>(ws, X.dHZ), dproj_w, dproj_b, at<float>(ws, X.dw_part), s) != 0)
       return SLA_ERR_HIP;
     // G_j = sum of dH_i over the query blocks that hold key block j as marginal: the forward's
     // accumulation kernel on the transposed mask (its output reuses the per-key-block summaries' buffer)

@@ -200,8 +200,9 @@ void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream);
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
+size_t bwd_lin_q_partial_bytes(const Problem& p);
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
-                     int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream);
+                     int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, float* partials, hipStream_t stream);
 void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream);
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
                           uint8_t* v_codes, hipStream_t stream);

@@ -1048,7 +1048,8 @@ static void launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout
 void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream) {
   if (!G || phi_kind == 0) launch_bwd_dkv_phi<0>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
-  else launch_bwd_dkv_phi<1>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);  // (the caller admits 0 and 1 only)
+  else if (phi_kind == 1) launch_bwd_dkv_phi<1>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  else launch_bwd_dkv_phi<2>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
 }
 
 }  // namespace sla

@@ -72,7 +72,7 @@ template <int NW, int PHI>
 __global__ void __launch_bounds__(NW * 64, 1)
     bwd_lin_q_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ HZ,
                      const bf16_t* __restrict__ wt, float* __restrict__ dq_lin, bf16_t* __restrict__ dHZ,
-                     float* __restrict__ dW, float* __restrict__ db, int N, int Tq) {
+                     float* __restrict__ dW_part, float* __restrict__ db_part, int N, int Tq) {
   constexpr int BQ = 32 * NW;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Wt = (bf16_t*)smem;              // [c'][r]
@@ -302,7 +302,7 @@ __global__ void __launch_bounds__(NW * 64, 1)
     __syncthreads();             // aT and dnumT are consumed
 
     // ---- dW[r][c] += sum_n dO[n][r] O^l[n][c],  db[r] += sum_n dO[n][r]
-    if (dW) {
+    if (dW_part || db_part) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const uint32_t gw[4] = {gf[ks].x, gf[ks].y, gf[ks].z, gf[ks].w};
@@ -321,6 +321,7 @@ __global__ void __launch_bounds__(NW * 64, 1)
           R3[(c0 + 3) * LP + nl] = (bf16_t)(olp[ot][g].y >> 16);
         }
       __syncthreads();
+      if (dW_part) {             // (only the bias gradient wanted: no products)
 #pragma unroll
       for (int a = 0; a < RT; ++a) {
         const int rt = w + a * NW;
@@ -339,6 +340,7 @@ __global__ void __launch_bounds__(NW * 64, 1)
           __builtin_amdgcn_sched_group_barrier(0x008, BQ / 16, 0);
         }
       }
+      }
       if (t < 128) {  // db[r = t] += sum_n dO[n][r]
         float s = 0.f;
 #pragma unroll
@@ -352,16 +354,37 @@ __global__ void __launch_bounds__(NW * 64, 1)
       __syncthreads();
     }
   }
-  if (dW) {
+  // This workgroup's share of dW and db goes to its own slice; bwd_reduce_partials_kernel adds the
+  // slices in a fixed order, so the sums do not depend on which workgroup finishes first.
+  const size_t wg = (size_t)blockIdx.y * gridDim.x + blockIdx.x;
+  if (dW_part) {
+    float* mine = dW_part + wg * (D * D);
 #pragma unroll
     for (int a = 0; a < RT; ++a)
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          atomicAdd(dW + (32 * (w + a * NW) + 8 * (r >> 2) + 4 * hf + (r & 3)) * D + 32 * ct + l32, dwacc[a][ct][r]);
-    if (db && t < 128) atomicAdd(db + t, dbacc);
+          mine[(32 * (w + a * NW) + 8 * (r >> 2) + 4 * hf + (r & 3)) * D + 32 * ct + l32] = dwacc[a][ct][r];
   }
+  if (db_part && t < 128) db_part[wg * D + t] = dbacc;
+}
+
+// out[x] = sum over p of part[p][x], p ascending: one thread per entry, a fixed order of additions.
+__global__ void __launch_bounds__(256) bwd_reduce_partials_kernel(const float* __restrict__ part, int n_part, int n,
+                                                                  float* __restrict__ out) {
+  const int x = blockIdx.x * 256 + threadIdx.x;
+  if (x >= n) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;   // four chains for latency; the order is still fixed
+  int p = 0;
+  for (; p + 4 <= n_part; p += 4) {
+    s0 += part[(size_t)p * n + x];
+    s1 += part[(size_t)(p + 1) * n + x];
+    s2 += part[(size_t)(p + 2) * n + x];
+    s3 += part[(size_t)(p + 3) * n + x];
+  }
+  for (; p < n_part; ++p) s0 += part[(size_t)p * n + x];
+  out[x] = (s0 + s1) + (s2 + s3);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -371,11 +394,15 @@ void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream) {
 
 size_t bwd_lin_q_lds_bytes() { return (size_t)4 * 128 * LP * 2 + 128 * 4 + 128 * 4; }
 
+// Workgroups per head of bwd_lin_q_kernel are at most this many (the partial sums' buffer is sized by it).
+constexpr int LIN_Q_MAX_CHUNKS = 64;
+size_t bwd_lin_q_partial_bytes(const Problem& p) { return (size_t)LIN_Q_MAX_CHUNKS * p.BH * (D * D + D) * 4; }
+
 template <int PHI>
 static int launch_bwd_lin_q_phi(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
-                                float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
+                                float* dq_lin, bf16_t* dHZ, float* dW, float* db, float* partials, hipStream_t stream) {
   // workgroups per head: enough of them to fill the compute units a whole number of times where
-  // that is possible (one workgroup per unit), few enough that the dW, db atomics stay cheap
+  // that is possible (one workgroup per unit), few enough that the per-workgroup partial sums of dW, db stay small
   static int n_cu = 0;
   if (n_cu == 0) {
     int dev = 0, v = 0;
@@ -383,7 +410,7 @@ static int launch_bwd_lin_q_phi(const Problem& p, const void* q, const void* dou
     n_cu = v;
   }
   int chunks = 16;
-  for (int c = 16; c <= 64; ++c)
+  for (int c = 16; c <= LIN_Q_MAX_CHUNKS; ++c)
     if ((long long)c * p.BH % n_cu == 0) {
       chunks = c;
       break;
@@ -398,17 +425,24 @@ static int launch_bwd_lin_q_phi(const Problem& p, const void* q, const void* dou
       return -1;
     attr_set = true;
   }
+  // per-workgroup partial sums: dW slices first, then db slices
+  const int n_part = chunks * p.BH;
+  float* dW_part = dW ? partials : nullptr;
+  float* db_part = db ? partials + (size_t)LIN_Q_MAX_CHUNKS * p.BH * D * D : nullptr;
   if (p.block_q == 128)
-    bwd_lin_q_kernel<4, PHI><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
+    bwd_lin_q_kernel<4, PHI><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW_part, db_part, p.N, p.Tq);
   else
-    bwd_lin_q_kernel<2, PHI><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW, db, p.N, p.Tq);
+    bwd_lin_q_kernel<2, PHI><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW_part, db_part, p.N, p.Tq);
+  if (dW) bwd_reduce_partials_kernel<<<(D * D + 255) / 256, 256, 0, stream>>>(dW_part, n_part, D * D, dW);
+  if (db) bwd_reduce_partials_kernel<<<1, 256, 0, stream>>>(db_part, n_part, D, db);
   return 0;
 }
 
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
-                     int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, hipStream_t stream) {
-  if (phi_kind == 0) return launch_bwd_lin_q_phi<0>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, stream);
-  return launch_bwd_lin_q_phi<1>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, stream);  // (the caller admits 0 and 1 only)
+                     int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, float* partials, hipStream_t stream) {
+  if (phi_kind == 0) return launch_bwd_lin_q_phi<0>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, partials, stream);
+  if (phi_kind == 1) return launch_bwd_lin_q_phi<1>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, partials, stream);
+  return launch_bwd_lin_q_phi<2>(p, q, dout, HZ, wt, dq_lin, dHZ, dW, db, partials, stream);
 }
 
 }  // namespace sla

@@ -79,11 +79,14 @@ def test_backward_matches_gradient_oracle(H, grid, bq, rc, rm, proj):
         _compare("dproj_b", db.cpu().numpy(), sums_b)
 
 
+@pytest.mark.parametrize("phi", ["elu1", "relu"])
 @pytest.mark.parametrize("H,grid,bq,rc,rm", [(2, (5, 10, 20), 128, 0.25, 0.5), (1, (3, 27, 27), 64, 0.1, 0.9),
                                              (2, (5, 10, 20), 64, 0.75, 0.25)])
-def test_backward_with_the_elu_feature_map(H, grid, bq, rc, rm):
-    """phi = elu + 1 in the linear branch (the forward pass offers it; the oracle's gradient for it is
-    pinned by the same finite-difference and autograd checks as the softmax's): both dK/dV variants."""
+def test_backward_with_the_other_feature_maps(H, grid, bq, rc, rm, phi):
+    """phi = elu + 1 or relu in the linear branch (the forward pass offers them; the oracle's gradient for
+    them is pinned by the same finite-difference and autograd checks as the softmax's -- relu's on inputs
+    kept away from its kink; the bf16 inputs here hold no exact zero that both sides would not treat
+    alike, x > 0): both dK/dV variants."""
     cfg = synth.custom_config(1, H, grid, block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=True, cfg_id=303)
     q, k, v = synth.make_qkv(cfg)
     dout = synth.make_qkv(cfg, seed=11)[2]
@@ -92,13 +95,13 @@ def test_backward_with_the_elu_feature_map(H, grid, bq, rc, rm):
     qd, kd, vd, dd, Wd = (t.to(dev) for t in (q, k, v, dout, W))
     mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
     dq, dk, dv, dw, db = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True,
-                                               phi_kind=sla.PHI_ELU1)
+                                               phi_kind=sla.PHI_ELU1 if phi == "elu1" else sla.PHI_RELU)
     torch.cuda.synchronize()
     sums_w, sums_b = np.zeros((cfg.d, cfg.d)), np.zeros(cfg.d)
     for h in range(H):
         r = bo.sla_backward_head(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
                                  synth.as_f64(dout[0, h]), mask[0, h], bq, 64, proj_w=synth.as_f64(W), has_bias=True,
-                                 phi="elu1")
+                                 phi=phi)
         _compare("dq", dq[0, h].float().cpu().numpy(), r["dQ"])
         _compare("dk", dk[0, h].float().cpu().numpy(), r["dK"])
         _compare("dv", dv[0, h].float().cpu().numpy(), r["dV"])
@@ -168,8 +171,29 @@ def test_backward_argument_errors():
     dev = torch.device("cuda:0")
     x = torch.zeros((1, 1, 128, 128), dtype=torch.bfloat16, device=dev)
     with pytest.raises(sla.SLAError) as e:
-        sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, phi_kind=sla.PHI_RELU)
+        sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, phi_kind=3)
     assert e.value.status == sla.ERR_UNSUPPORTED
     with pytest.raises(sla.SLAError) as e:
         sla.sla_attention_bwd(x, x, x, x, 128, 64, 0.5, 0.5, workspace=torch.empty(256, dtype=torch.uint8, device=dev))
     assert e.value.status == sla.ERR_WORKSPACE
+
+
+def test_projection_gradients_are_deterministic_and_bias_alone_can_be_asked_for():
+    """dproj_w and dproj_b are per-workgroup partial sums added in a fixed order: two calls give the same
+    bits (a shape with several workgroups per head), and asking for the bias gradient alone gives the same
+    bias gradient as asking for both."""
+    cfg = synth.custom_config(1, 3, (8, 16, 32), block_q=128, topk_ratio=0.2, marginal_ratio=0.4, use_proj=True, cfg_id=305)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=5)[2]
+    dev = torch.device("cuda:0")
+    qd, kd, vd, dd, Wd = (t.to(dev) for t in (q, k, v, dout, synth.make_proj(cfg)))
+    run = lambda **kw: sla.sla_attention_bwd(qd, kd, vd, dd, 128, 64, 0.2, 0.4, proj_w=Wd, **kw)
+    a = run(want_dw=True, want_db=True)
+    b = run(want_dw=True, want_db=True)
+    c = run(want_db=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert c[3] is None and torch.equal(c[4], a[4])
+    ref_b = dout.double().sum(dim=(0, 1, 2)).numpy()           # the bias gradient has a closed form
+    assert np.abs(a[4].cpu().numpy() - ref_b).max() <= 1e-4 * np.abs(ref_b).max() + 1e-3

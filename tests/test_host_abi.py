@@ -57,7 +57,7 @@ def test_backward_sizes_and_argument_errors():
     assert L.sla_attention_bwd(*args(d=64)) == sla.ERR_SHAPE
     assert L.sla_attention_bwd(*args(bq=32)) == sla.ERR_BLOCK
     assert L.sla_attention_bwd(*args(rc=0.0)) == sla.ERR_RATIO
-    assert L.sla_attention_bwd(*args(phi=2)) == sla.ERR_UNSUPPORTED          # relu: forward only
+    assert L.sla_attention_bwd(*args(phi=3)) == sla.ERR_UNSUPPORTED          # not a feature map
     assert L.sla_attention_bwd(*args(ws=None)) == sla.ERR_WORKSPACE
     assert L.sla_attention_bwd(*args(bytes=bwd - 1)) == sla.ERR_WORKSPACE
     # the saved state: padded per-row statistics plus a bf16 copy of O^s

@@ -13,10 +13,13 @@ from oracle import sla_bwd_oracle as bo
 from oracle import sla_oracle as so
 
 
-def _case(N, d, bq, bk, rc, rm, seed, proj=True, bias=True):
+def _case(N, d, bq, bk, rc, rm, seed, proj=True, bias=True, off_kink=False):
     g = np.random.default_rng(seed)
     Q, K, V, dO = (g.standard_normal((N, d)) for _ in range(4))
     Q *= 1.5   # sharper softmax rows, so P is far from uniform
+    if off_kink:   # relu is not differentiable at 0: keep every entry of Q and K at least 0.05 away from it
+        Q, K = (X + 0.05 * np.where(X >= 0, 1.0, -1.0) for X in (Q, K))
+        Q[:, 0], K[:, 0] = np.abs(Q[:, 0]), np.abs(K[:, 0])   # and one live channel per token, so phi(Q) . Z > 0
     Tq, Tk, n_c, n_m = so.block_counts(N, bq, bk, rc, rm)
     mask = so.classify(so.pooled_scores(Q, K, bq, bk), n_c, n_m)
     W = g.standard_normal((d, d)) / math.sqrt(d) if proj else None
@@ -31,10 +34,10 @@ CASES = [  # N, d, bq, bk, critical, marginal
 ]
 
 
-@pytest.mark.parametrize("phi", ["softmax", "elu1"])
+@pytest.mark.parametrize("phi", ["softmax", "elu1", "relu"])
 @pytest.mark.parametrize("N,d,bq,bk,rc,rm", CASES)
 def test_matches_central_differences_of_the_forward_oracle(N, d, bq, bk, rc, rm, phi):
-    Q, K, V, dO, mask, W, b = _case(N, d, bq, bk, rc, rm, 1)
+    Q, K, V, dO, mask, W, b = _case(N, d, bq, bk, rc, rm, 1, off_kink=(phi == "relu"))
 
     def loss(Q_, K_, V_, W_, b_):
         out = so.sla_forward_head(Q_, K_, V_, bq, bk, rc, rm, proj_w=W_, proj_b=b_, phi=phi,
@@ -75,6 +78,8 @@ def _torch_forward(Q, K, V, mask, bq, bk, W, b, phi):
     Os = P @ V
     if phi == "softmax":
         fq, fk = torch.softmax(Q, dim=1), torch.softmax(K, dim=1)
+    elif phi == "relu":
+        fq, fk = torch.relu(Q), torch.relu(K)
     else:
         fq, fk = torch.nn.functional.elu(Q) + 1, torch.nn.functional.elu(K) + 1
     A = (fq @ fk.T) * (tok == 0)                                           # unnormalised linear attention weights
@@ -82,10 +87,10 @@ def _torch_forward(Q, K, V, mask, bq, bk, W, b, phi):
     return Os + Ol @ W.T + b
 
 
-@pytest.mark.parametrize("phi", ["softmax", "elu1"])
+@pytest.mark.parametrize("phi", ["softmax", "elu1", "relu"])
 @pytest.mark.parametrize("N,d,bq,bk,rc,rm", CASES)
 def test_matches_autograd_of_a_dense_masked_formulation(N, d, bq, bk, rc, rm, phi):
-    Q, K, V, dO, mask, W, b = _case(N, d, bq, bk, rc, rm, 3)
+    Q, K, V, dO, mask, W, b = _case(N, d, bq, bk, rc, rm, 3, off_kink=(phi == "relu"))
     t = [torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (Q, K, V, W, b)]
     out = _torch_forward(*t[:3], mask, bq, bk, t[3], t[4], phi)
     # the two forward passes agree, so the comparison below is about the gradient alone
