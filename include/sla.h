@@ -50,9 +50,10 @@
  *     SLA_ERR_HIP reports a failed launch.  Nothing throws or aborts.
  *   - Supported: d == 128; block_k == 64; block_q in {64, 128}; 1 <= N with
  *     ceil(N/64) <= 8192; B*H*ceil(N/block_q) < 2^31; phi in sla_phi;
- *     quant_mode SLA_QUANT_QK_INT8_PV_FP8 (the paper's inference path) or
+ *     quant_mode SLA_QUANT_QK_INT8_PV_FP8 (the paper's inference path),
  *     SLA_QUANT_NONE (bf16 products: the training-time operator that
- *     sla_bwd.h differentiates; contiguous [B,H,N,d] tensors only).
+ *     sla_bwd.h differentiates) or SLA_QUANT_QK_INT8 (see sla_quant); the
+ *     last two take contiguous [B,H,N,d] tensors only.
  *   - Results are deterministic: no floating-point atomics anywhere (sla_bwd.h included).
  */
 #ifndef SLA_H_
@@ -85,7 +86,11 @@ typedef enum { SLA_PHI_SOFTMAX = 0, SLA_PHI_ELU1 = 1, SLA_PHI_RELU = 2 } sla_phi
 
 typedef enum {
   SLA_QUANT_NONE = 0,            /* bf16 products, fp32 accumulation and softmax: plain SLA (sla_attention_fwd only) */
-  SLA_QUANT_QK_INT8 = 1,         /* reserved: INT8 QK^T, 16-bit PV (not built) */
+  SLA_QUANT_QK_INT8 = 1,         /* scores from the INT8 codes of Q and of the smoothed K (integer products, exact), P and
+                                    V in bf16: separates the INT8 error from the FP8 error (sla_attention_fwd only).  A
+                                    diagnostic mode: the codes travel as bf16 numbers through the 16-bit matrix pipe, whose
+                                    products and fp32 sums of such integers are exact, so the scores are bit for bit what
+                                    an INT8 product gives */
   SLA_QUANT_QK_INT8_PV_FP8 = 2   /* INT8 QK^T with K-smoothing, FP8 E4M3 PV */
 } sla_quant;
 

@@ -166,9 +166,10 @@ def sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio
     return lib().sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, quant_mode)
 
 
-def alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, device="cuda"):
+def alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, device="cuda",
+                    quant_mode=QUANT_QK_INT8_PV_FP8):
     """Device scratch of the size the library asks for (torch allocations are 256-byte aligned)."""
-    nbytes = sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio)
+    nbytes = sla_workspace_bytes(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, quant_mode)
     if nbytes == 0:
         raise ValueError("invalid problem for sla_workspace_bytes")
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -178,7 +179,7 @@ def sla_attention_fwd(q, k, v, block_q, block_k, topk_ratio, marginal_ratio, pro
                       phi_kind=PHI_SOFTMAX, quant_mode=QUANT_QK_INT8_PV_FP8, workspace=None, out=None):
     B, H, N, d = _bf16_4d(q, k, v)
     if workspace is None:
-        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device, quant_mode)
     if out is None:
         out = torch.empty_like(q)
     st = lib().sla_attention_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, N, d, block_q, block_k,

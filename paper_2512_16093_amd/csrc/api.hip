@@ -131,9 +131,12 @@ void run_stats(const void* q, const void* k, const void* v, const void* proj_w, 
 
 // The unquantised forward pass (bf16 products): the launch sequence of sla_attention_fwd with
 // SLA_QUANT_NONE; save_lse2 / save_os, if given, receive what a backward pass can reuse.
+// With codes16 (SLA_QUANT_QK_INT8) the scores are the integer products of the INT8 codes of Q and of the
+// smoothed K: the codes travel as bf16 numbers, whose products and fp32 sums are exact, through the same
+// kernel; P and V stay 16-bit.
 int fwd_bf16(const void* q, const void* k, const void* v, void* out, const Problem& p, const void* proj_w,
              const void* proj_b, int phi_kind, void* ws, const Workspace& W, hipStream_t s, int rec, float* save_lse2,
-             void* save_os) {
+             void* save_os, bool codes16 = false) {
   const bool lin = p.n_m > 0;
   mark(s, rec, 0);
   run_stats(q, k, v, proj_w, p, ws, W, s);
@@ -142,14 +145,19 @@ int fwd_bf16(const void* q, const void* k, const void* v, void* out, const Probl
   launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
-  if (lin)
-    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
+  if (lin || codes16)
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, codes16, lin,
                    at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+  if (codes16)
+    launch_code_tensors(q, p, at<int8_t>(ws, W.k8), at<float>(ws, W.dq), at<bf16_t>(ws, W.qc), at<bf16_t>(ws, W.kc), s);
   mark(s, rec, 3);
   if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   mark(s, rec, 4);
-  launch_fwd_bf16(p, q, k, v, at<int32_t>(ws, W.crit), lin ? at<bf16_t>(ws, W.HZ) : nullptr, (const bf16_t*)proj_b,
-                  phi_kind, out, save_lse2, save_os, s);
+  const CodeScales cs{at<float>(ws, W.dq), at<float>(ws, W.dk), q};
+  if (launch_fwd_bf16(p, codes16 ? at<bf16_t>(ws, W.qc) : q, codes16 ? at<bf16_t>(ws, W.kc) : k, v, at<int32_t>(ws, W.crit),
+                      lin ? at<bf16_t>(ws, W.HZ) : nullptr, (const bf16_t*)proj_b, phi_kind, out, save_lse2, save_os,
+                      codes16 ? &cs : nullptr, s) != 0)
+    return SLA_ERR_HIP;
   mark(s, rec, 5);
   return launch_status();
 }
@@ -226,10 +234,10 @@ int sla_block_counts(int N, int block_q, int block_k, double topk_ratio, double 
 size_t sla_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k, double topk_ratio,
                            double marginal_ratio, int quant_mode) {
   Problem p;
-  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8 && quant_mode != SLA_QUANT_NONE) return 0;
+  if (quant_mode < SLA_QUANT_NONE || quant_mode > SLA_QUANT_QK_INT8_PV_FP8) return 0;
   if (make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p) != SLA_OK) return 0;
-  // the stage entry points take caller-chosen lists (up to every block critical or marginal)
-  return make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m).total;
+  // (sized by the given ratios; SLA_QUANT_QK_INT8 adds the two 16-bit code tensors)
+  return make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m, quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0).total;
 }
 
 int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,
@@ -256,20 +264,22 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   if ((st = make_layout(v, v_strides, H, N, &p.lv)) != SLA_OK) return st;
   if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
-  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8 && quant_mode != SLA_QUANT_NONE) return SLA_ERR_UNSUPPORTED;
-  if (quant_mode == SLA_QUANT_NONE) {  // the 16-bit path takes contiguous [B,H,N,d] tensors only
+  if (quant_mode < SLA_QUANT_NONE || quant_mode > SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) {  // the 16-bit kernels take contiguous [B,H,N,d] tensors only
     const Layout c = contiguous_layout(H, N);
     for (const Layout* L : {&p.lq, &p.lk, &p.lv, &p.lo})
       if (L->sb != c.sb || L->sh != c.sh || L->sn != c.sn) return SLA_ERR_LAYOUT;
   }
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m,
+                                     quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   const bool lin = p.n_m > 0;
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
-  if (quant_mode == SLA_QUANT_NONE)
-    return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, ws, W, s, rec, nullptr, nullptr);
+  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8)
+    return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, ws, W, s, rec, nullptr, nullptr,
+                    quant_mode == SLA_QUANT_QK_INT8);
   mark(s, rec, 0);
   run_stats(q, k, v, proj_w, p, ws, W, s);
   mark(s, rec, 1);
@@ -515,7 +525,8 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
     lse2 = (const float*)((const unsigned char*)saved + V.lse2);
     launch_bwd_delta(p, dout, (const unsigned char*)saved + V.os, at<float>(ws, X.delta), s);
   } else {
-    launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s);
+    if (launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s) != 0)
+      return SLA_ERR_HIP;
   }
   mark(s, rec, 2);
   // (with no marginal block there is no linear term: the projection and the bias receive no gradient)
@@ -539,11 +550,13 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
     launch_lin_accumulate(pt, at<uint32_t>(ws, X.mbits_t), at<bf16_t>(ws, X.dHZ), at<bf16_t>(ws, W.hz), s);
   }
   mark(s, rec, 3);
-  launch_bwd_dq(p, q, dout, k, v, at<int32_t>(ws, W.crit), lse2, at<float>(ws, X.delta),
-                lin ? at<float>(ws, X.dql) : nullptr, dq, s);
+  if (launch_bwd_dq(p, q, dout, k, v, at<int32_t>(ws, W.crit), lse2, at<float>(ws, X.delta),
+                    lin ? at<float>(ws, X.dql) : nullptr, dq, s) != 0)
+    return SLA_ERR_HIP;
   mark(s, rec, 4);
-  launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), lse2, at<float>(ws, X.delta),
-                 lin ? at<bf16_t>(ws, W.hz) : nullptr, phi_kind, dk, dv, s);
+  if (launch_bwd_dkv(p, q, dout, k, v, at<int8_t>(ws, W.mask), lse2, at<float>(ws, X.delta),
+                     lin ? at<bf16_t>(ws, W.hz) : nullptr, phi_kind, dk, dv, s) != 0)
+    return SLA_ERR_HIP;
   mark(s, rec, 5);
   return launch_status();
 }

@@ -111,12 +111,13 @@ struct Workspace {
   size_t hz;                // bf16 [BH,Tk,HZ_ROWS,D]
   size_t HZ;                // bf16 [BH,Tq,HZ_ROWS,D]
   size_t wfrag;             // bf16 [D,D]: the projection (identity if none) in the operand order of prep_kv
+  size_t qc, kc;            // bf16 [BH,N,D]: INT8 codes of Q and K as bf16 numbers (SLA_QUANT_QK_INT8 only)
   size_t total;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, size_t n_m) {
+inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, size_t n_m, size_t code_tensor_elems = 0) {
   Workspace w;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align256(o + bytes); return r; };
@@ -139,6 +140,8 @@ inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, siz
   w.hz = take(BH * Tk * HZ_ELEMS * 2);
   w.HZ = take(BH * Tq * HZ_ELEMS * 2);
   w.wfrag = take(D * D * 2);
+  w.qc = take(code_tensor_elems * 2);
+  w.kc = take(code_tensor_elems * 2);
   w.total = o;
   return w;
 }
@@ -189,15 +192,20 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
 // Backward pass (k_bwd.hip, k_bwd_lin.hip; the transposed bit matrix lives with lin_accumulate).
 size_t marginal_bits_t_bytes(const Problem& p);
 void launch_marginal_bits_t(const Problem& p, const int8_t* mask, uint32_t* mbits_t, hipStream_t stream);
-void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
-                      const int32_t* crit, float* lse2, float* delta, hipStream_t stream);
-void launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
-                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
-                     hipStream_t stream);
+int launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
+                     const int32_t* crit, float* lse2, float* delta, hipStream_t stream);
+// qk_scales: nullptr, or {delta_Q [BH,Tq], delta_K [BH,Tk]} when q and k hold INT8 codes (q_lin: the
+// original Q for the linear term's feature map)
+struct CodeScales { const float* dq; const float* dk; const void* q_lin; };
+int launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
+                    const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
+                    const CodeScales* codes, hipStream_t stream);
+void launch_code_tensors(const void* q, const Problem& p, const int8_t* k8, const float* dq, bf16_t* qc, bf16_t* kc,
+                         hipStream_t stream);
 void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float* delta, hipStream_t stream);
-void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
+int launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);
-void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+int launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                     const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream);
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
 size_t bwd_lin_q_partial_bytes(const Problem& p);

@@ -148,8 +148,13 @@ struct FwdEpilogue {
   int phi;
   float* save_lse2;    // [BH, 32 T32q] or nullptr: the rows' log-sum-exp (base 2), as bwd_stats_kernel<.., false> writes it
   bf16_t* save_os;     // [BH, N, D] or nullptr: O^s alone (for delta = dO . O^s of a later backward pass)
+  // CODES: q and k hold INT8 codes as bf16 numbers; a score is their (exact) product times
+  // delta_Q[i] delta_K[j] / sqrt(d), and the feature map of the linear term reads the original Q
+  const float* code_dq;  // [BH, Tq]
+  const float* code_dk;  // [BH, Tk]
+  const bf16_t* q_lin;   // [BH, N, D]
 };
-template <int NW, bool FWD>
+template <int NW, bool FWD, bool CODES = false>
 __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, const bf16_t* __restrict__ dout,
                                                             const int32_t* __restrict__ crit, float* __restrict__ lse2,
@@ -171,6 +176,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) o[ct] = v16f{};
   float m = -INFINITY;
+  const float qscale = CODES ? QK_LOG2 * fe.code_dq[(size_t)bh * dm.Tq + i] : QK_LOG2;
   v16f lacc = v16f{};  // register 0: the running sum of P over the keys (see the ones operand below)
   // key blocks travel memory -> registers -> LDS one step ahead, into the buffer the step before
   // last has left: one barrier per step
@@ -188,6 +194,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
   __syncthreads();
   for (int b = 0; b < dm.n_c; ++b) {
     const int j = crow[b];
+    const float c2 = CODES ? qscale * fe.code_dk[(size_t)bh * dm.Tk + j] : QK_LOG2;   // score -> base-2 logit
     const unsigned char* lds = lds_all + (b & 1) * 4 * TILE_B;
     unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
     {  // the next block (after the last one: the last one again), the same loads every time round -- see below
@@ -222,7 +229,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     // The reference m moves only when the block's maximum exceeds it by more than 2^8: P then stays
     // below 2^8 (harmless in bf16 and fp32) and the accumulators are rescaled a few times per row
     // instead of every step.  (mx is finite: a block holds at least one valid key.)
-    mx = fmaxf(mx, partner_f32(mx)) * QK_LOG2;
+    mx = fmaxf(mx, partner_f32(mx)) * c2;
     const bool moves = mx > m + 8.0f;
     if (__any(moves)) {
       const float m_new = moves ? mx : m;
@@ -237,7 +244,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kt][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], QK_LOG2, -m));
+      for (int r = 0; r < 16; ++r) s[kt][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], c2, -m));
     const uint4 ones = uint4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};  // bf16 1.0: sums P over the keys
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
@@ -284,7 +291,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const int c0 = 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1);
-        const uint4 qv = qok ? *(const uint4*)(q + head + qrow * D + c0) : uint4{0u, 0u, 0u, 0u};
+        const uint4 qv = qok ? *(const uint4*)((CODES ? fe.q_lin : q) + head + qrow * D + c0) : uint4{0u, 0u, 0u, 0u};
         x[8 * ks] = bf16_lo(qv.x); x[8 * ks + 1] = bf16_hi(qv.x); x[8 * ks + 2] = bf16_lo(qv.y); x[8 * ks + 3] = bf16_hi(qv.y);
         x[8 * ks + 4] = bf16_lo(qv.z); x[8 * ks + 5] = bf16_hi(qv.z); x[8 * ks + 6] = bf16_lo(qv.w); x[8 * ks + 7] = bf16_hi(qv.w);
       }
@@ -943,34 +950,43 @@ static bool allow_lds(K kernel) {
 
 static BwdDims bwd_dims(const Problem& p) { return BwdDims{p.N, p.Tq, p.Tk, p.n_c, p.Tq * (p.block_q / 32)}; }
 
-void launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
-                      const int32_t* crit, float* lse2, float* delta, hipStream_t stream) {
+// The launchers below return 0, or -1 when the kernel's LDS allowance could not be set (then nothing is
+// launched; the result of the attribute call is cached, the failure is reported on every call).
+int launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
+                     const int32_t* crit, float* lse2, float* delta, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   static const bool ok = allow_lds(bwd_stats_kernel<4, false>) && allow_lds(bwd_stats_kernel<2, false>);
-  if (!ok) return;  // (the launch below would fail the same way and be reported by the caller's status check)
-  const FwdEpilogue none{nullptr, nullptr, nullptr, 0, nullptr, nullptr};
+  if (!ok) return -1;
+  const FwdEpilogue none{nullptr, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
   if (p.block_q == 128)
     bwd_stats_kernel<4, false><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
                                                                       (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
   else
     bwd_stats_kernel<2, false><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
                                                                       (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
+  return 0;
 }
 
-// The unquantised forward pass: the same kernel with the output epilogue.
-void launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
-                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
-                     hipStream_t stream) {
+// The unquantised forward pass: the same kernel with the output epilogue; with `codes`, the same on
+// INT8 codes of Q and K (SLA_QUANT_QK_INT8: integer products, 16-bit P and V).
+int launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
+                    const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
+                    const CodeScales* codes, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
-  static const bool ok = allow_lds(bwd_stats_kernel<4, true>) && allow_lds(bwd_stats_kernel<2, true>);
-  if (!ok) return;
-  const FwdEpilogue fe{HZ, HZ ? proj_b : nullptr, (bf16_t*)out, phi_kind, save_lse2, (bf16_t*)save_os};
-  if (p.block_q == 128)
-    bwd_stats_kernel<4, true><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr,
-                                                                     crit, nullptr, nullptr, bwd_dims(p), fe);
-  else
-    bwd_stats_kernel<2, true><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr,
-                                                                     crit, nullptr, nullptr, bwd_dims(p), fe);
+  static const bool ok = allow_lds(bwd_stats_kernel<4, true>) && allow_lds(bwd_stats_kernel<2, true>) &&
+                         allow_lds(bwd_stats_kernel<4, true, true>) && allow_lds(bwd_stats_kernel<2, true, true>);
+  if (!ok) return -1;
+  const FwdEpilogue fe{HZ, HZ ? proj_b : nullptr, (bf16_t*)out, phi_kind, save_lse2, (bf16_t*)save_os,
+                       codes ? codes->dq : nullptr, codes ? codes->dk : nullptr, codes ? (const bf16_t*)codes->q_lin : nullptr};
+#define SLA_FWD16(NW, CODES) bwd_stats_kernel<NW, true, CODES><<<grid, NW * 64, KV_STAGE_BYTES, stream>>>( \
+      (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr, crit, nullptr, nullptr, bwd_dims(p), fe)
+  if (p.block_q == 128) {
+    if (codes) SLA_FWD16(4, true); else SLA_FWD16(4, false);
+  } else {
+    if (codes) SLA_FWD16(2, true); else SLA_FWD16(2, false);
+  }
+#undef SLA_FWD16
+  return 0;
 }
 
 // delta[bh][row] = dO[row] . O^s[row] from a saved O^s (rows beyond N: 0); one wavefront per 8 rows.
@@ -1002,22 +1018,23 @@ void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float*
                                                                      rows_padded, p.BH);
 }
 
-void launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
-                   const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream) {
+int launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
+                  const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   static const bool ok = allow_lds(bwd_dq_kernel<4>) && allow_lds(bwd_dq_kernel<2>);
-  if (!ok) return;
+  if (!ok) return -1;
   if (p.block_q == 128)
     bwd_dq_kernel<4><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
   else
     bwd_dq_kernel<2><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
                                                 lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
+  return 0;
 }
 
 constexpr int DKV1_TILES = 2;  // tiles per step of the one-key-block variant: 2 (78 KB of LDS per workgroup) runs compute_interleaved, 1 the plain step
 template <int PHI>
-static void launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+static int launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                                const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
   // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
   const int list_bytes = (2 * p.Tq + 15) & ~15;
@@ -1026,7 +1043,7 @@ static void launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout
   static const bool ok =
       hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess &&
       hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
-  if (!ok) return;
+  if (!ok) return -1;
   const int tiles = p.block_q / 32;  // of a query block: 2 or 4
   // Two key blocks per workgroup halve the bytes streamed where their lists coincide and idle half
   // a workgroup where they do not: worth it only when most blocks are critical (at the paper's
@@ -1042,14 +1059,15 @@ static void launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, (tiles == 4 ? 2 : 1) - (DKV1_TILES == 2 ? 1 : 0), bwd_dims(p));
   }
+  return 0;
 }
 
 // (the feature map matters to the prologue only -- the linear branch's share -- and only when G is given)
-void launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
-                    const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream) {
-  if (!G || phi_kind == 0) launch_bwd_dkv_phi<0>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
-  else if (phi_kind == 1) launch_bwd_dkv_phi<1>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
-  else launch_bwd_dkv_phi<2>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+int launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
+                   const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream) {
+  if (!G || phi_kind == 0) return launch_bwd_dkv_phi<0>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  if (phi_kind == 1) return launch_bwd_dkv_phi<1>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  return launch_bwd_dkv_phi<2>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
 }
 
 }  // namespace sla

@@ -258,6 +258,29 @@ __global__ void unfragment_kv_kernel(const int8_t* __restrict__ k8, const uint8_
   }
 }
 
+// SLA_QUANT_QK_INT8: the INT8 codes of Q and of the smoothed K as bf16 numbers (integers up to 127
+// are exact in bf16), [BH, N, D] contiguous, for the 16-bit attention kernel: its products of such
+// operands are the integer products, exactly (|sum| < 2^24 in the fp32 accumulator).
+// One workgroup per key block; the same for the query rows it covers.
+__global__ void __launch_bounds__(256) code_tensors_kernel(const bf16_t* __restrict__ q, const int8_t* __restrict__ k8,
+                                                           const float* __restrict__ dq, int N, int Tk, int H, int block_q, int Tq,
+                                                           Layout lq, bf16_t* __restrict__ qc, bf16_t* __restrict__ kc) {
+  const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk, b = bh / H, h = bh - b * H;
+  const size_t rec = ((size_t)bh * Tk + j) * KV_FRAG_BYTES;
+  for (int e = threadIdx.x; e < BK * D; e += 256) {
+    const int key = e / D, ch = e % D, row = j * BK + key;
+    if (row >= N) continue;
+    const size_t o = ((size_t)bh * N + row) * D + ch;
+    kc[o] = f32_to_bf16((float)k8[rec + kfrag_offset(key, ch)]);
+    // the query's code, decided exactly as the low-bit kernel decides it: rint(x / delta), clipped
+    const float dqi = dq[(size_t)bh * Tq + row / block_q];
+    const float x = bf16_to_f32(q[b * lq.sb + h * lq.sh + (long long)row * lq.sn + ch]);
+    float c = __builtin_rintf(x / dqi);
+    c = fminf(fmaxf(c, -127.f), 127.f);
+    qc[o] = f32_to_bf16(c);
+  }
+}
+
 __global__ void e4m3_encode_kernel(const float* __restrict__ in, uint8_t* __restrict__ out, size_t n) {
   const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   if (i < n) out[i] = (uint8_t)(cvt_pk_e4m3(clamp_e4m3(in[i]), 0.f, 0, false) & 0xff);
@@ -280,6 +303,11 @@ void launch_prep_kv(const void* k, const void* v, const Problem& p, const float*
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
                           uint8_t* v_codes, hipStream_t stream) {
   unfragment_kv_kernel<<<p.BH * p.Tk, 256, 0, stream>>>(k8, v8, p.N, p.Tk, k_codes, v_codes);
+}
+
+void launch_code_tensors(const void* q, const Problem& p, const int8_t* k8, const float* dq, bf16_t* qc, bf16_t* kc,
+                         hipStream_t stream) {
+  code_tensors_kernel<<<p.BH * p.Tk, 256, 0, stream>>>((const bf16_t*)q, k8, dq, p.N, p.Tk, p.H, p.block_q, p.Tq, p.lq, qc, kc);
 }
 
 void launch_e4m3_encode(const float* in, uint8_t* out, size_t n, hipStream_t stream) {

@@ -306,3 +306,36 @@ def test_unquantised_forward_rejects_strided_layouts():
     with pytest.raises(sla.SLAError) as e:
         sla.sla_attention_fwd_strided(qt, k, v, torch.empty_like(q), 128, 64, 0.5, 0.5, quant_mode=sla.QUANT_NONE)
     assert e.value.status == sla.ERR_LAYOUT
+
+
+@pytest.mark.parametrize("H,grid,bq,rc,rm,proj,phi", [
+    (2, (4, 16, 16), 64, 0.2, 0.4, True, "softmax"),       # the tiny named shape
+    (2, (5, 10, 20), 128, 0.25, 0.5, True, "softmax"),     # N = 1000, ragged in both block sizes
+    (1, (3, 27, 27), 128, 0.1, 0.2, False, "elu1"),        # N = 2187, identity projection
+    (1, (1, 9, 9), 128, 0.5, 0.5, True, "relu"),           # N = 81: one ragged query block
+    (1, (1, 5, 5), 64, 1.0, 0.0, False, "softmax"),        # N = 25: every block critical, no linear term
+])
+def test_int8_scores_mode_matches_oracle(H, grid, bq, rc, rm, proj, phi):
+    """quant_mode SLA_QUANT_QK_INT8 (INT8 Q.K^T with K-smoothing, 16-bit P and V) against the oracle's mode of
+    the same name, on the library's own mask: nothing is rounded to the 8-bit float here, so what is left
+    against the oracle is bf16 (P, the summaries, the output) -- the bar of the unquantised forward -- and
+    the distance to the exact branch is the INT8 error alone, smaller than the full low-bit path's."""
+    cfg = _cfg(H, grid, bq, rc, rm, proj=proj, cid=410)
+    q, k, v = synth.make_qkv(cfg)
+    W = synth.make_proj(cfg) if proj else None
+    qd, kd, vd, Wd = pu.to_dev(q, k, v, W)
+    kind = {"softmax": sla.PHI_SOFTMAX, "elu1": sla.PHI_ELU1, "relu": sla.PHI_RELU}[phi]
+    out8 = sla.sla_attention_fwd(qd, kd, vd, bq, 64, rc, rm, proj_w=Wd, phi_kind=kind, quant_mode=sla.QUANT_QK_INT8)
+    out88 = sla.sla_attention_fwd(qd, kd, vd, bq, 64, rc, rm, proj_w=Wd, phi_kind=kind)
+    mask = sla.sla_classify_blocks(qd, kd, bq, 64, rc, rm, want_scores=False)[0].cpu().numpy()
+    torch.cuda.synchronize()
+    for h in range(H):
+        args = (synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]), bq, 64, rc, rm)
+        kw = dict(proj_w=None if W is None else synth.as_f64(W), phi=phi, mask=mask[0, h])
+        ref = so.sla_forward_head(*args, quant=so.QUANT_QK_INT8, **kw)["out"]
+        exact = so.sla_forward_head(*args, quant=so.QUANT_NONE, **kw)["out"]
+        got = out8[0, h].float().cpu().numpy().astype(np.float64)
+        pu.check_output(got, ref, "INT8-scores mode, head %d" % h)
+        assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 5e-3
+        full = out88[0, h].float().cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(got - exact) <= np.linalg.norm(full - exact)     # INT8 alone errs less than INT8 + FP8

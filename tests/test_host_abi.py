@@ -162,7 +162,9 @@ def test_workspace_bytes():
                 (1, 2, 1024, 128, 96, 64, 0.2, 0.4), (1, 2, 1024, 128, 64, 64, 0.0, 0.4)):
         assert sla.sla_workspace_bytes(*bad) == 0
     assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_NONE) == w0   # the 16-bit path: same map
-    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_QK_INT8) == 0
+    # the INT8-scores mode adds the two 16-bit code tensors
+    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, sla.QUANT_QK_INT8) == w0 + 2 * 2 * 1024 * 128 * 2
+    assert sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4, 3) == 0
 
 
 def _fwd(q=FAKE, k=FAKE, v=FAKE, out=FAKE, B=1, H=2, N=1024, d=128, bq=64, bk=64, rc=0.2, rm=0.4,
@@ -178,7 +180,8 @@ def test_attention_fwd_argument_errors_are_found_before_any_launch():
     assert _fwd(bq=32) == sla.ERR_BLOCK and _fwd(bk=32) == sla.ERR_BLOCK
     assert _fwd(rc=0.0) == sla.ERR_RATIO and _fwd(rc=0.8, rm=0.4) == sla.ERR_RATIO
     assert _fwd(phi=7) == sla.ERR_UNSUPPORTED and _fwd(quant=3) == sla.ERR_UNSUPPORTED
-    assert _fwd(quant=1) == sla.ERR_UNSUPPORTED
+    assert _fwd(quant=-1) == sla.ERR_UNSUPPORTED
+    assert _fwd(quant=1, wsb=sla.sla_workspace_bytes(1, 2, 1024, 128, 64, 64, 0.2, 0.4)) == sla.ERR_WORKSPACE   # needs the larger map
     assert _fwd(quant=0, ws=None) == sla.ERR_WORKSPACE   # the 16-bit path checks its arguments the same way
     assert _fwd(ws=None) == sla.ERR_WORKSPACE
     assert _fwd(ws=ctypes.c_void_p(0x10010)) == sla.ERR_WORKSPACE          # misaligned
