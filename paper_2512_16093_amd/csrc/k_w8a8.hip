@@ -195,16 +195,23 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
   // product is taken transposed (weights as the A operand) so that a lane owns ONE token and runs
   // of four consecutive outputs.
   // The first product of a chain takes the pattern W8_BIAS_I as an inline constant (0.15915494 is
-  // the assembler's spelling of 1 / (2 pi)); written in assembly because the compiler would keep
-  // the constant in sixteen registers instead.  The compiler does not know this statement is an
-  // MFMA and adds no wait states after it: none are needed because the following products
-  // accumulate IN PLACE (destination = C operand, which the hardware forwards); that the register
-  // allocation keeps them in place is checked on the generated assembly by tests/test_build_checks.py.
-  auto chain = [&](const v4i (&b)[4], const v4i (&ar)[4]) {
+  // the assembler's spelling of 1 / (2 pi)); the compiler would keep the constant in sixteen
+  // registers instead.  Every product of a chain is an assembly statement whose accumulator is ONE
+  // in/out operand, so the chain accumulates in place by construction (destination = C operand,
+  // the case the hardware interlocks) whatever registers are allocated, and each product still
+  // takes its operands as they arrive.  The compiler does not know the statements hold
+  // matrix products and adds no wait states before a vector instruction that reads the result, so
+  // the data flow itself keeps every reader a whole chain (four dependent products, > 100 cycles)
+  // behind: a chain's result may only be read after it has been handed through the SECOND product
+  // of the next chain as `carry` (an in/out operand the statement does not touch; that product
+  // cannot issue before the next chain's first one has finished, 64 cycles after the carried
+  // chain's last one was issued), or, after the loop, through a statement of explicit wait states.
+  auto chain = [&](const v4i (&b)[4], const v4i (&ar)[4], v16i& carry) {
     v16i acc;
-    asm("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(acc) : "v"(b[0]), "v"(ar[0]));
-#pragma unroll
-    for (int ks = 1; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[ks], ar[ks], acc, 0, 0, 0);
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0.15915494" : "=&v"(acc) : "v"(b[0]), "v"(ar[0]));
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %2, %3, %0" : "+v"(acc), "+v"(carry) : "v"(b[1]), "v"(ar[1]));
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(b[2]), "v"(ar[2]));
+    asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(acc) : "v"(b[3]), "v"(ar[3]));
     return acc;
   };
   auto scale_in = [&](const v16i& acc, float sc, v16f& f) {
@@ -232,13 +239,16 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
         x.u = st[(ct * 4 + ks) * 64 + lane];
         b[ks] = x.v;
       }
-      acc0 = chain(b, a[0]);
+      acc0 = chain(b, a[0], pend);       // (from here on the previous chain's result may be read)
       v16f& ftile = facc[1][(ct + 3) & 3];
       scale_in(pend, pend_sc, ftile);
       asm volatile("" : "+v"(ftile) : : "memory");  // (the fmas stay in this window)
       asm volatile("" : "+v"(acc0) : : "memory");
       __builtin_amdgcn_sched_barrier(0);
-      pend = chain(b, a[1]);
+      {
+        v16i fresh = chain(b, a[1], acc0);
+        pend = fresh;
+      }
       pend_sc = sc;
       scale_in(acc0, sc, facc[0][ct]);
       asm volatile("" : "+v"(facc[0][ct]) : : "memory");
@@ -274,6 +284,8 @@ __global__ void __launch_bounds__(256, 2) w8a8_gemm_kernel(
     if (kb < KB) W8_STEP(kb, a0, a1)
   }
 #undef W8_STEP
+  // (the last chain's result: the wait states a vector read of a matrix product's result needs)
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(pend));
   scale_in(pend, pend_sc, facc[1][3]);
 
   // Epilogue: constant share out, bias in, bf16, through LDS so that rows leave as 256 contiguous
