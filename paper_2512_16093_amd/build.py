@@ -14,6 +14,9 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsla.so")
+# The same library with the attention kernel's hand-counted copy waits replaced by full waits
+# (-DSLA_FULL_WAITS): a checking build that a GPU test compares with the product build bit for bit.
+LIB_FULL_WAITS = os.path.join(HERE, "libsla_fullwaits.so")
 SOURCES = ["api.hip", "api_w8a8.hip", "k_classify.hip", "k_prep.hip", "k_linacc.hip", "k_sparse.hip", "k_w8a8.hip", "k_bwd.hip", "k_bwd_lin.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
@@ -48,13 +51,24 @@ def build(verbose=True):
         _run([hipcc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj])
         return src
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        for name in ex.map(one, zip(SOURCES, objs)):
+    check_obj = os.path.join(objdir, "k_sparse_fullwaits.o")
+
+    def check(_):
+        _run([hipcc] + FLAGS + ["-DSLA_FULL_WAITS", "-c", os.path.join(CSRC, "k_sparse.hip"), "-o", check_obj])
+        return "k_sparse.hip (-DSLA_FULL_WAITS)"
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        jobs = [ex.submit(one, pair) for pair in zip(SOURCES, objs)] + [ex.submit(check, None)]
+        for j in jobs:
+            name = j.result()
             if verbose:
                 print("compiled", name, flush=True)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    k_sparse_obj = os.path.join(objdir, "k_sparse.o")
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_FULL_WAITS] +
+         [check_obj if o == k_sparse_obj else o for o in objs])
     if verbose:
-        print("linked", LIB, flush=True)
+        print("linked", LIB, "and", LIB_FULL_WAITS, flush=True)
     return LIB
 
 

@@ -19,7 +19,9 @@
 // is arranged for every MFMA to have independent vector work of the same wavefront behind it:
 // the two 32-key halves of a block are pipelined against each other (while the matrix pipe
 // computes the scores of one half, the vector ALU turns the other half's scores into P codes),
-// and the P.V product runs one block behind.
+// and the P.V product runs one block behind.  A query's reference level only ever rises and is
+// usually final after a few blocks, so the step tests each half's maximum in its own lane first
+// and joins the lane pairs, rounds up and rescales only when some lane of the wavefront passes.
 //
 // Epilogue: O_s = acc * delta_V / l;  optional linear term phi(Q) H_i / (phi(Q).Z_i) as bf16 MFMA
 // (H_i already contains the output projection), bias, then a transposing pass through LDS so
@@ -122,12 +124,13 @@ __device__ __forceinline__ int half_max(v16i& s, int key0, int hf, int kvalid) {
     for (int q = 0; q < 16; ++q)
       if (key0 + 8 * (q >> 2) + 4 * hf + (q & 3) >= kvalid) s[q] = BIAS_FLOOR;
   }
-  int m0 = max(s[0], s[1]), m1 = max(s[2], s[3]);
-#pragma unroll
-  for (int q = 4; q < 16; q += 4) {
-    m0 = max(max(m0, s[q]), s[q + 1]);
-    m1 = max(max(m1, s[q + 2]), s[q + 3]);
-  }
+  // two chains of three-operand maxima (7 + 9 values), joined at the end: 8 instructions
+  int m0 = max(max(s[0], s[1]), s[2]), m1 = max(max(s[7], s[8]), s[9]);
+  m0 = max(max(m0, s[3]), s[4]);
+  m1 = max(max(m1, s[10]), s[11]);
+  m0 = max(max(m0, s[5]), s[6]);
+  m1 = max(max(m1, s[12]), s[13]);
+  m1 = max(max(m1, s[14]), s[15]);
   return max(m0, m1);
 }
 
@@ -140,8 +143,9 @@ struct BlockConsts {
   float lnb;   // log2(448) + nb: offs = lnb - r makes exp2(fma(x, c2s, offs)) = 448 * 2^(t - r)
 };
 __device__ __forceinline__ BlockConsts block_consts(float c2s) {
+  // (explicit fused operations: the values must not depend on what the compiler chooses to contract)
   const float nb = -__int_as_float(BIAS_I) * c2s;
-  return BlockConsts{c2s, __builtin_fmaf(c2s, SCORE_STEP, nb), LOG2_448 + nb};
+  return BlockConsts{c2s, __builtin_fmaf(c2s, SCORE_STEP, nb), __builtin_fmaf(c2s, -__int_as_float(BIAS_I), LOG2_448)};
 }
 
 // Row maximum over both lanes of the query -> new reference level r; returns offs (see above).
@@ -152,6 +156,12 @@ __device__ __forceinline__ float new_reference(int imax, const BlockConsts& bc, 
   const float cand = __builtin_ceilf(__builtin_fmaf(__int_as_float(imax), bc.c2s, bc.nbg));
   r = __builtin_amdgcn_fmed3f(r, cand, pos_inf);  // max(r, cand) in one instruction (both are finite)
   return bc.lnb - r;
+}
+
+// In-lane test value of a half's maximum: exceeds the (integer) reference level r exactly when the
+// rounded-up level of this lane's scores would.
+__device__ __forceinline__ float level_probe(int imax, const BlockConsts& bc) {
+  return __builtin_fmaf(__int_as_float(imax), bc.c2s, bc.nbg);
 }
 
 // Four biased scores (accumulator registers 4g .. 4g+3 of one half) -> four FP8 codes of P in
@@ -365,7 +375,13 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   // keys costs the other blocks nothing.
   const int last = n_c - 1;
   const bool has_tail = ragged && n_c > 0 && (crow[last] & JMASK) == A.Tk - 1;
+  // (SLA_FULL_WAITS: a checking build that waits for EVERY copy at each step instead of counting the
+  // copies still allowed in flight; results must be bit-identical to the counting build.)
+#ifdef SLA_FULL_WAITS
+  constexpr int WAIT_KEEP2 = 0x0070;
+#else
   constexpr int WAIT_KEEP2 = (2 * CH >= 16) ? 0x4070 : (0x0070 | (2 * CH));  // s_waitcnt vmcnt(2*CH) lgkmcnt(0)
+#endif
   constexpr int WAIT_ALL = 0x0070;                                            // s_waitcnt vmcnt(0) lgkmcnt(0)
   constexpr int WAIT_KEEP_ALL_VM = 0xC07F;                                    // s_waitcnt lgkmcnt(0) only (vmcnt 63)
   v16i s0, s1;
@@ -374,7 +390,7 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   int sc_prev = 127;          // E8M0 scale of the P codes of block b-1 (this lane's half of it)
 
 #define SB __builtin_amdgcn_sched_barrier(0);
-#define SLA_STEP(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)                                             \
+#define SLA_STEP_P(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)                                           \
   {                                                                                                   \
     const int b_ = (B);                                                                               \
     /* ---- phase 1 */                                                                                \
@@ -430,6 +446,86 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);                                                           \
     stage_barrier();                                                                                  \
   }
+
+  // The same step for unpaired workgroups, with the reference bookkeeping off the common path.  A
+  // query's level r only ever rises, and after the first few blocks it has usually reached its
+  // final value: a half's maximum is first tested in each lane alone (one fma and one compare: r
+  // is an integer, so the rounded-up level of a lane pair exceeds r exactly when one of its two
+  // lanes' own value does), and only if some lane of the wavefront passes does the wavefront join
+  // the lane pairs, round up and raise r (a wave-uniform branch).  The exponent offset is formed
+  // once per step, the scale of the codes just made is recomputed only in a step in which r moved
+  // (and in the one after it, when the two halves of a block may still sit at different levels),
+  // and the accumulators' level is looked at only then.
+#define SLA_RAISE(IMAX)                                                                                \
+  {                                                                                                   \
+    const auto sw_ = __builtin_amdgcn_permlane32_swap(IMAX, IMAX, false, false);                      \
+    const int im_ = max((int)sw_[0], (int)sw_[1]);                                                    \
+    const float cand_ = __builtin_ceilf(__builtin_fmaf(__int_as_float(im_), bc_.c2s, bc_.nbg));       \
+    r = __builtin_amdgcn_fmed3f(r, cand_, pos_inf);                                                   \
+    offs_ = bc_.lnb - r;                                                                              \
+    moved = 1;                                                                                        \
+  }
+#define SLA_STEP_F(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)                                           \
+  {                                                                                                   \
+    const int b_ = (B);                                                                               \
+    /* ---- phase 1 */                                                                                \
+    read4(VPREV, lane, 0, vfa);                                                                       \
+    read4(KNEXT, lane, 0, kfA);                                                                       \
+    fetch_rec(k8_bh, j4, KFILL);                                                                       \
+    const int jn_ = crow[min(b_ + 5, last)];                                                          \
+    const float dn_ = dk_of(j4);                                                                      \
+    const BlockConsts bc_ = block_consts(cq * d0);                                                    \
+    float offs_ = bc_.lnb - r;                                                                        \
+    const int moved_before = moved;                                                                   \
+    moved = 0;                                                                                        \
+    SB s1 = qk_step(kfB[0], q8[0], bias16);                                                           \
+    SB const int mA_ = half_max<false>(s0, 0, hf, 0);                                                 \
+    SB s1 = qk_step(kfB[1], q8[1], s1);                                                               \
+    SB if (__any(level_probe(mA_, bc_) > r)) SLA_RAISE(mA_)                                           \
+    const float rA_ = r;                                                                              \
+    SB s1 = qk_step(kfB[2], q8[2], s1);                                                               \
+    SB PBN[0] = codes_quad<false>(s0, 0, 0, hf, bc_.c2s, offs_, 0, PBN[0]);                           \
+    SB s1 = qk_step(kfB[3], q8[3], s1);                                                               \
+    SB PBN[1] = codes_quad<false>(s0, 1, 0, hf, bc_.c2s, offs_, 0, PBN[1]);                           \
+    SB pv_tile(vfa[0], vfa[1], PBP, sc_prev, acc[0]);                                                 \
+    SB PBN[2] = codes_quad<false>(s0, 2, 0, hf, bc_.c2s, offs_, 0, PBN[2]);                           \
+    SB pv_tile(vfa[2], vfa[3], PBP, sc_prev, acc[1]);                                                 \
+    SB PBN[3] = codes_quad<false>(s0, 3, 0, hf, bc_.c2s, offs_, 0, PBN[3]);                           \
+    /* anchor: the branch below must not draw this phase's pieces past it */                          \
+    asm volatile("" : "+v"(PBN), "+v"(s1), "+v"(acc[0]), "+v"(acc[1]));                               \
+    /* ---- phase 2 */                                                                                \
+    read4(VPREV, lane, 4, vfb);                                                                       \
+    read4(KNEXT, lane, 4, kfB);                                                                       \
+    fetch_rec(v8_bh, j2, VFILL);                                                                       \
+    SB s0 = qk_step(kfA[0], q8[0], bias16);                                                           \
+    SB const int mB_ = half_max<false>(s1, 32, hf, 0);                                                \
+    SB s0 = qk_step(kfA[1], q8[1], s0);                                                               \
+    SB if (__any(level_probe(mB_, bc_) > r)) SLA_RAISE(mB_)                                           \
+    SB s0 = qk_step(kfA[2], q8[2], s0);                                                               \
+    SB PBN[4] = codes_quad<false>(s1, 0, 32, hf, bc_.c2s, offs_, 0, PBN[4]);                          \
+    SB s0 = qk_step(kfA[3], q8[3], s0);                                                               \
+    SB PBN[5] = codes_quad<false>(s1, 1, 32, hf, bc_.c2s, offs_, 0, PBN[5]);                          \
+    SB pv_tile(vfb[0], vfb[1], PBP, sc_prev, acc[2]);                                                 \
+    SB PBN[6] = codes_quad<false>(s1, 2, 32, hf, bc_.c2s, offs_, 0, PBN[6]);                          \
+    SB pv_tile(vfb[2], vfb[3], PBP, sc_prev, acc[3]);                                                 \
+    SB PBN[7] = codes_quad<false>(s1, 3, 32, hf, bc_.c2s, offs_, 0, PBN[7]);                          \
+    SB pv_rowsum(ones, PBP, sc_prev, accl);                                                           \
+    j2 = j3; j3 = j4; j4 = jn_;                                                                       \
+    d0 = d1; d1 = d2; d2 = d3; d3 = dn_;                                                              \
+    /* anchor: keeps every piece inside this step */                                                  \
+    asm volatile("" : "+v"(PBN), "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(accl),  \
+                 "+v"(s0), "+s"(j4), "+s"(d3));                                                       \
+    SB if (moved | moved_before) {                                                                    \
+      if (__any(r - R > 64.f)) renormalise(r, R, Rm127, acc, accl);                                   \
+      sc_prev = level_scale(hf ? r : rA_, Rm127);   /* level of this lane's half of the new codes */  \
+    }                                                                                                 \
+    __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);                                                           \
+    stage_barrier();                                                                                  \
+  }
+#define SLA_STEP(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)                                             \
+  if constexpr (PAIRED) SLA_STEP_P(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)                           \
+  else SLA_STEP_F(B, KNEXT, VPREV, KFILL, VFILL, PBP, PBN)
+  int moved = 1;              // did the reference level of any query of this wavefront rise in the last step?
 
   if (n_c > 0) {  // (an empty list leaves only the linear term of the epilogue)
     // step 0 has no previous block: it multiplies all-zero P codes with this all-zero V slot
@@ -526,6 +622,9 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     }
   }
 #undef SLA_STEP
+#undef SLA_STEP_P
+#undef SLA_STEP_F
+#undef SLA_RAISE
 #undef SB
 
   // ---- normalise: O_s[q][ch] = acc * delta_V[ch] / l

@@ -339,3 +339,31 @@ def test_int8_scores_mode_matches_oracle(H, grid, bq, rc, rm, proj, phi):
         assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= 5e-3
         full = out88[0, h].float().cpu().numpy().astype(np.float64)
         assert np.linalg.norm(got - exact) <= np.linalg.norm(full - exact)     # INT8 alone errs less than INT8 + FP8
+
+
+def test_counted_copy_waits_agree_with_full_waits():
+    """The attention kernel waits for its asynchronous K/V copies by hand-counted `vmcnt` values.  A
+    second build of the library (-DSLA_FULL_WAITS) waits for every copy at each step instead; the two
+    must agree bit for bit (tiny named shape, a ragged one with query blocks of 128, one of 64)."""
+    import ctypes
+    import os
+    from paper_2512_16093_amd import build as b
+    assert os.path.exists(b.LIB_FULL_WAITS), "run python -m paper_2512_16093_amd.build"
+    L = ctypes.CDLL(b.LIB_FULL_WAITS)
+    c_int, c_dbl, c_vp, c_sz = ctypes.c_int, ctypes.c_double, ctypes.c_void_p, ctypes.c_size_t
+    L.sla_attention_fwd.restype = c_int
+    L.sla_attention_fwd.argtypes = [c_vp] * 4 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp]
+    for cfg in (synth.CONFIGS[0], _cfg(2, (5, 10, 20), 128, 0.25, 0.5), _cfg(1, (3, 27, 27), 128, 0.1, 0.2),
+                _cfg(2, (6, 7, 25), 64, 0.2, 0.4)):
+        q, k, v = pu.to_dev(*synth.make_qkv(cfg))
+        W = synth.make_proj(cfg).cuda()
+        ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+        ref = sla.sla_attention_fwd(q, k, v, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, proj_w=W, workspace=ws)
+        out = torch.empty_like(ref)
+        st = L.sla_attention_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), cfg.B, cfg.H, cfg.N, cfg.d,
+                                 cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, W.data_ptr(), None, 0,
+                                 sla.QUANT_QK_INT8_PV_FP8, ws.data_ptr(), ws.numel(),
+                                 torch.cuda.current_stream().cuda_stream)
+        assert st == 0
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), cfg.name
