@@ -52,8 +52,7 @@
  *     ceil(N/64) <= 8192; B*H*ceil(N/block_q) < 2^31; phi in sla_phi;
  *     quant_mode SLA_QUANT_QK_INT8_PV_FP8 (the paper's inference path),
  *     SLA_QUANT_NONE (bf16 products: the training-time operator that
- *     sla_bwd.h differentiates) or SLA_QUANT_QK_INT8 (see sla_quant); the
- *     last two take contiguous [B,H,N,d] tensors only.
+ *     sla_bwd.h differentiates) or SLA_QUANT_QK_INT8 (see sla_quant).
  *   - Results are deterministic: no floating-point atomics anywhere (sla_bwd.h included).
  */
 #ifndef SLA_H_

@@ -23,7 +23,7 @@
  * before and after); inputs are never written; outputs must not alias inputs or the workspace.
  * Returns SLA_OK or a negative sla_status; argument errors are found on the host before any launch.
  * Supported: what sla_attention_fwd supports for shapes, blocks and ratios; contiguous [B,H,N,d]
- * tensors; any phi_kind of sla_phi (relu's gradient is taken as 0 at x <= 0).
+ * tensors (other layouts: the _strided entry points below); any phi_kind of sla_phi (relu's gradient is taken as 0 at x <= 0).
  */
 #ifndef SLA_BWD_H_
 #define SLA_BWD_H_
@@ -64,7 +64,7 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
 
 /* ---- Handing the forward pass's statistics over (a training step: forward, then backward) ----
  *
- * sla_attention_fwd_train is sla_attention_fwd with SLA_QUANT_NONE (contiguous tensors; all
+ * sla_attention_fwd_train is sla_attention_fwd with SLA_QUANT_NONE (all
  * three feature maps) that also fills `saved` with what the backward pass would otherwise compute
  * again: every row's log-sum-exp over its critical keys and O^s.  sla_attention_bwd_saved is
  * sla_attention_bwd without its statistics pass: it takes them from `saved`, which must come from
@@ -85,6 +85,36 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
                             int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
                             const void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes,
                             sla_stream_t stream);
+
+/* ---- Token-major and packed layouts (Section 1.3: the operator sits between a QKV projection and
+ * an output projection that produce and consume token-major tensors; in training their gradients do
+ * too) ----
+ *
+ * The same calls for tensors that are not [B,H,N,d]-contiguous; strides as in sla.h (sla_strides:
+ * elements; channels contiguous; non-negative multiples of 8; token stride >= d; 16-byte aligned
+ * bases; else SLA_ERR_LAYOUT).  NULL strides = contiguous.  Results are bit-identical to the
+ * contiguous calls on the same values.  sla_attention_fwd_strided (sla.h) takes every quant_mode. */
+int sla_attention_fwd_train_strided(const void* q, const void* k, const void* v, void* out,
+                                    const sla_strides* q_strides, const sla_strides* k_strides,
+                                    const sla_strides* v_strides, const sla_strides* out_strides,
+                                    int B, int H, int N, int d, int block_q, int block_k,
+                                    double topk_ratio, double marginal_ratio, const void* proj_w, const void* proj_b,
+                                    int phi_kind, void* saved, size_t saved_bytes, void* workspace,
+                                    size_t workspace_bytes, sla_stream_t stream);
+
+/* One layout per tensor of the backward pass (HOST pointers, read during the call; any may be NULL
+ * = contiguous). */
+typedef struct {
+  const sla_strides *q, *k, *v, *dout, *dq, *dk, *dv;
+} sla_bwd_strides;
+
+/* sla_attention_bwd_saved (saved == NULL: sla_attention_bwd) with a layout per tensor; strides ==
+ * NULL: all contiguous.  Rows of dq, dk, dv must not overlap each other or any input (not checked). */
+int sla_attention_bwd_strided(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
+                              void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b,
+                              const sla_bwd_strides* strides, int B, int H, int N, int d, int block_q, int block_k,
+                              double topk_ratio, double marginal_ratio, int phi_kind, const void* saved,
+                              size_t saved_bytes, void* workspace, size_t workspace_bytes, sla_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -33,7 +33,7 @@ EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspac
 W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
                 "w8a8_quantize_act", "w8a8_gemm_fwd", "w8a8_debug_unpack")
 BWD_EXPORTS = ("sla_bwd_workspace_bytes", "sla_attention_bwd", "sla_saved_bytes", "sla_attention_fwd_train",
-               "sla_attention_bwd_saved")
+               "sla_attention_bwd_saved", "sla_attention_fwd_train_strided", "sla_attention_bwd_strided")
 N_STAGES = 5
 STAGE_NAMES = ("pool_stats", "scores_select", "prep_kv", "lin_accumulate", "sparse_fwd")
 
@@ -43,6 +43,11 @@ _lib = None
 class Strides(ctypes.Structure):
     """sla_strides of include/sla.h: element strides of the batch, head and token indices."""
     _fields_ = [("batch", ctypes.c_int64), ("head", ctypes.c_int64), ("token", ctypes.c_int64)]
+
+
+class BwdStrides(ctypes.Structure):
+    """sla_bwd_strides of include/sla_bwd.h: one layout (or NULL = contiguous) per tensor."""
+    _fields_ = [(n, ctypes.POINTER(Strides)) for n in ("q", "k", "v", "dout", "dq", "dk", "dv")]
 
 
 class SLAError(RuntimeError):
@@ -106,6 +111,13 @@ def lib():
         L.sla_attention_bwd_saved.restype = c_int
         L.sla_attention_bwd_saved.argtypes = ([c_vp] * 10 + [c_int] * 6 + [c_dbl, c_dbl, c_int, c_vp, c_sz, c_vp, c_sz,
                                               c_vp])
+        sp = ctypes.POINTER(Strides)
+        L.sla_attention_fwd_train_strided.restype = c_int
+        L.sla_attention_fwd_train_strided.argtypes = ([c_vp] * 4 + [sp] * 4 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_vp, c_int,
+                                                      c_vp, c_sz, c_vp, c_sz, c_vp])
+        L.sla_attention_bwd_strided.restype = c_int
+        L.sla_attention_bwd_strided.argtypes = ([c_vp] * 10 + [ctypes.POINTER(BwdStrides)] + [c_int] * 6 +
+                                                [c_dbl, c_dbl, c_int, c_vp, c_sz, c_vp, c_sz, c_vp])
         # include/w8a8.h
         L.w8a8_weight_bytes.restype = c_sz
         L.w8a8_weight_bytes.argtypes = [c_int, c_int]
@@ -446,3 +458,49 @@ def w8a8_debug_unpack(q, is_weight, R, K):
     _check(lib().w8a8_debug_unpack(_ptr(q), 1 if is_weight else 0, R, K, _ptr(codes), _ptr(scales), _stream()),
            "w8a8_debug_unpack")
     return codes, scales
+
+
+def _same_shape(*ts):
+    B, H, N, d = ts[0].shape
+    for t in ts:
+        if tuple(t.shape) != (B, H, N, d):
+            raise ValueError("all tensors must be indexed [B,H,N,d] with one shape")
+    return B, H, N, d
+
+
+def sla_attention_fwd_train_strided(q, k, v, out, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None, proj_b=None,
+                                    phi_kind=PHI_SOFTMAX, workspace=None, saved=None):
+    """sla_attention_fwd_train on tensors indexed [B,H,N,d] in any memory order with contiguous channels;
+    returns saved."""
+    B, H, N, d = _same_shape(q, k, v, out)
+    st_ = [_strides_of(t, n) for t, n in ((q, "q"), (k, "k"), (v, "v"), (out, "out"))]
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    if saved is None:
+        saved = torch.empty(sla_saved_bytes(B, H, N, d, block_q), dtype=torch.uint8, device=q.device)
+    st = lib().sla_attention_fwd_train_strided(_ptr(q), _ptr(k), _ptr(v), _ptr(out), *[ctypes.byref(x) for x in st_],
+                                               B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, _ptr(proj_w),
+                                               _ptr(proj_b), phi_kind, _ptr(saved), saved.numel(), _ptr(workspace),
+                                               workspace.numel(), _stream())
+    _check(st, "sla_attention_fwd_train_strided")
+    return saved
+
+
+def sla_attention_bwd_strided(q, k, v, dout, dq, dk, dv, block_q, block_k, topk_ratio, marginal_ratio, proj_w=None,
+                              want_dw=False, want_db=False, phi_kind=PHI_SOFTMAX, workspace=None, saved=None):
+    """sla_attention_bwd(_saved) on tensors indexed [B,H,N,d] in any memory order with contiguous channels;
+    dq, dk, dv are written in place; returns (dproj_w or None, dproj_b or None)."""
+    B, H, N, d = _same_shape(q, k, v, dout, dq, dk, dv)
+    names = ("q", "k", "v", "dout", "dq", "dk", "dv")
+    each = [_strides_of(t, n) for t, n in zip((q, k, v, dout, dq, dk, dv), names)]
+    bs = BwdStrides(*[ctypes.pointer(x) for x in each])
+    if workspace is None:
+        workspace = alloc_bwd_workspace(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, q.device)
+    dw = torch.empty((d, d), dtype=torch.float32, device=q.device) if want_dw else None
+    db = torch.empty((d,), dtype=torch.float32, device=q.device) if want_db else None
+    st = lib().sla_attention_bwd_strided(_ptr(q), _ptr(k), _ptr(v), _ptr(dout), _ptr(proj_w), _ptr(dq), _ptr(dk), _ptr(dv),
+                                         _ptr(dw), _ptr(db), ctypes.byref(bs), B, H, N, d, block_q, block_k, topk_ratio,
+                                         marginal_ratio, phi_kind, _ptr(saved), 0 if saved is None else saved.numel(),
+                                         _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_attention_bwd_strided")
+    return dw, db

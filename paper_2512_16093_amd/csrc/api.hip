@@ -83,7 +83,7 @@ int make_problem(int B, int H, int N, int d, int block_q, int block_k, double rc
   if ((long long)B * H > 65535 || rows >= (1ll << 31) - 8 || (long long)B * H * Tk >= (1ll << 31)) return SLA_ERR_SHAPE;
   p->B = B; p->H = H; p->N = N; p->block_q = block_q;
   p->BH = B * H; p->Tq = Tq; p->Tk = Tk; p->n_c = nc; p->n_m = nm;
-  p->lq = p->lk = p->lv = p->lo = contiguous_layout(H, N);
+  p->lq = p->lk = p->lv = p->lo = p->ld = p->ldq = p->ldk = p->ldv = contiguous_layout(H, N);
   return SLA_OK;
 }
 
@@ -265,11 +265,6 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
   if (quant_mode < SLA_QUANT_NONE || quant_mode > SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
-  if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) {  // the 16-bit kernels take contiguous [B,H,N,d] tensors only
-    const Layout c = contiguous_layout(H, N);
-    for (const Layout* L : {&p.lq, &p.lk, &p.lv, &p.lo})
-      if (L->sb != c.sb || L->sh != c.sh || L->sn != c.sn) return SLA_ERR_LAYOUT;
-  }
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m,
                                      quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
@@ -471,10 +466,25 @@ int sla_attention_fwd_train(const void* q, const void* k, const void* v, void* o
                             int block_q, int block_k, double topk_ratio, double marginal_ratio, const void* proj_w,
                             const void* proj_b, int phi_kind, void* saved, size_t saved_bytes, void* workspace,
                             size_t workspace_bytes, sla_stream_t stream) {
+  return sla_attention_fwd_train_strided(q, k, v, out, nullptr, nullptr, nullptr, nullptr, B, H, N, d, block_q, block_k,
+                                         topk_ratio, marginal_ratio, proj_w, proj_b, phi_kind, saved, saved_bytes,
+                                         workspace, workspace_bytes, stream);
+}
+
+int sla_attention_fwd_train_strided(const void* q, const void* k, const void* v, void* out, const sla_strides* q_strides,
+                                    const sla_strides* k_strides, const sla_strides* v_strides,
+                                    const sla_strides* out_strides, int B, int H, int N, int d, int block_q, int block_k,
+                                    double topk_ratio, double marginal_ratio, const void* proj_w, const void* proj_b,
+                                    int phi_kind, void* saved, size_t saved_bytes, void* workspace,
+                                    size_t workspace_bytes, sla_stream_t stream) {
   if (!q || !k || !v || !out || !saved) return SLA_ERR_NULL;
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
+  if ((st = make_layout(q, q_strides, H, N, &p.lq)) != SLA_OK) return st;
+  if ((st = make_layout(k, k_strides, H, N, &p.lk)) != SLA_OK) return st;
+  if ((st = make_layout(v, v_strides, H, N, &p.lv)) != SLA_OK) return st;
+  if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
   const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
@@ -489,8 +499,9 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
                       void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b, int B, int H, int N, int d,
                       int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
                       void* workspace, size_t workspace_bytes, sla_stream_t stream) {
-  return sla_attention_bwd_saved(q, k, v, dout, proj_w, dq, dk, dv, dproj_w, dproj_b, B, H, N, d, block_q, block_k,
-                                 topk_ratio, marginal_ratio, phi_kind, nullptr, 0, workspace, workspace_bytes, stream);
+  return sla_attention_bwd_strided(q, k, v, dout, proj_w, dq, dk, dv, dproj_w, dproj_b, nullptr, B, H, N, d, block_q,
+                                   block_k, topk_ratio, marginal_ratio, phi_kind, nullptr, 0, workspace, workspace_bytes,
+                                   stream);
 }
 
 int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
@@ -498,10 +509,29 @@ int sla_attention_bwd_saved(const void* q, const void* k, const void* v, const v
                             int block_q, int block_k, double topk_ratio, double marginal_ratio, int phi_kind,
                             const void* saved, size_t saved_bytes, void* workspace, size_t workspace_bytes,
                             sla_stream_t stream) {
+  return sla_attention_bwd_strided(q, k, v, dout, proj_w, dq, dk, dv, dproj_w, dproj_b, nullptr, B, H, N, d, block_q,
+                                   block_k, topk_ratio, marginal_ratio, phi_kind, saved, saved_bytes, workspace,
+                                   workspace_bytes, stream);
+}
+
+int sla_attention_bwd_strided(const void* q, const void* k, const void* v, const void* dout, const void* proj_w,
+                              void* dq, void* dk, void* dv, float* dproj_w, float* dproj_b,
+                              const sla_bwd_strides* strides, int B, int H, int N, int d, int block_q, int block_k,
+                              double topk_ratio, double marginal_ratio, int phi_kind, const void* saved,
+                              size_t saved_bytes, void* workspace, size_t workspace_bytes, sla_stream_t stream) {
   if (!q || !k || !v || !dout || !dq || !dk || !dv) return SLA_ERR_NULL;
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
+  if (strides) {
+    if ((st = make_layout(q, strides->q, H, N, &p.lq)) != SLA_OK) return st;
+    if ((st = make_layout(k, strides->k, H, N, &p.lk)) != SLA_OK) return st;
+    if ((st = make_layout(v, strides->v, H, N, &p.lv)) != SLA_OK) return st;
+    if ((st = make_layout(dout, strides->dout, H, N, &p.ld)) != SLA_OK) return st;
+    if ((st = make_layout(dq, strides->dq, H, N, &p.ldq)) != SLA_OK) return st;
+    if ((st = make_layout(dk, strides->dk, H, N, &p.ldk)) != SLA_OK) return st;
+    if ((st = make_layout(dv, strides->dv, H, N, &p.ldv)) != SLA_OK) return st;
+  }
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
   const SavedState V = make_saved(p);
   if (saved && (st = check_ws(saved, saved_bytes, V.total)) != SLA_OK) return st;

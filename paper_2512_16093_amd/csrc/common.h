@@ -168,6 +168,7 @@ struct Problem {
   int B, H, N, block_q;
   int BH, Tq, Tk, n_c, n_m;
   Layout lq, lk, lv, lo;  // of q, k, v and out
+  Layout ld, ldq, ldk, ldv;  // backward pass: of dout, dq, dk and dv
 };
 
 // Launchers (one per kernel file); every one only enqueues work on `stream`.

@@ -19,6 +19,8 @@
 // product that contracts over the channels reads its operand with one 16-byte read per step; a
 // product that contracts over the tile's tokens reads the same tile with the transposing LDS read
 // of gfx950 (ds_read_b64_tr_b16), so no transposed copy of any tensor is ever made.
+#include <initializer_list>
+
 #include "common.h"
 
 namespace sla {
@@ -67,9 +69,31 @@ __device__ __forceinline__ uint4 t_op(const unsigned char* tile, int tr_off, int
   return u.v;
 }
 // The same operand as n_op straight from memory (a workgroup's own rows, read once).
-__device__ __forceinline__ void own_rows(const bf16_t* x, long long row, int N, int hf, uint4 (&f)[8]) {
+// (x: the (b,h) slice's first token; sn: elements from one token to the next)
+__device__ __forceinline__ void own_rows(const bf16_t* x, long long sn, long long row, int N, int hf, uint4 (&f)[8]) {
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) f[ks] = row < N ? *(const uint4*)(x + row * D + 16 * ks + 8 * hf) : uint4{0u, 0u, 0u, 0u};
+  for (int ks = 0; ks < 8; ++ks) f[ks] = row < N ? *(const uint4*)(x + row * sn + 16 * ks + 8 * hf) : uint4{0u, 0u, 0u, 0u};
+}
+// A tensor's layout as the kernel uses it: the caller's (ST) or, for the instances that serve contiguous
+// [B,H,N,d] tensors only, compile-time strides (the row stride then folds into the address arithmetic).
+template <bool ST>
+__device__ __forceinline__ Layout lay(const Layout& L, int H, int N) {
+  if constexpr (ST) return L;
+  else return Layout{(long long)H * N * D, (long long)N * D, (long long)D};
+}
+#define SLA_BWD_LAYOUTS                                                                                         \
+  const Layout L_q = lay<ST>(dm.lq, dm.H, dm.N), L_k = lay<ST>(dm.lk, dm.H, dm.N), L_v = lay<ST>(dm.lv, dm.H, dm.N), \
+               L_d = lay<ST>(dm.ld, dm.H, dm.N), L_dq = lay<ST>(dm.ldq, dm.H, dm.N), L_dk = lay<ST>(dm.ldk, dm.H, dm.N), \
+               L_dv = lay<ST>(dm.ldv, dm.H, dm.N), L_o = lay<ST>(dm.lo, dm.H, dm.N);                              \
+  (void)L_q; (void)L_k; (void)L_v; (void)L_d; (void)L_dq; (void)L_dk; (void)L_dv; (void)L_o;
+// First token of slice bh = b H + h of a tensor laid out by L.
+__device__ __forceinline__ const bf16_t* slice_of(const bf16_t* x, const Layout& L, int bh, int H) {
+  const int b = bh / H;
+  return x + b * L.sb + (bh - b * H) * L.sh;
+}
+__device__ __forceinline__ bf16_t* slice_of(bf16_t* x, const Layout& L, int bh, int H) {
+  const int b = bh / H;
+  return x + b * L.sb + (bh - b * H) * L.sh;
 }
 
 // ROWS consecutive token rows of a [N, 128] tensor -> LDS tile(s), through registers (loaded one
@@ -78,29 +102,29 @@ template <int NT, int ROWS>
 struct RowStage {
   static constexpr int PER = ROWS * 16 / NT;
   uint4 pf[PER];
-  __device__ __forceinline__ void load(const bf16_t* x, long long r0, int N, int t) {
+  __device__ __forceinline__ void load(const bf16_t* x, long long sn, long long r0, int N, int t) {
     if (r0 + ROWS <= N) {  // (uniform) every row exists: no per-row test
 #pragma unroll
       for (int u = 0; u < PER; ++u) {
         const int c = u * NT + t;
-        pf[u] = *(const uint4*)(x + (r0 + (c >> 4)) * D + (c & 15) * 8);
+        pf[u] = *(const uint4*)(x + (r0 + (c >> 4)) * sn + (c & 15) * 8);
       }
     } else {
 #pragma unroll
       for (int u = 0; u < PER; ++u) {
         const int c = u * NT + t;
         const long long r = r0 + (c >> 4);
-        pf[u] = r < N ? *(const uint4*)(x + r * D + (c & 15) * 8) : uint4{0u, 0u, 0u, 0u};
+        pf[u] = r < N ? *(const uint4*)(x + r * sn + (c & 15) * 8) : uint4{0u, 0u, 0u, 0u};
       }
     }
   }
   // The same with rows beyond N replaced by row N - 1 and no branch: for callers that give such rows
   // a weight of exactly zero and want every call to issue the same loads (N > 0).
-  __device__ __forceinline__ void load_clamped(const bf16_t* x, int r0, int N, int t) {
+  __device__ __forceinline__ void load_clamped(const bf16_t* x, long long sn, int r0, int N, int t) {
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
       const int c = u * NT + t;
-      const uint4 got = *(const uint4*)(x + (size_t)min(r0 + (c >> 4), N - 1) * D + (c & 15) * 8);
+      const uint4 got = *(const uint4*)(x + (long long)min(r0 + (c >> 4), N - 1) * sn + (c & 15) * 8);
       pf[u] = got;  // (through a named value: assigning the dereferenced pointer straight to the member left the arrays in scratch memory)
     }
   }
@@ -114,7 +138,9 @@ struct RowStage {
 };
 
 struct BwdDims {
-  int N, Tq, Tk, n_c, T32q;
+  int N, Tq, Tk, n_c, T32q, H;
+  Layout lq, lk, lv, ld;      // of q, k, v and dout (dq, dk, dv: ldq, ldk, ldv; the forward's out: lo)
+  Layout ldq, ldk, ldv, lo;
 };
 
 // Workgroup -> (block, head) for a 1-D grid of 8 * ceil(T / 8) * BH workgroups.  Consecutive workgroup
@@ -152,9 +178,10 @@ struct FwdEpilogue {
   // delta_Q[i] delta_K[j] / sqrt(d), and the feature map of the linear term reads the original Q
   const float* code_dq;  // [BH, Tq]
   const float* code_dk;  // [BH, Tk]
-  const bf16_t* q_lin;   // [BH, N, D]
+  const bf16_t* q_lin;   // the original Q, laid out by lq_lin
+  Layout lq_lin;
 };
-template <int NW, bool FWD, bool CODES = false>
+template <int NW, bool FWD, bool CODES = false, bool ST = false>
 __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
                                                             const bf16_t* __restrict__ v, const bf16_t* __restrict__ dout,
                                                             const int32_t* __restrict__ crit, float* __restrict__ lse2,
@@ -162,14 +189,18 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_all[];  // two buffers of: K (2 tiles) then V (2 tiles) of a key block
   int i, bh;
   if (!xcd_block(dm.Tq, i, bh)) return;
+  SLA_BWD_LAYOUTS
   const int t = threadIdx.x, lane = t & 63, w = t >> 6, l32 = lane & 31, hf = lane >> 5;
   const int tr_off = tr_lane_offset(lane);
   const int T = i * NW + w;
   const long long qrow = 32ll * T + l32;
   const bool qok = qrow < dm.N;
-  const size_t head = (size_t)bh * dm.N * D;
+  const size_t head = (size_t)bh * dm.N * D;   // (of the library's own contiguous tensors)
+  const bf16_t* qh = slice_of(q, L_q, bh, dm.H);
+  const bf16_t* kh = slice_of(k, L_k, bh, dm.H);
+  const bf16_t* vh = slice_of(v, L_v, bh, dm.H);
   uint4 qf[8];
-  own_rows(q + head, qrow, dm.N, hf, qf);
+  own_rows(qh, L_q.sn, qrow, dm.N, hf, qf);
   const int32_t* crow = crit + ((size_t)bh * dm.Tq + i) * dm.n_c;
   RowStage<NW * 64, 64> sk, sv;
   v16f o[4];
@@ -181,8 +212,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
   // key blocks travel memory -> registers -> LDS one step ahead, into the buffer the step before
   // last has left: one barrier per step
   if (dm.n_c > 0) {
-    sk.load(k + head, 64ll * crow[0], dm.N, t);
-    sv.load(v + head, 64ll * crow[0], dm.N, t);
+    sk.load(kh, L_k.sn, 64ll * crow[0], dm.N, t);
+    sv.load(vh, L_v.sn, 64ll * crow[0], dm.N, t);
     sk.store(lds_all, t);
     sv.store(lds_all + 2 * TILE_B, t);
   }
@@ -199,8 +230,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
     unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
     {  // the next block (after the last one: the last one again), the same loads every time round -- see below
       const int jn = 64 * crow[min(b + 1, dm.n_c - 1)];
-      sk.load_clamped(k + head, jn, dm.N, t);
-      sv.load_clamped(v + head, jn, dm.N, t);
+      sk.load_clamped(kh, L_k.sn, jn, dm.N, t);
+      sv.load_clamped(vh, L_v.sn, jn, dm.N, t);
     }
     v16f s[2];
     float mx = -INFINITY;
@@ -291,7 +322,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const int c0 = 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1);
-        const uint4 qv = qok ? *(const uint4*)((CODES ? fe.q_lin : q) + head + qrow * D + c0) : uint4{0u, 0u, 0u, 0u};
+        const bf16_t* ql = CODES ? slice_of(fe.q_lin, fe.lq_lin, bh, dm.H) + qrow * fe.lq_lin.sn : qh + qrow * L_q.sn;
+        const uint4 qv = qok ? *(const uint4*)(ql + c0) : uint4{0u, 0u, 0u, 0u};
         x[8 * ks] = bf16_lo(qv.x); x[8 * ks + 1] = bf16_hi(qv.x); x[8 * ks + 2] = bf16_lo(qv.y); x[8 * ks + 3] = bf16_hi(qv.y);
         x[8 * ks + 4] = bf16_lo(qv.z); x[8 * ks + 5] = bf16_hi(qv.z); x[8 * ks + 6] = bf16_lo(qv.w); x[8 * ks + 7] = bf16_hi(qv.w);
       }
@@ -352,14 +384,14 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_stats_kernel(con
       for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
         for (int g = 0; g < 4; ++g)
-          *(uint2*)(fe.out + head + qrow * D + 32 * ct + 8 * g + 4 * hf) =
+          *(uint2*)(slice_of(fe.out, L_o, bh, dm.H) + qrow * L_o.sn + 32 * ct + 8 * g + 4 * hf) =
               uint2{pack_bf16x2(o[ct][4 * g], o[ct][4 * g + 1]), pack_bf16x2(o[ct][4 * g + 2], o[ct][4 * g + 3])};
     }
     return;
   }
   float dl = 0.f;
   if (qok && dm.n_c > 0) {
-    const bf16_t* drow = dout + head + qrow * D;
+    const bf16_t* drow = slice_of(dout, L_d, bh, dm.H) + qrow * L_d.sn;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -387,7 +419,7 @@ __device__ __forceinline__ void store_grad4(bf16_t* dst, const float* lin, float
   *(uint2*)dst = uint2{pack_bf16x2(a0, a1), pack_bf16x2(a2, a3)};
 }
 
-template <int NW>
+template <int NW, bool ST = false>
 __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
                                                          const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                          const int32_t* __restrict__ crit, const float* __restrict__ lse2,
@@ -400,10 +432,13 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
   const int tr_off = tr_lane_offset(lane);
   const int T = i * NW + w;
   const long long qrow = 32ll * T + l32;
-  const size_t head = (size_t)bh * dm.N * D;
+  SLA_BWD_LAYOUTS
+  const size_t head = (size_t)bh * dm.N * D;   // (of the library's own contiguous tensors)
+  const bf16_t* kh = slice_of(k, L_k, bh, dm.H);
+  const bf16_t* vh = slice_of(v, L_v, bh, dm.H);
   uint4 qf[8], dof[8];
-  own_rows(q + head, qrow, dm.N, hf, qf);
-  own_rows(dout + head, qrow, dm.N, hf, dof);
+  own_rows(slice_of(q, L_q, bh, dm.H), L_q.sn, qrow, dm.N, hf, qf);
+  own_rows(slice_of(dout, L_d, bh, dm.H), L_d.sn, qrow, dm.N, hf, dof);
   const size_t sidx = (size_t)bh * dm.T32q * 32 + 32 * T + l32;
   const float lse_q = lse2[sidx], delta_q = delta[sidx];
   const int32_t* crow = crit + ((size_t)bh * dm.Tq + i) * dm.n_c;
@@ -412,8 +447,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) acc[ct] = v16f{};
   if (dm.n_c > 0) {
-    sk.load(k + head, 64ll * crow[0], dm.N, t);
-    sv.load(v + head, 64ll * crow[0], dm.N, t);
+    sk.load(kh, L_k.sn, 64ll * crow[0], dm.N, t);
+    sv.load(vh, L_v.sn, 64ll * crow[0], dm.N, t);
     sk.store(lds_all, t);
     sv.store(lds_all + 2 * TILE_B, t);
   }
@@ -429,8 +464,8 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
     unsigned char* lds_next = lds_all + ((b + 1) & 1) * 4 * TILE_B;
     {  // the next block (after the last one: the last one again), the same loads every time round -- see below
       const int jn = 64 * crow[min(b + 1, dm.n_c - 1)];
-      sk.load_clamped(k + head, jn, dm.N, t);
-      sv.load_clamped(v + head, jn, dm.N, t);
+      sk.load_clamped(kh, L_k.sn, jn, dm.N, t);
+      sv.load_clamped(vh, L_v.sn, jn, dm.N, t);
     }
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt) {
@@ -484,13 +519,14 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
     __syncthreads();
   }
   if (qrow < dm.N) {
-    const size_t row = head + qrow * D;
+    const size_t row = head + qrow * D;          // (the linear branch's share: the library's own tensor)
+    bf16_t* dqrow = slice_of(dq, L_dq, bh, dm.H) + qrow * L_dq.sn;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int ch = 32 * ct + 8 * g + 4 * hf;
-        store_grad4(dq + row + ch, dq_lin ? dq_lin + row + ch : nullptr, acc[ct][4 * g] * INV_SQRT_D,
+        store_grad4(dqrow + ch, dq_lin ? dq_lin + row + ch : nullptr, acc[ct][4 * g] * INV_SQRT_D,
                     acc[ct][4 * g + 1] * INV_SQRT_D, acc[ct][4 * g + 2] * INV_SQRT_D, acc[ct][4 * g + 3] * INV_SQRT_D);
       }
   }
@@ -507,7 +543,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) bwd_dq_kernel(const 
 // layout of the sparse-branch kernels (lane = key, registers = channels).
 constexpr int GP = 136;  // row pitch of the staged G (elements)
 template <int NT, int PHI>
-__device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, size_t row,
+__device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,   // (the token's rows)
                                                 bool ok, const bf16_t* __restrict__ rec, bf16_t* gc, float* gz, int t,
                                                 int lane, v16f (&dk_share)[4], v16f (&dv_share)[4]) {
   const int l32 = lane & 31, hf = lane >> 5;
@@ -529,8 +565,8 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
     uint4 kv = uint4{0u, 0u, 0u, 0u};
     vf[ks] = kv;
     if (ok) {
-      kv = *(const uint4*)(k + row + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
-      vf[ks] = *(const uint4*)(v + row + 16 * ks + 8 * hf);
+      kv = *(const uint4*)(k + 32 * (ks >> 1) + 16 * hf + 8 * (ks & 1));
+      vf[ks] = *(const uint4*)(v + 16 * ks + 8 * hf);
     }
     cv[8 * ks] = bf16_lo(kv.x); cv[8 * ks + 1] = bf16_hi(kv.x); cv[8 * ks + 2] = bf16_lo(kv.y); cv[8 * ks + 3] = bf16_hi(kv.y);
     cv[8 * ks + 4] = bf16_lo(kv.z); cv[8 * ks + 5] = bf16_hi(kv.z); cv[8 * ks + 6] = bf16_lo(kv.w); cv[8 * ks + 7] = bf16_hi(kv.w);
@@ -587,7 +623,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int c0 = 32 * ct + 8 * g + 4 * hf;
-      kw[ct][g] = ok ? *(const uint2*)(k + row + c0) : uint2{0u, 0u};
+      kw[ct][g] = ok ? *(const uint2*)(k + c0) : uint2{0u, 0u};
       const float xk[4] = {bf16_lo(kw[ct][g].x), bf16_hi(kw[ct][g].x), bf16_lo(kw[ct][g].y), bf16_hi(kw[ct][g].y)};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -616,7 +652,7 @@ __device__ __forceinline__ void linear_kv_share(const bf16_t* __restrict__ k, co
 // (KB = 2, 64 query rows per step.)  With KB = 1 a workgroup of two wavefronts serves one key block
 // over its own list, 64 query rows per step as well, and two workgroups share a compute unit: every
 // staged tile then serves one key block only, but no wavefront ever sits out.
-template <int KB, int TILES, int PHI>
+template <int KB, int TILES, int PHI, bool ST = false>
 __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout,
                                                       const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
                                                       const int8_t* __restrict__ mask, const float* __restrict__ lse2,
@@ -655,12 +691,16 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
     for (int x = 0; x < NT / 64; ++x) nq += wcnt[x];
     __syncthreads();
   }
-  const size_t head = (size_t)bh * dm.N * D;
+  SLA_BWD_LAYOUTS
+  const bf16_t* kh = slice_of(k, L_k, bh, dm.H);
+  const bf16_t* vh = slice_of(v, L_v, bh, dm.H);
+  const bf16_t* qh = slice_of(q, L_q, bh, dm.H);
+  const bf16_t* doh = slice_of(dout, L_d, bh, dm.H);
   const long long key = 64ll * (KB * J + half) + 32 * (w & 1) + l32;
   const bool kok = key < dm.N;
   uint4 kf[8], vf[8];
-  own_rows(k + head, key, dm.N, hf, kf);
-  own_rows(v + head, key, dm.N, hf, vf);
+  own_rows(kh, L_k.sn, key, dm.N, hf, kf);
+  own_rows(vh, L_v.sn, key, dm.N, hf, vf);
   // the accumulators start from the linear branch's share (G = nullptr: there is none); dK is scaled
   // by 1 / sqrt(d) at the end, so its share goes in multiplied by sqrt(d)
   v16f dkt[4], dvt[4];
@@ -669,7 +709,7 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
     constexpr int LIN_B = 128 * GP * 2 + 128 * 4;
     static_assert(KB * LIN_B <= 2 * BUF_B, "the staged G fits in the staging buffers");
     const int jb = min(KB * J + half, dm.Tk - 1);  // (the missing second block of an odd last pair: its keys do not exist)
-    linear_kv_share<128, PHI>(k + head, v + head, (size_t)(kok ? key : 0) * D, kok, G + ((size_t)bh * dm.Tk + jb) * HZ_ELEMS,
+    linear_kv_share<128, PHI>(kh + (kok ? key : 0) * L_k.sn, vh + (kok ? key : 0) * L_v.sn, kok, G + ((size_t)bh * dm.Tk + jb) * HZ_ELEMS,
                          (bf16_t*)(lds + half * LIN_B), (float*)(lds + half * LIN_B + 128 * GP * 2), t & 127, lane, dkt, dvt);
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
@@ -694,8 +734,8 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
 #define DKV_LOAD(SQ, SD, PS, STEP)                                                                   \
   {                                                                                                  \
     const int r_ = rows_of(min((STEP), steps - 1));                                                  \
-    SQ.load_clamped(q + head, r_, dm.N, t);                                                          \
-    SD.load_clamped(dout + head, r_, dm.N, t);                                                       \
+    SQ.load_clamped(qh, L_q.sn, r_, dm.N, t);                                                      \
+    SD.load_clamped(doh, L_d.sn, r_, dm.N, t);                                                     \
     PS = ((t & ROWS) ? delta : lse2)[(size_t)bh * dm.T32q * 32 + r_ + (t & (ROWS - 1))];             \
   }
 #define DKV_STORE(SQ, SD, PS, BUF)                                                                   \
@@ -928,15 +968,16 @@ __global__ void __launch_bounds__(128 * KB) bwd_dkv_kernel(const bf16_t* __restr
 #undef DKV_LOAD
 #undef DKV_STORE
   if (kok) {
-    const size_t row = head + key * D;
+    bf16_t* dkrow = slice_of(dk, L_dk, bh, dm.H) + key * L_dk.sn;
+    bf16_t* dvrow = slice_of(dv, L_dv, bh, dm.H) + key * L_dv.sn;
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int ch = 32 * ct + 8 * g + 4 * hf;
-        store_grad4(dk + row + ch, nullptr, dkt[ct][4 * g] * INV_SQRT_D, dkt[ct][4 * g + 1] * INV_SQRT_D,
+        store_grad4(dkrow + ch, nullptr, dkt[ct][4 * g] * INV_SQRT_D, dkt[ct][4 * g + 1] * INV_SQRT_D,
                     dkt[ct][4 * g + 2] * INV_SQRT_D, dkt[ct][4 * g + 3] * INV_SQRT_D);
-        store_grad4(dv + row + ch, nullptr, dvt[ct][4 * g], dvt[ct][4 * g + 1], dvt[ct][4 * g + 2], dvt[ct][4 * g + 3]);
+        store_grad4(dvrow + ch, nullptr, dvt[ct][4 * g], dvt[ct][4 * g + 1], dvt[ct][4 * g + 2], dvt[ct][4 * g + 3]);
       }
   }
 }
@@ -948,22 +989,36 @@ static bool allow_lds(K kernel) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, KV_STAGE_BYTES) == hipSuccess;
 }
 
-static BwdDims bwd_dims(const Problem& p) { return BwdDims{p.N, p.Tq, p.Tk, p.n_c, p.Tq * (p.block_q / 32)}; }
+// Do all of these layouts equal the contiguous [B,H,N,d] one?  (Then the instances with compile-time strides serve.)
+static bool contiguous(const Problem& p, std::initializer_list<const Layout*> ls) {
+  const Layout c = contiguous_layout(p.H, p.N);
+  for (const Layout* L : ls)
+    if (L->sb != c.sb || L->sh != c.sh || L->sn != c.sn) return false;
+  return true;
+}
+
+static BwdDims bwd_dims(const Problem& p) {
+  return BwdDims{p.N, p.Tq, p.Tk, p.n_c, p.Tq * (p.block_q / 32), p.H, p.lq, p.lk, p.lv, p.ld, p.ldq, p.ldk, p.ldv, p.lo};
+}
 
 // The launchers below return 0, or -1 when the kernel's LDS allowance could not be set (then nothing is
 // launched; the result of the attribute call is cached, the failure is reported on every call).
 int launch_bwd_stats(const Problem& p, const void* q, const void* k, const void* v, const void* dout,
                      const int32_t* crit, float* lse2, float* delta, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
-  static const bool ok = allow_lds(bwd_stats_kernel<4, false>) && allow_lds(bwd_stats_kernel<2, false>);
+  static const bool ok = allow_lds(bwd_stats_kernel<4, false>) && allow_lds(bwd_stats_kernel<2, false>) &&
+                         allow_lds(bwd_stats_kernel<4, false, false, true>) && allow_lds(bwd_stats_kernel<2, false, false, true>);
   if (!ok) return -1;
-  const FwdEpilogue none{nullptr, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr};
-  if (p.block_q == 128)
-    bwd_stats_kernel<4, false><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
-                                                                      (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
-  else
-    bwd_stats_kernel<2, false><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v,
-                                                                      (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none);
+  const FwdEpilogue none{nullptr, nullptr, nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, p.lq};
+  const bool st = !contiguous(p, {&p.lq, &p.lk, &p.lv, &p.ld});
+#define SLA_STATS(NW, ST) bwd_stats_kernel<NW, false, false, ST><<<grid, NW * 64, KV_STAGE_BYTES, stream>>>( \
+      (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)dout, crit, lse2, delta, bwd_dims(p), none)
+  if (p.block_q == 128) {
+    if (st) SLA_STATS(4, true); else SLA_STATS(4, false);
+  } else {
+    if (st) SLA_STATS(2, true); else SLA_STATS(2, false);
+  }
+#undef SLA_STATS
   return 0;
 }
 
@@ -974,33 +1029,42 @@ int launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* 
                     const CodeScales* codes, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
   static const bool ok = allow_lds(bwd_stats_kernel<4, true>) && allow_lds(bwd_stats_kernel<2, true>) &&
-                         allow_lds(bwd_stats_kernel<4, true, true>) && allow_lds(bwd_stats_kernel<2, true, true>);
+                         allow_lds(bwd_stats_kernel<4, true, true>) && allow_lds(bwd_stats_kernel<2, true, true>) &&
+                         allow_lds(bwd_stats_kernel<4, true, false, true>) && allow_lds(bwd_stats_kernel<2, true, false, true>) &&
+                         allow_lds(bwd_stats_kernel<4, true, true, true>) && allow_lds(bwd_stats_kernel<2, true, true, true>);
   if (!ok) return -1;
   const FwdEpilogue fe{HZ, HZ ? proj_b : nullptr, (bf16_t*)out, phi_kind, save_lse2, (bf16_t*)save_os,
-                       codes ? codes->dq : nullptr, codes ? codes->dk : nullptr, codes ? (const bf16_t*)codes->q_lin : nullptr};
-#define SLA_FWD16(NW, CODES) bwd_stats_kernel<NW, true, CODES><<<grid, NW * 64, KV_STAGE_BYTES, stream>>>( \
-      (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr, crit, nullptr, nullptr, bwd_dims(p), fe)
+                       codes ? codes->dq : nullptr, codes ? codes->dk : nullptr, codes ? (const bf16_t*)codes->q_lin : nullptr, p.lq};
+  BwdDims dm = bwd_dims(p);
+  if (codes) dm.lq = dm.lk = contiguous_layout(p.H, p.N);   // the code tensors are the library's own
+  const bool st = codes ? !contiguous(p, {&p.lv, &p.lo}) : !contiguous(p, {&p.lq, &p.lk, &p.lv, &p.lo});
+#define SLA_FWD16(NW, CODES, ST) bwd_stats_kernel<NW, true, CODES, ST><<<grid, NW * 64, KV_STAGE_BYTES, stream>>>( \
+      (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, nullptr, crit, nullptr, nullptr, dm, fe)
+#define SLA_FWD16_ST(NW, CODES) { if (st) SLA_FWD16(NW, CODES, true); else SLA_FWD16(NW, CODES, false); }
   if (p.block_q == 128) {
-    if (codes) SLA_FWD16(4, true); else SLA_FWD16(4, false);
+    if (codes) SLA_FWD16_ST(4, true) else SLA_FWD16_ST(4, false)
   } else {
-    if (codes) SLA_FWD16(2, true); else SLA_FWD16(2, false);
+    if (codes) SLA_FWD16_ST(2, true) else SLA_FWD16_ST(2, false)
   }
+#undef SLA_FWD16_ST
 #undef SLA_FWD16
   return 0;
 }
 
 // delta[bh][row] = dO[row] . O^s[row] from a saved O^s (rows beyond N: 0); one wavefront per 8 rows.
 __global__ void __launch_bounds__(256) bwd_delta_kernel(const bf16_t* __restrict__ dout, const bf16_t* __restrict__ os,
-                                                        float* __restrict__ delta, int N, int rows_padded, int BH) {
+                                                        float* __restrict__ delta, int N, int rows_padded, int BH, int H,
+                                                        Layout ld) {
   const long long gr = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);  // padded row index over all heads
   if (gr >= (long long)BH * rows_padded) return;
   const int bh = (int)(gr / rows_padded), row = (int)(gr - (long long)bh * rows_padded), part = threadIdx.x & 7;
   float s = 0.f;
   if (row < N) {
-    const size_t off = ((size_t)bh * N + row) * D + 16 * part;
+    const size_t off = ((size_t)bh * N + row) * D + 16 * part;   // (O^s: the library's own tensor)
+    const bf16_t* drow = slice_of(dout, ld, bh, H) + (long long)row * ld.sn + 16 * part;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const uint4 a = *(const uint4*)(dout + off + 8 * h), b = *(const uint4*)(os + off + 8 * h);
+      const uint4 a = *(const uint4*)(drow + 8 * h), b = *(const uint4*)(os + off + 8 * h);
       s += bf16_lo(a.x) * bf16_lo(b.x) + bf16_hi(a.x) * bf16_hi(b.x) + bf16_lo(a.y) * bf16_lo(b.y) + bf16_hi(a.y) * bf16_hi(b.y) +
            bf16_lo(a.z) * bf16_lo(b.z) + bf16_hi(a.z) * bf16_hi(b.z) + bf16_lo(a.w) * bf16_lo(b.w) + bf16_hi(a.w) * bf16_hi(b.w);
     }
@@ -1015,25 +1079,29 @@ void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float*
   const int rows_padded = p.Tq * p.block_q;
   const long long total = (long long)p.BH * rows_padded;
   bwd_delta_kernel<<<(unsigned)((total + 31) / 32), 256, 0, stream>>>((const bf16_t*)dout, (const bf16_t*)os, delta, p.N,
-                                                                     rows_padded, p.BH);
+                                                                     rows_padded, p.BH, p.H, p.ld);
 }
 
 int launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                   const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream) {
   const unsigned grid = (unsigned)(8 * ((p.Tq + 7) / 8) * p.BH);
-  static const bool ok = allow_lds(bwd_dq_kernel<4>) && allow_lds(bwd_dq_kernel<2>);
+  static const bool ok = allow_lds(bwd_dq_kernel<4>) && allow_lds(bwd_dq_kernel<2>) && allow_lds(bwd_dq_kernel<4, true>) &&
+                         allow_lds(bwd_dq_kernel<2, true>);
   if (!ok) return -1;
-  if (p.block_q == 128)
-    bwd_dq_kernel<4><<<grid, 256, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
-                                                lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
-  else
-    bwd_dq_kernel<2><<<grid, 128, KV_STAGE_BYTES, stream>>>((const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit,
-                                                lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p));
+  const bool st = !contiguous(p, {&p.lq, &p.lk, &p.lv, &p.ld, &p.ldq});
+#define SLA_DQ(NW, ST) bwd_dq_kernel<NW, ST><<<grid, NW * 64, KV_STAGE_BYTES, stream>>>( \
+      (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, crit, lse2, delta, dq_lin, (bf16_t*)dq, bwd_dims(p))
+  if (p.block_q == 128) {
+    if (st) SLA_DQ(4, true); else SLA_DQ(4, false);
+  } else {
+    if (st) SLA_DQ(2, true); else SLA_DQ(2, false);
+  }
+#undef SLA_DQ
   return 0;
 }
 
 constexpr int DKV1_TILES = 2;  // tiles per step of the one-key-block variant: 2 (78 KB of LDS per workgroup) runs compute_interleaved, 1 the plain step
-template <int PHI>
+template <int PHI, bool ST>
 static int launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                                const float* lse2, const float* delta, const bf16_t* G, void* dk, void* dv, hipStream_t stream) {
   // dynamic LDS: two staging buffers, the rows' lse and delta, the list of query blocks
@@ -1041,8 +1109,8 @@ static int launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout,
   const int lds2 = 2 * 4 * TILE_B + 2 * 2 * 64 * 4 + list_bytes;
   const int lds1 = 2 * 2 * DKV1_TILES * TILE_B + 2 * 2 * 32 * DKV1_TILES * 4 + list_bytes;
   static const bool ok =
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess &&
-      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES, PHI>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<2, 2, PHI, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess &&
+      hipFuncSetAttribute((const void*)bwd_dkv_kernel<1, DKV1_TILES, PHI, ST>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256) == hipSuccess;
   if (!ok) return -1;
   const int tiles = p.block_q / 32;  // of a query block: 2 or 4
   // Two key blocks per workgroup halve the bytes streamed where their lists coincide and idle half
@@ -1051,11 +1119,11 @@ static int launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout,
   const bool paired = 2 * p.n_c > p.Tk;
   if (paired) {
     const int pairs = (p.Tk + 1) / 2;
-    bwd_dkv_kernel<2, 2, PHI><<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds2, stream>>>(
+    bwd_dkv_kernel<2, 2, PHI, ST><<<(unsigned)(8 * ((pairs + 7) / 8) * p.BH), 256, lds2, stream>>>(
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, tiles == 4 ? 1 : 0, bwd_dims(p));
   } else {
-    bwd_dkv_kernel<1, DKV1_TILES, PHI><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
+    bwd_dkv_kernel<1, DKV1_TILES, PHI, ST><<<(unsigned)(8 * ((p.Tk + 7) / 8) * p.BH), 128, lds1, stream>>>(
         (const bf16_t*)q, (const bf16_t*)dout, (const bf16_t*)k, (const bf16_t*)v, mask, lse2, delta, G,
         (bf16_t*)dk, (bf16_t*)dv, (tiles == 4 ? 2 : 1) - (DKV1_TILES == 2 ? 1 : 0), bwd_dims(p));
   }
@@ -1065,9 +1133,15 @@ static int launch_bwd_dkv_phi(const Problem& p, const void* q, const void* dout,
 // (the feature map matters to the prologue only -- the linear branch's share -- and only when G is given)
 int launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,
                    const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream) {
-  if (!G || phi_kind == 0) return launch_bwd_dkv_phi<0>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
-  if (phi_kind == 1) return launch_bwd_dkv_phi<1>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
-  return launch_bwd_dkv_phi<2>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  const int phi = G ? phi_kind : 0;
+  if (contiguous(p, {&p.lq, &p.lk, &p.lv, &p.ld, &p.ldk, &p.ldv})) {
+    if (phi == 0) return launch_bwd_dkv_phi<0, false>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+    if (phi == 1) return launch_bwd_dkv_phi<1, false>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+    return launch_bwd_dkv_phi<2, false>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  }
+  if (phi == 0) return launch_bwd_dkv_phi<0, true>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  if (phi == 1) return launch_bwd_dkv_phi<1, true>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
+  return launch_bwd_dkv_phi<2, true>(p, q, dout, k, v, mask, lse2, delta, G, dk, dv, stream);
 }
 
 }  // namespace sla

@@ -72,7 +72,7 @@ template <int NW, int PHI>
 __global__ void __launch_bounds__(NW * 64, 1)
     bwd_lin_q_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ HZ,
                      const bf16_t* __restrict__ wt, float* __restrict__ dq_lin, bf16_t* __restrict__ dHZ,
-                     float* __restrict__ dW_part, float* __restrict__ db_part, int N, int Tq) {
+                     float* __restrict__ dW_part, float* __restrict__ db_part, int N, int Tq, int H, Layout lq, Layout ld) {
   constexpr int BQ = 32 * NW;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Wt = (bf16_t*)smem;              // [c'][r]
@@ -112,7 +112,10 @@ __global__ void __launch_bounds__(NW * 64, 1)
     // ---- this wavefront's 32 tokens
     const long long n = (long long)i * BQ + nl;
     const bool ok = n < N;
-    const size_t row = ((size_t)bh * N + (ok ? n : 0)) * D;
+    const size_t row = ((size_t)bh * N + (ok ? n : 0)) * D;   // (in the library's own dq_lin)
+    const int b_ = bh / H, h_ = bh - b_ * H;
+    const bf16_t* qrow = q + b_ * lq.sb + h_ * lq.sh + (long long)(ok ? n : 0) * lq.sn;
+    const bf16_t* drow = dout + b_ * ld.sb + h_ * ld.sh + (long long)(ok ? n : 0) * ld.sn;
     float av[64];                // a = phi(Q[n]) at channels 16 ks + 8 hf + kk  (index 8 ks + kk)
     uint4 af[8], gf[8];
 #pragma unroll
@@ -120,8 +123,8 @@ __global__ void __launch_bounds__(NW * 64, 1)
       uint4 qv = uint4{0u, 0u, 0u, 0u};
       gf[ks] = qv;
       if (ok) {
-        qv = *(const uint4*)(q + row + 16 * ks + 8 * hf);
-        gf[ks] = *(const uint4*)(dout + row + 16 * ks + 8 * hf);
+        qv = *(const uint4*)(qrow + 16 * ks + 8 * hf);
+        gf[ks] = *(const uint4*)(drow + 16 * ks + 8 * hf);
       }
       unpack8(qv, &av[8 * ks]);
     }
@@ -219,7 +222,7 @@ __global__ void __launch_bounds__(NW * 64, 1)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int c0 = 32 * ct + 8 * g + 4 * hf;
-        qw[ct][g] = ok ? *(const uint2*)(q + row + c0) : uint2{0u, 0u};
+        qw[ct][g] = ok ? *(const uint2*)(qrow + c0) : uint2{0u, 0u};
         const float xq[4] = {bf16_lo(qw[ct][g].x), bf16_hi(qw[ct][g].x), bf16_lo(qw[ct][g].y), bf16_hi(qw[ct][g].y)};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -430,9 +433,9 @@ static int launch_bwd_lin_q_phi(const Problem& p, const void* q, const void* dou
   float* dW_part = dW ? partials : nullptr;
   float* db_part = db ? partials + (size_t)LIN_Q_MAX_CHUNKS * p.BH * D * D : nullptr;
   if (p.block_q == 128)
-    bwd_lin_q_kernel<4, PHI><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW_part, db_part, p.N, p.Tq);
+    bwd_lin_q_kernel<4, PHI><<<grid, 256, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW_part, db_part, p.N, p.Tq, p.H, p.lq, p.ld);
   else
-    bwd_lin_q_kernel<2, PHI><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW_part, db_part, p.N, p.Tq);
+    bwd_lin_q_kernel<2, PHI><<<grid, 128, lds, stream>>>((const bf16_t*)q, (const bf16_t*)dout, HZ, wt, dq_lin, dHZ, dW_part, db_part, p.N, p.Tq, p.H, p.lq, p.ld);
   if (dW) bwd_reduce_partials_kernel<<<(D * D + 255) / 256, 256, 0, stream>>>(dW_part, n_part, D * D, dW);
   if (db) bwd_reduce_partials_kernel<<<1, 256, 0, stream>>>(db_part, n_part, D, db);
   return 0;

@@ -197,3 +197,34 @@ def test_projection_gradients_are_deterministic_and_bias_alone_can_be_asked_for(
     assert c[3] is None and torch.equal(c[4], a[4])
     ref_b = dout.double().sum(dim=(0, 1, 2)).numpy()           # the bias gradient has a closed form
     assert np.abs(a[4].cpu().numpy() - ref_b).max() <= 1e-4 * np.abs(ref_b).max() + 1e-3
+
+
+@pytest.mark.parametrize("bq,rc,rm", [(128, 0.25, 0.5), (64, 0.75, 0.25)])
+def test_training_step_on_token_major_tensors_gives_the_same_bits(bq, rc, rm):
+    """sla_attention_fwd_train_strided + sla_attention_bwd_strided on [B,N,H,d] memory (q, k, v packed in one
+    [B,N,3,H,d] buffer, gradients written into another): bit-identical to the contiguous calls, which the tests
+    above check against the oracle.  Both dK/dV variants (one and two key blocks per workgroup)."""
+    cfg = synth.custom_config(2, 2, (5, 10, 20), block_q=bq, topk_ratio=rc, marginal_ratio=rm, use_proj=True, cfg_id=306)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=13)[2]
+    dev = torch.device("cuda:0")
+    qd, kd, vd, dd, Wd = (t.to(dev) for t in (q, k, v, dout, synth.make_proj(cfg)))
+    out_ref, saved_ref = sla.sla_attention_fwd_train(qd, kd, vd, bq, 64, rc, rm, proj_w=Wd)
+    ref = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True, saved=saved_ref)
+    B, H, N, d = qd.shape
+    packed = torch.stack([t.permute(0, 2, 1, 3) for t in (qd, kd, vd)], dim=2).contiguous()      # [B,N,3,H,d]
+    qv, kv, vv = (packed[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    dtm = dd.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    out_tm = torch.empty((B, N, H, d), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
+    saved = sla.sla_attention_fwd_train_strided(qv, kv, vv, out_tm, bq, 64, rc, rm, proj_w=Wd)
+    assert torch.equal(out_tm, out_ref) and torch.equal(saved, saved_ref)
+    grads = torch.full((B, N, 3, H, d), 7.0, dtype=torch.bfloat16, device=dev)
+    gq, gk, gv = (grads[:, :, i].permute(0, 2, 1, 3) for i in range(3))
+    for sv in (saved, None):                          # from the saved statistics, and recomputing them
+        dw, db = sla.sla_attention_bwd_strided(qv, kv, vv, dtm, gq, gk, gv, bq, 64, rc, rm, proj_w=Wd, want_dw=True,
+                                               want_db=True, saved=sv)
+        torch.cuda.synchronize()
+        if sv is None:
+            ref = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True)
+        for got, want in zip((gq, gk, gv, dw, db), ref):
+            assert torch.equal(got, want)

@@ -299,13 +299,24 @@ def test_unquantised_forward_matches_oracle(H, grid, bq, rc, rm, proj, phi):
         assert np.linalg.norm(got - r["out"]) / np.linalg.norm(r["out"]) <= 5e-3
 
 
-def test_unquantised_forward_rejects_strided_layouts():
-    cfg = _cfg(2, (1, 9, 9), 128, 0.5, 0.5)            # two heads: token-major memory differs from head-major
-    q, k, v = pu.to_dev(*synth.make_qkv(cfg))
-    qt = q.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)          # token-major memory
-    with pytest.raises(sla.SLAError) as e:
-        sla.sla_attention_fwd_strided(qt, k, v, torch.empty_like(q), 128, 64, 0.5, 0.5, quant_mode=sla.QUANT_NONE)
-    assert e.value.status == sla.ERR_LAYOUT
+@pytest.mark.parametrize("mode", ["none", "qk_int8"])
+def test_sixteen_bit_forward_takes_token_major_layouts(mode):
+    """The strided entry point with SLA_QUANT_NONE / SLA_QUANT_QK_INT8 on [B,N,H,d] memory and on one packed
+    [B,N,3,H,d] buffer, token-major output: bit-identical to the contiguous call (which is oracle-checked above)."""
+    cfg = _cfg(3, (3, 27, 27), 128, 0.1, 0.2, cid=411)
+    cfg = synth.custom_config(2, 3, (3, 27, 27), block_q=128, topk_ratio=0.1, marginal_ratio=0.2, cfg_id=411)
+    q, k, v = pu.to_dev(*pu.make_qkv_threaded(cfg))
+    W = synth.make_proj(cfg).cuda()
+    qm = sla.QUANT_NONE if mode == "none" else sla.QUANT_QK_INT8
+    ref = sla.sla_attention_fwd(q, k, v, 128, 64, 0.1, 0.2, proj_w=W, quant_mode=qm)
+    B, H, N, d = q.shape
+    packed = torch.stack([t.permute(0, 2, 1, 3) for t in (q, k, v)], dim=2).contiguous()      # [B,N,3,H,d]
+    views = [packed[:, :, i].permute(0, 2, 1, 3) for i in range(3)]
+    out_tm = torch.full((B, N, H, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = sla.alloc_workspace(B, H, N, d, 128, 64, 0.1, 0.2, quant_mode=qm)
+    sla.sla_attention_fwd_strided(*views, out_tm.permute(0, 2, 1, 3), 128, 64, 0.1, 0.2, proj_w=W, quant_mode=qm, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out_tm.permute(0, 2, 1, 3), ref)
 
 
 @pytest.mark.parametrize("H,grid,bq,rc,rm,proj,phi", [

@@ -74,6 +74,22 @@ def test_backward_sizes_and_argument_errors():
     assert L.sla_attention_fwd_train(*(f[:14] + [9]), WS, sv, WS, big, None) == sla.ERR_UNSUPPORTED
 
 
+def test_strided_training_entry_points_check_layouts_on_the_host():
+    L = sla.lib()
+    big = 1 << 44
+    bad = sla.Strides(2 * 1000 * 128, 1000 * 128, 100)            # token stride below d
+    odd = sla.Strides(2 * 1000 * 128 + 4, 1000 * 128, 128)        # not a multiple of 8 elements
+    sv = sla.sla_saved_bytes(1, 2, 1000, 128, 128)
+    f = lambda qs: L.sla_attention_fwd_train_strided(FAKE, FAKE, FAKE, FAKE, qs, None, None, None, 1, 2, 1000, 128, 128, 64,
+                                                     0.25, 0.5, None, None, 0, WS, sv, WS, big, None)
+    assert f(ctypes.byref(bad)) == sla.ERR_LAYOUT and f(ctypes.byref(odd)) == sla.ERR_LAYOUT
+    bs = sla.BwdStrides(None, None, None, None, None, ctypes.pointer(bad), None)
+    g = lambda st, q=FAKE: L.sla_attention_bwd_strided(q, FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None, None, st, 1, 2, 1000,
+                                                       128, 128, 64, 0.25, 0.5, 0, None, 0, WS, big, None)
+    assert g(ctypes.byref(bs)) == sla.ERR_LAYOUT
+    assert g(None, q=None) == sla.ERR_NULL
+
+
 def test_static_scratch_entry_point_argument_errors():
     # sla_classify_blocks_static: every refusal happens on the host, before the GPU is touched
     L = sla.lib()
