@@ -147,6 +147,27 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
                               const void* proj_w, const void* proj_b, int phi_kind, int quant_mode,
                               void* workspace, size_t workspace_bytes, sla_stream_t stream);
 
+/* The low-bit forward pass (SLA_QUANT_QK_INT8_PV_FP8) in two calls, for callers that want the K/V-side
+ * work out of the way early -- e.g. enqueued as soon as the QKV projection has written q, k, v, while
+ * other work of the block still runs (Section 1.3: the operator sits right behind that projection):
+ *   sla_fwd_prepass   steps 1-2, the quantisation of K and V, the per-block linear summaries and their
+ *                     sums over the marginal blocks: everything the attention kernel reads, left in
+ *                     `workspace` (its contents are then DEFINED until the next call that uses it);
+ *   sla_fwd_attend    the attention kernel with the fused linear term: reads q and the workspace a
+ *                     sla_fwd_prepass call on the same q, sizes, blocks, ratios and phi_kind left,
+ *                     writes out.  proj_w belongs to the first call, proj_b to the second.
+ * Together they enqueue exactly the kernels of sla_attention_fwd_strided and give the same bits.
+ * Strides as there (HOST pointers; NULL = [B,H,N,d] contiguous). */
+int sla_fwd_prepass(const void* q, const void* k, const void* v, const sla_strides* q_strides,
+                    const sla_strides* k_strides, const sla_strides* v_strides,
+                    int B, int H, int N, int d, int block_q, int block_k,
+                    double topk_ratio, double marginal_ratio, const void* proj_w, int phi_kind,
+                    void* workspace, size_t workspace_bytes, sla_stream_t stream);
+int sla_fwd_attend(const void* q, void* out, const sla_strides* q_strides, const sla_strides* out_strides,
+                   int B, int H, int N, int d, int block_q, int block_k,
+                   double topk_ratio, double marginal_ratio, const void* proj_b, int phi_kind,
+                   void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
 /* Steps 1-2 alone.
  *   mask           out  int8  [B,H,Tq,Tk], values +1 / 0 / -1
  *   crit_idx       out  int32 [B,H,Tq,n_crit], ascending j          (may be NULL)

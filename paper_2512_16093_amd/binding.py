@@ -26,7 +26,7 @@ ERR_STATIC_LIMIT = -9
 STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
-           "sla_attention_fwd", "sla_attention_fwd_strided", "sla_classify_blocks", "sla_classify_blocks_static",
+           "sla_attention_fwd", "sla_attention_fwd_strided", "sla_fwd_prepass", "sla_fwd_attend", "sla_classify_blocks", "sla_classify_blocks_static",
            "sla_sparse_attn_fwd",
            "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv",
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
@@ -80,6 +80,10 @@ def lib():
         L.sla_attention_fwd_strided.restype = c_int
         L.sla_attention_fwd_strided.argtypes = ([c_vp] * 4 + [ctypes.POINTER(Strides)] * 4 + [c_int] * 6 +
                                                 [c_dbl, c_dbl, c_vp, c_vp, c_int, c_int, c_vp, c_sz, c_vp])
+        L.sla_fwd_prepass.restype = c_int
+        L.sla_fwd_prepass.argtypes = [c_vp] * 3 + [ctypes.POINTER(Strides)] * 3 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_int, c_vp, c_sz, c_vp]
+        L.sla_fwd_attend.restype = c_int
+        L.sla_fwd_attend.argtypes = [c_vp] * 2 + [ctypes.POINTER(Strides)] * 2 + [c_int] * 6 + [c_dbl, c_dbl, c_vp, c_int, c_vp, c_sz, c_vp]
         L.sla_classify_blocks.restype = c_int
         L.sla_classify_blocks.argtypes = [c_vp, c_vp] + [c_int] * 6 + [c_dbl, c_dbl] + [c_vp] * 4 + [c_vp, c_sz, c_vp]
         L.sla_classify_blocks_static.restype = c_int
@@ -504,3 +508,23 @@ def sla_attention_bwd_strided(q, k, v, dout, dq, dk, dv, block_q, block_k, topk_
                                          _ptr(workspace), workspace.numel(), _stream())
     _check(st, "sla_attention_bwd_strided")
     return dw, db
+
+
+def sla_fwd_prepass(q, k, v, block_q, block_k, topk_ratio, marginal_ratio, workspace, proj_w=None, phi_kind=PHI_SOFTMAX):
+    """The K/V-side part of the low-bit forward pass; leaves its results in `workspace` for sla_fwd_attend.
+    Tensors indexed [B,H,N,d] in any memory order with contiguous channels."""
+    B, H, N, d = _same_shape(q, k, v)
+    sq, sk, sv = (_strides_of(t, n) for t, n in ((q, "q"), (k, "k"), (v, "v")))
+    st = lib().sla_fwd_prepass(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(sq), ctypes.byref(sk), ctypes.byref(sv), B, H, N, d,
+                               block_q, block_k, topk_ratio, marginal_ratio, _ptr(proj_w), phi_kind, _ptr(workspace),
+                               workspace.numel(), _stream())
+    _check(st, "sla_fwd_prepass")
+
+
+def sla_fwd_attend(q, out, block_q, block_k, topk_ratio, marginal_ratio, workspace, proj_b=None, phi_kind=PHI_SOFTMAX):
+    """The attention kernel on a workspace sla_fwd_prepass filled for the same q and parameters."""
+    B, H, N, d = _same_shape(q, out)
+    sq, so_ = _strides_of(q, "q"), _strides_of(out, "out")
+    st = lib().sla_fwd_attend(_ptr(q), _ptr(out), ctypes.byref(sq), ctypes.byref(so_), B, H, N, d, block_q, block_k,
+                              topk_ratio, marginal_ratio, _ptr(proj_b), phi_kind, _ptr(workspace), workspace.numel(), _stream())
+    _check(st, "sla_fwd_attend")

@@ -162,6 +162,34 @@ int fwd_bf16(const void* q, const void* k, const void* v, void* out, const Probl
   return launch_status();
 }
 
+// The low-bit forward pass in two parts.  run_prepass: statistics, block classification, K/V quantisation with
+// the linear summaries, marginal accumulation -- everything the attention kernel reads from the workspace.
+// run_attend: the attention kernel with the fused linear epilogue.
+void run_prepass(const void* q, const void* k, const void* v, const void* proj_w, const Problem& p, int phi_kind,
+                 void* ws, const Workspace& W, hipStream_t s, int rec) {
+  const bool lin = p.n_m > 0;
+  mark(s, rec, 0);
+  run_stats(q, k, v, proj_w, p, ws, W, s);
+  mark(s, rec, 1);
+  launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
+  launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
+                lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
+  mark(s, rec, 2);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
+                 at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
+  mark(s, rec, 3);
+  if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
+  mark(s, rec, 4);
+}
+
+void run_attend(const void* q, void* out, const void* proj_b, const Problem& p, int phi_kind, void* ws,
+                const Workspace& W, hipStream_t s) {
+  launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
+                    at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
+                    (const bf16_t*)proj_b, phi_kind, p.n_m > 0, out, false, nullptr, at<int32_t>(ws, W.pair_list),
+                    at<int32_t>(ws, W.pair_len), s);
+}
+
 // What sla_attention_fwd_train hands to sla_attention_bwd_saved: the rows' base-2 log-sum-exp
 // (fp32, padded to whole query blocks), then O^s (bf16 [BH, N, D]).
 struct SavedState {
@@ -269,29 +297,47 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
                                      quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
-  void* ws = workspace;
-  const bool lin = p.n_m > 0;
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
   if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8)
-    return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, ws, W, s, rec, nullptr, nullptr,
+    return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, workspace, W, s, rec, nullptr, nullptr,
                     quant_mode == SLA_QUANT_QK_INT8);
-  mark(s, rec, 0);
-  run_stats(q, k, v, proj_w, p, ws, W, s);
-  mark(s, rec, 1);
-  launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
-  launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
-                lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
-  mark(s, rec, 2);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
-                 at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
-  mark(s, rec, 3);
-  if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
-  mark(s, rec, 4);
-  launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
-                    at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
-                    (const bf16_t*)proj_b, phi_kind, lin, out, false, nullptr, at<int32_t>(ws, W.pair_list),
-                    at<int32_t>(ws, W.pair_len), s);
+  run_prepass(q, k, v, proj_w, p, phi_kind, workspace, W, s, rec);
+  run_attend(q, out, proj_b, p, phi_kind, workspace, W, s);
   mark(s, rec, 5);
+  return launch_status();
+}
+
+int sla_fwd_prepass(const void* q, const void* k, const void* v, const sla_strides* q_strides,
+                    const sla_strides* k_strides, const sla_strides* v_strides, int B, int H, int N, int d,
+                    int block_q, int block_k, double topk_ratio, double marginal_ratio, const void* proj_w,
+                    int phi_kind, void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  if (!q || !k || !v) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  if ((st = make_layout(q, q_strides, H, N, &p.lq)) != SLA_OK) return st;
+  if ((st = make_layout(k, k_strides, H, N, &p.lk)) != SLA_OK) return st;
+  if ((st = make_layout(v, v_strides, H, N, &p.lv)) != SLA_OK) return st;
+  if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  run_prepass(q, k, v, proj_w, p, phi_kind, workspace, W, (hipStream_t)stream, -1);
+  return launch_status();
+}
+
+int sla_fwd_attend(const void* q, void* out, const sla_strides* q_strides, const sla_strides* out_strides, int B,
+                   int H, int N, int d, int block_q, int block_k, double topk_ratio, double marginal_ratio,
+                   const void* proj_b, int phi_kind, void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  if (!q || !out) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
+  if (st != SLA_OK) return st;
+  if ((st = make_layout(q, q_strides, H, N, &p.lq)) != SLA_OK) return st;
+  if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
+  if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
+  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  run_attend(q, out, proj_b, p, phi_kind, workspace, W, (hipStream_t)stream);
   return launch_status();
 }
 

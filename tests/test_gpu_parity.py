@@ -378,3 +378,22 @@ def test_counted_copy_waits_agree_with_full_waits():
         assert st == 0
         torch.cuda.synchronize()
         assert torch.equal(out, ref), cfg.name
+
+
+def test_prepass_and_attend_give_the_bits_of_the_single_call():
+    """sla_fwd_prepass + sla_fwd_attend (here on token-major memory, with a bias, the second call enqueued on the
+    same stream later) against sla_attention_fwd on the same values."""
+    cfg = synth.custom_config(2, 3, (3, 27, 27), block_q=128, topk_ratio=0.1, marginal_ratio=0.2, cfg_id=412)
+    q, k, v = pu.to_dev(*pu.make_qkv_threaded(cfg))
+    W = synth.make_proj(cfg).cuda()
+    bias = torch.linspace(-0.5, 0.5, cfg.d).to(torch.bfloat16).cuda()
+    ref = sla.sla_attention_fwd(q, k, v, 128, 64, 0.1, 0.2, proj_w=W, proj_b=bias)
+    tm = [t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v)]
+    out = torch.full((cfg.B, cfg.N, cfg.H, cfg.d), float("nan"), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+    ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, 128, 64, 0.1, 0.2)
+    ws.fill_(0xFF)
+    sla.sla_fwd_prepass(*tm, 128, 64, 0.1, 0.2, ws, proj_w=W)
+    torch.cuda.synchronize()                      # (anything may run in between; the workspace holds the state)
+    sla.sla_fwd_attend(tm[0], out, 128, 64, 0.1, 0.2, ws, proj_b=bias)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)

@@ -90,6 +90,19 @@ def test_strided_training_entry_points_check_layouts_on_the_host():
     assert g(None, q=None) == sla.ERR_NULL
 
 
+def test_two_call_forward_argument_errors():
+    L = sla.lib()
+    big = 1 << 44
+    pre = lambda **kw: L.sla_fwd_prepass(kw.get("q", FAKE), FAKE, FAKE, None, None, None, 1, 2, kw.get("N", 1000), 128,
+                                         kw.get("bq", 128), 64, 0.25, 0.5, None, kw.get("phi", 0), kw.get("ws", WS),
+                                         kw.get("bytes", big), None)
+    att = lambda **kw: L.sla_fwd_attend(FAKE, kw.get("out", FAKE), None, None, 1, 2, 1000, 128, 128, 64, kw.get("rc", 0.25),
+                                        0.5, None, 0, kw.get("ws", WS), kw.get("bytes", big), None)
+    assert pre(q=None) == sla.ERR_NULL and pre(N=0) == sla.ERR_SHAPE and pre(bq=96) == sla.ERR_BLOCK
+    assert pre(phi=5) == sla.ERR_UNSUPPORTED and pre(ws=None) == sla.ERR_WORKSPACE and pre(bytes=64) == sla.ERR_WORKSPACE
+    assert att(out=None) == sla.ERR_NULL and att(rc=2.0) == sla.ERR_RATIO and att(bytes=64) == sla.ERR_WORKSPACE
+
+
 def test_static_scratch_entry_point_argument_errors():
     # sla_classify_blocks_static: every refusal happens on the host, before the GPU is touched
     L = sla.lib()
