@@ -61,6 +61,19 @@ __device__ __forceinline__ int cvt_pk_e4m3(float a, float b, int old, bool hi) {
   return hi ? __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, true) : __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, false);
 }
 
+// INT8 code of x at scale 1 / inv: round(x * inv) to the nearest integer, ties to even, as the low byte
+// (two's complement) of the returned word.  Adding 1.5 * 2^23 inside the fma does the rounding;
+// |x * inv| <= 127 (to rounding) by the choice of scale, so no clamp is needed.  A true division would
+// differ only at rounding ties.
+__device__ __forceinline__ uint32_t int8_code_word(float x, float inv) {
+  return __float_as_uint(__builtin_fmaf(x, inv, 12582912.0f));
+}
+// The low bytes of four such words, first in the lowest byte.
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
+  return __builtin_amdgcn_perm(__builtin_amdgcn_perm(b3, b2, 0x0c0c0400u), __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u),
+                               0x05040100u);
+}
+
 // Value held by the partner lane (lane ^ 32) of a 64-wide wavefront.
 __device__ __forceinline__ float partner_f32(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);

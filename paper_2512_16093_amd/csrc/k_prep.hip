@@ -272,12 +272,10 @@ __global__ void __launch_bounds__(256) code_tensors_kernel(const bf16_t* __restr
     if (row >= N) continue;
     const size_t o = ((size_t)bh * N + row) * D + ch;
     kc[o] = f32_to_bf16((float)k8[rec + kfrag_offset(key, ch)]);
-    // the query's code, decided exactly as the low-bit kernel decides it: rint(x / delta), clipped
+    // the query's code, decided exactly as the low-bit kernel decides it
     const float dqi = dq[(size_t)bh * Tq + row / block_q];
     const float x = bf16_to_f32(q[b * lq.sb + h * lq.sh + (long long)row * lq.sn + ch]);
-    float c = __builtin_rintf(x / dqi);
-    c = fminf(fmaxf(c, -127.f), 127.f);
-    qc[o] = f32_to_bf16(c);
+    qc[o] = f32_to_bf16((float)(int8_t)(int8_code_word(x, 1.0f / dqi) & 0xffu));
   }
 }
 

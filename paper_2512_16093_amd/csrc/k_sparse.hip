@@ -268,25 +268,31 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const int b_ = __builtin_amdgcn_readfirstlane(bh / A.H), h_ = bh - b_ * A.H;
   const bf16_t* qptr = A.q + b_ * A.lq.sb + h_ * A.lq.sh + (qok ? qrow : 0) * A.lq.sn;
 
-  // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each)
+  // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each).  The rows are
+  // requested here; the codes are formed behind the first K/V copies (below), under their latency.
   const float dqi = A.dq[(size_t)rowid];
-  v4i q8[4];
+  uint4 qraw[8];
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    float x[16];
-    load_q16(qptr + 32 * s + 16 * hf, qok, x);
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint32_t wv = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float c = __builtin_rintf(x[4 * g + e] / dqi);
-        c = fminf(fmaxf(c, -127.f), 127.f);
-        wv |= ((uint32_t)((int)c) & 0xffu) << (8 * e);
-      }
-      q8[s][g] = (int)wv;
+    qraw[2 * s] = qraw[2 * s + 1] = make_uint4(0, 0, 0, 0);
+    if (qok) {
+      qraw[2 * s] = ((const uint4*)(qptr + 32 * s + 16 * hf))[0];
+      qraw[2 * s + 1] = ((const uint4*)(qptr + 32 * s + 16 * hf))[1];
     }
   }
+  v4i q8[4];
+  auto quantise_q = [&]() {
+    const float inv = 1.0f / dqi;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t wq[8] = {qraw[2 * s].x, qraw[2 * s].y, qraw[2 * s].z, qraw[2 * s].w,
+                              qraw[2 * s + 1].x, qraw[2 * s + 1].y, qraw[2 * s + 1].z, qraw[2 * s + 1].w};
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        q8[s][g] = (int)pack_low_bytes(int8_code_word(bf16_lo(wq[2 * g]), inv), int8_code_word(bf16_hi(wq[2 * g]), inv),
+                                       int8_code_word(bf16_lo(wq[2 * g + 1]), inv), int8_code_word(bf16_hi(wq[2 * g + 1]), inv));
+    }
+  };
   const float cq = dqi * (LOG2E / 11.313708498984761f) * 67108864.f;  // log2(e) / sqrt(d) * delta_Q * 2^26 (see BIAS_I)
 
   v16f acc[4], accl = v16f{};
@@ -541,6 +547,12 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     fetch_rec(v8_bh, j0, vst0);
     fetch_rec(k8_bh, j3, kst3);
     fetch_rec(v8_bh, j1, vst1);
+    {  // (the codes are formed from here on: behind the copies just issued)
+      uint32_t anchor = qraw[0].x;
+      asm volatile("" : "+v"(anchor));
+      qraw[0].x = anchor;
+    }
+    quantise_q();
     __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);  // K(0), K(1) have landed
     stage_barrier();
     read4(kst0, lane, 0, kfA);
@@ -708,17 +720,20 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     }
   }
 
-  // ---- transpose through LDS (per wavefront: 32 rows x 32 channels fp32 at a time) and store
+  // ---- transpose through LDS (per wavefront: 32 rows x 32 channels fp32 at a time) and store.
+  // Wavefront w stages in K slot w, which nobody reads or fills any more (the drain barrier above came
+  // after the last read of a K slot and after every copy had landed), so no workgroup barrier is
+  // needed: a wavefront's LDS operations execute in the order it issues them.
   unsigned char* my = (unsigned char*)(w == 0 ? kst0 : w == 1 ? kst1 : w == 2 ? kst2 : kst3);
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) {
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();   // (compiler fence: the stores below stay behind the reads of the pass before)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const v16f& a = acc[ct];
       *(float4*)(my + l32 * EPI_STRIDE + (8 * g + 4 * hf) * 4) = make_float4(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]);
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int rr = it * 8 + (lane >> 3), c4 = lane & 7;
