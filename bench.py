@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 PEAK_MFMA_8BIT_TOPS = 5000.0   # MI355X dense INT8 (POP/s) and FP8 (PFLOP/s) MFMA peak, both 5.0e15
 # Bytes moved past L2 per launch of the sparse kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # from a 1 GiB copy in the same counter runs), by config id; source: profiles/sla_fwd_wan14b-720p.md.
-SPARSE_TRAFFIC_BYTES = {4: 18.00e9}
+SPARSE_TRAFFIC_BYTES = {4: 18.51e9}
 
 
 # Linear layers of a Wan2.1-14B DiT block (hidden 5120, feed-forward 13824) on the 75600 tokens of a
@@ -40,9 +40,9 @@ W8A8_SHAPES = {"attn_proj": (75600, 5120, 5120), "ffn_up": (75600, 5120, 13824),
 
 # Bytes moved past L2 per launch of the product kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0), by shape;
 # source: profiles/w8a8_linear_wan14b.md.
-W8A8_TRAFFIC_BYTES = {"attn_proj": 6.49e9}
+W8A8_TRAFFIC_BYTES = {"attn_proj": 5.42e9}
 # The backward pass's dominant kernel, by (config, kernel); source: profiles/sla_bwd_wan14b-720p.md.
-BWD_TRAFFIC_BYTES = {(4, "bwd_dkv_kernel"): 164.0e9}
+BWD_TRAFFIC_BYTES = {(4, "bwd_dkv_kernel"): 163.6e9}
 
 
 def parse():
