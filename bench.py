@@ -59,9 +59,9 @@ def parse():
                          "shape; sla_bwd: the SLA backward pass (each a JSON line of its own metric)")
     ap.add_argument("--w8a8-shape", choices=tuple(W8A8_SHAPES), default="attn_proj",
                     help="which Linear layer of a Wan-14B block, on the 75600 tokens of a 720P clip")
-    ap.add_argument("--quant", choices=("int8fp8", "none"), default="int8fp8",
-                    help="sla workload: the paper's low-bit inference path (default) or the unquantised bf16 forward "
-                         "(plain SLA, the training-time operator)")
+    ap.add_argument("--quant", choices=("int8fp8", "qk_int8", "none"), default="int8fp8",
+                    help="sla workload: the paper's low-bit inference path (default), INT8 scores with a 16-bit P.V "
+                         "(qk_int8), or the unquantised bf16 forward (plain SLA, the training-time operator)")
     ap.add_argument("--saved-state", action="store_true",
                     help="sla_bwd workload: hand the backward pass the statistics of a training forward pass "
                          "(sla_attention_fwd_train, run once outside the timed region) instead of recomputing them")
@@ -98,7 +98,7 @@ def make_inputs(cfg, synth, torch):
     return q, k, v
 
 
-def cpu_baseline(cfg, q, k, v, W, budget_s, low_bit=True):
+def cpu_baseline(cfg, q, k, v, W, budget_s, quant_name="int8fp8"):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload:
     head 0 in full for the per-head work (pooling, scores, classification, quantisation,
     linear summaries) and as many query blocks as the budget allows for the per-block work;
@@ -118,11 +118,11 @@ def cpu_baseline(cfg, q, k, v, W, budget_s, low_bit=True):
     t0 = time.perf_counter()
     scores = so.pooled_scores(Q, K, cfg.block_q, cfg.block_k)
     mask = so.classify(scores, n_c, n_m)
-    if low_bit:
+    if quant_name != "none":
         so.quantize_q(Q, cfg.block_q)
         so.quantize_k(K, cfg.block_k)
         so.quantize_v(V)
-    quant = so.QUANT_QK_INT8_PV_FP8 if low_bit else so.QUANT_NONE
+    quant = {"int8fp8": so.QUANT_QK_INT8_PV_FP8, "qk_int8": so.QUANT_QK_INT8, "none": so.QUANT_NONE}[quant_name]
     if n_m:
         so.linear_summaries(K, V, cfg.block_k)
     t_head = time.perf_counter() - t0
@@ -385,11 +385,13 @@ def main():
         out = torch.empty((cfg.B, cfg.N, cfg.H, cfg.d), dtype=torch.bfloat16, device=dev).permute(0, 2, 1, 3)
     else:
         out = torch.empty_like(qd)
-    ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, dev)
     Tq, Tk, n_c, n_m = sla.sla_block_counts(cfg.N, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
 
     low_bit = args.quant == "int8fp8"
-    qmode = sla.QUANT_QK_INT8_PV_FP8 if low_bit else sla.QUANT_NONE
+    qmode = {"int8fp8": sla.QUANT_QK_INT8_PV_FP8, "qk_int8": sla.QUANT_QK_INT8, "none": sla.QUANT_NONE}[args.quant]
+
+    ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio, dev,
+                             quant_mode=qmode)
 
     def step():
         if args.layout == "bnhd":
@@ -428,7 +430,6 @@ def main():
     # HBM-bound stages: algorithmic bytes (each operand once) over the stage's median time
     bhnd = float(cfg.B * cfg.H) * cfg.N * cfg.d
     hz_row = 129 * 128 * 2.0                      # one block summary: 128 x 128 + 128 bf16 values
-    lin = n_m > 0 and low_bit
     stage_bytes = {
         "pool_stats": 6.0 * bhnd,                                                  # Q, K, V read once (bf16)
         "prep_kv": 4.0 * bhnd + (2.0 * bhnd if low_bit else 0.0) + (cfg.B * cfg.H * Tk * hz_row if n_m > 0 else 0.0),
@@ -451,10 +452,12 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_kind": "median of the timed calls (HIP events)",
         "ms_per_step_wall_mean": ms_wall_mean, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8/fp8-e4m3 (fp32 accumulate; bf16 linear branch)" if low_bit else "bf16 (fp32 accumulate and softmax)",
+        "dtype": "int8/fp8-e4m3 (fp32 accumulate; bf16 linear branch)" if low_bit else
+                 ("int8 codes carried as bf16 for Q.K^T, bf16 P.V (fp32 accumulate and softmax)" if args.quant == "qk_int8"
+                  else "bf16 (fp32 accumulate and softmax)"),
         "data": "synthetic",
         "config": {"workload": "%s%s: B=%d H=%d N=%d d=%d block_q=%d block_k=%d critical=%.2f marginal=%.2f seed=0 layout=%s"
-                               % (cfg.name, "" if low_bit else " unquantised", cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q,
+                               % (cfg.name, {"int8fp8": "", "qk_int8": " INT8 scores on the 16-bit pipe", "none": " unquantised"}[args.quant], cfg.B, cfg.H, cfg.N, cfg.d, cfg.block_q,
                                   cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio,
                                   "[B,H,N,d]" if args.layout == "bhnd" else "[B,N,H,d]"),
                    "n_crit": n_c, "n_marg": n_m, "Tq": Tq, "Tk": Tk},
@@ -470,7 +473,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle sample ...", file=sys.stderr, flush=True)
-        result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, W, args.cpu_seconds, low_bit)
+        result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, W, args.cpu_seconds, args.quant)
     print(json.dumps(result))
 
 
