@@ -84,6 +84,38 @@ def copy_calibration(torch, dev):
     del a, b
 
 
+def measured_rates(torch, sla, dev):
+    """What this chip sustains for the bounding resource ALONE, to set beside the published peaks: the three
+    matrix instructions the kernels use (every SIMD issuing nothing else, ~8 ms launches so the clock settles;
+    the mean of the last two of four launches) and a plain 1 GiB device copy (bytes read + written)."""
+    n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+    scratch = torch.empty(2 * n_cu * 256, dtype=torch.float32, device=dev)
+    out = {}
+    for kind, iters, key in (("int8", 60000, "mfma_int8_TOPs"), ("fp8", 30000, "mfma_fp8_TFLOPs"), ("bf16", 60000, "mfma_bf16_TFLOPs")):
+        times = []
+        for _ in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ops = sla.sla_calibrate_mfma(kind, iters, scratch)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        out[key] = round(ops / (sum(times[2:]) / 2 * 1e-3) / 1e12, 1)
+    a = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    times = []
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        b.copy_(a)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    out["device_copy_GBps"] = round(2.0 * (1 << 30) / (sum(times[2:]) / 2 * 1e-3) / 1e9, 1)
+    del a, b, scratch
+    return out
+
+
 def make_inputs(cfg, synth, torch):
     """All heads of the seeded config, generated on the host (threaded over heads), then uploaded."""
     shape = (cfg.B, cfg.H, cfg.N, cfg.d)
@@ -206,6 +238,10 @@ def main_w8a8(args):
                                   "unit": "GB/s", "frac": 3.0 * M * K / (t_quant * 1e-3) / 1e9 / 8000.0},
         "context": "the paper reports no kernel-level number for its W8A8 Linear layers",
     }
+    rates = measured_rates(torch, sla, torch.device("cuda:0"))   # what the matrix pipe and a device copy sustain by themselves
+    result["measured_rates"] = rates
+    result["roofline"]["mfma_alone"] = rates["mfma_int8_TOPs"]
+    result["roofline"]["frac_of_mfma_alone"] = round(achieved / rates["mfma_int8_TOPs"], 4)
     if not args.no_cpu_baseline:
         from oracle import w8a8_oracle as wo      # cpu_baseline leg: allowed to call the oracle
         try:
@@ -322,6 +358,10 @@ def main_bwd(args):
                      "launch_ms": t_dom, "ops_per_launch": ops},
         "context": "the paper reports no number for its finetuning stage",
     }
+    rates = measured_rates(torch, sla, dev)   # what the matrix pipe and a device copy sustain by themselves
+    result["measured_rates"] = rates
+    result["roofline"]["mfma_alone"] = rates["mfma_bf16_TFLOPs"]
+    result["roofline"]["frac_of_mfma_alone"] = round(achieved / rates["mfma_bf16_TFLOPs"], 4)
     if not args.no_cpu_baseline:
         from oracle import sla_bwd_oracle as bo   # cpu_baseline leg: allowed to call the oracle
         from oracle import sla_oracle as so
@@ -471,6 +511,15 @@ def main():
                      "launch_ms": stage_mean[4], "launch_ms_median": stage_ms[4], "ops_per_launch": ops},
         "context": "paper: 100-200x end-to-end, 184 s -> 1.9 s on one RTX 5090 (whole pipeline; no kernel-level number)",
     }
+    # beside the published peaks: what the matrix pipe and a device copy sustain on this chip by themselves
+    rates = measured_rates(torch, sla, dev)
+    result["measured_rates"] = rates
+    if low_bit:  # half of the kernel's operations are INT8, half FP8: the harmonic mean of the two rates
+        alone = 2.0 / (1.0 / rates["mfma_int8_TOPs"] + 1.0 / rates["mfma_fp8_TFLOPs"])
+    else:
+        alone = rates["mfma_bf16_TFLOPs"]
+    result["roofline"]["mfma_alone"] = round(alone, 1)
+    result["roofline"]["frac_of_mfma_alone"] = round(achieved / alone, 4)
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, W, args.cpu_seconds, args.quant)

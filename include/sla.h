@@ -233,6 +233,17 @@ int sla_profile_enable(int max_calls);
 int sla_profile_reset(void);
 int sla_profile_read(float* stage_ms, int max_calls, int* n_calls);
 
+/* Measurement aid (Section 1.1 names the INT8 and FP8 matrix units the method runs on; the
+ * benchmark sets what a kernel achieves beside what those units sustain on the chip at hand):
+ * enqueues a kernel in which every SIMD issues nothing but independent matrix products of one
+ * kind -- kind 0: INT8 32x32x32, 1: FP8 32x32x64, 2: bf16 32x32x16 -- `iters` rounds of four
+ * per wavefront, two workgroups of four wavefronts per compute unit, no memory traffic.
+ * *ops (HOST pointer) receives the number of operations (2 per multiply-add) the launch
+ * performs; the caller times the launch.  scratch: device memory of at least 2048 bytes per
+ * compute unit (results nobody reads), else SLA_ERR_WORKSPACE; another kind: SLA_ERR_UNSUPPORTED;
+ * iters < 1: SLA_ERR_SHAPE. */
+int sla_calibrate_mfma(int kind, int iters, void* scratch, size_t scratch_bytes, double* ops, sla_stream_t stream);
+
 /* Format check: converts n fp32 values (device) to FP8 E4M3 codes (device) with
  * the same instruction sequence the kernels use for P and V (round to nearest
  * even, saturating at +-448).  For tests of the number format only. */

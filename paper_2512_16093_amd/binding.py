@@ -28,7 +28,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
            "sla_attention_fwd", "sla_attention_fwd_strided", "sla_fwd_prepass", "sla_fwd_attend", "sla_classify_blocks", "sla_classify_blocks_static",
            "sla_sparse_attn_fwd",
-           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv",
+           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv", "sla_calibrate_mfma",
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
 W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
                 "w8a8_quantize_act", "w8a8_gemm_fwd", "w8a8_debug_unpack")
@@ -94,6 +94,8 @@ def lib():
         L.sla_linear_attn_fwd.argtypes = [c_vp] * 6 + [c_int, c_vp] + [c_int] * 6 + [c_vp, c_sz, c_vp]
         L.sla_debug_e4m3_encode.restype = c_int
         L.sla_debug_e4m3_encode.argtypes = [c_vp, c_vp, c_sz, c_vp]
+        L.sla_calibrate_mfma.restype = c_int
+        L.sla_calibrate_mfma.argtypes = [c_int, c_int, c_vp, c_sz, ctypes.POINTER(ctypes.c_double), c_vp]
         L.sla_debug_quantize_kv.restype = c_int
         L.sla_debug_quantize_kv.argtypes = [c_vp, c_vp] + [c_int] * 5 + [c_vp] * 5 + [c_vp, c_sz, c_vp]
         L.sla_profile_enable.restype = c_int
@@ -355,6 +357,18 @@ def sla_debug_e4m3_encode(x):
     out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
     _check(lib().sla_debug_e4m3_encode(_ptr(x), _ptr(out), x.numel(), _stream()), "sla_debug_e4m3_encode")
     return out
+
+
+MFMA_KINDS = {"int8": 0, "fp8": 1, "bf16": 2}
+
+
+def sla_calibrate_mfma(kind, iters, scratch):
+    """Enqueues the matrix-pipe-only loop of one instruction kind ("int8", "fp8", "bf16") on the current stream;
+    returns the number of operations the launch performs (the caller times it)."""
+    ops = ctypes.c_double(0.0)
+    _check(lib().sla_calibrate_mfma(MFMA_KINDS[kind], iters, _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                    ctypes.byref(ops), _stream()), "sla_calibrate_mfma")
+    return ops.value
 
 
 def sla_debug_quantize_kv(k, v, block_k=64, workspace=None):

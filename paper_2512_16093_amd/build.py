@@ -17,7 +17,7 @@ LIB = os.path.join(HERE, "libsla.so")
 # The same library with the attention kernel's hand-counted copy waits replaced by full waits
 # (-DSLA_FULL_WAITS): a checking build that a GPU test compares with the product build bit for bit.
 LIB_FULL_WAITS = os.path.join(HERE, "libsla_fullwaits.so")
-SOURCES = ["api.hip", "api_w8a8.hip", "k_classify.hip", "k_prep.hip", "k_linacc.hip", "k_sparse.hip", "k_w8a8.hip", "k_bwd.hip", "k_bwd_lin.hip"]
+SOURCES = ["api.hip", "api_w8a8.hip", "k_classify.hip", "k_prep.hip", "k_linacc.hip", "k_sparse.hip", "k_w8a8.hip", "k_bwd.hip", "k_bwd_lin.hip", "k_calib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
          "-Wno-inline-asm"]  # (the asynchronous-copy helpers name m0 in their clobber lists on purpose)

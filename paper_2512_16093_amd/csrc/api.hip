@@ -473,6 +473,18 @@ int sla_debug_e4m3_encode(const float* in, uint8_t* out, size_t n, sla_stream_t 
   return launch_status();
 }
 
+int sla_calibrate_mfma(int kind, int iters, void* scratch, size_t scratch_bytes, double* ops, sla_stream_t stream) {
+  if (!scratch || !ops) return SLA_ERR_NULL;
+  if (kind < 0 || kind > 2) return SLA_ERR_UNSUPPORTED;
+  if (iters < 1) return SLA_ERR_SHAPE;
+  int dev = 0, n_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+    return SLA_ERR_HIP;
+  if (scratch_bytes < (size_t)2 * n_cu * 256 * sizeof(float)) return SLA_ERR_WORKSPACE;
+  *ops = launch_mfma_rate(kind, iters, n_cu, (float*)scratch, (hipStream_t)stream);
+  return launch_status();
+}
+
 int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int d, int block_k,
                           int8_t* k_codes, float* k_scale, float* k_mean, uint8_t* v_codes, float* v_scale,
                           void* workspace, size_t workspace_bytes, sla_stream_t stream) {

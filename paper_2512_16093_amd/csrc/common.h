@@ -223,6 +223,7 @@ int launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void
                     const float* lse2, const float* delta, const bf16_t* G, int phi_kind, void* dk, void* dv, hipStream_t stream);
 void launch_bwd_wt(const bf16_t* proj_w, bf16_t* wt, hipStream_t stream);
 size_t bwd_lin_q_partial_bytes(const Problem& p);
+double launch_mfma_rate(int kind, int iters, int n_cu, float* sink, hipStream_t stream);
 int launch_bwd_lin_q(const Problem& p, const void* q, const void* dout, const bf16_t* HZ, const bf16_t* wt,
                      int phi_kind, float* dq_lin, bf16_t* dHZ, float* dW, float* db, float* partials, hipStream_t stream);
 void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream);
