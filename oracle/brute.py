@@ -127,9 +127,10 @@ def brute_e4m3(x):
     return -r if x < 0 else r
 
 
-def _int8(x, delta):
-    """Symmetric 8-bit code: Python's round() is round-half-to-even."""
-    return float(max(-127, min(127, round(x / delta))))
+def _int8(x, amax):
+    """Symmetric 8-bit code at the scale amax / 127, from the quotient 127 x / amax (whose numerator is
+    exact for 16-bit inputs, so exact ties are ties): Python's round() is round-half-to-even."""
+    return float(max(-127, min(127, round(127.0 * x / amax)))) if amax > 0 else 0.0
 
 
 def brute_sparse_quant(Q, K, V, mask, block_q, block_k, pv_fp8=True, reference="ceil_log2",
@@ -154,19 +155,21 @@ def brute_sparse_quant(Q, K, V, mask, block_q, block_k, pv_fp8=True, reference="
         amax = max(abs(K[n][c] - mu[c]) for n in toks for c in range(d))
         dk.append(amax / 127.0 if amax > 0 else 1.0)
         for n in toks:
-            K8[n] = [_int8(K[n][c] - mu[c], dk[j]) for c in range(d)]
+            K8[n] = [_int8(K[n][c] - mu[c], amax) for c in range(d)]
     Q8, dq = [None] * N, []
     for i in range(Tq):
         toks = range(i * block_q, min((i + 1) * block_q, N))
         amax = max(abs(Q[n][c]) for n in toks for c in range(d))
         dq.append(amax / 127.0 if amax > 0 else 1.0)
         for n in toks:
-            Q8[n] = [_int8(Q[n][c], dq[i]) for c in range(d)]
-    dv = []
+            Q8[n] = [_int8(Q[n][c], amax) for c in range(d)]
+    dv, vmax = [], []
     for c in range(dv_):
         amax = max(abs(V[n][c]) for n in range(N))
+        vmax.append(amax)
         dv.append(amax / 448.0 if amax > 0 else 1.0)
-    V8 = [[brute_e4m3(V[n][c] / dv[c]) if pv_fp8 else V[n][c] / dv[c] for c in range(dv_)] for n in range(N)]
+    scaled = lambda n, c: 448.0 * V[n][c] / vmax[c] if vmax[c] > 0 else V[n][c]   # V / dv with an exact numerator
+    V8 = [[brute_e4m3(scaled(n, c)) if pv_fp8 else scaled(n, c) for c in range(dv_)] for n in range(N)]
 
     log2e = 1.0 / math.log(2.0)
     out, lse = [], []

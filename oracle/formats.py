@@ -75,3 +75,15 @@ def e4m3_encode(x):
 def int8_quantize(x, delta):
     """Symmetric INT8 code clip(rint(x / delta), -127, 127) as float64 integers."""
     return np.clip(np.rint(np.asarray(x, dtype=np.float64) / delta), -INT8_MAX, INT8_MAX)
+
+
+def int8_codes(x, amax):
+    """Symmetric INT8 codes of a block whose largest magnitude is amax, i.e. with the scale amax / 127:
+    clip(rint(127 x / amax), -127, 127) as float64 integers (zeros when amax is 0).  The quotient is
+    formed from the product 127 x, which is exact for 16-bit inputs, so a value that lies exactly half
+    way between two codes is seen as the tie it is and goes to the even code; dividing by the rounded
+    scale amax / 127 instead would let that scale's last bit decide such ties."""
+    x = np.asarray(x, dtype=np.float64)
+    if amax <= 0:
+        return np.zeros_like(x)
+    return np.clip(np.rint(x * INT8_MAX / amax), -INT8_MAX, INT8_MAX)

@@ -103,7 +103,8 @@ def quantize_k(K, block_k, smooth=True):
 
     mu = channel mean of K over all N tokens; K~ = K - mu; per block
     delta_j = max|K~_j| / 127 (1 if the block is all zero); codes are
-    clip(rint(K~ / delta_j), -127, 127).  Returns (codes [N, d] as float64
+    clip(rint(K~ / delta_j), -127, 127), the quotient taken as 127 K~ / max|K~_j|
+    (formats.int8_codes: exact ties stay ties).  Returns (codes [N, d] as float64
     integers, delta [Tk], mu [d])."""
     N, d = K.shape
     mu = K.mean(axis=0) if smooth else np.zeros(d)
@@ -114,7 +115,7 @@ def quantize_k(K, block_k, smooth=True):
     for j, s in enumerate(sl):
         amax = np.abs(Kt[s]).max()
         delta[j] = amax / formats.INT8_MAX if amax > 0 else 1.0
-        codes[s] = formats.int8_quantize(Kt[s], delta[j])
+        codes[s] = formats.int8_codes(Kt[s], amax)
     return codes, delta, mu
 
 
@@ -127,16 +128,19 @@ def quantize_q(Q, block_q):
     for i, s in enumerate(sl):
         amax = np.abs(Q[s]).max()
         delta[i] = amax / formats.INT8_MAX if amax > 0 else 1.0
-        codes[s] = formats.int8_quantize(Q[s], delta[i])
+        codes[s] = formats.int8_codes(Q[s], amax)
     return codes, delta
 
 
 def quantize_v(V, fp8=True):
     """Per-channel scale over all tokens, delta[c] = max_n |V[n, c]| / 448 (1 if
-    zero); returns (V / delta rounded to E4M3 if fp8 else unrounded, delta [d])."""
+    zero); returns (V / delta rounded to E4M3 if fp8 else unrounded, delta [d]).
+    The quotient is taken as 448 V / max|V| (the product is exact for 16-bit inputs), so
+    that a value exactly half way between two E4M3 values is rounded as the tie it is
+    instead of by the last bit of the rounded scale."""
     amax = np.abs(V).max(axis=0)
     delta = np.where(amax > 0, amax / formats.E4M3_MAX, 1.0)
-    Vs = V / delta
+    Vs = np.where(amax > 0, V * formats.E4M3_MAX / np.where(amax > 0, amax, 1.0), V)
     return (formats.e4m3_round(Vs) if fp8 else Vs), delta
 
 

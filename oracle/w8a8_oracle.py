@@ -46,7 +46,7 @@ def quantize_blockwise(A, block=BLOCK):
             amax = np.abs(A[rs, cs]).max()
             s = amax / formats.INT8_MAX if amax > 0 else 1.0
             scales[r, c] = s
-            codes[rs, cs] = formats.int8_quantize(A[rs, cs], s)
+            codes[rs, cs] = formats.int8_codes(A[rs, cs], amax)   # rint(127 x / amax): exact ties stay ties
     return codes, scales
 
 

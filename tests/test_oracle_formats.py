@@ -96,3 +96,28 @@ def test_int8_quantize_range_and_ties():
     assert np.abs(c * d - y).max() <= d / 2 + 1e-15
     ref = torch.round(torch.from_numpy(y / d)).numpy()  # torch.round is half-to-even
     assert np.array_equal(c, ref)
+
+
+def test_codes_at_exact_ties_follow_the_rule_not_the_rounding_of_the_scale():
+    """16-bit inputs make quotients that are exactly half way between two codes common (x = amax / 2 gives
+    63.5); such a value must go to the even code whatever the last bit of amax / 127 is.  Checked against
+    exact rational arithmetic."""
+    from fractions import Fraction
+    amaxes = [1.90625, 3.0, 0.2890625, 5.5, 7.25, 100.0, 0.01171875]         # bf16 values
+    for amax in amaxes:
+        xs = np.array([amax * f for f in (0.5, 0.25, 0.75, 0.125, 1.0, -0.5, -0.75, 0.3125)])
+        xs = formats.bf16_round(xs)
+        got = formats.int8_codes(xs, amax)
+        for x, c in zip(xs, got):
+            t = Fraction(float(x)) * 127 / Fraction(amax)
+            lo = t.numerator // t.denominator
+            frac = t - lo
+            want = lo + 1 if frac > Fraction(1, 2) else lo if frac < Fraction(1, 2) else lo + (lo % 2)
+            assert c == want, (amax, x, c, want)
+    # the case that showed it: 448 * 1.4296875 / 1.90625 is 336, half way between 320 and 352 -> 320 (even mantissa)
+    from oracle import sla_oracle as so
+    V = np.array([[1.90625], [1.4296875], [-1.4296875], [0.953125]])
+    V8, dv = so.quantize_v(V)
+    assert np.array_equal(V8[:, 0], [448.0, 320.0, -320.0, 224.0]) and dv[0] == 1.90625 / 448
+    assert np.array_equal(formats.int8_codes(np.zeros(3), 0.0), np.zeros(3))
+

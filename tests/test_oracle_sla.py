@@ -138,8 +138,8 @@ def test_brute_force_notices_misplaced_rounding(monkeypatch):
     monkeypatch.setattr(formats, "e4m3_round", p_unrounded)
     assert np.abs(so.sparse_branch_quant(Q, K, V, mask, 32, 16) - ref).max() > 1e-6
     monkeypatch.setattr(formats, "e4m3_round", real_round)
-    monkeypatch.setattr(formats, "int8_quantize",
-                        lambda x, delta: np.clip(np.trunc(np.asarray(x) / delta), -127, 127))
+    monkeypatch.setattr(formats, "int8_codes",
+                        lambda x, amax: np.clip(np.trunc(np.asarray(x) * 127.0 / amax), -127, 127))
     assert np.abs(so.sparse_branch_quant(Q, K, V, mask, 32, 16) - ref).max() > 1e-6
 
 
@@ -290,7 +290,7 @@ def test_online_softmax_equals_two_pass_when_nothing_is_rounded(monkeypatch):
     # is the online-softmax recurrence, which must equal the exact branch.
     cfg, Q, K, V = _tiny()
     mask = so.classify(so.pooled_scores(Q, K, 64, 64), 3, 6)
-    monkeypatch.setattr(formats, "int8_quantize", lambda x, delta: np.asarray(x) / delta)
+    monkeypatch.setattr(formats, "int8_codes", lambda x, amax: np.asarray(x) * 127.0 / amax)
     monkeypatch.setattr(formats, "e4m3_round", lambda x: np.asarray(x, dtype=np.float64))
     ex = so.sparse_branch_exact(Q, K, V, mask, 64, 64)
     for ref in ("running", "ceil_log2"):
