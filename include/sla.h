@@ -258,6 +258,13 @@ int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int
                           uint8_t* v_codes, float* v_scale,
                           void* workspace, size_t workspace_bytes, sla_stream_t stream);
 
+/* The same for Q: its INT8 codes int8 [B,H,N,d] and the per-query-block scales fp32
+ * [B,H,ceil(N/block_q)] (step 3: symmetric, scale = max|block| / 127, round to nearest, ties to the
+ * even code).  Either output may be NULL. */
+int sla_debug_quantize_q(const void* q, int B, int H, int N, int d, int block_q,
+                         int8_t* q_codes, float* q_scale,
+                         void* workspace, size_t workspace_bytes, sla_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

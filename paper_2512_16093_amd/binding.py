@@ -28,7 +28,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = ("sla_version", "sla_status_string", "sla_block_counts", "sla_workspace_bytes",
            "sla_attention_fwd", "sla_attention_fwd_strided", "sla_fwd_prepass", "sla_fwd_attend", "sla_classify_blocks", "sla_classify_blocks_static",
            "sla_sparse_attn_fwd",
-           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv", "sla_calibrate_mfma",
+           "sla_linear_attn_fwd", "sla_debug_e4m3_encode", "sla_debug_quantize_kv", "sla_debug_quantize_q", "sla_calibrate_mfma",
            "sla_profile_enable", "sla_profile_reset", "sla_profile_read")
 W8A8_EXPORTS = ("w8a8_weight_bytes", "w8a8_quantize_weight", "w8a8_workspace_bytes", "w8a8_linear_fwd",
                 "w8a8_quantize_act", "w8a8_gemm_fwd", "w8a8_debug_unpack")
@@ -94,6 +94,8 @@ def lib():
         L.sla_linear_attn_fwd.argtypes = [c_vp] * 6 + [c_int, c_vp] + [c_int] * 6 + [c_vp, c_sz, c_vp]
         L.sla_debug_e4m3_encode.restype = c_int
         L.sla_debug_e4m3_encode.argtypes = [c_vp, c_vp, c_sz, c_vp]
+        L.sla_debug_quantize_q.restype = c_int
+        L.sla_debug_quantize_q.argtypes = [c_vp] + [c_int] * 5 + [c_vp, c_vp] + [c_vp, c_sz, c_vp]
         L.sla_calibrate_mfma.restype = c_int
         L.sla_calibrate_mfma.argtypes = [c_int, c_int, c_vp, c_sz, ctypes.POINTER(ctypes.c_double), c_vp]
         L.sla_debug_quantize_kv.restype = c_int
@@ -387,6 +389,20 @@ def sla_debug_quantize_kv(k, v, block_k=64, workspace=None):
                                      _ptr(vc), _ptr(vs), _ptr(workspace), workspace.numel(), _stream())
     _check(st, "sla_debug_quantize_kv")
     return kc, ks, km, vc, vs
+
+
+def sla_debug_quantize_q(q, block_q=128, workspace=None):
+    """Returns (q_codes int8 [B,H,N,d], q_scale fp32 [B,H,Tq])."""
+    B, H, N, d = _bf16_4d(q)
+    Tq = -(-N // block_q)
+    if workspace is None:
+        workspace = alloc_workspace(B, H, N, d, block_q, 64, 1.0, 0.0, q.device)
+    qc = torch.empty((B, H, N, d), dtype=torch.int8, device=q.device)
+    qs = torch.empty((B, H, Tq), dtype=torch.float32, device=q.device)
+    st = lib().sla_debug_quantize_q(_ptr(q), B, H, N, d, block_q, _ptr(qc), _ptr(qs), _ptr(workspace), workspace.numel(),
+                                    _stream())
+    _check(st, "sla_debug_quantize_q")
+    return qc, qs
 
 
 def sla_profile_enable(max_calls):

@@ -121,10 +121,17 @@ inline void mark(hipStream_t s, int rec, int idx) {
 template <class T>
 T* at(void* ws, size_t off) { return (T*)((unsigned char*)ws + off); }
 
+// The forward entry points' workspace (one size serves all of them): with room for the INT8 codes of Q,
+// whole groups of 128 rows per (b,h).
+size_t q8_rows(const Problem& p) { return (size_t)((p.N + 127) / 128) * 128; }
+Workspace fwd_workspace(const Problem& p, size_t n_c, size_t n_m, size_t code_tensor_elems = 0) {
+  return make_workspace(p.BH, p.Tq, p.Tk, n_c, n_m, code_tensor_elems, q8_rows(p));
+}
+
 void run_stats(const void* q, const void* k, const void* v, const void* proj_w, const Problem& p, void* ws,
-               const Workspace& W, hipStream_t s) {
+               const Workspace& W, hipStream_t s, bool want_q8 = false) {
   launch_pool_stats(q, k, v, p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.dq),
-                    at<uint32_t>(ws, W.amax_v), s);
+                    at<uint32_t>(ws, W.amax_v), want_q8 ? at<int8_t>(ws, W.q8) : nullptr, s);
   launch_finalize_stats(p, at<float>(ws, W.kbar), at<uint32_t>(ws, W.amax_v), at<float>(ws, W.mu_k),
                         at<float>(ws, W.dv), (const bf16_t*)proj_w, at<bf16_t>(ws, W.wfrag), s);
 }
@@ -139,17 +146,17 @@ int fwd_bf16(const void* q, const void* k, const void* v, void* out, const Probl
              void* save_os, bool codes16 = false) {
   const bool lin = p.n_m > 0;
   mark(s, rec, 0);
-  run_stats(q, k, v, proj_w, p, ws, W, s);
+  run_stats(q, k, v, proj_w, p, ws, W, s, codes16);
   mark(s, rec, 1);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
   launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
   if (lin || codes16)
-    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, codes16, lin,
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, codes16, lin,
                    at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   if (codes16)
-    launch_code_tensors(q, p, at<int8_t>(ws, W.k8), at<float>(ws, W.dq), at<bf16_t>(ws, W.qc), at<bf16_t>(ws, W.kc), s);
+    launch_code_tensors(p, at<int8_t>(ws, W.q8), at<int8_t>(ws, W.k8), at<bf16_t>(ws, W.qc), at<bf16_t>(ws, W.kc), s);
   mark(s, rec, 3);
   if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   mark(s, rec, 4);
@@ -169,13 +176,13 @@ void run_prepass(const void* q, const void* k, const void* v, const void* proj_w
                  void* ws, const Workspace& W, hipStream_t s, int rec) {
   const bool lin = p.n_m > 0;
   mark(s, rec, 0);
-  run_stats(q, k, v, proj_w, p, ws, W, s);
+  run_stats(q, k, v, proj_w, p, ws, W, s, true);
   mark(s, rec, 1);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.scores), s);
   launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   mark(s, rec, 3);
   if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
@@ -184,7 +191,7 @@ void run_prepass(const void* q, const void* k, const void* v, const void* proj_w
 
 void run_attend(const void* q, void* out, const void* proj_b, const Problem& p, int phi_kind, void* ws,
                 const Workspace& W, hipStream_t s) {
-  launch_sparse_fwd(q, p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
+  launch_sparse_fwd(q, at<int8_t>(ws, W.q8), p, at<int32_t>(ws, W.crit), p.n_c, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8),
                     at<float>(ws, W.dq), at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ),
                     (const bf16_t*)proj_b, phi_kind, p.n_m > 0, out, false, nullptr, at<int32_t>(ws, W.pair_list),
                     at<int32_t>(ws, W.pair_len), s);
@@ -265,7 +272,7 @@ size_t sla_workspace_bytes(int B, int H, int N, int d, int block_q, int block_k,
   if (quant_mode < SLA_QUANT_NONE || quant_mode > SLA_QUANT_QK_INT8_PV_FP8) return 0;
   if (make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p) != SLA_OK) return 0;
   // (sized by the given ratios; SLA_QUANT_QK_INT8 adds the two 16-bit code tensors)
-  return make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m, quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0).total;
+  return fwd_workspace(p, p.n_c, p.n_m, quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0).total;
 }
 
 int sla_attention_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,
@@ -293,8 +300,7 @@ int sla_attention_fwd_strided(const void* q, const void* k, const void* v, void*
   if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
   if (quant_mode < SLA_QUANT_NONE || quant_mode > SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m,
-                                     quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0);
+  const Workspace W = fwd_workspace(p, p.n_c, p.n_m, quant_mode == SLA_QUANT_QK_INT8 ? (size_t)p.BH * p.N * D : 0);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
@@ -319,7 +325,7 @@ int sla_fwd_prepass(const void* q, const void* k, const void* v, const sla_strid
   if ((st = make_layout(k, k_strides, H, N, &p.lk)) != SLA_OK) return st;
   if ((st = make_layout(v, v_strides, H, N, &p.lv)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  const Workspace W = fwd_workspace(p, p.n_c, p.n_m);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   run_prepass(q, k, v, proj_w, p, phi_kind, workspace, W, (hipStream_t)stream, -1);
   return launch_status();
@@ -335,7 +341,7 @@ int sla_fwd_attend(const void* q, void* out, const sla_strides* q_strides, const
   if ((st = make_layout(q, q_strides, H, N, &p.lq)) != SLA_OK) return st;
   if ((st = make_layout(out, out_strides, H, N, &p.lo)) != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  const Workspace W = fwd_workspace(p, p.n_c, p.n_m);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   run_attend(q, out, proj_b, p, phi_kind, workspace, W, (hipStream_t)stream);
   return launch_status();
@@ -384,13 +390,13 @@ int sla_classify_blocks(const void* q, const void* k, int B, int H, int N, int d
   Problem p;
   int st = make_problem(B, H, N, d, block_q, block_k, topk_ratio, marginal_ratio, &p);
   if (st != SLA_OK) return st;
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, p.n_c, p.n_m);
+  const Workspace W = fwd_workspace(p, p.n_c, p.n_m);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   // V is not an input here: the statistics pass reads K in its place (its V outputs are unused)
   launch_pool_stats(q, k, k, p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.dq),
-                    at<uint32_t>(ws, W.amax_v), s);
+                    at<uint32_t>(ws, W.amax_v), nullptr, s);
   float* sc = pooled_scores ? pooled_scores : at<float>(ws, W.scores);
   launch_scores(p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), sc, s);
   launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, nullptr, s);
@@ -411,7 +417,7 @@ int sla_classify_blocks_static(const void* q, const void* k, int B, int H, int N
   hipStream_t s = (hipStream_t)stream;
   // the same kernels as sla_classify_blocks; the statistics pass zeroes what it accumulates into
   launch_pool_stats(q, k, k, p, at<float>(ws, C.qbar), at<float>(ws, C.kbar), at<float>(ws, C.dq),
-                    at<uint32_t>(ws, C.amax_v), s);
+                    at<uint32_t>(ws, C.amax_v), nullptr, s);
   float* sc = pooled_scores ? pooled_scores : at<float>(ws, C.scores);
   launch_scores(p, at<float>(ws, C.qbar), at<float>(ws, C.kbar), sc, s);
   launch_select(p, sc, mask, crit_idx, p.n_m > 0 ? marg_idx : nullptr, nullptr, s);
@@ -429,14 +435,14 @@ int sla_sparse_attn_fwd(const void* q, const void* k, const void* v, const int32
   if (quant_mode != SLA_QUANT_QK_INT8_PV_FP8) return SLA_ERR_UNSUPPORTED;
   // the internal index lists are not used here, so the smallest workspace that
   // sla_workspace_bytes can return for this shape is enough
-  const Workspace Wmin = make_workspace(p.BH, p.Tq, p.Tk, 1, 0);
+  const Workspace Wmin = fwd_workspace(p, 1, 0);
   if ((st = check_ws(workspace, workspace_bytes, Wmin.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
-  run_stats(q, k, v, nullptr, p, ws, Wmin, s);
-  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<float>(ws, Wmin.dv), at<bf16_t>(ws, Wmin.wfrag), 0, true,
+  run_stats(q, k, v, nullptr, p, ws, Wmin, s, true);
+  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<float>(ws, Wmin.dv), at<uint32_t>(ws, Wmin.amax_v), at<bf16_t>(ws, Wmin.wfrag), 0, true,
                  false, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8), at<float>(ws, Wmin.dk), nullptr, s);
-  launch_sparse_fwd(q, p, crit_idx, n_crit, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8),
+  launch_sparse_fwd(q, at<int8_t>(ws, Wmin.q8), p, crit_idx, n_crit, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8),
                     at<float>(ws, Wmin.dq), at<float>(ws, Wmin.dk), at<float>(ws, Wmin.dv), nullptr, nullptr, 0,
                     false, out_s, true, lse, nullptr, nullptr, s);
   return launch_status();
@@ -451,17 +457,17 @@ int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_
   int st = make_problem(B, H, N, d, block_q, block_k, 1.0, 0.0, &p);
   if (st != SLA_OK) return st;
   if (phi_kind < SLA_PHI_SOFTMAX || phi_kind > SLA_PHI_RELU) return SLA_ERR_UNSUPPORTED;
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, 1, 0);
+  const Workspace W = fwd_workspace(p, 1, 0);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
-  run_stats(q, k, v, proj_w, p, ws, W, s);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true, nullptr,
+  run_stats(q, k, v, proj_w, p, ws, W, s, true);
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, false, true, nullptr,
                  nullptr, nullptr, at<bf16_t>(ws, W.hz), s);
   launch_marginal_bits(p, mask, at<uint32_t>(ws, W.m0), s);
   launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
   // the attention kernel with an empty critical list leaves only the linear term
-  launch_sparse_fwd(q, p, nullptr, 0, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dq),
+  launch_sparse_fwd(q, at<int8_t>(ws, W.q8), p, nullptr, 0, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dq),
                     at<float>(ws, W.dk), at<float>(ws, W.dv), at<bf16_t>(ws, W.HZ), (const bf16_t*)proj_b,
                     phi_kind, true, out_l, true, nullptr, nullptr, nullptr, s);
   return launch_status();
@@ -492,18 +498,35 @@ int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int
   Problem p;
   int st = make_problem(B, H, N, d, 64, block_k, 1.0, 0.0, &p);
   if (st != SLA_OK) return st;
-  const Workspace W = make_workspace(p.BH, p.Tq, p.Tk, 1, 0);
+  const Workspace W = fwd_workspace(p, 1, 0);
   if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   run_stats(k, k, v, nullptr, p, ws, W, s);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), 0, true, false,
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), 0, true, false,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), nullptr, s);
   launch_unfragment_kv(p, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), k_codes, v_codes, s);
   const size_t bhd = (size_t)p.BH * D * 4;
   if (k_scale && hipMemcpyAsync(k_scale, at<float>(ws, W.dk), (size_t)p.BH * p.Tk * 4, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
   if (k_mean && hipMemcpyAsync(k_mean, at<float>(ws, W.mu_k), bhd, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
   if (v_scale && hipMemcpyAsync(v_scale, at<float>(ws, W.dv), bhd, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
+  return launch_status();
+}
+
+int sla_debug_quantize_q(const void* q, int B, int H, int N, int d, int block_q, int8_t* q_codes, float* q_scale,
+                         void* workspace, size_t workspace_bytes, sla_stream_t stream) {
+  if (!q) return SLA_ERR_NULL;
+  Problem p;
+  int st = make_problem(B, H, N, d, block_q, BK, 1.0, 0.0, &p);
+  if (st != SLA_OK) return st;
+  const Workspace W = fwd_workspace(p, 1, 0);
+  if ((st = check_ws(workspace, workspace_bytes, W.total)) != SLA_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  void* ws = workspace;
+  launch_pool_stats(q, q, q, p, at<float>(ws, W.qbar), at<float>(ws, W.kbar), at<float>(ws, W.dq),
+                    at<uint32_t>(ws, W.amax_v), at<int8_t>(ws, W.q8), s);
+  if (q_codes) launch_unpack_q8(p, at<int8_t>(ws, W.q8), q_codes, s);
+  if (q_scale && hipMemcpyAsync(q_scale, at<float>(ws, W.dq), (size_t)p.BH * p.Tq * 4, hipMemcpyDeviceToDevice, s) != hipSuccess) return SLA_ERR_HIP;
   return launch_status();
 }
 
@@ -622,7 +645,7 @@ int sla_attention_bwd_strided(const void* q, const void* k, const void* v, const
   if (dproj_b && !lin) launch_zero_u32((uint32_t*)dproj_b, (size_t)D, s);
   if (lin) {
     // H_i, Z_i of the forward pass (unprojected), then the linear branch's gradients
-    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
                    at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
     launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
     launch_bwd_wt((const bf16_t*)proj_w, at<bf16_t>(ws, X.wt), s);

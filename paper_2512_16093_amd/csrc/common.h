@@ -68,6 +68,21 @@ __device__ __forceinline__ int cvt_pk_e4m3(float a, float b, int old, bool hi) {
 __device__ __forceinline__ uint32_t int8_code_word(float x, float inv) {
   return __float_as_uint(__builtin_fmaf(x, inv, 12582912.0f));
 }
+// The same code with exact ties: 127 x / amax as a correctly rounded quotient (the product 127 x is exact for a
+// 16-bit x; one Newton step on the reciprocal's estimate, whose residual the fma forms exactly), so a value that
+// lies exactly half way between two codes reaches the rounding as the tie it is and goes to the even code --
+// with the multiply above the last bit of the reciprocal decides such values, and 16-bit inputs make them common
+// (x = amax / 2 is one).  ramax = 1 / amax (0 if amax is 0: all codes 0).
+__device__ __forceinline__ uint32_t int8_code_word_exact(float x, float amax, float ramax) {
+  const float y = x * 127.0f;
+  const float t0 = y * ramax;
+  const float r = __builtin_fmaf(-t0, amax, y);
+  const float t1 = __builtin_fmaf(r, ramax, t0);
+  return __float_as_uint(t1 + 12582912.0f);
+}
+// Where channel c's code sits in a row of the Q code tensor: the 64 bytes a lane half of the attention kernel
+// takes as its B operands are contiguous (lane half hf holds channels 32 s + 16 hf + 0..15 of step s = 0..3).
+__host__ __device__ inline int q8_byte_offset(int c) { return 64 * ((c >> 4) & 1) + 16 * (c >> 5) + (c & 15); }
 // The low bytes of four such words, first in the lowest byte.
 __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3) {
   return __builtin_amdgcn_perm(__builtin_amdgcn_perm(b3, b2, 0x0c0c0400u), __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u),
@@ -113,6 +128,7 @@ __device__ __forceinline__ int vfrag_offset(int key, int ch) {
 struct Workspace {
   size_t qbar, kbar;        // fp32 [BH,Tq,D], [BH,Tk,D] block means
   size_t dq;                // fp32 [BH,Tq]  per-query-block INT8 scale
+  size_t q8;                // int8 [BH, ceil(N/128)*128, D]: codes of Q, a row's 128 bytes in q8_byte_offset order
   size_t mu_k, amax_v, dv;  // fp32 [BH,D]   channel mean of K, max|V| (as uint bits), V scale
   size_t dk;                // fp32 [BH,Tk]  per-key-block INT8 scale
   size_t scores;            // fp32 [BH,Tq,Tk]
@@ -130,13 +146,15 @@ struct Workspace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, size_t n_m, size_t code_tensor_elems = 0) {
+inline Workspace make_workspace(size_t BH, size_t Tq, size_t Tk, size_t n_c, size_t n_m, size_t code_tensor_elems = 0,
+                                size_t q8_rows = 0) {
   Workspace w;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o = align256(o + bytes); return r; };
   w.qbar = take(BH * Tq * D * 4);
   w.kbar = take(BH * Tk * D * 4);
   w.dq = take(BH * Tq * 4);
+  w.q8 = take(BH * q8_rows * D);
   w.mu_k = take(BH * D * 4);
   w.amax_v = take(BH * D * 4);
   w.dv = take(BH * D * 4);
@@ -186,19 +204,19 @@ struct Problem {
 
 // Launchers (one per kernel file); every one only enqueues work on `stream`.
 void launch_pool_stats(const void* q, const void* k, const void* v, const Problem& p, float* qbar,
-                       float* kbar, float* dq, uint32_t* amax_v, hipStream_t stream);
+                       float* kbar, float* dq, uint32_t* amax_v, int8_t* q8, hipStream_t stream);
 void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,
                            float* dv, const bf16_t* proj_w, bf16_t* wfrag, hipStream_t stream);
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores, hipStream_t stream);
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
                    uint32_t* mbits, hipStream_t stream);
-void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
+void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv, const uint32_t* amax_v,
                     const bf16_t* wfrag, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream);
 void launch_marginal_bits(const Problem& p, const int8_t* mask, uint32_t* mbits, hipStream_t stream);
 void launch_lin_accumulate(const Problem& p, const uint32_t* mbits, const bf16_t* hz, bf16_t* HZ,
                            hipStream_t stream);
-void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
+void launch_sparse_fwd(const void* q, const int8_t* q8, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
                        const uint8_t* v8, const float* dq, const float* dk, const float* dv,
                        const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
                        void* out, bool out_f32, float* lse, int32_t* pair_list, int32_t* pair_len,
@@ -214,8 +232,8 @@ struct CodeScales { const float* dq; const float* dk; const void* q_lin; };
 int launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* v, const int32_t* crit,
                     const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, void* out, float* save_lse2, void* save_os,
                     const CodeScales* codes, hipStream_t stream);
-void launch_code_tensors(const void* q, const Problem& p, const int8_t* k8, const float* dq, bf16_t* qc, bf16_t* kc,
-                         hipStream_t stream);
+void launch_unpack_q8(const Problem& p, const int8_t* q8, int8_t* q_codes, hipStream_t stream);
+void launch_code_tensors(const Problem& p, const int8_t* q8, const int8_t* k8, bf16_t* qc, bf16_t* kc, hipStream_t stream);
 void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float* delta, hipStream_t stream);
 int launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);

@@ -20,8 +20,9 @@ __global__ void __launch_bounds__(256) pool_stats_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     int N, int block_q, int Tq, int Tk, int groups, int H, Layout lq, Layout lk, Layout lv,
     float* __restrict__ qbar, float* __restrict__ kbar, float* __restrict__ dq,
-    uint32_t* __restrict__ amax_v) {
+    uint32_t* __restrict__ amax_v, int8_t* __restrict__ q8) {
   __shared__ float sQ[16][2][D];
+  __shared__ float s_qmax[2];
   __shared__ float sK[16][2][D];
   __shared__ float sV[16][D];
   __shared__ float sQa[2][256];
@@ -34,11 +35,14 @@ __global__ void __launch_bounds__(256) pool_stats_kernel(
   const int row0 = g * 128;
 
   float qs[2][8] = {}, ks[2][8] = {}, va[8] = {}, qa[2] = {0.f, 0.f};
+  uint4 qkeep[8];  // this thread's Q values, kept for the codes (formed once the block maxima are known)
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
     const int row = row0 + rg + 16 * r, half = r >> 2;
+    qkeep[r] = make_uint4(0u, 0u, 0u, 0u);
     if (row < N) {
       const uint4 xq = *(const uint4*)(qs_ + row * lq.sn + cg * 8);
+      qkeep[r] = xq;
       const uint4 xk = *(const uint4*)(ks_ + row * lk.sn + cg * 8);
       const uint4 xv = *(const uint4*)(vs_ + row * lv.sn + cg * 8);
       const uint32_t wq[4] = {xq.x, xq.y, xq.z, xq.w}, wk[4] = {xk.x, xk.y, xk.z, xk.w},
@@ -108,11 +112,33 @@ __global__ void __launch_bounds__(256) pool_stats_kernel(
       if (block_q == 64) {
         if (cnt0 > 0) dq[(size_t)bh * Tq + 2 * g] = m0 > 0.f ? m0 / 127.0f : 1.0f;
         if (cnt1 > 0) dq[(size_t)bh * Tq + 2 * g + 1] = m1 > 0.f ? m1 / 127.0f : 1.0f;
+        s_qmax[0] = m0;
+        s_qmax[1] = m1;
       } else {
         const float m = fmaxf(m0, m1);
         dq[(size_t)bh * Tq + g] = m > 0.f ? m / 127.0f : 1.0f;
+        s_qmax[0] = s_qmax[1] = m;
       }
     }
+  }
+  // ---- INT8 codes of Q at the scale just found (max|Q block| / 127), ties exact: every row's 128 bytes in the
+  // order the attention kernel's lanes take them (q8_byte_offset); this thread: 8 adjacent bytes of 8 rows.
+  if (q8 == nullptr) return;  // (uniform)
+  __syncthreads();
+  int8_t* dst = q8 + ((size_t)(bh * groups + g) * 128) * D + q8_byte_offset(cg * 8);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int rl = rg + 16 * r;
+    if (row0 + rl >= N) continue;
+    const float amax = s_qmax[r >> 2], ramax = amax > 0.f ? 1.0f / amax : 0.f;
+    const uint32_t wq[4] = {qkeep[r].x, qkeep[r].y, qkeep[r].z, qkeep[r].w};
+    uint32_t c[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      c[2 * e] = int8_code_word_exact(bf16_lo(wq[e]), amax, ramax);
+      c[2 * e + 1] = int8_code_word_exact(bf16_hi(wq[e]), amax, ramax);
+    }
+    *(uint2*)(dst + (size_t)rl * D) = make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
   }
 }
 
@@ -326,14 +352,14 @@ void launch_zero_u32(uint32_t* p, size_t n, hipStream_t stream) {
 }
 
 void launch_pool_stats(const void* q, const void* k, const void* v, const Problem& p, float* qbar,
-                       float* kbar, float* dq, uint32_t* amax_v, hipStream_t stream) {
+                       float* kbar, float* dq, uint32_t* amax_v, int8_t* q8, hipStream_t stream) {
   const size_t n = (size_t)p.BH * D;
   zero_u32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(amax_v, n);
   const int groups = (p.N + 127) / 128;
   pool_stats_kernel<<<p.BH * groups, 256, 0, stream>>>((const bf16_t*)q, (const bf16_t*)k,
                                                         (const bf16_t*)v, p.N, p.block_q, p.Tq, p.Tk,
                                                         groups, p.H, p.lq, p.lk, p.lv, qbar, kbar, dq,
-                                                        amax_v);
+                                                        amax_v, q8);
 }
 
 void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* amax_v, float* mu_k,

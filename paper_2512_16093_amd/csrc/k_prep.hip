@@ -24,7 +24,8 @@ constexpr int STAGE_STRIDE = 2 * D + 16;  // bytes per staged hz row (padded aga
 template <int PHI>
 __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk, int H, Layout lk, Layout lv,
-    const float* __restrict__ mu_k, const float* __restrict__ dv, const bf16_t* __restrict__ wfrag,
+    const float* __restrict__ mu_k, const float* __restrict__ dv, const uint32_t* __restrict__ amax_v,
+    const bf16_t* __restrict__ wfrag,
     int want_quant, int want_linear, int8_t* __restrict__ k8, uint8_t* __restrict__ v8,
     float* __restrict__ dk, bf16_t* __restrict__ hz) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[128 * STAGE_STRIDE + 4 * D * 4];
@@ -63,17 +64,17 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
   }
 
   if (want_quant) {
-    float mu[8], dvc[8];
+    float mu[8], vmax[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       mu[e] = mu_k[(size_t)bh * D + cg * 8 + e];
-      dvc[e] = dv[(size_t)bh * D + cg * 8 + e];
+      vmax[e] = __uint_as_float(amax_v[(size_t)bh * D + cg * 8 + e]);  // max|V| of the channel (its scale is this / 448)
     }
-    float rdv[8];  // 1 / delta_V, refined to (almost always) the correctly rounded reciprocal
+    float rvm[8];  // 1 / max|V|, refined to (almost always) the correctly rounded reciprocal; 0 for an all-zero channel
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float r0 = __builtin_amdgcn_rcpf(dvc[e]);
-      rdv[e] = __builtin_fmaf(__builtin_fmaf(-dvc[e], r0, 1.0f), r0, r0);
+      const float r0 = __builtin_amdgcn_rcpf(vmax[e]);
+      rvm[e] = vmax[e] > 0.f ? __builtin_fmaf(__builtin_fmaf(-vmax[e], r0, 1.0f), r0, r0) : 0.f;
     }
     float kt[4][8], amax = 0.f;
 #pragma unroll
@@ -111,12 +112,14 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
       float x[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        // quotient by reciprocal + one correction step: the correctly rounded v / delta_V for the
-        // magnitudes that occur here, at a third of the cost of the general division sequence
+        // v / delta_V = 448 v / max|V|: the product 448 v is exact for a 16-bit v, and reciprocal + one
+        // correction step (the fma forms the residual exactly) gives the correctly rounded quotient, so a
+        // value exactly half way between two FP8 values reaches the conversion as the tie it is -- at a
+        // third of the cost of the general division sequence
         const uint32_t word = (e >> 1) == 0 ? vraw[r].x : (e >> 1) == 1 ? vraw[r].y : (e >> 1) == 2 ? vraw[r].z : vraw[r].w;
-        const float vf = (e & 1) ? bf16_hi(word) : bf16_lo(word);
-        float qv = vf * rdv[e];
-        qv = __builtin_fmaf(__builtin_fmaf(-qv, dvc[e], vf), rdv[e], qv);
+        const float vf = ((e & 1) ? bf16_hi(word) : bf16_lo(word)) * E4M3_MAX;
+        float qv = vf * rvm[e];
+        qv = __builtin_fmaf(__builtin_fmaf(-qv, vmax[e], vf), rvm[e], qv);
         x[r] = clamp_e4m3(qv);
       }
       int code = cvt_pk_e4m3(x[0], x[1], 0, false);
@@ -258,24 +261,29 @@ __global__ void unfragment_kv_kernel(const int8_t* __restrict__ k8, const uint8_
   }
 }
 
+__global__ void unpack_q8_kernel(const int8_t* __restrict__ q8, int N, int q8_rows, size_t total, int8_t* __restrict__ q_codes) {
+  const size_t x = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (x >= total) return;
+  const int ch = (int)(x % D);
+  const size_t row = (x / D) % N, bh = x / ((size_t)D * N);
+  q_codes[x] = q8[(bh * q8_rows + row) * D + q8_byte_offset(ch)];
+}
+
 // SLA_QUANT_QK_INT8: the INT8 codes of Q and of the smoothed K as bf16 numbers (integers up to 127
 // are exact in bf16), [BH, N, D] contiguous, for the 16-bit attention kernel: its products of such
 // operands are the integer products, exactly (|sum| < 2^24 in the fp32 accumulator).
 // One workgroup per key block; the same for the query rows it covers.
-__global__ void __launch_bounds__(256) code_tensors_kernel(const bf16_t* __restrict__ q, const int8_t* __restrict__ k8,
-                                                           const float* __restrict__ dq, int N, int Tk, int H, int block_q, int Tq,
-                                                           Layout lq, bf16_t* __restrict__ qc, bf16_t* __restrict__ kc) {
-  const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk, b = bh / H, h = bh - b * H;
+__global__ void __launch_bounds__(256) code_tensors_kernel(const int8_t* __restrict__ q8, const int8_t* __restrict__ k8,
+                                                           int N, int Tk, int q8_rows, bf16_t* __restrict__ qc,
+                                                           bf16_t* __restrict__ kc) {
+  const int bh = blockIdx.x / Tk, j = blockIdx.x % Tk;
   const size_t rec = ((size_t)bh * Tk + j) * KV_FRAG_BYTES;
   for (int e = threadIdx.x; e < BK * D; e += 256) {
     const int key = e / D, ch = e % D, row = j * BK + key;
     if (row >= N) continue;
     const size_t o = ((size_t)bh * N + row) * D + ch;
     kc[o] = f32_to_bf16((float)k8[rec + kfrag_offset(key, ch)]);
-    // the query's code, decided exactly as the low-bit kernel decides it
-    const float dqi = dq[(size_t)bh * Tq + row / block_q];
-    const float x = bf16_to_f32(q[b * lq.sb + h * lq.sh + (long long)row * lq.sn + ch]);
-    qc[o] = f32_to_bf16((float)(int8_t)(int8_code_word(x, 1.0f / dqi) & 0xffu));
+    qc[o] = f32_to_bf16((float)q8[((size_t)bh * q8_rows + row) * D + q8_byte_offset(ch)]);  // the low-bit kernel's own codes
   }
 }
 
@@ -284,18 +292,18 @@ __global__ void e4m3_encode_kernel(const float* __restrict__ in, uint8_t* __rest
   if (i < n) out[i] = (uint8_t)(cvt_pk_e4m3(clamp_e4m3(in[i]), 0.f, 0, false) & 0xff);
 }
 
-void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv,
+void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv, const uint32_t* amax_v,
                     const bf16_t* wfrag, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream) {
   const unsigned grid = (unsigned)(p.BH * p.Tk);
   const bf16_t* kk = (const bf16_t*)k;
   const bf16_t* vv = (const bf16_t*)v;
   if (phi_kind == 0)
-    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, wfrag, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
   else if (phi_kind == 1)
-    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, wfrag, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
   else
-    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, wfrag, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
 }
 
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
@@ -303,9 +311,13 @@ void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8,
   unfragment_kv_kernel<<<p.BH * p.Tk, 256, 0, stream>>>(k8, v8, p.N, p.Tk, k_codes, v_codes);
 }
 
-void launch_code_tensors(const void* q, const Problem& p, const int8_t* k8, const float* dq, bf16_t* qc, bf16_t* kc,
-                         hipStream_t stream) {
-  code_tensors_kernel<<<p.BH * p.Tk, 256, 0, stream>>>((const bf16_t*)q, k8, dq, p.N, p.Tk, p.H, p.block_q, p.Tq, p.lq, qc, kc);
+void launch_unpack_q8(const Problem& p, const int8_t* q8, int8_t* q_codes, hipStream_t stream) {
+  const size_t total = (size_t)p.BH * p.N * D;
+  unpack_q8_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(q8, p.N, (p.N + 127) / 128 * 128, total, q_codes);
+}
+
+void launch_code_tensors(const Problem& p, const int8_t* q8, const int8_t* k8, bf16_t* qc, bf16_t* kc, hipStream_t stream) {
+  code_tensors_kernel<<<p.BH * p.Tk, 256, 0, stream>>>(q8, k8, p.N, p.Tk, (p.N + 127) / 128 * 128, qc, kc);
 }
 
 void launch_e4m3_encode(const float* in, uint8_t* out, size_t n, hipStream_t stream) {

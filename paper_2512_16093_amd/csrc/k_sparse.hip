@@ -32,6 +32,7 @@ namespace sla {
 
 struct SparseDims {
   int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32, H;
+  int q8_rows;       // rows per (b,h) of the Q code tensor (N rounded up to whole groups of 128)
   int TqW, ustride;  // workgroup tiles per (b,h); entries per row of the paired lists (see PAIRED)
   Layout lq, lo;  // of q and out
 };
@@ -40,6 +41,7 @@ struct SparseDims {
 // fetch them through the scalar unit.
 struct SparseArgs {
   const bf16_t* __restrict__ q;
+  const int8_t* __restrict__ q8;
   const int32_t* __restrict__ crit;
   const int8_t* __restrict__ k8;
   const uint8_t* __restrict__ v8;
@@ -52,7 +54,7 @@ struct SparseArgs {
   float* __restrict__ lse;
   int N, Tq, Tk, n_c, total, per_xcd, phi, has_lin, out_f32, H;
   Layout lq, lo;
-  int TqW, ustride;
+  int TqW, ustride, q8_rows;
   const int32_t* __restrict__ ulen;
 };
 
@@ -228,14 +230,14 @@ __device__ __forceinline__ void stage_barrier() {
 // what it computed: zero codes contribute nothing, the reference level is put back.
 template <int NW, bool PAIRED>
 __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
-    const bf16_t* __restrict__ q_, const int32_t* __restrict__ crit_, const int8_t* __restrict__ k8_,
+    const bf16_t* __restrict__ q_, const int8_t* __restrict__ q8_, const int32_t* __restrict__ crit_, const int8_t* __restrict__ k8_,
     const uint8_t* __restrict__ v8_, const float* __restrict__ dq_, const float* __restrict__ dk_,
     const float* __restrict__ dv_, const bf16_t* __restrict__ HZ_, const bf16_t* __restrict__ bias_,
     void* __restrict__ out_, float* __restrict__ lse_, const int32_t* __restrict__ ulen_, const SparseDims dims) {
   static_assert(!PAIRED || NW == 4, "paired mode: four wavefronts, two per query block of 64");
-  const SparseArgs A = {q_, crit_, k8_, v8_, dq_, dk_, dv_, HZ_, bias_, out_, lse_, dims.N, dims.Tq, dims.Tk,
+  const SparseArgs A = {q_, q8_, crit_, k8_, v8_, dq_, dk_, dv_, HZ_, bias_, out_, lse_, dims.N, dims.Tq, dims.Tk,
                         dims.n_c, dims.total, dims.per_xcd, dims.phi, dims.has_lin, dims.out_f32, dims.H,
-                        dims.lq, dims.lo, dims.TqW, dims.ustride, ulen_};
+                        dims.lq, dims.lo, dims.TqW, dims.ustride, dims.q8_rows, ulen_};
   constexpr int NT = NW * 64;
   constexpr int CH = 2 * (KV_FRAG_BYTES / 16) / NT;  // 16-byte chunks per thread per block
   constexpr int BQ = NW * 32;
@@ -268,31 +270,15 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
   const int b_ = __builtin_amdgcn_readfirstlane(bh / A.H), h_ = bh - b_ * A.H;
   const bf16_t* qptr = A.q + b_ * A.lq.sb + h_ * A.lq.sh + (qok ? qrow : 0) * A.lq.sn;
 
-  // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each).  The rows are
-  // requested here; the codes are formed behind the first K/V copies (below), under their latency.
+  // ---- Q block -> INT8 B operands (4 steps of 32 channels; this lane: 16 of each): the codes were made
+  // with the block statistics (exact ties, see int8_code_word_exact); a lane half's 64 bytes are contiguous.
   const float dqi = A.dq[(size_t)rowid];
-  uint4 qraw[8];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    qraw[2 * s] = qraw[2 * s + 1] = make_uint4(0, 0, 0, 0);
-    if (qok) {
-      qraw[2 * s] = ((const uint4*)(qptr + 32 * s + 16 * hf))[0];
-      qraw[2 * s + 1] = ((const uint4*)(qptr + 32 * s + 16 * hf))[1];
-    }
-  }
   v4i q8[4];
-  auto quantise_q = [&]() {
-    const float inv = 1.0f / dqi;
+  {
+    const v4i* src = (const v4i*)(A.q8 + ((size_t)bh * A.q8_rows + (qok ? qrow : 0)) * D + 64 * hf);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const uint32_t wq[8] = {qraw[2 * s].x, qraw[2 * s].y, qraw[2 * s].z, qraw[2 * s].w,
-                              qraw[2 * s + 1].x, qraw[2 * s + 1].y, qraw[2 * s + 1].z, qraw[2 * s + 1].w};
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        q8[s][g] = (int)pack_low_bytes(int8_code_word(bf16_lo(wq[2 * g]), inv), int8_code_word(bf16_hi(wq[2 * g]), inv),
-                                       int8_code_word(bf16_lo(wq[2 * g + 1]), inv), int8_code_word(bf16_hi(wq[2 * g + 1]), inv));
-    }
-  };
+    for (int s = 0; s < 4; ++s) q8[s] = qok ? src[s] : v4i{0, 0, 0, 0};
+  }
   const float cq = dqi * (LOG2E / 11.313708498984761f) * 67108864.f;  // log2(e) / sqrt(d) * delta_Q * 2^26 (see BIAS_I)
 
   v16f acc[4], accl = v16f{};
@@ -547,12 +533,6 @@ __global__ void __launch_bounds__(NW * 64, 2) sparse_fwd_kernel(
     fetch_rec(v8_bh, j0, vst0);
     fetch_rec(k8_bh, j3, kst3);
     fetch_rec(v8_bh, j1, vst1);
-    {  // (the codes are formed from here on: behind the copies just issued)
-      uint32_t anchor = qraw[0].x;
-      asm volatile("" : "+v"(anchor));
-      qraw[0].x = anchor;
-    }
-    quantise_q();
     __builtin_amdgcn_s_waitcnt(WAIT_KEEP2);  // K(0), K(1) have landed
     stage_barrier();
     read4(kst0, lane, 0, kfA);
@@ -797,7 +777,7 @@ __global__ void __launch_bounds__(256) pair_union_kernel(const int32_t* __restri
   if (t == 255) ulen[row] = base + incl;
 }
 
-void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
+void launch_sparse_fwd(const void* q, const int8_t* q8, const Problem& p, const int32_t* crit, int n_c, const int8_t* k8,
                        const uint8_t* v8, const float* dq, const float* dk, const float* dv,
                        const bf16_t* HZ, const bf16_t* proj_b, int phi_kind, bool has_linear,
                        void* out, bool out_f32, float* lse, int32_t* pair_list, int32_t* pair_len,
@@ -812,6 +792,7 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
   dm.has_lin = has_linear ? 1 : 0;
   dm.out_f32 = out_f32 ? 1 : 0;
   dm.H = p.H;
+  dm.q8_rows = (p.N + 127) / 128 * 128;
   dm.lq = p.lq;
   dm.lo = p.lo;
   const bool paired = p.block_q == 64 && n_c > 0 && pair_list && pair_len;
@@ -823,13 +804,13 @@ void launch_sparse_fwd(const void* q, const Problem& p, const int32_t* crit, int
   if (paired) {
     pair_union_kernel<<<(unsigned)(p.BH * dm.TqW), 256, 0, stream>>>(crit, p.Tq, n_c, dm.TqW, dm.ustride, pair_list,
                                                                      pair_len);
-    sparse_fwd_kernel<4, true><<<grid, 256, 0, stream>>>((const bf16_t*)q, pair_list, k8, v8, dq, dk, dv, HZ, bias, out,
+    sparse_fwd_kernel<4, true><<<grid, 256, 0, stream>>>((const bf16_t*)q, q8, pair_list, k8, v8, dq, dk, dv, HZ, bias, out,
                                                          lse, pair_len, dm);
   } else if (p.block_q == 128) {
-    sparse_fwd_kernel<4, false><<<grid, 256, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse,
+    sparse_fwd_kernel<4, false><<<grid, 256, 0, stream>>>((const bf16_t*)q, q8, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse,
                                                           nullptr, dm);
   } else {
-    sparse_fwd_kernel<2, false><<<grid, 128, 0, stream>>>((const bf16_t*)q, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse,
+    sparse_fwd_kernel<2, false><<<grid, 128, 0, stream>>>((const bf16_t*)q, q8, crit, k8, v8, dq, dk, dv, HZ, bias, out, lse,
                                                           nullptr, dm);
   }
 }

@@ -61,13 +61,17 @@ def test_quantised_operands_match_oracle(case):
         assert np.abs(km[0, h] - mu).max() < 2e-6
         assert np.allclose(ks[0, h], dk, rtol=1e-5)
         assert np.allclose(vs[0, h], dv, rtol=1e-6)
-        # codes are decided in fp32 on the GPU and fp64 here: equal except at rounding ties
+        # K codes: the smoothed K is formed in fp32 on the GPU and in fp64 here, so a code may differ where
+        # the two differences fall on either side of a rounding boundary (about one code in 10^5)
         dkc = kc[0, h].astype(np.float64) - K8
-        assert np.abs(dkc).max() <= 1 and (dkc != 0).mean() < 1e-3
-        Vg = formats.e4m3_decode(vc[0, h])
-        differs = Vg != V8
-        assert differs.mean() < 1e-3
-        assert (np.abs(Vg - V8)[differs] <= 2.0 ** -3 * np.abs(V8)[differs] + 2.0 ** -9).all()
+        assert np.abs(dkc).max() <= 1 and (dkc != 0).mean() < 1e-4
+        # V and Q are quantised from the 16-bit inputs themselves: the same codes, exact ties included
+        assert np.array_equal(formats.e4m3_decode(vc[0, h]), V8)
+    qc, qs = (t.cpu().numpy() for t in sla.sla_debug_quantize_q(q.cuda(), cfg.block_q))
+    for h in range(cfg.H):
+        Q8, dq = so.quantize_q(synth.as_f64(q[0, h]), cfg.block_q)
+        assert np.allclose(qs[0, h], dq, rtol=1e-6)
+        assert np.array_equal(qc[0, h].astype(np.float64), Q8)
 
 
 @pytest.mark.parametrize("case", [None] + RAGGED)

@@ -263,6 +263,8 @@ def test_stage_entry_points_argument_errors():
     assert L.sla_linear_attn_fwd(FAKE, FAKE, FAKE, FAKE, None, None, 0, FAKE, 1, 2, 1024, 128, 64, 64,
                                  None, big, None) == sla.ERR_WORKSPACE
     assert L.sla_debug_e4m3_encode(None, FAKE, 4, None) == sla.ERR_NULL
+    assert L.sla_debug_quantize_q(None, 1, 2, 1024, 128, 64, None, None, WS, big, None) == sla.ERR_NULL
+    assert L.sla_debug_quantize_q(FAKE, 1, 2, 1024, 128, 96, None, None, WS, big, None) == sla.ERR_BLOCK
     ops = ctypes.c_double(0.0)
     assert L.sla_calibrate_mfma(0, 10, None, big, ctypes.byref(ops), None) == sla.ERR_NULL
     assert L.sla_calibrate_mfma(0, 10, WS, big, None, None) == sla.ERR_NULL
