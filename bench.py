@@ -471,7 +471,7 @@ def main():
     bhnd = float(cfg.B * cfg.H) * cfg.N * cfg.d
     hz_row = 129 * 128 * 2.0                      # one block summary: 128 x 128 + 128 bf16 values
     stage_bytes = {
-        "pool_stats": 6.0 * bhnd,                                                  # Q, K, V read once (bf16)
+        "pool_stats": 6.0 * bhnd + (1.0 * bhnd if args.quant != "none" else 0.0),  # Q, K, V read once (bf16); Q codes written
         "prep_kv": 4.0 * bhnd + (2.0 * bhnd if low_bit else 0.0) + (cfg.B * cfg.H * Tk * hz_row if n_m > 0 else 0.0),
         "lin_accumulate": cfg.B * cfg.H * (Tk + Tq) * hz_row if n_m > 0 else 0.0,  # summaries in once, sums out once
     }
