@@ -30,7 +30,7 @@ PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
 PEAK_MFMA_8BIT_TOPS = 5000.0   # MI355X dense INT8 (POP/s) and FP8 (PFLOP/s) MFMA peak, both 5.0e15
 # Bytes moved past L2 per launch of the sparse kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # from a 1 GiB copy in the same counter runs), by config id; source: profiles/sla_fwd_wan14b-720p.md.
-SPARSE_TRAFFIC_BYTES = {4: 18.51e9}
+SPARSE_TRAFFIC_BYTES = {4: 18.11e9}
 
 
 # Linear layers of a Wan2.1-14B DiT block (hidden 5120, feed-forward 13824) on the 75600 tokens of a
@@ -40,9 +40,9 @@ W8A8_SHAPES = {"attn_proj": (75600, 5120, 5120), "ffn_up": (75600, 5120, 13824),
 
 # Bytes moved past L2 per launch of the product kernel (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0), by shape;
 # source: profiles/w8a8_linear_wan14b.md.
-W8A8_TRAFFIC_BYTES = {"attn_proj": 5.42e9}
+W8A8_TRAFFIC_BYTES = {"attn_proj": 5.30e9}
 # The backward pass's dominant kernel, by (config, kernel); source: profiles/sla_bwd_wan14b-720p.md.
-BWD_TRAFFIC_BYTES = {(4, "bwd_dkv_kernel"): 163.6e9}
+BWD_TRAFFIC_BYTES = {(4, "bwd_dkv_kernel"): 163.7e9}
 
 
 def parse():
@@ -71,6 +71,23 @@ def parse():
                     help="also run a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB) a few times, so that "
                          "FETCH_SIZE / WRITE_SIZE counter runs of this command can be scaled by a kernel of known traffic")
     return ap.parse_args()
+
+
+def traffic_from_profile(name, cfg_id):
+    """HBM bytes per launch of the dominant kernel as the committed rocprofv3 summary of this command states them
+    (profiles/<name>: the line that ends in "per launch (the `roofline.traffic` of the bench line)"); the typed-in
+    constant above is used if the file cannot be read, None for configs the summary does not cover."""
+    import re
+    if cfg_id != 4:
+        return None, None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", name)
+    try:
+        m = re.search(r"= ([0-9.]+) GB per launch \(the `roofline.traffic`", open(path).read())
+        if m:
+            return float(m.group(1)) * 1e9, "profiles/%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)" % name
+    except OSError:
+        pass
+    return None, None
 
 
 def copy_calibration(torch, dev):
@@ -354,7 +371,8 @@ def main_bwd(args):
         "stage_ms": dict(zip(BWD_STAGE_NAMES, [round(x, 4) for x in stage_ms])),
         "roofline": {"kernel": kname, "bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_MFMA_BF16_TFLOPS,
-                     "traffic": BWD_TRAFFIC_BYTES.get((cfg.cfg_id, kname)), "traffic_unit": "bytes per launch",
+                     "traffic": (traffic_from_profile("sla_bwd_wan14b-720p.md", cfg.cfg_id)[0] if kname == "bwd_dkv_kernel" else None)
+                                or BWD_TRAFFIC_BYTES.get((cfg.cfg_id, kname)), "traffic_unit": "bytes per launch",
                      "launch_ms": t_dom, "ops_per_launch": ops},
         "context": "the paper reports no number for its finetuning stage",
     }
@@ -487,6 +505,9 @@ def main():
     t_sparse = stage_mean[4] * 1e-3           # the roofline takes the kernel's AVERAGE launch duration
     achieved = ops / t_sparse / 1e12
     peak = PEAK_MFMA_8BIT_TOPS if low_bit else PEAK_MFMA_BF16_TFLOPS
+    traffic, traffic_src = traffic_from_profile("sla_fwd_wan14b-720p.md", cfg.cfg_id)
+    if traffic is None and cfg.cfg_id in SPARSE_TRAFFIC_BYTES:
+        traffic, traffic_src = SPARSE_TRAFFIC_BYTES[cfg.cfg_id], "constant in bench.py (from the same summary)"
     result = {
         "metric": "sla_fwd_dense_equiv_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ms_per_step_kind": "median of the timed calls (HIP events)",
@@ -505,9 +526,8 @@ def main():
         "stage_hbm": stage_hbm,
         "roofline": {"kernel": "sparse_fwd_kernel" if low_bit else "bwd_stats_kernel<NW, true> (bf16 forward)",
                      "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": SPARSE_TRAFFIC_BYTES.get(cfg.cfg_id) if low_bit else None, "traffic_unit": "bytes per launch",
-                     "traffic_source": "profiles/sla_fwd_wan14b-720p.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)"
-                                       if low_bit and cfg.cfg_id in SPARSE_TRAFFIC_BYTES else None,
+                     "traffic": traffic if low_bit else None, "traffic_unit": "bytes per launch",
+                     "traffic_source": traffic_src if low_bit else None,
                      "launch_ms": stage_mean[4], "launch_ms_median": stage_ms[4], "ops_per_launch": ops},
         "context": "paper: 100-200x end-to-end, 184 s -> 1.9 s on one RTX 5090 (whole pipeline; no kernel-level number)",
     }
