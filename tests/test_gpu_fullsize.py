@@ -187,3 +187,18 @@ def test_named_config_backward_sampled_parity(cfg_id, head):
             worst = max(worst, fro)
             assert err <= 3e-2 and fro <= 1e-2 and cos >= 0.999, (cfg.name, name, i, err, fro, cos)
     print("%s backward: worst sampled relative Frobenius error %.3e" % (cfg.name, worst))
+
+
+def test_longest_sequence_the_library_accepts():
+    """N = 8192 key blocks of 64 (the stated limit: one more token is SLA_ERR_SHAPE), one head: the widest
+    instantiation of the selection kernel (128 scores per lane), 4096 query blocks per head in the attention
+    kernel's XCD split, 11 chunks of the marginal accumulation.  Masks on every row, outputs on the first,
+    middle and last query block."""
+    cfg = synth.custom_config(1, 1, (32, 128, 128), block_q=128, topk_ratio=0.02, marginal_ratio=0.05, cfg_id=800,
+                              name="longest")
+    assert cfg.N == 8192 * 64
+    assert sla.sla_workspace_bytes(1, 1, cfg.N + 1, cfg.d, 128, 64, 0.02, 0.05) == 0
+    q, k, v, W, out, mask = _forward_and_mask(cfg)
+    print("oracle on head 0", flush=True)
+    worst, cmin, nbad = _check_head(cfg, q, k, v, W, out, mask, 0, _edge_blocks(cfg))
+    print("%s: sampled max-abs %.3e, min cosine %.6f, tie-excused mask entries %d" % (cfg.name, worst, cmin, nbad))
