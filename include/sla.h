@@ -17,7 +17,10 @@
  *      its critical blocks, in one pass in ascending j.  K is smoothed (channel
  *      mean over all N tokens removed) and quantised to INT8 with one scale per
  *      key block, Q to INT8 with one scale per query block, V to FP8 E4M3 with
- *      one scale per channel.  With t = log2(e) * (Q8.K8) dq dk / sqrt(d) the
+ *      one scale per channel: scale = max|.| / 127 (INT8) or / 448 (FP8), code =
+ *      value / scale rounded to nearest with ties to even -- the quotient taken
+ *      as 127 x / max (448 v / max), so that a 16-bit value lying exactly between
+ *      two codes is rounded as the tie it is.  With t = log2(e) * (Q8.K8) dq dk / sqrt(d) the
  *      base-2 logit (the integer product is exact), each query keeps a reference
  *      level r, an INTEGER: after every run of 32 keys r = max(r, ceil(largest t
  *      of the run)).  The weights of the run are P = 448 * 2^(t - r), at most 448,

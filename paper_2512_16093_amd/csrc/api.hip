@@ -153,7 +153,7 @@ int fwd_bf16(const void* q, const void* k, const void* v, void* out, const Probl
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
   if (lin || codes16)
-    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, codes16, lin,
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, codes16, lin,
                    at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   if (codes16)
     launch_code_tensors(p, at<int8_t>(ws, W.q8), at<int8_t>(ws, W.k8), at<bf16_t>(ws, W.qc), at<bf16_t>(ws, W.kc), s);
@@ -182,7 +182,7 @@ void run_prepass(const void* q, const void* k, const void* v, const void* proj_w
   launch_select(p, at<float>(ws, W.scores), nullptr, at<int32_t>(ws, W.crit), nullptr,
                 lin ? at<uint32_t>(ws, W.m0) : nullptr, s);
   mark(s, rec, 2);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, true, lin,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
   mark(s, rec, 3);
   if (lin) launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
@@ -440,7 +440,7 @@ int sla_sparse_attn_fwd(const void* q, const void* k, const void* v, const int32
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   run_stats(q, k, v, nullptr, p, ws, Wmin, s, true);
-  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<float>(ws, Wmin.dv), at<uint32_t>(ws, Wmin.amax_v), at<bf16_t>(ws, Wmin.wfrag), 0, true,
+  launch_prep_kv(k, v, p, at<float>(ws, Wmin.mu_k), at<uint32_t>(ws, Wmin.amax_v), at<bf16_t>(ws, Wmin.wfrag), 0, true,
                  false, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8), at<float>(ws, Wmin.dk), nullptr, s);
   launch_sparse_fwd(q, at<int8_t>(ws, Wmin.q8), p, crit_idx, n_crit, at<int8_t>(ws, Wmin.k8), at<uint8_t>(ws, Wmin.v8),
                     at<float>(ws, Wmin.dq), at<float>(ws, Wmin.dk), at<float>(ws, Wmin.dv), nullptr, nullptr, 0,
@@ -462,7 +462,7 @@ int sla_linear_attn_fwd(const void* q, const void* k, const void* v, const int8_
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   run_stats(q, k, v, proj_w, p, ws, W, s, true);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, false, true, nullptr,
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, false, true, nullptr,
                  nullptr, nullptr, at<bf16_t>(ws, W.hz), s);
   launch_marginal_bits(p, mask, at<uint32_t>(ws, W.m0), s);
   launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
@@ -503,7 +503,7 @@ int sla_debug_quantize_kv(const void* k, const void* v, int B, int H, int N, int
   hipStream_t s = (hipStream_t)stream;
   void* ws = workspace;
   run_stats(k, k, v, nullptr, p, ws, W, s);
-  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), 0, true, false,
+  launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), 0, true, false,
                  at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), nullptr, s);
   launch_unfragment_kv(p, at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), k_codes, v_codes, s);
   const size_t bhd = (size_t)p.BH * D * 4;
@@ -645,7 +645,7 @@ int sla_attention_bwd_strided(const void* q, const void* k, const void* v, const
   if (dproj_b && !lin) launch_zero_u32((uint32_t*)dproj_b, (size_t)D, s);
   if (lin) {
     // H_i, Z_i of the forward pass (unprojected), then the linear branch's gradients
-    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<float>(ws, W.dv), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
+    launch_prep_kv(k, v, p, at<float>(ws, W.mu_k), at<uint32_t>(ws, W.amax_v), at<bf16_t>(ws, W.wfrag), phi_kind, false, true,
                    at<int8_t>(ws, W.k8), at<uint8_t>(ws, W.v8), at<float>(ws, W.dk), at<bf16_t>(ws, W.hz), s);
     launch_lin_accumulate(p, at<uint32_t>(ws, W.m0), at<bf16_t>(ws, W.hz), at<bf16_t>(ws, W.HZ), s);
     launch_bwd_wt((const bf16_t*)proj_w, at<bf16_t>(ws, X.wt), s);

@@ -210,7 +210,7 @@ void launch_finalize_stats(const Problem& p, const float* kbar, const uint32_t* 
 void launch_scores(const Problem& p, const float* qbar, const float* kbar, float* scores, hipStream_t stream);
 void launch_select(const Problem& p, const float* scores, int8_t* mask, int32_t* crit, int32_t* marg,
                    uint32_t* mbits, hipStream_t stream);
-void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv, const uint32_t* amax_v,
+void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const uint32_t* amax_v,
                     const bf16_t* wfrag, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream);
 void launch_marginal_bits(const Problem& p, const int8_t* mask, uint32_t* mbits, hipStream_t stream);

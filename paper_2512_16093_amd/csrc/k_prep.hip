@@ -24,7 +24,7 @@ constexpr int STAGE_STRIDE = 2 * D + 16;  // bytes per staged hz row (padded aga
 template <int PHI>
 __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int N, int Tk, int H, Layout lk, Layout lv,
-    const float* __restrict__ mu_k, const float* __restrict__ dv, const uint32_t* __restrict__ amax_v,
+    const float* __restrict__ mu_k, const uint32_t* __restrict__ amax_v,
     const bf16_t* __restrict__ wfrag,
     int want_quant, int want_linear, int8_t* __restrict__ k8, uint8_t* __restrict__ v8,
     float* __restrict__ dk, bf16_t* __restrict__ hz) {
@@ -292,18 +292,18 @@ __global__ void e4m3_encode_kernel(const float* __restrict__ in, uint8_t* __rest
   if (i < n) out[i] = (uint8_t)(cvt_pk_e4m3(clamp_e4m3(in[i]), 0.f, 0, false) & 0xff);
 }
 
-void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const float* dv, const uint32_t* amax_v,
+void launch_prep_kv(const void* k, const void* v, const Problem& p, const float* mu_k, const uint32_t* amax_v,
                     const bf16_t* wfrag, int phi_kind, bool want_quant, bool want_linear, int8_t* k8,
                     uint8_t* v8, float* dk, bf16_t* hz, hipStream_t stream) {
   const unsigned grid = (unsigned)(p.BH * p.Tk);
   const bf16_t* kk = (const bf16_t*)k;
   const bf16_t* vv = (const bf16_t*)v;
   if (phi_kind == 0)
-    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<0><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
   else if (phi_kind == 1)
-    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<1><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
   else
-    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, dv, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
+    prep_kv_kernel<2><<<grid, 256, 0, stream>>>(kk, vv, p.N, p.Tk, p.H, p.lk, p.lv, mu_k, amax_v, wfrag, want_quant, want_linear, k8, v8, dk, hz);
 }
 
 void launch_unfragment_kv(const Problem& p, const int8_t* k8, const uint8_t* v8, int8_t* k_codes,
