@@ -17,10 +17,10 @@ import parity_util as pu
 pytestmark = pytest.mark.gpu
 
 
-def _forward_and_mask(cfg):
-    print("config", cfg.name, "generating inputs", flush=True)
-    q, k, v = pu.make_qkv_threaded(cfg)
-    W = synth.make_proj(cfg)
+def _forward_and_mask(cfg, seed=0):
+    print("config", cfg.name, "seed", seed, "generating inputs", flush=True)
+    q, k, v = pu.make_qkv_threaded(cfg, seed=seed)
+    W = synth.make_proj(cfg, seed=seed)
     qd, kd, vd = pu.to_dev(q, k, v)
     Wd = None if W is None else W.cuda()
     print("running GPU forward", flush=True)
@@ -61,10 +61,12 @@ def _edge_blocks(cfg):
     return sorted(b for b in blocks if 0 <= b < Tq)
 
 
-@pytest.mark.parametrize("cfg_id,heads", [(1, (0, 11)), (2, (5,)), (3, (0, 20, 39)), (5, (3,)), (6, (21,))])
-def test_named_config_sampled_parity(cfg_id, heads):
+# (config, heads checked, seed): every named config with seed 0; two more seeds on the 480P shapes
+@pytest.mark.parametrize("cfg_id,heads,seed", [(1, (0, 11), 0), (2, (5,), 0), (3, (0, 20, 39), 0), (5, (3,), 0), (6, (21,), 0),
+                                               (1, (7,), 1), (3, (33,), 2)])
+def test_named_config_sampled_parity(cfg_id, heads, seed):
     cfg = synth.CONFIGS[cfg_id]
-    q, k, v, W, out, mask = _forward_and_mask(cfg)
+    q, k, v, W, out, mask = _forward_and_mask(cfg, seed)
     worst, cmin, nbad = 0.0, 1.0, 0
     for h in heads:
         print("oracle on head", h, flush=True)
