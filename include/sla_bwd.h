@@ -72,7 +72,11 @@ int sla_attention_bwd(const void* q, const void* k, const void* v, const void* d
  * formed from the bf16 O^s, a difference far below the tolerance of the result).
  *   saved   device, 256-byte aligned, sla_saved_bytes(...) bytes; opaque; written by the forward
  *           entry point, read by the backward one; NULL in sla_attention_bwd_saved = recompute
- *           (exactly sla_attention_bwd). */
+ *           (exactly sla_attention_bwd).  The buffer starts with a record of the problem it was
+ *           filled for (B, H, N, block_q, critical blocks per row).  The backward pass checks it ON
+ *           THE DEVICE (the host cannot read it without synchronising): a buffer that was not filled
+ *           for the same problem makes every gradient NaN instead of plausibly wrong; the call
+ *           itself still returns SLA_OK. */
 size_t sla_saved_bytes(int B, int H, int N, int d, int block_q);
 
 int sla_attention_fwd_train(const void* q, const void* k, const void* v, void* out, int B, int H, int N, int d,

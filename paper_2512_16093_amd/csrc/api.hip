@@ -197,17 +197,23 @@ void run_attend(const void* q, void* out, const void* proj_b, const Problem& p, 
                     at<int32_t>(ws, W.pair_len), s);
 }
 
-// What sla_attention_fwd_train hands to sla_attention_bwd_saved: the rows' base-2 log-sum-exp
-// (fp32, padded to whole query blocks), then O^s (bf16 [BH, N, D]).
+// What sla_attention_fwd_train hands to sla_attention_bwd_saved: a header naming the problem the state
+// belongs to (SavedHeader; checked on the device by the backward pass, which cannot read it on the host
+// without synchronising), the rows' base-2 log-sum-exp (fp32, padded to whole query blocks), then O^s
+// (bf16 [BH, N, D]).
 struct SavedState {
-  size_t lse2, os, total;
+  size_t hdr, lse2, os, total;
 };
 SavedState make_saved(const Problem& p) {
   SavedState v;
-  v.lse2 = 0;
-  v.os = align256((size_t)p.BH * p.Tq * p.block_q * 4);
+  v.hdr = 0;
+  v.lse2 = 256;
+  v.os = v.lse2 + align256((size_t)p.BH * p.Tq * p.block_q * 4);
   v.total = v.os + align256((size_t)p.BH * p.N * D * 2);
   return v;
+}
+SavedHeader saved_header(const Problem& p) {
+  return SavedHeader{SAVED_MAGIC, p.B, p.H, p.N, p.block_q, p.n_c, 0, 0};
 }
 
 // Scratch of the backward pass, laid out after the forward pass's workspace map.
@@ -572,6 +578,7 @@ int sla_attention_fwd_train_strided(const void* q, const void* k, const void* v,
   const SavedState V = make_saved(p);
   if ((st = check_ws(saved, saved_bytes, V.total)) != SLA_OK) return st;
   const int rec = (g_prof.ev && g_prof.used < g_prof.capacity) ? g_prof.used++ : -1;
+  launch_write_saved_header(saved_header(p), at<SavedHeader>(saved, V.hdr), (hipStream_t)stream);
   return fwd_bf16(q, k, v, out, p, proj_w, proj_b, phi_kind, workspace, W, (hipStream_t)stream, rec,
                   at<float>(saved, V.lse2), at<bf16_t>(saved, V.os));
 }
@@ -633,8 +640,9 @@ int sla_attention_bwd_strided(const void* q, const void* k, const void* v, const
   mark(s, rec, 1);
   const float* lse2 = at<float>(ws, X.lse2);
   if (saved) {  // the forward pass's statistics: only delta = dO . O^s is left to do
-    lse2 = (const float*)((const unsigned char*)saved + V.lse2);
-    launch_bwd_delta(p, dout, (const unsigned char*)saved + V.os, at<float>(ws, X.delta), s);
+    launch_bwd_delta(p, dout, (const unsigned char*)saved + V.os, (const SavedHeader*)((const unsigned char*)saved + V.hdr),
+                     saved_header(p), (const float*)((const unsigned char*)saved + V.lse2), at<float>(ws, X.lse2),
+                     at<float>(ws, X.delta), s);
   } else {
     if (launch_bwd_stats(p, q, k, v, dout, at<int32_t>(ws, W.crit), at<float>(ws, X.lse2), at<float>(ws, X.delta), s) != 0)
       return SLA_ERR_HIP;

@@ -234,7 +234,12 @@ int launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* 
                     const CodeScales* codes, hipStream_t stream);
 void launch_unpack_q8(const Problem& p, const int8_t* q8, int8_t* q_codes, hipStream_t stream);
 void launch_code_tensors(const Problem& p, const int8_t* q8, const int8_t* k8, bf16_t* qc, bf16_t* kc, hipStream_t stream);
-void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float* delta, hipStream_t stream);
+// First bytes of the state a training forward pass saves: which problem it belongs to.
+constexpr int SAVED_MAGIC = 0x534C4153;
+struct SavedHeader { int magic, B, H, N, block_q, n_c, pad0, pad1; };
+void launch_write_saved_header(const SavedHeader& h, SavedHeader* dst, hipStream_t stream);
+void launch_bwd_delta(const Problem& p, const void* dout, const void* os, const SavedHeader* hdr, const SavedHeader& want,
+                      const float* lse_saved, float* lse2, float* delta, hipStream_t stream);
 int launch_bwd_dq(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int32_t* crit,
                    const float* lse2, const float* delta, const float* dq_lin, void* dq, hipStream_t stream);
 int launch_bwd_dkv(const Problem& p, const void* q, const void* dout, const void* k, const void* v, const int8_t* mask,

@@ -1051,12 +1051,34 @@ int launch_fwd_bf16(const Problem& p, const void* q, const void* k, const void* 
   return 0;
 }
 
+// (the header's 256 bytes are written in full, so that two buffers filled for one problem are the same bytes)
+__global__ void write_saved_header_kernel(SavedHeader h, int* __restrict__ dst) {
+  const int v[8] = {h.magic, h.B, h.H, h.N, h.block_q, h.n_c, h.pad0, h.pad1};
+  int x = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    if ((int)threadIdx.x == e) x = v[e];
+  dst[threadIdx.x] = x;
+}
+
+void launch_write_saved_header(const SavedHeader& h, SavedHeader* dst, hipStream_t stream) {
+  write_saved_header_kernel<<<1, 64, 0, stream>>>(h, (int*)dst);
+}
+
 // delta[bh][row] = dO[row] . O^s[row] from a saved O^s (rows beyond N: 0); one wavefront per 8 rows.
+// The saved state's header must name this problem (shape, query block size, critical blocks per row): a
+// buffer that no training forward pass of the same problem filled gives delta = lse = NaN, and with them NaN in
+// every gradient, instead of plausible wrong numbers (the host cannot look without synchronising).
 __global__ void __launch_bounds__(256) bwd_delta_kernel(const bf16_t* __restrict__ dout, const bf16_t* __restrict__ os,
+                                                        const SavedHeader* __restrict__ hdr, SavedHeader want,
+                                                        const float* __restrict__ lse_saved, float* __restrict__ lse2,
                                                         float* __restrict__ delta, int N, int rows_padded, int BH, int H,
                                                         Layout ld) {
   const long long gr = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);  // padded row index over all heads
   if (gr >= (long long)BH * rows_padded) return;
+  const SavedHeader got = *hdr;
+  const bool mine = got.magic == want.magic && got.B == want.B && got.H == want.H && got.N == want.N &&
+                    got.block_q == want.block_q && got.n_c == want.n_c;
   const int bh = (int)(gr / rows_padded), row = (int)(gr - (long long)bh * rows_padded), part = threadIdx.x & 7;
   float s = 0.f;
   if (row < N) {
@@ -1072,13 +1094,17 @@ __global__ void __launch_bounds__(256) bwd_delta_kernel(const bf16_t* __restrict
   s += __shfl_xor(s, 1);
   s += __shfl_xor(s, 2);
   s += __shfl_xor(s, 4);
-  if (part == 0) delta[gr] = s;
+  if (part == 0) {  // (the log-sum-exp goes to the workspace copy the other kernels read: poisoned alike)
+    delta[gr] = mine ? s : __builtin_nanf("");
+    lse2[gr] = mine ? lse_saved[gr] : __builtin_nanf("");
+  }
 }
 
-void launch_bwd_delta(const Problem& p, const void* dout, const void* os, float* delta, hipStream_t stream) {
+void launch_bwd_delta(const Problem& p, const void* dout, const void* os, const SavedHeader* hdr, const SavedHeader& want,
+                      const float* lse_saved, float* lse2, float* delta, hipStream_t stream) {
   const int rows_padded = p.Tq * p.block_q;
   const long long total = (long long)p.BH * rows_padded;
-  bwd_delta_kernel<<<(unsigned)((total + 31) / 32), 256, 0, stream>>>((const bf16_t*)dout, (const bf16_t*)os, delta, p.N,
+  bwd_delta_kernel<<<(unsigned)((total + 31) / 32), 256, 0, stream>>>((const bf16_t*)dout, (const bf16_t*)os, hdr, want, lse_saved, lse2, delta, p.N,
                                                                      rows_padded, p.BH, p.H, p.ld);
 }
 

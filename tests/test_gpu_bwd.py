@@ -228,3 +228,21 @@ def test_training_step_on_token_major_tensors_gives_the_same_bits(bq, rc, rm):
             ref = sla.sla_attention_bwd(qd, kd, vd, dd, bq, 64, rc, rm, proj_w=Wd, want_dw=True, want_db=True)
         for got, want in zip((gq, gk, gv, dw, db), ref):
             assert torch.equal(got, want)
+
+
+def test_saved_state_of_another_problem_poisons_the_gradients():
+    """The state a training forward pass saves names its problem; handed to a backward pass with another number of
+    critical blocks per row (same sizes, so the byte count matches) every gradient comes out NaN, not plausibly wrong."""
+    cfg = synth.custom_config(1, 2, (5, 10, 20), block_q=128, topk_ratio=0.25, marginal_ratio=0.5, cfg_id=330)
+    q, k, v = synth.make_qkv(cfg)
+    dout = synth.make_qkv(cfg, seed=7)[2]
+    W = synth.make_proj(cfg)
+    qd, kd, vd, dd, Wd = (t.cuda() for t in (q, k, v, dout, W))
+    out, saved = sla.sla_attention_fwd_train(qd, kd, vd, 128, 64, 0.25, 0.5, proj_w=Wd)
+    good = sla.sla_attention_bwd(qd, kd, vd, dd, 128, 64, 0.25, 0.5, proj_w=Wd, saved=saved)
+    assert all(torch.isfinite(g.float()).all() for g in good[:3])
+    bad = sla.sla_attention_bwd(qd, kd, vd, dd, 128, 64, 0.5, 0.5, proj_w=Wd, saved=saved)   # 8 critical blocks, not 4
+    assert all(torch.isnan(g.float()).any() for g in bad[:3])
+    junk = torch.zeros_like(saved)
+    assert torch.isnan(sla.sla_attention_bwd(qd, kd, vd, dd, 128, 64, 0.25, 0.5, proj_w=Wd, saved=junk)[0].float()).any()
+

@@ -60,9 +60,9 @@ def test_backward_sizes_and_argument_errors():
     assert L.sla_attention_bwd(*args(phi=3)) == sla.ERR_UNSUPPORTED          # not a feature map
     assert L.sla_attention_bwd(*args(ws=None)) == sla.ERR_WORKSPACE
     assert L.sla_attention_bwd(*args(bytes=bwd - 1)) == sla.ERR_WORKSPACE
-    # the saved state: padded per-row statistics plus a bf16 copy of O^s
+    # the saved state: a 256-byte header, padded per-row statistics, a bf16 copy of O^s
     sv = sla.sla_saved_bytes(1, 2, 1000, 128, 128)
-    assert sv == (2 * 1024 * 4 + 255) // 256 * 256 + (2 * 1000 * 128 * 2 + 255) // 256 * 256
+    assert sv == 256 + (2 * 1024 * 4 + 255) // 256 * 256 + (2 * 1000 * 128 * 2 + 255) // 256 * 256
     assert sla.sla_saved_bytes(1, 2, 1000, 64, 128) == 0 and sla.sla_saved_bytes(1, 2, 1000, 128, 96) == 0
     a = args()
     assert L.sla_attention_bwd_saved(*a[:19], WS, sv - 1, *a[19:]) == sla.ERR_WORKSPACE
