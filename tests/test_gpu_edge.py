@@ -128,3 +128,34 @@ def test_degenerate_inputs_unquantised_forward_and_backward(name):
         scale = max(np.abs(b).max(), 1.0)
         assert np.linalg.norm(a - b) <= 1e-2 * max(np.linalg.norm(b), np.sqrt(b.size)), "%s %s: Frobenius" % (name, key)
         assert np.abs(a - b).max() <= 3e-2 * scale, "%s %s: element" % (name, key)
+
+
+@pytest.mark.parametrize("bq", [128, 64])
+@pytest.mark.parametrize("n_c", [2, 5, 6, 7, 8, 9, 17])
+def test_every_list_length_through_the_sparse_stage(n_c, bq):
+    """The attention kernel's main loop takes four list entries per round, up to three more one by one, and the
+    ragged last key block apart: lists of every remainder, with and without the last block, chosen at random
+    (ascending, as the classification delivers them), through sla_sparse_attn_fwd against the oracle on the same mask.
+    With query blocks of 64 the kernel merges the lists of adjacent blocks (17 query blocks: the last pair has one)."""
+    cfg = synth.custom_config(1, 2, (6, 7, 25), block_q=bq, topk_ratio=0.2, marginal_ratio=0.4, cfg_id=710)   # N = 1050, Tk = 17
+    q, k, v = synth.make_qkv(cfg)
+    Tq, Tk = -(-cfg.N // bq), -(-cfg.N // 64)
+    rng = np.random.default_rng(1000 * n_c + bq)
+    masks = np.full((1, cfg.H, Tq, Tk), -1, dtype=np.int8)
+    for h in range(cfg.H):
+        for i in range(Tq):
+            pick = rng.choice(Tk, size=n_c, replace=False)
+            if i % 3 == 0 and (Tk - 1) not in pick:      # a third of the rows must end in the ragged block
+                pick[0] = Tk - 1
+            if i % 3 == 1 and n_c < Tk:                  # a third must not
+                pick = rng.choice(Tk - 1, size=n_c, replace=False)
+            masks[0, h, i, pick] = 1
+    crit = pu.lists_from_mask(masks)
+    out, lse = sla.sla_sparse_attn_fwd(*pu.to_dev(q, k, v, crit), bq, 64)
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for h in range(cfg.H):
+        ref, ref_lse = so.sparse_branch_quant(synth.as_f64(q[0, h]), synth.as_f64(k[0, h]), synth.as_f64(v[0, h]),
+                                              masks[0, h], bq, 64, return_lse=True, ref_tile=pu.REF_TILE)
+        pu.check_output(out[0, h], ref, "n_c %d head %d" % (n_c, h))
+        dl = np.abs(lse[0, h] - ref_lse)
+        assert dl.max() < 2e-2 and np.median(dl) < 1e-5
