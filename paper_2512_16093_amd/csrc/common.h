@@ -61,18 +61,13 @@ __device__ __forceinline__ int cvt_pk_e4m3(float a, float b, int old, bool hi) {
   return hi ? __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, true) : __builtin_amdgcn_cvt_pk_fp8_f32(a, b, old, false);
 }
 
-// INT8 code of x at scale 1 / inv: round(x * inv) to the nearest integer, ties to even, as the low byte
-// (two's complement) of the returned word.  Adding 1.5 * 2^23 inside the fma does the rounding;
-// |x * inv| <= 127 (to rounding) by the choice of scale, so no clamp is needed.  A true division would
-// differ only at rounding ties.
-__device__ __forceinline__ uint32_t int8_code_word(float x, float inv) {
-  return __float_as_uint(__builtin_fmaf(x, inv, 12582912.0f));
-}
-// The same code with exact ties: 127 x / amax as a correctly rounded quotient (the product 127 x is exact for a
-// 16-bit x; one Newton step on the reciprocal's estimate, whose residual the fma forms exactly), so a value that
-// lies exactly half way between two codes reaches the rounding as the tie it is and goes to the even code --
-// with the multiply above the last bit of the reciprocal decides such values, and 16-bit inputs make them common
-// (x = amax / 2 is one).  ramax = 1 / amax (0 if amax is 0: all codes 0).
+// INT8 code of x at the scale amax / 127, as the low byte (two's complement) of the returned word: the correctly
+// rounded quotient 127 x / amax (the product 127 x is exact for a 16-bit x; the reciprocal's estimate takes one
+// correction step whose residual the fma forms exactly), rounded to the nearest integer, ties to even, by adding
+// 1.5 * 2^23.  A value that lies exactly half way between two codes so reaches the rounding as the tie it is --
+// multiplying by a rounded reciprocal of the scale instead would let that reciprocal's last bit decide such
+// values, and 16-bit inputs make them common (x = amax / 2 is one).  |x| <= amax, so no clamp is needed.
+// ramax = 1 / amax (0 if amax is 0: all codes 0).
 __device__ __forceinline__ uint32_t int8_code_word_exact(float x, float amax, float ramax) {
   const float y = x * 127.0f;
   const float t0 = y * ramax;
