@@ -65,6 +65,9 @@ def parse():
     ap.add_argument("--saved-state", action="store_true",
                     help="sla_bwd workload: hand the backward pass the statistics of a training forward pass "
                          "(sla_attention_fwd_train, run once outside the timed region) instead of recomputing them")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="sla workload: leave out the short runs of the other two workloads (W8A8 Linear layer, SLA "
+                         "backward) that the default invocation appends to its line as `other_workloads`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget for the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -287,7 +290,7 @@ def main_w8a8(args):
         result["cpu_baseline"] = {"value": ops / full / 1e12, "unit": "TOP/s", "cores": int(cores), "kind": "oracle",
                                   "sample": "%d tokens x %d outputs x all %d features in %.2f s; extrapolated to "
                                             "%d x %d = %.0f s" % (rows, cols, K, t, M, N, full)}
-    print(json.dumps(result))
+    return result
 
 
 BWD_STAGE_NAMES = ("block_mask", "softmax_stats", "linear_branch", "dq", "dkv")
@@ -408,7 +411,7 @@ def main_bwd(args):
                                   "kind": "oracle",
                                   "sample": "one head of %d tokens (the first %d of head 0) in %.2f s; scaled by "
                                             "heads x (N / %d)^2 = %.0f s" % (Ns, Ns, t, Ns, full)}
-    print(json.dumps(result))
+    return result
 
 
 def main():
@@ -418,9 +421,11 @@ def main():
               "no collective); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if args.workload == "w8a8":
-        return main_w8a8(args)
+        print(json.dumps(main_w8a8(args)))
+        return
     if args.workload == "sla_bwd":
-        return main_bwd(args)
+        print(json.dumps(main_bwd(args)))
+        return
     import torch
     from paper_2512_16093_amd import binding as sla
     from paper_2512_16093_amd import synth
@@ -543,6 +548,27 @@ def main():
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, q, k, v, W, args.cpu_seconds, args.quant)
+    if not args.only_headline and args.quant == "int8fp8" and args.layout == "bhnd" and cfg.cfg_id == 4:
+        # The other two workloads of this file, timed in the same run (each is also a line of its own under
+        # --workload): short runs, their own metrics; a failure there is reported and leaves the headline alone.
+        del qd, kd, vd, out, ws
+        torch.cuda.empty_cache()
+        other = {}
+        for name, fn, over in (("w8a8_linear", main_w8a8, {"workload": "w8a8", "steps": 20, "warmup": 3}),
+                               ("sla_bwd", main_bwd, {"workload": "sla_bwd", "steps": 5, "warmup": 1})):
+            a2 = argparse.Namespace(**vars(args))
+            for key, val in over.items():
+                setattr(a2, key, val)
+            a2.no_cpu_baseline, a2.copy_calibration = True, False
+            try:
+                print("[bench] also timing %s ..." % name, file=sys.stderr, flush=True)
+                r = fn(a2)
+                other[name] = {k_: r[k_] for k_ in ("metric", "value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config",
+                                                    "stage_ms", "roofline") if k_ in r}
+            except Exception as exc:   # (never takes the headline line down)
+                other[name] = {"error": repr(exc)}
+            torch.cuda.empty_cache()
+        result["other_workloads"] = other
     print(json.dumps(result))
 
 
