@@ -401,3 +401,30 @@ def test_prepass_and_attend_give_the_bits_of_the_single_call():
     sla.sla_fwd_attend(tm[0], out, 128, 64, 0.1, 0.2, ws, proj_b=bias)
     torch.cuda.synchronize()
     assert torch.equal(out, ref)
+
+
+def test_forward_can_be_captured_in_a_graph_and_replayed():
+    """The forward call only enqueues kernels (no allocation, no synchronisation, clearing by a kernel), so it can
+    be recorded into a HIP graph: three replays on fresh inputs, with eager calls and synchronisations in between,
+    give the bits of the eager call every time."""
+    cfg = _cfg(2, (5, 10, 20), 128, 0.25, 0.5, cid=440)
+    W = synth.make_proj(cfg).cuda()
+    args = (cfg.block_q, cfg.block_k, cfg.topk_ratio, cfg.marginal_ratio)
+    qd, kd, vd = pu.to_dev(*synth.make_qkv(cfg, seed=9))
+    ws = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, *args)
+    ws_eager = sla.alloc_workspace(cfg.B, cfg.H, cfg.N, cfg.d, *args)
+    out = torch.empty_like(qd)
+    sla.sla_attention_fwd(qd, kd, vd, *args, proj_w=W, workspace=ws, out=out)     # (first call outside the capture)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sla.sla_attention_fwd(qd, kd, vd, *args, proj_w=W, workspace=ws, out=out)
+    for seed in (0, 1, 2):
+        q, k, v = pu.to_dev(*synth.make_qkv(cfg, seed=seed))
+        qd.copy_(q); kd.copy_(k); vd.copy_(v)
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = sla.sla_attention_fwd(q, k, v, *args, proj_w=W, workspace=ws_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), "replay %d differs from the eager call" % seed
