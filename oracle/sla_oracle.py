@@ -19,7 +19,8 @@ Pins (tests/test_oracle_sla.py): all-critical + no quantisation against dense
 softmax attention from a library; the exact mode and the low-bit sparse branch
 (both reference rules, both refresh intervals, both row sums, both low-bit
 modes) against the scalar-loop restatement in oracle/brute.py; formats against
-library conversions; closed-form rankings; textbook linear attention;
+library conversions, code rounding at exact ties against rational arithmetic
+(tests/test_oracle_formats.py); closed-form rankings; textbook linear attention;
 invariants.  Parity unpinned by the paper itself (no outside value exists; the
 readings define them): the choice of feature map, the meaning of "marginal",
 the projection form, and which of the equivalent-before-rounding variants of
