@@ -200,3 +200,15 @@ def test_sampled_evaluation_equals_the_full_one_on_the_sampled_blocks():
             else:
                 assert np.isnan(part[name][ks[j]]).all()
     assert part["dW"] is None and part["db"] is None
+
+
+def test_relu_derivative_switches_exactly_at_zero():
+    """The finite-difference pins keep away from relu's kink, so where the derivative switches is pinned apart:
+    1 for x > 0, 0 at and below 0 (the one-sided derivative from the left), to the last representable step."""
+    X = np.array([[-1.0, -0.005, -np.finfo(np.float64).tiny, 0.0, np.finfo(np.float64).tiny, 0.005, 2.0]])
+    dP = np.full_like(X, 3.0)
+    got = bo.feature_map_grad(X, np.maximum(X, 0.0), dP, "relu")
+    assert np.array_equal(got, np.array([[0.0, 0.0, 0.0, 0.0, 3.0, 3.0, 3.0]]))
+    # elu + 1: exp(x) for x <= 0 (continuous at 0 with value 1), 1 above
+    got = bo.feature_map_grad(X, None, dP, "elu1")
+    assert np.allclose(got, 3.0 * np.array([[np.exp(-1.0), np.exp(-0.005), 1.0, 1.0, 1.0, 1.0, 1.0]]), rtol=1e-15)
