@@ -81,7 +81,11 @@ def traffic_from_profile(name, cfg_id):
     (profiles/<name>: the line that ends in "per launch (the `roofline.traffic` of the bench line)"); the typed-in
     constant above is used if the file cannot be read, None for configs the summary does not cover."""
     import re
-    if cfg_id != 4:
+    if isinstance(name, dict):        # config id -> summary file
+        name = name.get(cfg_id)
+    elif cfg_id != 4:
+        name = None
+    if name is None:
         return None, None
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", name)
     try:
@@ -510,7 +514,7 @@ def main():
     t_sparse = stage_mean[4] * 1e-3           # the roofline takes the kernel's AVERAGE launch duration
     achieved = ops / t_sparse / 1e12
     peak = PEAK_MFMA_8BIT_TOPS if low_bit else PEAK_MFMA_BF16_TFLOPS
-    traffic, traffic_src = traffic_from_profile("sla_fwd_wan14b-720p.md", cfg.cfg_id)
+    traffic, traffic_src = traffic_from_profile({4: "sla_fwd_wan14b-720p.md", 2: "sla_fwd_dense-quant.md"}, cfg.cfg_id)
     if traffic is None and cfg.cfg_id in SPARSE_TRAFFIC_BYTES:
         traffic, traffic_src = SPARSE_TRAFFIC_BYTES[cfg.cfg_id], "constant in bench.py (from the same summary)"
     result = {
