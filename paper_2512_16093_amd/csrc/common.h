@@ -67,13 +67,24 @@ __device__ __forceinline__ int cvt_pk_e4m3(float a, float b, int old, bool hi) {
 // 1.5 * 2^23.  A value that lies exactly half way between two codes so reaches the rounding as the tie it is --
 // multiplying by a rounded reciprocal of the scale instead would let that reciprocal's last bit decide such
 // values, and 16-bit inputs make them common (x = amax / 2 is one).  |x| <= amax, so no clamp is needed.
-// ramax = 1 / amax (0 if amax is 0: all codes 0).
-__device__ __forceinline__ uint32_t int8_code_word_exact(float x, float amax, float ramax) {
-  const float y = x * 127.0f;
-  const float t0 = y * ramax;
-  const float r = __builtin_fmaf(-t0, amax, y);
-  const float t1 = __builtin_fmaf(r, ramax, t0);
-  return __float_as_uint(t1 + 12582912.0f);
+// The caller passes the block's maximum through code_scale() once: amax brought into the range where its
+// reciprocal is finite (a power-of-two factor `up`, exact, for maxima below 2^-100: 16-bit inputs reach down to
+// 2^-133), that reciprocal (0 if amax is 0: all codes 0), and k = 127 * up (448 * up for the FP8 quotient).
+struct CodeScale { float amax, ramax, k; };
+__device__ __forceinline__ CodeScale code_scale(float amax, float levels) {
+  const float up = amax < 0x1p-100f ? 0x1p64f : 1.0f;
+  const float a = amax * up;
+  return CodeScale{a, a > 0.f ? 1.0f / a : 0.f, levels * up};
+}
+// levels * x / amax, correctly rounded (exact where the quotient is representable: ties stay ties).
+__device__ __forceinline__ float exact_quotient(float x, const CodeScale& cs) {
+  const float y = x * cs.k;
+  const float t0 = y * cs.ramax;
+  const float r = __builtin_fmaf(-t0, cs.amax, y);
+  return __builtin_fmaf(r, cs.ramax, t0);
+}
+__device__ __forceinline__ uint32_t int8_code_word_exact(float x, const CodeScale& cs) {
+  return __float_as_uint(exact_quotient(x, cs) + 12582912.0f);
 }
 // Where channel c's code sits in a row of the Q code tensor: the 64 bytes a lane half of the attention kernel
 // takes as its B operands are contiguous (lane half hf holds channels 32 s + 16 hf + 0..15 of step s = 0..3).

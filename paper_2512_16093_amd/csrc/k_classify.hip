@@ -130,13 +130,13 @@ __global__ void __launch_bounds__(256) pool_stats_kernel(
   for (int r = 0; r < 8; ++r) {
     const int rl = rg + 16 * r;
     if (row0 + rl >= N) continue;
-    const float amax = s_qmax[r >> 2], ramax = amax > 0.f ? 1.0f / amax : 0.f;
+    const CodeScale cs = code_scale(s_qmax[r >> 2], 127.0f);
     const uint32_t wq[4] = {qkeep[r].x, qkeep[r].y, qkeep[r].z, qkeep[r].w};
     uint32_t c[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      c[2 * e] = int8_code_word_exact(bf16_lo(wq[e]), amax, ramax);
-      c[2 * e + 1] = int8_code_word_exact(bf16_hi(wq[e]), amax, ramax);
+      c[2 * e] = int8_code_word_exact(bf16_lo(wq[e]), cs);
+      c[2 * e + 1] = int8_code_word_exact(bf16_hi(wq[e]), cs);
     }
     *(uint2*)(dst + (size_t)rl * D) = make_uint2(pack_low_bytes(c[0], c[1], c[2], c[3]), pack_low_bytes(c[4], c[5], c[6], c[7]));
   }

@@ -64,17 +64,12 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
   }
 
   if (want_quant) {
-    float mu[8], vmax[8];
+    float mu[8];
+    CodeScale vcs[8];  // per channel: max|V| (its scale is this / 448), its reciprocal, 448
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       mu[e] = mu_k[(size_t)bh * D + cg * 8 + e];
-      vmax[e] = __uint_as_float(amax_v[(size_t)bh * D + cg * 8 + e]);  // max|V| of the channel (its scale is this / 448)
-    }
-    float rvm[8];  // 1 / max|V|, refined to (almost always) the correctly rounded reciprocal; 0 for an all-zero channel
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float r0 = __builtin_amdgcn_rcpf(vmax[e]);
-      rvm[e] = vmax[e] > 0.f ? __builtin_fmaf(__builtin_fmaf(-vmax[e], r0, 1.0f), r0, r0) : 0.f;
+      vcs[e] = code_scale(__uint_as_float(amax_v[(size_t)bh * D + cg * 8 + e]), E4M3_MAX);
     }
     float kt[4][8], amax = 0.f;
 #pragma unroll
@@ -117,9 +112,7 @@ __global__ void __launch_bounds__(256, 4) prep_kv_kernel(
         // value exactly half way between two FP8 values reaches the conversion as the tie it is -- at a
         // third of the cost of the general division sequence
         const uint32_t word = (e >> 1) == 0 ? vraw[r].x : (e >> 1) == 1 ? vraw[r].y : (e >> 1) == 2 ? vraw[r].z : vraw[r].w;
-        const float vf = ((e & 1) ? bf16_hi(word) : bf16_lo(word)) * E4M3_MAX;
-        float qv = vf * rvm[e];
-        qv = __builtin_fmaf(__builtin_fmaf(-qv, vmax[e], vf), rvm[e], qv);
+        const float qv = exact_quotient((e & 1) ? bf16_hi(word) : bf16_lo(word), vcs[e]);
         x[r] = clamp_e4m3(qv);
       }
       int code = cvt_pk_e4m3(x[0], x[1], 0, false);

@@ -75,7 +75,7 @@ __global__ void __launch_bounds__(256) w8a8_quantize_kernel(const bf16_t* __rest
   // codes = the correctly rounded quotient 127 x / amax, rounded to the nearest integer with ties to even
   // (int8_code_word_exact: exact ties stay ties -- with 16-bit inputs they are common, x = amax / 2 is one);
   // the two's-complement low byte of the returned word is the code; |x / s| <= 127.
-  const float ramax = amax > 0.f ? 1.0f / amax : 0.f;
+  const CodeScale cs = code_scale(amax, 127.0f);
   const float sgn = (negate_odd && (kb & 1)) ? -1.0f : 1.0f;
   unsigned char* out = (unsigned char*)blk;
 #pragma unroll
@@ -84,8 +84,8 @@ __global__ void __launch_bounds__(256) w8a8_quantize_kernel(const bf16_t* __rest
     uint32_t b[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      b[2 * e] = int8_code_word_exact(sgn * bf16_lo(wd[e]), amax, ramax);
-      b[2 * e + 1] = int8_code_word_exact(sgn * bf16_hi(wd[e]), amax, ramax);
+      b[2 * e] = int8_code_word_exact(sgn * bf16_lo(wd[e]), cs);
+      b[2 * e + 1] = int8_code_word_exact(sgn * bf16_hi(wd[e]), cs);
     }
     const uint32_t lo = __builtin_amdgcn_perm(__builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u),
                                               __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u), 0x05040100u);

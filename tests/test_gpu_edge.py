@@ -159,3 +159,24 @@ def test_every_list_length_through_the_sparse_stage(n_c, bq):
         pu.check_output(out[0, h], ref, "n_c %d head %d" % (n_c, h))
         dl = np.abs(lse[0, h] - ref_lse)
         assert dl.max() < 2e-2 and np.median(dl) < 1e-5
+
+
+def test_codes_of_blocks_with_tiny_maxima():
+    """Blocks whose largest magnitude is far below the reciprocal's range (16-bit inputs reach 2^-133; 1 / 2^-130
+    overflows fp32): the quotient is formed on a rescaled maximum, the codes are still the oracle's."""
+    from oracle import formats
+    cfg = synth.custom_config(1, 1, (2, 8, 16), block_q=128, topk_ratio=0.5, marginal_ratio=0.5, cfg_id=730)   # N = 256
+    q, k, v = synth.make_qkv(cfg)
+    q, v = q.float(), v.float()
+    q[:, :, :128] *= 2.0 ** -128          # first query block: maxima near 2^-126, most values denormal in bf16
+    v[..., 3] *= 2.0 ** -127
+    v[..., 7] *= 2.0 ** -110
+    q, v = q.to(torch.bfloat16), v.to(torch.bfloat16)
+    qc, qs = (t.cpu().numpy() for t in sla.sla_debug_quantize_q(q.cuda(), 128))
+    vc = sla.sla_debug_quantize_kv(k.cuda(), v.cuda())[3].cpu().numpy()
+    Q8, dq = so.quantize_q(synth.as_f64(q[0, 0]), 128)
+    assert np.array_equal(qc[0, 0].astype(np.float64), Q8) and np.allclose(qs[0, 0], dq, rtol=1e-6)
+    assert np.array_equal(formats.e4m3_decode(vc[0, 0]), so.quantize_v(synth.as_f64(v[0, 0]))[0])
+    out = sla.sla_attention_fwd(q.cuda(), k.cuda(), v.cuda(), 128, 64, 0.5, 0.5).float().cpu().numpy()
+    r = pu.oracle_head(cfg, q, k, v, 0, 0, None)
+    pu.check_output(out[0, 0], r["out"], "tiny maxima")
